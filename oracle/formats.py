@@ -1,0 +1,63 @@
+"""Storage formats used by the bit-spec layer: bfloat16 and OCP FP8 e4m3fn (Sec. 5.2 of the
+paper uses per-tensor scaled FP8; the workload fixes e4m3 for weights, activations, gradients).
+
+Test infrastructure only (see the package header).  Pinned: every function here is checked in
+``tests/test_oracle_formats.py`` against the format definitions (exhaustive decode tables,
+round-trips, hand-computed ties) and against PyTorch's CPU casts, which are an independent
+implementation of the same IEEE-style round-to-nearest-even conversions.
+"""
+import numpy as np
+
+E4M3_MAX = 448.0  # largest finite e4m3fn magnitude: 2^8 * 1.75
+
+
+def bf16_to_f32(bits):
+    """uint16 bfloat16 patterns -> float32 values (exact: bf16 is the top half of a float32)."""
+    bits = np.asarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f32_to_bf16_rne(x):
+    """float32 -> bfloat16 patterns (uint16), round to nearest, ties to even.  NaN not handled."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = (u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)
+    return r.astype(np.uint16)
+
+
+def e4m3_to_f32(codes):
+    """uint8 e4m3fn codes -> float32.  1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent 0 is
+    subnormal (m * 2^-9); there is no infinity; S.1111.111 is NaN."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    s = (c >> 7) & 1
+    e = (c >> 3) & 15
+    m = c & 7
+    mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(s == 1, -mag, mag).astype(np.float32)
+
+
+def f32_to_e4m3_rne_sat(x):
+    """float32 -> e4m3fn codes (uint8): clamp to +-448, then round to nearest, ties to even;
+    subnormals are kept (no flush); the sign of zero is kept."""
+    x = np.asarray(x, dtype=np.float32)
+    neg = np.signbit(x)
+    a = np.minimum(np.abs(x).astype(np.float64), E4M3_MAX)
+    # exponent of the binade that holds a (clamped below at the subnormal binade 2^-6)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6, 8)
+    # re-derive with frexp to be safe against log2 rounding at binade edges
+    mant, ex = np.frexp(a)            # a = mant * 2^ex, mant in [0.5, 1)
+    e_exact = np.where(a > 0, ex - 1, -6)
+    e = np.clip(e_exact, -6, 8).astype(np.int64)
+    step = np.exp2((e - 3).astype(np.float64))      # spacing of representable values in that binade
+    q = np.rint(a / step)                            # half-to-even, exact scaling by a power of two
+    # q is in [0, 16]; q == 16 carries into the next binade
+    carry = q >= 16
+    e = np.where(carry, e + 1, e)
+    q = np.where(carry, 8, q).astype(np.int64)
+    sub = q < 8                                      # below the smallest normal of binade -6
+    code = np.where(sub, q, ((e + 7) << 3) | (q - 8))
+    code = code | (neg.astype(np.int64) << 7)
+    return code.astype(np.uint8)

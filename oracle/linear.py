@@ -1,0 +1,69 @@
+"""The sparse linear layer of Sec. 5.1: Z = X S(W)^T and grad_W = MVUE(grad_Z^T) X.
+
+Test infrastructure only (see the package header).  Both products are the plain definitions,
+evaluated in float64 on exactly the quantised operands the storage formats hold (bf16 or e4m3
+decoded without error), so the only difference to a finite-precision GEMM is accumulation
+rounding.  Pinned (tests/test_oracle_linear.py): a pure-Python triple loop on tiny shapes,
+linearity, and -- for the weight gradient -- convergence of the mean over seeds to the dense
+product grad_Z^T X.
+"""
+import numpy as np
+
+from . import formats
+from . import projection
+from . import mvue
+
+
+def decode_activations(codes, dtype="bf16"):
+    """Stored activation / gradient patterns -> exact float64 values."""
+    if dtype == "bf16":
+        return formats.bf16_to_f32(codes).astype(np.float64)
+    if dtype == "e4m3":
+        return formats.e4m3_to_f32(codes).astype(np.float64)
+    raise ValueError("dtype must be 'bf16' or 'e4m3'")
+
+
+def linear_fwd(x_codes, vals, meta, dtype="bf16", x_scale=1.0, w_scale=1.0):
+    """Z = (x_scale * w_scale) * X . decode(vals, meta)^T   in float64.  X: (T, I), result (T, O)."""
+    X = decode_activations(x_codes, dtype)
+    Wd = projection.decode_packed(vals, meta, dtype)
+    return (X @ Wd.T) * (np.float64(np.float32(x_scale)) * np.float64(np.float32(w_scale)))
+
+
+def linear_fwd_loops(X, Wd):
+    """Triple loop Z[t][o] = sum_i X[t][i] Wd[o][i] for tiny shapes (pure Python floats)."""
+    T, I = X.shape
+    O = Wd.shape[0]
+    Z = [[0.0] * O for _ in range(T)]
+    for t in range(T):
+        for o in range(O):
+            acc = 0.0
+            for i in range(I):
+                acc += float(X[t][i]) * float(Wd[o][i])
+            Z[t][o] = acc
+    return np.array(Z, dtype=np.float64)
+
+
+def mvue_dense(dy_codes, seed, offset, dtype="bf16"):
+    """theta = MVUE(dY^T)^T as a dense-with-zeros (T, O) float64 matrix of the STORED operand values
+    (for e4m3 these are theta/2; the factor 2 belongs to the epilogue scale)."""
+    vals, meta = mvue.mvue_pack(dy_codes, seed, offset, dtype)
+    return projection.decode_packed(vals, meta, dtype).T            # (O, T) -> (T, O)
+
+
+def linear_wgrad(dy_codes, x_codes, seed, offset, dtype="bf16", dy_scale=1.0, x_scale=1.0):
+    """grad_W = scale * MVUE(dY^T) X in float64: (O, I).  scale = dy_scale * x_scale, times 2 for
+    e4m3 because the stored sparse operand holds theta / 2."""
+    theta = mvue_dense(dy_codes, seed, offset, dtype)               # (T, O)
+    X = decode_activations(x_codes, dtype)
+    scale = np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale))
+    if dtype == "e4m3":
+        scale = scale * 2.0
+    return (theta.T @ X) * scale
+
+
+def linear_wgrad_dense(dy_codes, x_codes, dtype="bf16", dy_scale=1.0, x_scale=1.0):
+    """The dense product grad_Z^T X that MVUE estimates without bias."""
+    dY = decode_activations(dy_codes, dtype)
+    X = decode_activations(x_codes, dtype)
+    return (dY.T @ X) * (np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale)))

@@ -1,0 +1,194 @@
+"""Minimum-variance unbiased 2:4 sparsifier for the output gradient (Sec. 5.1 of the paper).
+
+Test infrastructure only (see the package header).
+
+The paper names the estimator (MVUE applied to grad_Z^T in grad_W = MVUE(grad_Z^T) X) and states
+its properties -- unbiased, minimum variance, 2:4 -- but gives no formula; it defers to the
+work it cites.  The algorithm below is therefore specified from those properties alone:
+
+For a group g in R^4 (four consecutive tokens of one output channel -- the contraction index of
+grad_Z^T X is the token index, and hardware 2:4 sparsity lies along the contraction), an
+estimator theta with two recorded positions, theta_i = g_i / pi_i when i is recorded (inclusion
+probability pi_i, sum pi_i = 2, pi_i <= 1) and 0 otherwise, is unbiased with total variance
+sum_i g_i^2 (1/pi_i - 1).  Minimising over pi gives pi_i proportional to |g_i|, capped at 1:
+
+  m_i = |g_i|, mx = max m, c = lowest index attaining mx, r = sum of the other three.
+  capped case (mx > r):   pi_c = 1, pi_i = m_i / r;   theta_c = g_c, theta_i = sign(g_i) r.
+  uncapped case:          pi_i = 2 m_i / s, s = sum m; theta_i = sign(g_i) s / 2.
+
+Several joint distributions have these marginals; the one fixed here is systematic sampling
+with one uniform u in [0,1) per group: lay the magnitudes (capped case: without element c) on a
+line in index order with prefix sums P0, P1, P2 and total L.  Uncapped: h = L/2 and the two
+recorded positions are the intervals holding tau0 = u*h and tau1 = tau0 + h.  Capped: h = L and
+the second recorded position is the interval holding tau0 = u*h.  The interval holding tau is
+found as #{k in {0,1,2} : P_k <= tau}.  Guards that only act when floating-point rounding or an
+all-zero line breaks the exact-arithmetic guarantees: uncapped i0 <- min(i0, 2),
+i1 <- min(3, max(i1, i0 + 1)); capped j <- c xor 1 if j == c.  A recorded element whose
+magnitude is zero gets the value +0.  Positions are recorded in ascending order.
+
+Arithmetic order (bit-spec, float32, no fused multiply-add):
+  r = ((m0' + m1') + m2') + m3' with m_c' = 0;  P0 = l0, P1 = P0 + l1, P2 = P1 + l2, L = P2 + l3 on
+  the chosen line l; h = L or 0.5*L; tau0 = u*h; tau1 = tau0 + h; comparisons are exact.
+  bf16 storage: the common magnitude is RNE_bf16(h), element c keeps its input pattern.
+  e4m3 storage: theta can reach twice the largest input, so the stored operand is theta/2
+  (RNE_e4m3 of 0.5*h, or of 0.5*|g_c| for element c) and the GEMM epilogue multiplies by 2.
+
+Pinned (tests/test_oracle_mvue.py): worked groups, exactly-two-positions invariant, empirical
+inclusion frequencies against the closed-form pi, Monte-Carlo mean against g with the closed-
+form variance, optimality of pi against random feasible alternatives, continuity of the two
+branches at mx == r, and invariance of groups that are already 2:4 with equal magnitudes.
+Whether this joint distribution equals the one used by the work the paper cites is unpinned
+(that text is not available here); every property the paper itself states is pinned.
+"""
+import numpy as np
+
+from . import formats
+from . import rng as _rng
+
+
+# --------------------------------------------------------------------------- closed forms
+
+def inclusion_probabilities(g):
+    """(n, 4) float64 groups -> (n, 4) optimal inclusion probabilities."""
+    m = np.abs(np.asarray(g, dtype=np.float64)).reshape(-1, 4)
+    n = m.shape[0]
+    rows = np.arange(n)
+    mx = m.max(axis=1)
+    c = np.argmax(m == mx[:, None], axis=1)
+    mo = m.copy()
+    mo[rows, c] = 0.0
+    r = mo.sum(axis=1)
+    s = m.sum(axis=1)
+    capped = mx > r
+    with np.errstate(divide="ignore", invalid="ignore"):
+        pi_unc = np.where(s[:, None] > 0, 2.0 * m / s[:, None], 0.0)
+        pi_cap = np.where(r[:, None] > 0, mo / r[:, None], 0.0)
+    pi_cap[rows, c] = 1.0
+    return np.where(capped[:, None], pi_cap, pi_unc)
+
+
+def total_variance(g):
+    """Closed-form sum_i Var(theta_i) = sum_i g_i^2 (1/pi_i - 1) over elements with g_i != 0."""
+    g = np.asarray(g, dtype=np.float64).reshape(-1, 4)
+    pi = inclusion_probabilities(g)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        term = np.where(g != 0, g * g * (1.0 / pi - 1.0), 0.0)
+    return term.sum(axis=1)
+
+
+# --------------------------------------------------------------------------- selection core
+
+def _select(m, u, ft):
+    """Systematic-sampling selection on magnitudes m (n,4) with uniforms u (n,), all in dtype ft.
+
+    Returns pos0 < pos1 (recorded positions), h (the common magnitude of non-capped recorded
+    elements), capped (bool) and c (index of the maximum)."""
+    m = np.ascontiguousarray(m, dtype=ft)
+    u = np.ascontiguousarray(u, dtype=ft)
+    n = m.shape[0]
+    rows = np.arange(n)
+    mx = m.max(axis=1)
+    c = np.argmax(m == mx[:, None], axis=1)
+    mo = m.copy()
+    mo[rows, c] = ft(0)
+    r = ((mo[:, 0] + mo[:, 1]) + mo[:, 2]) + mo[:, 3]
+    capped = mx > r
+    line = np.where(capped[:, None], mo, m)
+    P0 = line[:, 0]
+    P1 = P0 + line[:, 1]
+    P2 = P1 + line[:, 2]
+    L = P2 + line[:, 3]
+    h = np.where(capped, L, ft(0.5) * L).astype(ft)
+    tau0 = (u * h).astype(ft)
+    tau1 = (tau0 + h).astype(ft)
+    i0 = (P0 <= tau0).astype(np.int64) + (P1 <= tau0) + (P2 <= tau0)
+    i1 = (P0 <= tau1).astype(np.int64) + (P1 <= tau1) + (P2 <= tau1)
+    i0u = np.minimum(i0, 2)
+    i1u = np.minimum(3, np.maximum(i1, i0u + 1))
+    j = np.where(i0 == c, c ^ 1, i0)
+    pos0 = np.where(capped, np.minimum(c, j), i0u)
+    pos1 = np.where(capped, np.maximum(c, j), i1u)
+    return pos0, pos1, h, capped, c
+
+
+# --------------------------------------------------------------------------- math layer
+
+def mvue_sample(g, u):
+    """float64 estimator: groups g (n,4), uniforms u (n,) -> dense theta (n,4) and positions (n,2)."""
+    g = np.asarray(g, dtype=np.float64).reshape(-1, 4)
+    m = np.abs(g)
+    pos0, pos1, h, capped, c = _select(m, np.asarray(u, dtype=np.float64), np.float64)
+    n = g.shape[0]
+    rows = np.arange(n)
+    theta = np.zeros_like(g)
+    for pos in (pos0, pos1):
+        gi = g[rows, pos]
+        val = np.where(gi != 0, np.copysign(h, gi), 0.0)
+        val = np.where(capped & (pos == c), gi, val)
+        theta[rows, pos] = val
+    return theta, np.stack([pos0, pos1], axis=1)
+
+
+# --------------------------------------------------------------------------- bit-spec layer
+
+def mvue_groups_bits(g_codes, u, dtype="bf16"):
+    """Bit-exact estimator on stored patterns.
+
+    g_codes : (n,4) uint16 bf16 patterns or uint8 e4m3 codes; u : (n,) float32 in [0,1).
+    Returns (vals (n,2) patterns in ascending position order, nibble (n,) = pos0 | pos1 << 2).
+    For e4m3 the returned codes hold theta/2."""
+    if dtype == "bf16":
+        g_codes = np.asarray(g_codes, dtype=np.uint16).reshape(-1, 4)
+        gf = formats.bf16_to_f32(g_codes)
+        sign_mask = np.uint16(0x8000)
+    elif dtype == "e4m3":
+        g_codes = np.asarray(g_codes, dtype=np.uint8).reshape(-1, 4)
+        gf = formats.e4m3_to_f32(g_codes)
+        sign_mask = np.uint8(0x80)
+    else:
+        raise ValueError("dtype must be 'bf16' or 'e4m3'")
+    m = np.abs(gf).astype(np.float32)
+    pos0, pos1, h, capped, c = _select(m, np.asarray(u, dtype=np.float32), np.float32)
+    n = m.shape[0]
+    rows = np.arange(n)
+    if dtype == "bf16":
+        hq = formats.f32_to_bf16_rne(h)
+    else:
+        hq = formats.f32_to_e4m3_rne_sat((np.float32(0.5) * h).astype(np.float32))
+    out = []
+    for pos in (pos0, pos1):
+        code = g_codes[rows, pos]
+        mi = m[rows, pos]
+        common = np.where(mi == 0, 0, (code & sign_mask) | hq).astype(g_codes.dtype)
+        if dtype == "bf16":
+            own = code
+        else:
+            own = (code & sign_mask) | formats.f32_to_e4m3_rne_sat((np.float32(0.5) * mi).astype(np.float32))
+        out.append(np.where(capped & (pos == c), own, common).astype(g_codes.dtype))
+    vals = np.stack(out, axis=1)
+    nib = (pos0 | (pos1 << 2)).astype(np.uint8)
+    return vals, nib
+
+
+def group_ids(T, O):
+    """gid[k, o] = k * O + o for token group k = t // 4 and output channel o."""
+    return (np.arange(T // 4, dtype=np.uint64)[:, None] * np.uint64(O) + np.arange(O, dtype=np.uint64)[None, :])
+
+
+def mvue_pack(dy_codes, seed, offset, dtype="bf16"):
+    """MVUE(dY^T) in packed 2:4 form.
+
+    dy_codes : (T, O) stored patterns of the output gradient (bf16 uint16 / e4m3 uint8).
+    Returns vals (O, T/2) and meta (O, T/8): row o holds, for token groups k = 0.. in order, the two
+    recorded values and the nibble pos0 | pos1 << 2 (even k in the low nibble of byte k // 2)."""
+    dy_codes = np.asarray(dy_codes)
+    T, O = dy_codes.shape
+    if T % 8 != 0:
+        raise ValueError("T must be a multiple of 8 (two groups per metadata byte)")
+    g = dy_codes.reshape(T // 4, 4, O).transpose(0, 2, 1).reshape(-1, 4)       # [(k, o), 4]
+    u = _rng.uniform24(seed, offset, group_ids(T, O).reshape(-1))
+    vals, nib = mvue_groups_bits(g, u, dtype)
+    vals = vals.reshape(T // 4, O, 2).transpose(1, 0, 2).reshape(O, T // 2)
+    nib = nib.reshape(T // 4, O).T.reshape(O, T // 8, 2)
+    meta = (nib[:, :, 0] | (nib[:, :, 1] << 4)).astype(np.uint8)
+    return np.ascontiguousarray(vals), np.ascontiguousarray(meta)

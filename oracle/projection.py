@@ -1,0 +1,215 @@
+"""2:4 soft-threshold projection S_soft, MSE-optimal scale beta, and the packed 2:4 format.
+
+Test infrastructure only (see the package header).
+
+Math layer (float64) -- the paper's definitions written out:
+  * ``soft_threshold``   Sec. 4.1, the displayed definition of S_soft (t = |t_2| of the
+                         ascending magnitude order = third-largest magnitude of the group);
+  * ``soft_threshold_sorted_form``  the same function as the appendix proof of Theorem 1 writes
+                         it for a magnitude-sorted group (used as a cross-check);
+  * ``hard_threshold`` / ``hard_threshold_mask``  Sec. 2, Eq. (hard-thresholding);
+  * ``beta_mse``         Sec. 4.2, beta = w^T S_soft(w) / ||S_soft(w)||^2;
+  * ``beta_l1``          Sec. 4.2, the L1-preserving variant the paper compares with;
+  * ``flip_rate``        Sec. 3.3, r_k = ||m(w_k) xor m(w_{k-1})||_1 / d.
+
+Bit-spec layer (float32 + integers) -- the rounding sequence a bf16 / e4m3 packed operand forces:
+  * ``project_pack``     S(w) = beta * S_soft(w) on bf16 inputs -> (values, 2-bit metadata, amax);
+  * ``decode_packed``    packed (values, metadata) -> dense-with-zeros matrix;
+  * ``kept_positions``   metadata -> the two recorded positions per group.
+
+Readings taken where the paper is silent (all restated in the design notes of the repository):
+  * ties: the VALUES of S_soft do not depend on how ties are broken (every element whose
+    magnitude equals t maps to 0); only the two RECORDED positions do.  Rule: rank by magnitude
+    descending, then index ascending; ranks 0 and 1 are recorded, in ascending index order.
+    Magnitude order is the unsigned order of the bf16 pattern with the sign bit cleared.
+  * sign of a kept-but-zero value: the literal forms a - t and a + t give +0 at a tie.
+  * rounding: sd = a -/+ t in float32, p = sd * beta in float32 (beta a float32 input),
+    bf16 path: value = RNE_bf16(p); e4m3 path: q = p / val_scale (float32 division), clamp to
+    +-448, value = RNE_e4m3(q).  amax = max |p| over recorded values (float32).
+
+Pinned (tests/test_oracle_projection.py): worked groups, the appendix's sorted form, the 2:4
+invariant, idempotence (projection), homogeneity, the 2-delta continuity bound of the Theorem 1
+proof, agreement of supports with the hard threshold, optimality of beta, and
+decode(pack(w)) against the float64 definition.
+"""
+import numpy as np
+
+from . import formats
+
+
+# --------------------------------------------------------------------------- math layer
+
+def _groups(a):
+    a = np.asarray(a, dtype=np.float64)
+    if a.shape[-1] % 4 != 0:
+        raise ValueError("last dimension must be a multiple of 4 (the method is defined on whole groups)")
+    return a.reshape(-1, 4)
+
+
+def soft_threshold(a):
+    """S_soft of Sec. 4.1 applied block-wise along the last axis (float64)."""
+    a = np.asarray(a, dtype=np.float64)
+    g = _groups(a)
+    t = np.sort(np.abs(g), axis=1)[:, 1:2]           # ascending magnitudes |t1|<=|t2|<=..: t = |t2|
+    out = np.where(g >= t, g - t, np.where(g <= -t, g + t, 0.0))
+    # the middle case (-t, t) -> 0 takes precedence only where the intervals do not overlap; for
+    # t == 0 the first and third intervals both contain 0 and both give 0, so no ambiguity.
+    return out.reshape(a.shape)
+
+
+def soft_threshold_sorted_form(a):
+    """The appendix's way of writing S_soft: after sorting a group by magnitude the result is
+    [0, 0, sign(a3)(|a3|-|a2|), sign(a4)(|a4|-|a2|)] put back in place (float64)."""
+    a = np.asarray(a, dtype=np.float64)
+    g = _groups(a)
+    order = np.argsort(np.abs(g), axis=1, kind="stable")
+    srt = np.take_along_axis(g, order, axis=1)
+    t = np.abs(srt[:, 1])
+    res_sorted = np.zeros_like(srt)
+    res_sorted[:, 2] = np.sign(srt[:, 2]) * (np.abs(srt[:, 2]) - t)
+    res_sorted[:, 3] = np.sign(srt[:, 3]) * (np.abs(srt[:, 3]) - t)
+    out = np.zeros_like(g)
+    np.put_along_axis(out, order, res_sorted, axis=1)
+    return out.reshape(a.shape)
+
+
+def hard_threshold(a):
+    """S_h of Sec. 2: keep a_i where |a_i| >= t, t the 2nd-largest magnitude of the group."""
+    a = np.asarray(a, dtype=np.float64)
+    g = _groups(a)
+    t = np.sort(np.abs(g), axis=1)[:, 2:3]
+    return np.where(np.abs(g) >= t, g, 0.0).reshape(a.shape)
+
+
+def hard_threshold_mask(a):
+    """0/1 mask of S_h (support of the kept elements), same shape as ``a``."""
+    a = np.asarray(a, dtype=np.float64)
+    g = _groups(a)
+    t = np.sort(np.abs(g), axis=1)[:, 2:3]
+    return (np.abs(g) >= t).reshape(a.shape)
+
+
+def beta_mse(w):
+    """Sec. 4.2: argmin_beta ||w - beta S_soft(w)||^2 = <w, S_soft(w)> / ||S_soft(w)||^2 (float64)."""
+    w = np.asarray(w, dtype=np.float64)
+    s = soft_threshold(w)
+    den = float(np.sum(s * s))
+    if den == 0.0:
+        raise ValueError("S_soft(w) is identically zero: beta is undefined")
+    return float(np.sum(w * s)) / den
+
+
+def beta_l1(w):
+    """Sec. 4.2: the L1-norm preserving scale ||w||_1 / ||S_soft(w)||_1 (comparison variant)."""
+    w = np.asarray(w, dtype=np.float64)
+    s = soft_threshold(w)
+    return float(np.sum(np.abs(w))) / float(np.sum(np.abs(s)))
+
+
+def flip_rate(mask_now, mask_before):
+    """Sec. 3.3: fraction of positions whose 0/1 mask changed between two iterations."""
+    a = np.asarray(mask_now, dtype=bool)
+    b = np.asarray(mask_before, dtype=bool)
+    return float(np.count_nonzero(a ^ b)) / a.size
+
+
+# --------------------------------------------------------------------------- bit-spec layer
+
+def rank_positions(w_bits):
+    """bf16 patterns (..., I) -> (idx0, idx1, third_mag_bits) per group of 4 along the last axis.
+
+    Ranking key: magnitude field (pattern & 0x7FFF) descending, then index ascending.
+    idx0 < idx1 are the positions of ranks 0 and 1; third_mag_bits is the magnitude field of rank 2.
+    """
+    bits = np.asarray(w_bits, dtype=np.uint16)
+    mag = (bits & np.uint16(0x7FFF)).astype(np.int64).reshape(-1, 4)
+    n = mag.shape[0]
+    rank = np.zeros((n, 4), dtype=np.int64)
+    for i in range(4):
+        for j in range(4):
+            if i == j:
+                continue
+            beats = (mag[:, j] > mag[:, i]) | ((mag[:, j] == mag[:, i]) & (j < i))
+            rank[:, i] += beats
+    kept = rank < 2
+    pos = np.tile(np.arange(4), (n, 1))
+    idx0 = np.where(kept, pos, 9).min(axis=1)
+    idx1 = np.where(kept, pos, -1).max(axis=1)
+    third = np.take_along_axis(mag, np.argmax(rank == 2, axis=1)[:, None], axis=1)[:, 0]
+    return idx0, idx1, third.astype(np.uint16)
+
+
+def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
+    """beta * S_soft(W) on a bf16 matrix, packed 2:4.
+
+    w_bits : uint16 (O, I) bf16 patterns, groups of 4 along I.
+    Returns (vals, meta, amax):
+      vals : (O, I/2) uint16 bf16 patterns, or uint8 e4m3 codes -- the two recorded values of each
+             group in ascending position order;
+      meta : (O, I/8) uint8 -- per group a nibble idx0 | idx1 << 2; the even group of a pair sits in
+             the low nibble;
+      amax : float32 max |p| over the recorded values before the storage rounding.
+    """
+    w_bits = np.asarray(w_bits, dtype=np.uint16)
+    O, I = w_bits.shape
+    if I % 8 != 0:
+        raise ValueError("I must be a multiple of 8 (two groups per metadata byte)")
+    beta32 = np.float32(beta)
+    idx0, idx1, third = rank_positions(w_bits)
+    a = formats.bf16_to_f32(w_bits).reshape(-1, 4)
+    t = formats.bf16_to_f32(third)                                    # >= 0
+    rows = np.arange(a.shape[0])
+    out_vals = []
+    amax = np.float32(0.0)
+    for idx in (idx0, idx1):
+        ai = a[rows, idx]
+        sd = (ai - np.copysign(t, ai)).astype(np.float32)             # a - t  or  a + t, one float32 op
+        p = (sd * beta32).astype(np.float32)
+        if p.size:
+            amax = max(amax, np.float32(np.max(np.abs(p))))
+        if val_dtype == "bf16":
+            if float(val_scale) != 1.0:
+                raise ValueError("val_scale must be 1 for bf16 values")
+            out_vals.append(formats.f32_to_bf16_rne(p))
+        elif val_dtype == "e4m3":
+            q = (p / np.float32(val_scale)).astype(np.float32)
+            out_vals.append(formats.f32_to_e4m3_rne_sat(q))
+        else:
+            raise ValueError("val_dtype must be 'bf16' or 'e4m3'")
+    vals = np.stack(out_vals, axis=1).reshape(O, I // 2)
+    nib = (idx0 | (idx1 << 2)).astype(np.uint8).reshape(O, I // 8, 2)
+    meta = (nib[:, :, 0] | (nib[:, :, 1] << 4)).astype(np.uint8)
+    return vals, meta, np.float32(amax)
+
+
+def kept_positions(meta):
+    """(O, I/8) metadata bytes -> (idx0, idx1) arrays of shape (O, I/4)."""
+    meta = np.asarray(meta, dtype=np.uint8)
+    O = meta.shape[0]
+    nib = np.stack([meta & 0xF, meta >> 4], axis=2).reshape(O, -1)
+    return (nib & 3).astype(np.int64), ((nib >> 2) & 3).astype(np.int64)
+
+
+def decode_packed(vals, meta, val_dtype="bf16"):
+    """Packed (vals, meta) -> dense-with-zeros float64 (O, I) holding the exact stored values."""
+    idx0, idx1 = kept_positions(meta)
+    O, G = idx0.shape
+    v = formats.bf16_to_f32(vals) if val_dtype == "bf16" else formats.e4m3_to_f32(vals)
+    v = v.astype(np.float64).reshape(O, G, 2)
+    dense = np.zeros((O, G, 4), dtype=np.float64)
+    r, g = np.meshgrid(np.arange(O), np.arange(G), indexing="ij")
+    dense[r, g, idx0] = v[:, :, 0]
+    # a well-formed group has idx0 != idx1; if they coincide the later write wins, as documented
+    dense[r, g, idx1] = v[:, :, 1]
+    return dense.reshape(O, G * 4)
+
+
+def structural_mask(meta):
+    """(O, I/8) metadata -> boolean (O, I) mask of the recorded positions."""
+    idx0, idx1 = kept_positions(meta)
+    O, G = idx0.shape
+    m = np.zeros((O, G, 4), dtype=bool)
+    r, g = np.meshgrid(np.arange(O), np.arange(G), indexing="ij")
+    m[r, g, idx0] = True
+    m[r, g, idx1] = True
+    return m.reshape(O, G * 4)

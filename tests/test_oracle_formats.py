@@ -1,0 +1,71 @@
+"""Pins for oracle/formats.py: format definitions, exhaustive tables, and PyTorch's CPU casts as an
+independent implementation of the same conversions."""
+import numpy as np
+import torch
+
+from oracle import formats as F
+
+
+def test_bf16_decode_is_top_half_of_float32():
+    assert F.bf16_to_f32(np.array([0x3F80, 0xC000, 0x0000, 0x8000, 0x3DCD], dtype=np.uint16)).tolist()[:2] == [1.0, -2.0]
+    x = F.bf16_to_f32(np.array([0x3DCD], dtype=np.uint16))[0]
+    assert abs(float(x) - 0.1) < 0.1 * 2 ** -8
+
+
+def test_bf16_roundtrip_all_finite_patterns():
+    allb = np.arange(65536, dtype=np.uint16)
+    f = F.bf16_to_f32(allb)
+    fin = np.isfinite(f)
+    assert np.array_equal(F.f32_to_bf16_rne(f[fin]), allb[fin])
+
+
+def test_bf16_rne_ties_by_hand():
+    # 1 + 2^-8 lies exactly between 1.0 (even mantissa) and 1 + 2^-7: ties to even -> 1.0
+    assert F.f32_to_bf16_rne(np.array([1.0 + 2.0 ** -8], dtype=np.float32))[0] == 0x3F80
+    # 1 + 3*2^-8 lies between 1+2^-7 (odd) and 1+2^-6 (even) -> 1+2^-6
+    assert F.f32_to_bf16_rne(np.array([1.0 + 3 * 2.0 ** -8], dtype=np.float32))[0] == 0x3F82
+    # just above the tie rounds up
+    assert F.f32_to_bf16_rne(np.array([np.nextafter(np.float32(1.0 + 2.0 ** -8), np.float32(2))], dtype=np.float32))[0] == 0x3F81
+
+
+def test_bf16_rne_matches_torch_cast():
+    rng = np.random.default_rng(1)
+    y = (rng.standard_normal(500000) * np.exp(rng.uniform(-20, 20, 500000))).astype(np.float32)
+    ref = torch.from_numpy(y).to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(ref, F.f32_to_bf16_rne(y))
+
+
+def test_e4m3_decode_table_by_definition():
+    assert F.e4m3_to_f32(np.array([0x38], dtype=np.uint8))[0] == 1.0          # e=7,m=0
+    assert F.e4m3_to_f32(np.array([0x7E], dtype=np.uint8))[0] == 448.0        # e=15,m=6
+    assert F.e4m3_to_f32(np.array([0x01], dtype=np.uint8))[0] == 2.0 ** -9    # smallest subnormal
+    assert F.e4m3_to_f32(np.array([0x08], dtype=np.uint8))[0] == 2.0 ** -6    # smallest normal
+    assert F.e4m3_to_f32(np.array([0xC4], dtype=np.uint8))[0] == -3.0
+    assert np.isnan(F.e4m3_to_f32(np.array([0x7F], dtype=np.uint8))[0])
+    allc = np.arange(256, dtype=np.uint8)
+    ref = torch.from_numpy(allc.copy()).view(torch.float8_e4m3fn).float().numpy()
+    got = F.e4m3_to_f32(allc)
+    assert np.array_equal(np.isnan(ref), np.isnan(got))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(ref[ok], got[ok])
+
+
+def test_e4m3_encode_roundtrip_and_ties():
+    allc = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    assert np.array_equal(F.f32_to_e4m3_rne_sat(F.e4m3_to_f32(allc)), allc)
+    # 1.0625 is halfway between 1.0 (m=0, even) and 1.125 (m=1): ties to even -> 1.0
+    assert F.f32_to_e4m3_rne_sat(np.array([1.0625], dtype=np.float32))[0] == 0x38
+    # 1.1875 halfway between 1.125 (odd) and 1.25 (even) -> 1.25
+    assert F.f32_to_e4m3_rne_sat(np.array([1.1875], dtype=np.float32))[0] == 0x3A
+    # saturation and subnormal rounding: 2^-10 is half the smallest subnormal -> ties to even -> 0
+    assert F.f32_to_e4m3_rne_sat(np.array([1e6, -1e6, 2.0 ** -10, 3 * 2.0 ** -10], dtype=np.float32)).tolist() == [0x7E, 0xFE, 0x00, 0x02]
+    # 15.5 * 2^-6 * ... carry into the next binade: 1.96875 -> 2.0
+    assert F.f32_to_e4m3_rne_sat(np.array([1.96875], dtype=np.float32))[0] == 0x40
+
+
+def test_e4m3_encode_matches_torch_cast_in_range():
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(300000) * np.exp(rng.uniform(-12, 5, 300000))).astype(np.float32)
+    x = np.clip(x, -448, 448)
+    ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(ref, F.f32_to_e4m3_rne_sat(x))

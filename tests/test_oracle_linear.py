@@ -1,0 +1,101 @@
+"""Pins for oracle/linear.py: the two products of Sec. 5.1 against brute force and their algebra."""
+import numpy as np
+
+from oracle import formats as F
+from oracle import linear as Lin
+from oracle import mvue as M
+from oracle import projection as P
+
+
+def _bf16(rng, shape, std):
+    return F.f32_to_bf16_rne((rng.standard_normal(shape) * std).astype(np.float32))
+
+
+def test_forward_against_triple_loop_and_dense_with_zeros():
+    rng = np.random.default_rng(0)
+    wb = _bf16(rng, (8, 16), 0.02)
+    xb = _bf16(rng, (12, 16), 1.0)
+    vals, meta, _ = P.project_pack(wb, 1.5)
+    Z = Lin.linear_fwd(xb, vals, meta)
+    Wd = P.decode_packed(vals, meta)
+    X = F.bf16_to_f32(xb).astype(np.float64)
+    assert np.allclose(Z, Lin.linear_fwd_loops(X, Wd), rtol=1e-13, atol=1e-18)
+    # a transposed operand or a wrong contraction axis would fail this non-square case
+    assert Z.shape == (12, 8)
+    # against the float64 definition of S(W) (before bf16 storage rounding of the values)
+    exact = X @ (1.5 * P.soft_threshold(F.bf16_to_f32(wb).astype(np.float64))).T
+    assert np.abs(Z - exact).max() <= 2.0 ** -8 * np.abs(X).sum(axis=1).max() * np.abs(Wd).max()
+
+
+def test_forward_scales_and_linearity():
+    rng = np.random.default_rng(1)
+    wb = _bf16(rng, (8, 32), 0.02)
+    vals, meta, _ = P.project_pack(wb, 1.0)
+    x1 = F.f32_to_bf16_rne(np.round(rng.standard_normal((4, 32)) * 4).astype(np.float32))
+    x2 = F.f32_to_bf16_rne(np.round(rng.standard_normal((4, 32)) * 4).astype(np.float32))
+    xs = F.f32_to_bf16_rne(F.bf16_to_f32(x1) + F.bf16_to_f32(x2))      # small integers: exact sum
+    Z1, Z2, Zs = (Lin.linear_fwd(x, vals, meta) for x in (x1, x2, xs))
+    assert np.allclose(Z1 + Z2, Zs, rtol=1e-13, atol=1e-18)
+    assert np.allclose(Lin.linear_fwd(x1, vals, meta, x_scale=0.5, w_scale=4.0), 2.0 * Z1)
+
+
+def test_forward_e4m3_decodes_codes():
+    rng = np.random.default_rng(2)
+    wb = _bf16(rng, (8, 16), 0.02)
+    vals, meta, amax = P.project_pack(wb, 1.5, "e4m3", np.float32(0.0002))
+    x = F.f32_to_e4m3_rne_sat((rng.standard_normal((4, 16)) * 50).astype(np.float32))
+    Z = Lin.linear_fwd(x, vals, meta, "e4m3", x_scale=0.02, w_scale=0.0002)
+    Wd = P.decode_packed(vals, meta, "e4m3")
+    want = Lin.linear_fwd_loops(F.e4m3_to_f32(x).astype(np.float64), Wd) * (np.float64(np.float32(0.02)) * np.float64(np.float32(0.0002)))
+    assert np.allclose(Z, want, rtol=1e-13)
+
+
+def test_wgrad_against_loops_on_the_sparsified_operand():
+    rng = np.random.default_rng(3)
+    T, O, I = 16, 8, 8
+    dy = _bf16(rng, (T, O), 1e-3)
+    xb = _bf16(rng, (T, I), 1.0)
+    dW = Lin.linear_wgrad(dy, xb, 7, 1)
+    theta = Lin.mvue_dense(dy, 7, 1)                       # (T, O)
+    X = F.bf16_to_f32(xb).astype(np.float64)
+    want = Lin.linear_fwd_loops(theta.T, X.T)              # dW[o][i] = sum_t theta[t][o] X[t][i]
+    assert dW.shape == (O, I)
+    assert np.allclose(dW, want, rtol=1e-13, atol=1e-20)
+    # theta is 2:4 along tokens for every channel
+    assert np.all(np.count_nonzero(theta.reshape(T // 4, 4, O), axis=1) <= 2)
+
+
+def test_wgrad_mean_over_seeds_converges_to_dense_gradient():
+    rng = np.random.default_rng(4)
+    T, O, I = 32, 8, 8
+    dy = _bf16(rng, (T, O), 1e-3)
+    xb = _bf16(rng, (T, I), 1.0)
+    dense = Lin.linear_wgrad_dense(dy, xb)
+    n = 10000
+    acc = np.zeros_like(dense)
+    acc2 = np.zeros_like(dense)
+    for seed in range(n):
+        d = Lin.linear_wgrad(dy, xb, seed, 0)
+        acc += d
+        acc2 += d * d
+    mean = acc / n
+    sd = np.sqrt(np.maximum(acc2 / n - mean ** 2, 0) / n)
+    # unbiased up to the deterministic bf16 rounding of the kept magnitudes (relative 2^-8 per term)
+    X = np.abs(F.bf16_to_f32(xb).astype(np.float64))
+    G = np.abs(F.bf16_to_f32(dy).astype(np.float64))
+    rounding = 2.0 ** -8 * (G.T @ X)
+    assert np.all(np.abs(mean - dense) <= 5 * sd + rounding)
+    # and the estimate is genuinely noisy for a single seed (it is a sparsifier, not the identity)
+    assert np.abs(Lin.linear_wgrad(dy, xb, 0, 0) - dense).max() > 10 * np.abs(mean - dense).max()
+
+
+def test_wgrad_e4m3_doubles_the_stored_half_theta():
+    rng = np.random.default_rng(5)
+    T, O, I = 16, 8, 8
+    dy = F.f32_to_e4m3_rne_sat((rng.standard_normal((T, O)) * 60).astype(np.float32))
+    x = F.f32_to_e4m3_rne_sat((rng.standard_normal((T, I)) * 60).astype(np.float32))
+    dW = Lin.linear_wgrad(dy, x, 2, 3, "e4m3", dy_scale=0.5, x_scale=0.25)
+    vals, meta = M.mvue_pack(dy, 2, 3, "e4m3")
+    half_theta = P.decode_packed(vals, meta, "e4m3").T
+    want = (half_theta.T @ F.e4m3_to_f32(x).astype(np.float64)) * 2 * 0.5 * 0.25
+    assert np.allclose(dW, want, rtol=1e-13)

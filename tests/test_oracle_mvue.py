@@ -1,0 +1,198 @@
+"""Pins for oracle/mvue.py (the 2:4 minimum-variance unbiased estimator of Sec. 5.1)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import formats as F
+from oracle import mvue as M
+from oracle import rng as R
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "mvue_groups.txt")
+
+
+def _golden():
+    rows = []
+    for line in open(GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        g, u, th, pos = [np.array(p.split(), dtype=np.float64) for p in line.split("|")]
+        rows.append((g, float(u[0]), th, pos.astype(int)))
+    return rows
+
+
+def test_golden_groups_math_and_bitspec():
+    for g, u, th, pos in _golden():
+        theta, p = M.mvue_sample(g[None, :], np.array([u]))
+        assert np.array_equal(theta[0], th), (g, u, theta)
+        assert p[0].tolist() == pos.tolist(), (g, u, p)
+        # every golden number is exact in bf16, so the bit-spec layer must agree exactly
+        codes = F.f32_to_bf16_rne(g.astype(np.float32))[None, :]
+        vals, nib = M.mvue_groups_bits(codes, np.array([u], dtype=np.float32))
+        assert (int(nib[0]) & 3, int(nib[0]) >> 2) == (pos[0], pos[1])
+        got = F.bf16_to_f32(vals[0]).astype(np.float64)
+        assert got[0] == th[pos[0]] and got[1] == th[pos[1]]
+
+
+def test_probabilities_closed_form_cases():
+    pi = M.inclusion_probabilities(np.array([[1, 1, 1, 1], [10, 1, 1, 1], [0, 0, 7, 0], [4, 3, 2, 1.0]]))
+    assert np.allclose(pi[0], 0.5)
+    assert np.allclose(pi[1], [1, 1 / 3, 1 / 3, 1 / 3])
+    assert pi[2].tolist() == [0, 0, 1, 0]
+    assert np.allclose(pi[3], [0.8, 0.6, 0.4, 0.2])
+    g = np.random.default_rng(0).standard_normal((1000, 4))
+    pi = M.inclusion_probabilities(g)
+    assert np.allclose(pi.sum(axis=1), 2.0) and pi.max() <= 1.0 + 1e-15 and pi.min() >= 0
+
+
+def test_probabilities_minimise_the_variance():
+    """No feasible pi' (sum 2, 0 < pi' <= 1) has lower sum g_i^2 (1/pi'_i - 1)."""
+    rng = np.random.default_rng(1)
+    g = rng.standard_normal((200, 4)) * np.exp(rng.uniform(-2, 2, (200, 4)))
+    best = M.total_variance(g)
+    for _ in range(200):
+        alt = rng.dirichlet(np.ones(4) * rng.uniform(0.3, 5), size=200) * 2
+        ok = alt.max(axis=1) <= 1.0
+        var = (g * g * (1.0 / alt - 1.0)).sum(axis=1)
+        assert np.all(var[ok] >= best[ok] * (1 - 1e-12))
+    # and a local perturbation of the optimum does not improve it
+    pi = M.inclusion_probabilities(g)
+    for i in range(4):
+        for j in range(4):
+            if i == j:
+                continue
+            alt = pi.copy()
+            alt[:, i] += 1e-4
+            alt[:, j] -= 1e-4
+            ok = (alt.max(axis=1) <= 1.0) & (alt.min(axis=1) > 0)
+            var = (g * g * (1.0 / alt - 1.0)).sum(axis=1)
+            assert np.all(var[ok] >= best[ok] * (1 - 1e-12))
+
+
+def test_exactly_two_positions_and_at_most_two_nonzeros():
+    rng = np.random.default_rng(2)
+    g = rng.standard_normal((5000, 4)) * np.exp(rng.uniform(-3, 3, (5000, 4)))
+    g[rng.random((5000, 4)) < 0.2] = 0
+    u = rng.random(5000)
+    theta, pos = M.mvue_sample(g, u)
+    assert np.all(pos[:, 0] < pos[:, 1]) and pos.min() >= 0 and pos.max() <= 3
+    assert np.all(np.count_nonzero(theta, axis=1) <= 2)
+    rows = np.arange(5000)
+    off = np.ones_like(theta, dtype=bool)
+    off[rows, pos[:, 0]] = False
+    off[rows, pos[:, 1]] = False
+    assert np.all(theta[off] == 0)
+    assert np.all((theta == 0) | (np.sign(theta) == np.sign(g)))
+
+
+def test_inclusion_frequencies_and_unbiasedness_with_closed_form_variance():
+    """Mean over 10^4 draws converges to g with the standard error the closed-form variance predicts."""
+    rng = np.random.default_rng(3)
+    groups = np.concatenate([rng.standard_normal((20, 4)), rng.standard_normal((20, 4)) * np.array([8, 1, 1, 1]),
+                             np.array([[1, 1, 1, 1], [3, 1, 1, 1], [0, 2, 0, -5], [1e-3, 2e-3, -1e-3, 5e-4]])])
+    n = 10000
+    u = R.uniform24(11, 0, np.arange(n)).astype(np.float64)
+    pi = M.inclusion_probabilities(groups)
+    var = M.total_variance(groups)
+    for k, g in enumerate(groups):
+        theta, pos = M.mvue_sample(np.tile(g, (n, 1)), u)
+        freq = np.zeros(4)
+        for i in range(4):
+            freq[i] = np.mean((pos[:, 0] == i) | (pos[:, 1] == i))
+        sel = g != 0
+        assert np.all(np.abs(freq[sel] - pi[k][sel]) <= 5 * np.sqrt(pi[k][sel] * (1 - pi[k][sel]) / n) + 2e-7), (g, freq, pi[k])
+        mean = theta.mean(axis=0)
+        per_elem_var = np.where(sel, g * g * (1 / np.where(sel, pi[k], 1) - 1), 0)
+        assert np.all(np.abs(mean - g) <= 5 * np.sqrt(per_elem_var / n) + 1e-9 * np.abs(g).max()), (g, mean)
+        emp = theta.var(axis=0).sum()
+        assert abs(emp - var[k]) <= 0.1 * var[k] + 1e-12
+
+
+def test_branches_agree_at_the_cap_boundary():
+    """At mx == r both formulas give pi_c = 1 and the same values (continuity of the estimator's law)."""
+    u = (np.arange(97) + 0.37) / 97         # off the interval edges, where a 1e-9 shift flips the pick
+    for g in ([3.0, 1, 1, 1], [1, 4.0, 2, 1], [0.5, 0.25, 0.25, 1.0]):
+        g = np.array(g)
+        lo = g.copy()
+        hi = g.copy()
+        c = np.argmax(np.abs(g))
+        lo[c] -= 1e-9
+        hi[c] += 1e-9
+        tl, _ = M.mvue_sample(np.tile(lo, (97, 1)), u)
+        th, _ = M.mvue_sample(np.tile(hi, (97, 1)), u)
+        assert np.abs(tl - th).max() < 1e-8
+
+
+def test_already_sparse_equal_magnitude_groups_are_fixed_points():
+    u = np.linspace(0, 1, 50, endpoint=False)
+    for g in ([2.0, 0, 2, 0], [0, -1.5, 0, 1.5], [7.0, 7, 0, 0], [0, 0, -3.0, -3.0]):
+        theta, _ = M.mvue_sample(np.tile(np.array(g), (50, 1)), u)
+        assert np.array_equal(theta, np.tile(np.array(g), (50, 1)))
+    # a group with a single nonzero is returned unchanged as well
+    theta, _ = M.mvue_sample(np.tile(np.array([0, 0, 0, -9.0]), (50, 1)), u)
+    assert np.array_equal(theta, np.tile(np.array([0, 0, 0, -9.0]), (50, 1)))
+
+
+def test_tiny_elements_next_to_a_large_one_keep_the_large_one():
+    """float32 sums can absorb tiny magnitudes entirely (r rounds to 0); element c must still be kept."""
+    g = np.array([[1.0, 2.0 ** -30, 0, 0], [0, 0, 2.0 ** -40, 1.0]], dtype=np.float32)
+    codes = F.f32_to_bf16_rne(g)
+    for u in (0.0, 0.5, 0.999):
+        vals, nib = M.mvue_groups_bits(codes, np.full(2, u, dtype=np.float32))
+        dense = np.zeros((2, 4))
+        for k in range(2):
+            p0, p1 = int(nib[k]) & 3, int(nib[k]) >> 2
+            assert p0 < p1
+            dense[k, p0], dense[k, p1] = F.bf16_to_f32(vals[k])
+        assert dense[0, 0] == 1.0 and dense[1, 3] == 1.0
+
+
+def test_bitspec_layer_tracks_math_layer_on_bf16_inputs():
+    rng = np.random.default_rng(4)
+    codes = F.f32_to_bf16_rne((rng.standard_normal((20000, 4)) * 1e-3).astype(np.float32))
+    u = R.uniform24(5, 6, np.arange(20000))
+    vals, nib = M.mvue_groups_bits(codes, u)
+    g = F.bf16_to_f32(codes).astype(np.float64)
+    theta, pos = M.mvue_sample(g, u.astype(np.float64))
+    # float32 vs float64 selection can differ only when tau lands within rounding of a boundary
+    same = ((nib & 3) == pos[:, 0]) & ((nib >> 2) == pos[:, 1])
+    assert same.mean() > 0.9999
+    rows = np.arange(20000)[same]
+    got0 = F.bf16_to_f32(vals[same, 0]).astype(np.float64)
+    want0 = theta[rows, pos[same, 0]]
+    assert np.all(np.abs(got0 - want0) <= np.abs(want0) * 2.0 ** -8)
+
+
+def test_e4m3_bitspec_stores_half_theta():
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((4000, 4)) * 100).astype(np.float32)
+    codes = F.f32_to_e4m3_rne_sat(np.clip(x, -448, 448))
+    u = R.uniform24(1, 1, np.arange(4000))
+    vals, nib = M.mvue_groups_bits(codes, u, "e4m3")
+    g = F.e4m3_to_f32(codes).astype(np.float64)
+    theta, pos = M.mvue_sample(g, u.astype(np.float64))
+    same = ((nib & 3) == pos[:, 0]) & ((nib >> 2) == pos[:, 1])
+    assert same.mean() > 0.999
+    rows = np.arange(4000)[same]
+    for k in range(2):
+        got = 2.0 * F.e4m3_to_f32(vals[same, k]).astype(np.float64)
+        want = theta[rows, pos[same, k]]
+        assert np.all(np.abs(got - want) <= np.maximum(np.abs(want) * 2.0 ** -4, 2.0 ** -9))
+    assert np.all(np.abs(F.e4m3_to_f32(vals)) <= 448)
+
+
+def test_pack_layout_and_group_ids():
+    rng = np.random.default_rng(6)
+    T, O = 32, 8
+    dy = F.f32_to_bf16_rne((rng.standard_normal((T, O)) * 1e-3).astype(np.float32))
+    vals, meta = M.mvue_pack(dy, 3, 9)
+    assert vals.shape == (O, T // 2) and meta.shape == (O, T // 8)
+    # recompute one group by hand: tokens 8..11 of channel 5 -> gid = 2 * O + 5
+    k, o = 2, 5
+    u = R.uniform24(3, 9, np.array([k * O + o], dtype=np.uint64))
+    v1, n1 = M.mvue_groups_bits(dy[4 * k:4 * k + 4, o][None, :], u)
+    assert vals[o, 2 * k:2 * k + 2].tolist() == v1[0].tolist()
+    assert (int(meta[o, k // 2]) >> (4 * (k % 2))) & 0xF == int(n1[0])
+    with pytest.raises(ValueError):
+        M.mvue_pack(dy[:12], 0, 0)

@@ -1,0 +1,196 @@
+"""Pins for oracle/projection.py (Sec. 4.1 soft threshold, Sec. 4.2 beta, packed 2:4 format)."""
+import os
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import formats as F
+from oracle import projection as P
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "soft_threshold_groups.txt")
+
+
+def _golden():
+    rows = []
+    for line in open(GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        a, s, p = [np.array(part.split(), dtype=np.float64) for part in line.split("|")]
+        rows.append((a, s, p.astype(int)))
+    return rows
+
+
+def test_golden_groups_math_layer():
+    for a, s, _ in _golden():
+        assert np.array_equal(P.soft_threshold(a), s), (a, s)
+        assert np.array_equal(P.soft_threshold_sorted_form(a), s), (a, s)
+
+
+def test_golden_groups_bitspec_positions_and_values():
+    for a, s, pos in _golden():
+        # all golden numbers are exactly representable in bf16
+        wb = F.f32_to_bf16_rne(np.concatenate([a, a]).astype(np.float32)).reshape(1, 8)
+        vals, meta, amax = P.project_pack(wb, 1.0)
+        nib = int(meta[0, 0]) & 0xF
+        assert (nib & 3, nib >> 2) == (pos[0], pos[1]), (a, nib)
+        assert int(meta[0, 0]) >> 4 == nib
+        got = F.bf16_to_f32(vals[0, :2])
+        assert got[0] == s[pos[0]] and got[1] == s[pos[1]]
+        assert np.array_equal(P.decode_packed(vals, meta)[0, :4], s)
+        assert amax == np.float32(np.max(np.abs(s)))
+
+
+def test_north_star_example_and_its_beta():
+    a = np.array([1, -3, 0.5, 2.0])
+    assert P.soft_threshold(a).tolist() == [0, -2, 0, 1]
+    # beta = <w, S> / |S|^2 = (6 + 2) / (4 + 1)
+    assert P.beta_mse(a) == pytest.approx(1.6, rel=0, abs=1e-15)
+    # L1 variant: (1+3+.5+2)/(2+1)
+    assert P.beta_l1(a) == pytest.approx(6.5 / 3)
+
+
+def test_kept_but_zero_value_is_plus_zero_and_negative_zero_inputs():
+    wb = F.f32_to_bf16_rne(np.array([[-3, -1, -1, 0, -0.0, 0, -0.0, 0]], dtype=np.float32))
+    vals, meta, _ = P.project_pack(wb, 1.5)
+    assert vals[0].tolist() == [F.f32_to_bf16_rne(np.array([-3.0], dtype=np.float32))[0], 0x0000, 0x0000, 0x0000]
+    assert meta[0, 0] == (0 | (1 << 2)) | ((0 | (1 << 2)) << 4)
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.lists(st.floats(-8, 8, allow_nan=False, width=32), min_size=4, max_size=4))
+def test_invariants_on_single_groups(vals):
+    a = np.array(vals, dtype=np.float64)
+    s = P.soft_threshold(a)
+    assert np.count_nonzero(s) <= 2                                   # result lies in the 2:4 set
+    assert np.all(np.abs(s) <= np.abs(a) + 0.0)                       # shrinkage
+    assert np.all((s == 0) | (np.sign(s) == np.sign(a)))              # sign preserved
+    assert np.allclose(P.soft_threshold(s), s, rtol=0, atol=0)        # projection: idempotent
+    assert np.allclose(P.soft_threshold_sorted_form(a), s, rtol=0, atol=0)
+    c = 1.75
+    assert np.allclose(P.soft_threshold(c * a), c * s, rtol=1e-15, atol=0)   # positive homogeneity
+    assert np.allclose(P.soft_threshold(-a), -s, rtol=0, atol=0)             # odd
+    # permutation equivariance
+    perm = np.array([2, 0, 3, 1])
+    assert np.array_equal(P.soft_threshold(a[perm]), s[perm])
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.lists(st.floats(-4, 4, allow_nan=False, width=32), min_size=4, max_size=4),
+       st.lists(st.floats(-1, 1, allow_nan=False, width=32), min_size=4, max_size=4),
+       st.floats(1e-6, 0.5))
+def test_continuity_bound_of_theorem_1(vals, direction, delta):
+    """The proof of Theorem 1 bounds each output coordinate's change by 2*delta when every input
+    coordinate moves by at most delta."""
+    a = np.array(vals, dtype=np.float64)
+    e = np.array(direction, dtype=np.float64) * delta
+    d = np.abs(P.soft_threshold(a + e) - P.soft_threshold(a)).max()
+    assert d <= 2 * np.abs(e).max() + 1e-12
+
+
+def test_continuity_across_the_flip_boundary():
+    """At |a2| = |a3| (the flip boundary in the proof's case 2) three outputs are zero and the
+    function has no jump, unlike the hard threshold."""
+    base = np.array([0.1, 1.0, -1.0, 3.0])
+    for eps in (1e-3, 1e-6, 1e-9):
+        lo = P.soft_threshold(base + np.array([0, eps, 0, 0]))
+        hi = P.soft_threshold(base + np.array([0, 0, -eps, 0]))
+        mid = P.soft_threshold(base)
+        assert np.count_nonzero(mid) == 1
+        assert np.abs(lo - mid).max() <= 2 * eps and np.abs(hi - mid).max() <= 2 * eps
+        # the hard threshold jumps by ~1 between the two sides
+        assert np.abs(P.hard_threshold(base + np.array([0, eps, 0, 0])) - P.hard_threshold(base + np.array([0, 0, -eps, 0]))).max() > 0.9
+
+
+def test_support_matches_hard_threshold_without_ties():
+    rng = np.random.default_rng(3)
+    w = rng.standard_normal((64, 256))
+    assert np.array_equal(P.soft_threshold(w) != 0, P.hard_threshold_mask(w))
+    # with ties the soft support is a subset
+    w2 = np.round(rng.standard_normal((64, 256)) * 2)
+    assert np.all((P.soft_threshold(w2) != 0) <= P.hard_threshold_mask(w2))
+
+
+def test_beta_minimises_the_mse_and_gaussian_value():
+    rng = np.random.default_rng(4)
+    w = rng.standard_normal((256, 1024)) * 0.02
+    b = P.beta_mse(w)
+    s = P.soft_threshold(w)
+    mse = lambda beta: np.sum((w - beta * s) ** 2)
+    assert mse(b) < mse(b * 1.001) and mse(b) < mse(b * 0.999)
+    # derivative of the quadratic vanishes at b
+    assert abs(np.sum((w - b * s) * s)) < 1e-9 * np.sum(s * s)
+    # for i.i.d. Gaussian groups the optimum is scale invariant; Monte-Carlo value ~1.48
+    assert 1.45 < b < 1.52
+    assert P.beta_mse(3.0 * w) == pytest.approx(b, rel=1e-12)
+    with pytest.raises(ValueError):
+        P.beta_mse(np.ones((2, 8)))
+
+
+def test_flip_rate_definition():
+    a = np.array([1, 1, 0, 0, 1, 0, 1, 0], dtype=bool)
+    b = np.array([1, 0, 1, 0, 1, 0, 1, 0], dtype=bool)
+    assert P.flip_rate(a, b) == 2 / 8
+
+
+def _random_bf16(rng, shape, std=0.02):
+    return F.f32_to_bf16_rne((rng.standard_normal(shape) * std).astype(np.float32))
+
+
+@pytest.mark.parametrize("beta", [1.0, 1.4830322265625, 0.73])
+def test_pack_decode_equals_rounded_definition_bf16(beta):
+    rng = np.random.default_rng(5)
+    wb = _random_bf16(rng, (48, 512))
+    vals, meta, amax = P.project_pack(wb, beta)
+    dense = P.decode_packed(vals, meta)
+    w = F.bf16_to_f32(wb).astype(np.float64)
+    exact = np.float64(np.float32(beta)) * P.soft_threshold(w)
+    # the stored value is the bf16 rounding of the float64 definition up to one double rounding:
+    # relative error <= 2^-8 (half an ulp of the 8-bit significand, relative to the binade base) + 2^-23
+    err = np.abs(dense - exact)
+    assert np.all(err <= np.abs(exact) * (2.0 ** -8 + 2.0 ** -23) + 1e-45)
+    # and on almost all elements it IS the RNE rounding of the exact value
+    rne = F.bf16_to_f32(F.f32_to_bf16_rne(exact.astype(np.float32))).astype(np.float64)
+    assert np.mean(rne == dense) > 0.999
+    # structure
+    idx0, idx1 = P.kept_positions(meta)
+    assert np.all(idx0 < idx1)
+    assert np.array_equal(P.structural_mask(meta).reshape(48, -1, 4).sum(axis=2), np.full((48, 128), 2))
+    assert np.all((dense != 0) <= P.structural_mask(meta))
+    assert amax == np.float32(np.abs(exact).max()) or abs(float(amax) - np.abs(exact).max()) <= 2.0 ** -23 * np.abs(exact).max()
+
+
+def test_pack_e4m3_against_definition():
+    rng = np.random.default_rng(6)
+    wb = _random_bf16(rng, (32, 256))
+    w = F.bf16_to_f32(wb).astype(np.float64)
+    beta = 1.48
+    exact = np.float64(np.float32(beta)) * P.soft_threshold(w)
+    scale = np.float32(np.abs(exact).max() / 448.0)
+    vals, meta, amax = P.project_pack(wb, beta, "e4m3", scale)
+    assert vals.dtype == np.uint8 and vals.shape == (32, 128)
+    dense = P.decode_packed(vals, meta, "e4m3") * np.float64(scale)
+    # e4m3 half-ulp is 2^-4 relative for normals; absolute 2^-10 * scale for subnormals
+    tol = np.maximum(np.abs(exact) * (2.0 ** -4 + 2.0 ** -20), np.float64(scale) * 2.0 ** -10 * 1.001)
+    assert np.all(np.abs(dense - exact) <= tol)
+    assert np.max(np.abs(P.decode_packed(vals, meta, "e4m3"))) <= 448.0
+    # same positions as the bf16 packing: the selection does not depend on the value type
+    _, meta16, _ = P.project_pack(wb, beta)
+    assert np.array_equal(meta, meta16)
+    with pytest.raises(ValueError):
+        P.project_pack(wb, beta, "bf16", 2.0)
+
+
+def test_tie_break_rule_exhaustive_small_alphabet():
+    """All 3^4 groups over magnitudes {0,1,2} with mixed signs: recorded positions follow
+    (magnitude desc, index asc) computed here by an explicit sort."""
+    import itertools
+    for combo in itertools.product([0.0, 1.0, -1.0, 2.0, -2.0], repeat=4):
+        a = np.array(combo, dtype=np.float32)
+        order = sorted(range(4), key=lambda i: (-abs(a[i]), i))
+        want = sorted(order[:2])
+        wb = F.f32_to_bf16_rne(np.concatenate([a, a])).reshape(1, 8)
+        _, meta, _ = P.project_pack(wb, 1.0)
+        nib = int(meta[0, 0]) & 0xF
+        assert [nib & 3, nib >> 2] == want, (combo, nib)

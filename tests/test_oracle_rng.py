@@ -1,0 +1,85 @@
+"""Pins for oracle/rng.py: known answers from an independent scalar re-derivation, and statistics."""
+import numpy as np
+
+from oracle import rng
+
+
+def _scalar_reference(seed, offset, gid):
+    """Scalar Python-int evaluation written from the specification text, step by step."""
+    M = (1 << 64) - 1
+
+    def fin(z):
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9 & M
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EB & M
+        return z ^ (z >> 31)
+
+    key = fin((seed & M) ^ fin((offset + 0x9E3779B97F4A7C15) & M))
+    k0, k1 = key & 0xFFFFFFFF, key >> 32
+    m = 0xFFFFFFFF
+    x = ((gid & m) ^ k0)
+    x = (x + (gid >> 32) * 0x9E3779B9) & m
+    x ^= x >> 17
+    x = x * 0xED5AD4BB & m
+    x = (x + k1) & m
+    x ^= x >> 11
+    x = x * 0xAC4C1B51 & m
+    x ^= x >> 15
+    x = x * 0x31848BAB & m
+    x ^= x >> 14
+    return x
+
+
+def test_known_answers_against_scalar_reference():
+    cases = [(0, 0, 0), (0, 0, 1), (1, 0, 0), (0, 1, 0), (2 ** 63 + 5, 77, 123456789), (3, 4, (1 << 40) + 17),
+             (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF)]
+    for seed, offset, gid in cases:
+        k0, k1 = rng.derive_key(seed, offset)
+        got = int(rng.draw_u32(k0, k1, np.array([gid], dtype=np.uint64))[0])
+        assert got == _scalar_reference(seed, offset, gid), (seed, offset, gid)
+
+
+def test_key_derivation_fixed_values():
+    # SplitMix64's first output for state 0 is the finalizer of the golden-ratio increment
+    assert rng.mix64(0x9E3779B97F4A7C15) == 0xE220A8397B1DCDAF
+    assert rng.derive_key(0, 0) == ((rng.mix64(0xE220A8397B1DCDAF)) & 0xFFFFFFFF, rng.mix64(0xE220A8397B1DCDAF) >> 32)
+
+
+def test_uniform_is_exact_24_bit_fraction_in_unit_interval():
+    u = rng.uniform24(9, 2, np.arange(100000))
+    assert u.dtype == np.float32 and u.min() >= 0.0 and u.max() < 1.0
+    assert np.array_equal(u * np.float32(2 ** 24), np.round(u * np.float32(2 ** 24)))
+
+
+def _chi2_z(u, bins):
+    h, _ = np.histogram(u, bins=bins, range=(0, 1))
+    e = len(u) / bins
+    return (((h - e) ** 2 / e).sum() - (bins - 1)) / np.sqrt(2 * (bins - 1))
+
+
+def test_uniformity_and_serial_correlation_over_group_ids():
+    for seed, offset in [(0, 0), (1, 0), (0, 1), (12345, 678)]:
+        u = rng.uniform24(seed, offset, np.arange(1 << 21)).astype(np.float64)
+        assert abs(_chi2_z(u, 256)) < 5 and abs(_chi2_z(u, 4096)) < 5
+        assert abs(u.mean() - 0.5) < 5 * (1 / np.sqrt(12 * len(u)))
+        for lag in (1, 2, 256, 3072):
+            assert abs(np.corrcoef(u[:-lag], u[lag:])[0, 1]) < 5 / np.sqrt(len(u))
+
+
+def test_sequential_seeds_and_offsets_decorrelate():
+    gids = np.array([0, 5, 1 << 20], dtype=np.uint64)
+    us = np.array([rng.uniform24(s, 0, gids) for s in range(20000)], dtype=np.float64)
+    uo = np.array([rng.uniform24(7, o, gids) for o in range(20000)], dtype=np.float64)
+    for arr in (us, uo):
+        for col in range(arr.shape[1]):
+            x = arr[:, col]
+            assert abs(x.mean() - 0.5) < 5 / np.sqrt(12 * len(x))
+            assert abs(np.corrcoef(x[:-1], x[1:])[0, 1]) < 5 / np.sqrt(len(x))
+            assert abs(_chi2_z(x, 64)) < 5
+    # the same gid under neighbouring seeds vs. neighbouring gids under one seed
+    assert abs(np.corrcoef(us[:, 0], us[:, 1])[0, 1]) < 5 / np.sqrt(len(us))
+
+
+def test_draw_is_a_bijection_of_the_low_word():
+    k0, k1 = rng.derive_key(1, 2)
+    x = rng.draw_u32(k0, k1, np.arange(1 << 16, dtype=np.uint64))
+    assert len(np.unique(x)) == 1 << 16
