@@ -12,31 +12,40 @@ estimator theta with two recorded positions, theta_i = g_i / pi_i when i is reco
 probability pi_i, sum pi_i = 2, pi_i <= 1) and 0 otherwise, is unbiased with total variance
 sum_i g_i^2 (1/pi_i - 1).  Minimising over pi gives pi_i proportional to |g_i|, capped at 1:
 
-  m_i = |g_i|, mx = max m, c = lowest index attaining mx, r = sum of the other three.
+  m_i = |g_i|, mx = max m, c = an index attaining mx, r = sum of the other three.
   capped case (mx > r):   pi_c = 1, pi_i = m_i / r;   theta_c = g_c, theta_i = sign(g_i) r.
   uncapped case:          pi_i = 2 m_i / s, s = sum m; theta_i = sign(g_i) s / 2.
 
 Several joint distributions have these marginals; the one fixed here is systematic sampling
-with one uniform u in [0,1) per group: lay the magnitudes (capped case: without element c) on a
-line in index order with prefix sums P0, P1, P2 and total L.  Uncapped: h = L/2 and the two
-recorded positions are the intervals holding tau0 = u*h and tau1 = tau0 + h.  Capped: h = L and
-the second recorded position is the interval holding tau0 = u*h.  The interval holding tau is
-found as #{k in {0,1,2} : P_k <= tau}.  Guards that only act when floating-point rounding or an
-all-zero line breaks the exact-arithmetic guarantees: uncapped i0 <- min(i0, 2),
-i1 <- min(3, max(i1, i0 + 1)); capped j <- c xor 1 if j == c.  A recorded element whose
-magnitude is zero gets the value +0.  Positions are recorded in ascending order.
+with one uniform u in [0,1) per group, written so that both cases share one branch-free
+sequence of steps:
 
-Arithmetic order (bit-spec, float32, no fused multiply-add):
-  r = ((m0' + m1') + m2') + m3' with m_c' = 0;  P0 = l0, P1 = P0 + l1, P2 = P1 + l2, L = P2 + l3 on
-  the chosen line l; h = L or 0.5*L; tau0 = u*h; tau1 = tau0 + h; comparisons are exact.
-  bf16 storage: the common magnitude is RNE_bf16(h), element c keeps its input pattern.
+  1. Lo = sum of the three non-maximal magnitudes, taken as (b + d) + mid with
+     a = max(m0,m1), b = min(m0,m1), cc = max(m2,m3), d = min(m2,m3), mx = max(a,cc), mid = min(a,cc).
+  2. clamp = mx if Lo == 0 else Lo;  l_i = min(m_i, clamp).   (Capped case: the maximum is cut
+     down to the total of the others, so its interval is half of the line and is always hit;
+     uncapped case and single-nonzero groups: nothing changes.)
+  3. Lay l on a line in index order: P0 = l0, P1 = P0 + l1, P2 = P1 + l2, L = P2 + l3; h = L / 2.
+  4. tau0 = u * h, tau1 = tau0 + h; the interval holding tau is #{k in {0,1,2} : P_k <= tau}.
+     i0 = min(interval(tau0), 2); i1 = min(3, max(interval(tau1), i0 + 1)).  The min / max only act
+     when rounding or a degenerate line (zeros) breaks the exact-arithmetic guarantee i0 < i1.
+  5. The value recorded at position p is g_p itself when m_p > h (the capped maximum) or m_p == 0
+     (a zero dragged in by step 4), else sign(g_p) * h.
+
+In exact arithmetic this gives the marginals above (capped: L = 2 Lo, h = Lo = r; uncapped: l = m,
+h = s/2 and every m_i <= h).
+
+Arithmetic order (bit-spec, float32, no fused multiply-add): exactly the operations written in
+steps 1-4, each rounded to float32; comparisons are exact.
+  bf16 storage: sign(g_p) * h is stored as sign bit | RNE_bf16(h); g_p itself keeps its pattern.
   e4m3 storage: theta can reach twice the largest input, so the stored operand is theta/2
-  (RNE_e4m3 of 0.5*h, or of 0.5*|g_c| for element c) and the GEMM epilogue multiplies by 2.
+  (sign | RNE_e4m3(0.5*h), or sign | RNE_e4m3(0.5*m_p) where g_p itself is recorded) and the GEMM
+  epilogue multiplies by 2.
 
 Pinned (tests/test_oracle_mvue.py): worked groups, exactly-two-positions invariant, empirical
 inclusion frequencies against the closed-form pi, Monte-Carlo mean against g with the closed-
-form variance, optimality of pi against random feasible alternatives, continuity of the two
-branches at mx == r, and invariance of groups that are already 2:4 with equal magnitudes.
+form variance, optimality of pi against random feasible alternatives, continuity of the law
+at mx == r, groups with one, two or no nonzeros, and a maximum that dwarfs the other elements.
 Whether this joint distribution equals the one used by the work the paper cites is unpinned
 (that text is not available here); every property the paper itself states is pinned.
 """
@@ -79,36 +88,31 @@ def total_variance(g):
 # --------------------------------------------------------------------------- selection core
 
 def _select(m, u, ft):
-    """Systematic-sampling selection on magnitudes m (n,4) with uniforms u (n,), all in dtype ft.
-
-    Returns pos0 < pos1 (recorded positions), h (the common magnitude of non-capped recorded
-    elements), capped (bool) and c (index of the maximum)."""
+    """Steps 1-4 of the module header on magnitudes m (n,4) with uniforms u (n,), all in dtype ft.
+    Returns the recorded positions pos0 < pos1 and h."""
     m = np.ascontiguousarray(m, dtype=ft)
     u = np.ascontiguousarray(u, dtype=ft)
-    n = m.shape[0]
-    rows = np.arange(n)
-    mx = m.max(axis=1)
-    c = np.argmax(m == mx[:, None], axis=1)
-    mo = m.copy()
-    mo[rows, c] = ft(0)
-    r = ((mo[:, 0] + mo[:, 1]) + mo[:, 2]) + mo[:, 3]
-    capped = mx > r
-    line = np.where(capped[:, None], mo, m)
+    a = np.maximum(m[:, 0], m[:, 1])
+    b = np.minimum(m[:, 0], m[:, 1])
+    cc = np.maximum(m[:, 2], m[:, 3])
+    d = np.minimum(m[:, 2], m[:, 3])
+    mx = np.maximum(a, cc)
+    mid = np.minimum(a, cc)
+    Lo = ((b + d) + mid).astype(ft)
+    clamp = np.where(Lo == 0, mx, Lo).astype(ft)
+    line = np.minimum(m, clamp[:, None])
     P0 = line[:, 0]
-    P1 = P0 + line[:, 1]
-    P2 = P1 + line[:, 2]
-    L = P2 + line[:, 3]
-    h = np.where(capped, L, ft(0.5) * L).astype(ft)
+    P1 = (P0 + line[:, 1]).astype(ft)
+    P2 = (P1 + line[:, 2]).astype(ft)
+    L = (P2 + line[:, 3]).astype(ft)
+    h = (ft(0.5) * L).astype(ft)
     tau0 = (u * h).astype(ft)
     tau1 = (tau0 + h).astype(ft)
     i0 = (P0 <= tau0).astype(np.int64) + (P1 <= tau0) + (P2 <= tau0)
     i1 = (P0 <= tau1).astype(np.int64) + (P1 <= tau1) + (P2 <= tau1)
-    i0u = np.minimum(i0, 2)
-    i1u = np.minimum(3, np.maximum(i1, i0u + 1))
-    j = np.where(i0 == c, c ^ 1, i0)
-    pos0 = np.where(capped, np.minimum(c, j), i0u)
-    pos1 = np.where(capped, np.maximum(c, j), i1u)
-    return pos0, pos1, h, capped, c
+    pos0 = np.minimum(i0, 2)
+    pos1 = np.minimum(3, np.maximum(i1, pos0 + 1))
+    return pos0, pos1, h
 
 
 # --------------------------------------------------------------------------- math layer
@@ -117,15 +121,14 @@ def mvue_sample(g, u):
     """float64 estimator: groups g (n,4), uniforms u (n,) -> dense theta (n,4) and positions (n,2)."""
     g = np.asarray(g, dtype=np.float64).reshape(-1, 4)
     m = np.abs(g)
-    pos0, pos1, h, capped, c = _select(m, np.asarray(u, dtype=np.float64), np.float64)
+    pos0, pos1, h = _select(m, np.asarray(u, dtype=np.float64), np.float64)
     n = g.shape[0]
     rows = np.arange(n)
     theta = np.zeros_like(g)
     for pos in (pos0, pos1):
         gi = g[rows, pos]
-        val = np.where(gi != 0, np.copysign(h, gi), 0.0)
-        val = np.where(capped & (pos == c), gi, val)
-        theta[rows, pos] = val
+        mi = m[rows, pos]
+        theta[rows, pos] = np.where((mi > h) | (mi == 0), gi, np.copysign(h, gi))
     return theta, np.stack([pos0, pos1], axis=1)
 
 
@@ -148,7 +151,7 @@ def mvue_groups_bits(g_codes, u, dtype="bf16"):
     else:
         raise ValueError("dtype must be 'bf16' or 'e4m3'")
     m = np.abs(gf).astype(np.float32)
-    pos0, pos1, h, capped, c = _select(m, np.asarray(u, dtype=np.float32), np.float32)
+    pos0, pos1, h = _select(m, np.asarray(u, dtype=np.float32), np.float32)
     n = m.shape[0]
     rows = np.arange(n)
     if dtype == "bf16":
@@ -159,12 +162,12 @@ def mvue_groups_bits(g_codes, u, dtype="bf16"):
     for pos in (pos0, pos1):
         code = g_codes[rows, pos]
         mi = m[rows, pos]
-        common = np.where(mi == 0, 0, (code & sign_mask) | hq).astype(g_codes.dtype)
+        common = ((code & sign_mask) | hq).astype(g_codes.dtype)
         if dtype == "bf16":
             own = code
         else:
             own = (code & sign_mask) | formats.f32_to_e4m3_rne_sat((np.float32(0.5) * mi).astype(np.float32))
-        out.append(np.where(capped & (pos == c), own, common).astype(g_codes.dtype))
+        out.append(np.where((mi > h) | (mi == 0), own, common).astype(g_codes.dtype))
     vals = np.stack(out, axis=1)
     nib = (pos0 | (pos1 << 2)).astype(np.uint8)
     return vals, nib
