@@ -1,0 +1,186 @@
+/*
+ * sste.h -- C ABI of the S-STE 2:4 sparse linear-layer hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-layer work of one S-STE training
+ * iteration (arXiv 2409.09099):
+ *   Sec. 4   S(W) = beta * S_soft(W): the 2:4 soft-threshold projection with a frozen per-tensor scale,
+ *   Sec. 5.1 Z = X S(W)^T (forward) and grad_W = MVUE(grad_Z^T) X (weight gradient),
+ *   Sec. 5.2 optionally with FP8 (OCP e4m3fn) operands and per-tensor scales.
+ *
+ * Conventions shared by every entry point
+ *   - All matrices are row-major.  W is O x I (out x in), X is T x I, Z and dY are T x O, dW is O x I.
+ *     Groups of four lie along the contraction axis: along I for W, along T (tokens) for dY.
+ *   - Every data pointer is DEVICE memory owned by the caller (any HIP allocation, e.g. a PyTorch
+ *     tensor).  The library never allocates, frees or retains device memory.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues kernels on that stream and returns; it never synchronises.
+ *   - The return value is an sste_status.  Arguments are validated on the host before anything is
+ *     launched; on error nothing has been enqueued and sste_last_error() describes the reason.
+ *   - Leading dimensions (ld*) are in elements.  Base pointers and row starts must be 16-byte
+ *     aligned, hence ld* must be a multiple of 8 (bf16, 2-byte) / 16 (e4m3, 1-byte) / 4 (float).
+ *   - Inputs must be finite.  The order used by the projection treats the 15-bit magnitude field of a
+ *     bf16 as an unsigned integer, so it is total even for NaN patterns; nothing else is specified
+ *     for non-finite inputs.
+ *
+ * Packed 2:4 operand ("vals" + "meta"), the format produced by sste_project_pack and
+ * sste_mvue_materialize and consumed by sste_linear_fwd:
+ *   vals : R x K/2 elements, row-major.  For each group of 4 consecutive k the two recorded values in
+ *          ascending position order.
+ *   meta : R x K/8 bytes, row-major.  One nibble per group: pos0 | pos1 << 2 with pos0 < pos1 the
+ *          positions (0..3) of the two recorded values inside the group; the even group of a pair
+ *          occupies the low nibble of its byte.
+ */
+#ifndef SSTE_H
+#define SSTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SSTE_OK = 0,
+  SSTE_ERR_NULL = 1,        /* a required pointer is NULL */
+  SSTE_ERR_SHAPE = 2,       /* negative size, or a size the method itself does not allow */
+  SSTE_ERR_ALIGN = 3,       /* pointer or leading dimension breaks the 16-byte rule */
+  SSTE_ERR_DTYPE = 4,       /* unknown or inconsistent element type */
+  SSTE_ERR_VALUE = 5,       /* beta / scale not finite or not > 0 */
+  SSTE_ERR_WORKSPACE = 6,   /* workspace NULL or too small */
+  SSTE_ERR_UNSUPPORTED = 7, /* valid problem, but no kernel covers this shape */
+  SSTE_ERR_HIP = 8          /* the HIP runtime refused a launch */
+} sste_status;
+
+typedef enum {
+  SSTE_BF16 = 0,   /* bfloat16 */
+  SSTE_F8E4M3 = 1  /* OCP FP8 e4m3fn: bias 7, max 448, no infinity */
+} sste_dtype;
+
+/*
+ * Projection + scale + pack (Sec. 4.1 displayed definition of S_soft; Sec. 4.2 fixed scale beta).
+ *
+ * For every group a of four consecutive elements of a row of W: t = third-largest magnitude;
+ * the two largest magnitudes are recorded, each as beta * (a_i - t) or beta * (a_i + t) by its sign.
+ * Ties: rank by magnitude descending, then index ascending; ranks 0 and 1 are recorded (the values
+ * do not depend on the tie-break, only the recorded positions do).  A recorded element whose
+ * magnitude equals t is stored as +0.
+ * Rounding: sd = a -/+ t and p = sd * beta are single float32 operations; bf16 values store
+ * RNE_bf16(p); e4m3 values store RNE_e4m3(clamp(p / val_scale, +-448)) with a true float32 division.
+ *
+ *   W         in   device, bf16, O x I, leading dimension ldw (>= I, multiple of 8)
+ *   O, I      in   O >= 0; I >= 0 and a multiple of 8 (whole groups, two per metadata byte)
+ *   beta      in   frozen per-tensor scale, finite and > 0
+ *   val_dtype in   SSTE_BF16 or SSTE_F8E4M3: element type of `vals`
+ *   val_scale in   finite and > 0; must be 1 for SSTE_BF16
+ *   vals      out  device, O x I/2 elements of val_dtype, contiguous rows
+ *   meta      out  device, O x I/8 bytes, contiguous rows
+ *   amax_out  out  device float* or NULL.  If given, receives max |p| over all recorded values
+ *                  (before division by val_scale and storage rounding); 0 for an empty matrix.
+ * Errors: NULL -> ERR_NULL (W/vals/meta may be NULL only if O*I == 0); bad sizes -> ERR_SHAPE;
+ * misalignment -> ERR_ALIGN; bad beta/scale -> ERR_VALUE; bad dtype -> ERR_DTYPE.
+ */
+int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta,
+                      int val_dtype, float val_scale,
+                      void* vals, void* meta, float* amax_out, void* hip_stream);
+
+/*
+ * Forward GEMM with a 2:4-sparse weight operand (Sec. 5.1: Z_l = X_l S(W_l)^T).
+ *
+ *   Z = (x_scale * w_scale) * X * decode(vals, meta)^T,  float32 accumulation, Z stored as bf16 (RNE).
+ *
+ *   X        in   device, T x I of `dtype`, leading dimension ldx
+ *   T, I, O  in   T >= 0; O >= 0 and a multiple of 8; I a multiple of 64 (bf16) / 128 (e4m3)
+ *   dtype    in   element type of X and of vals (both operands share it)
+ *   x_scale, w_scale  in  finite, > 0: dequantisation scales (1 for bf16 operands in the paper's setting)
+ *   vals, meta  in   packed S(W): O x I/2 and O x I/8 as written by sste_project_pack
+ *   Z        out  device, T x O bf16, leading dimension ldz (multiple of 8)
+ * Metadata nibbles are trusted to be well formed (pos0 != pos1); malformed ones give an unspecified
+ * but memory-safe result.
+ */
+int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale,
+                    const void* vals, const void* meta, int64_t O, float w_scale,
+                    void* Z, int64_t ldz, void* hip_stream);
+
+/*
+ * Weight-gradient GEMM with the output gradient sparsified 2:4 on the fly by the minimum-variance
+ * unbiased estimator (Sec. 5.1: grad_W = MVUE(grad_Z^T) X).
+ *
+ *   dW (+)= scale * MVUE(dY^T; seed, offset) * X,   scale = dy_scale * x_scale (times 2 for e4m3, whose
+ *   sparsified operand is stored halved), float32 accumulation, dW float32.
+ *
+ * The estimator works on groups of four consecutive tokens t = 4k..4k+3 of one output channel o.
+ * Its uniform number is a pure function of (seed, offset, group id = k * O + o), so the result does
+ * not depend on tiling or on how the token axis is split.  See sste_mvue_materialize for the rule.
+ *
+ *   dY       in   device, T x O of `dtype`, leading dimension lddy
+ *   X        in   device, T x I of `dtype`, leading dimension ldx
+ *   T, O, I  in   T a multiple of 64 (bf16) / 128 (e4m3); O, I >= 0 and multiples of 8 (bf16) / 16 (e4m3)
+ *   seed, offset  in  random stream id (e.g. layer seed, training step)
+ *   dW       out  device, O x I float32, leading dimension lddw (multiple of 4)
+ *   accumulate in 0: dW is overwritten; 1: the product is added to dW
+ *   workspace     device scratch of at least sste_wgrad_workspace_bytes(T, O, I, dtype) bytes, 16-byte
+ *                 aligned; holds split-K partial sums that are reduced in a fixed order, so the result
+ *                 is bitwise reproducible from run to run.  May be NULL when that size is 0.
+ */
+int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                      const void* X, int64_t I, int64_t ldx, float x_scale,
+                      uint64_t seed, uint64_t offset,
+                      float* dW, int64_t lddw, int accumulate,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of scratch sste_linear_wgrad needs for this problem (0 if it needs none; 0 on bad arguments). */
+size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
+
+/*
+ * The estimator of sste_linear_wgrad written out as a packed 2:4 operand (same device function).
+ * Used to check the sparsifier bit for bit; also usable as a stand-alone pre-pass.
+ *
+ * Rule for a group g (Sec. 5.1 names the estimator; the sampling scheme is this library's):
+ *   m_i = |g_i| in float32; Lo = (min(m0,m1) + min(m2,m3)) + min(max(m0,m1), max(m2,m3));
+ *   clamp = Lo == 0 ? max m : Lo; l_i = min(m_i, clamp); P0 = l0, P1 = P0 + l1, P2 = P1 + l2,
+ *   L = P2 + l3, h = L / 2; u = (x >> 8) * 2^-24 with x the 32-bit draw below; tau0 = u * h,
+ *   tau1 = tau0 + h; i(tau) = #{k : P_k <= tau}; pos0 = min(i(tau0), 2), pos1 = min(3, max(i(tau1), pos0 + 1)).
+ *   Recorded value at p: g_p itself if m_p > h or m_p == 0, else sign(g_p) * h (h rounded to the
+ *   storage type).  e4m3 stores half of these values.
+ *   Draw: key = mix64(seed ^ mix64(offset + 0x9E3779B97F4A7C15)) (SplitMix64 finalizer), k0 = low,
+ *   k1 = high word; x = (gid & 0xFFFFFFFF) ^ k0; x += (gid >> 32) * 0x9E3779B9; x ^= x >> 17;
+ *   x *= 0xED5AD4BB; x += k1; x ^= x >> 11; x *= 0xAC4C1B51; x ^= x >> 15; x *= 0x31848BAB; x ^= x >> 14.
+ *
+ *   dY    in   device, T x O of `dtype`, leading dimension lddy;  T a multiple of 8, O >= 0
+ *   vals  out  device, O x T/2 elements of `dtype`;  meta out: O x T/8 bytes (packed format above, K = T)
+ */
+int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype,
+                          uint64_t seed, uint64_t offset, void* vals, void* meta, void* hip_stream);
+
+/*
+ * MSE-optimal scale of Sec. 4.2: beta = <W, S_soft(W)> / ||S_soft(W)||^2, computed once from the
+ * initial weights and then frozen by the caller.  Products are formed in float32 and summed in
+ * float64 in a fixed order (reproducible).
+ *
+ *   W          in   device, bf16, O x I, leading dimension ldw
+ *   beta_out   out  device float*; receives beta, or NaN if S_soft(W) is identically zero
+ *   workspace       device scratch of at least sste_beta_workspace_bytes(O, I) bytes, 16-byte aligned
+ */
+int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t sste_beta_workspace_bytes(int64_t O, int64_t I);
+
+/*
+ * Flip count of Sec. 3.3 (numerator of the flip rate r_k): number of positions whose recorded /
+ * not-recorded state differs between two metadata arrays of the same O x I/8 shape.
+ *   count_out  out  device uint64_t*; overwritten
+ */
+int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I,
+                    unsigned long long* count_out, void* hip_stream);
+
+/* Message for the most recent non-OK status returned on the calling thread ("" if none). */
+const char* sste_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sste_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSTE_H */

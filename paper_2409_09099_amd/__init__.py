@@ -1,0 +1,21 @@
+"""S-STE 2:4 sparse linear-layer hot path for AMD MI355X (gfx950): Python binding of libsste.so.
+
+The functions here have the names of the C entry points declared in ``include/sste.h`` and only
+marshal arguments (pointers, sizes, strides, the current HIP stream); every step of the path runs in
+the library's HIP kernels.  PyTorch provides device memory and streams, nothing else.  Importing
+this package does not load the library; the first call does, and it fails loudly if the library
+cannot be loaded.
+"""
+from .binding import (  # noqa: F401
+    BF16,
+    F8E4M3,
+    SsteError,
+    compute_beta,
+    flip_count,
+    library,
+    linear_fwd,
+    linear_wgrad,
+    mvue_materialize,
+    project_pack,
+    wgrad_workspace_bytes,
+)

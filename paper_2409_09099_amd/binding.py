@@ -1,0 +1,166 @@
+"""ctypes binding of libsste.so: argument marshalling only."""
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+BF16 = 0
+F8E4M3 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsste.so")
+_lib = None
+
+_STATUS = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_ALIGN", 4: "ERR_DTYPE", 5: "ERR_VALUE",
+           6: "ERR_WORKSPACE", 7: "ERR_UNSUPPORTED", 8: "ERR_HIP"}
+
+
+class SsteError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"sste status {status} ({_STATUS.get(status, '?')}): {message}")
+        self.status = status
+
+
+def library() -> ctypes.CDLL:
+    """Loads libsste.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build
+        build.build_library(verbose=False)
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, f32, vp, ci, u64, sz = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_size_t
+    lib.sste_version.restype = ci
+    lib.sste_last_error.restype = ctypes.c_char_p
+    lib.sste_project_pack.argtypes = [vp, i64, i64, i64, f32, ci, f32, vp, vp, vp, vp]
+    lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
+    lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
+    lib.sste_wgrad_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.sste_wgrad_workspace_bytes.restype = sz
+    lib.sste_mvue_materialize.argtypes = [vp, i64, i64, i64, ci, u64, u64, vp, vp, vp]
+    lib.sste_compute_beta.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
+    lib.sste_beta_workspace_bytes.argtypes = [i64, i64]
+    lib.sste_beta_workspace_bytes.restype = sz
+    lib.sste_flip_count.argtypes = [vp, vp, i64, i64, vp, vp]
+    for name in ("sste_project_pack", "sste_linear_fwd", "sste_linear_wgrad", "sste_mvue_materialize",
+                 "sste_compute_beta", "sste_flip_count"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise SsteError(status, library().sste_last_error().decode())
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr() if t.numel() > 0 else None
+
+
+def _matrix(t: torch.Tensor, itemsize: int, name: str) -> Tuple[int, int, int]:
+    """(rows, cols, leading dimension in elements) of a 2-D device tensor with unit inner stride."""
+    if t.dim() != 2:
+        raise ValueError(f"{name} must be 2-D")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.element_size() != itemsize:
+        raise ValueError(f"{name} must have {itemsize}-byte elements")
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError(f"{name} must have unit stride along its last axis")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0) if t.shape[0] == 1 else t.shape[1])
+    return t.shape[0], t.shape[1], max(ld, t.shape[1])
+
+
+def _esize(dtype: int) -> int:
+    return 1 if dtype == F8E4M3 else 2
+
+
+def project_pack(W: torch.Tensor, beta: float, val_dtype: int = BF16, val_scale: float = 1.0,
+                 vals: Optional[torch.Tensor] = None, meta: Optional[torch.Tensor] = None,
+                 amax_out: Optional[torch.Tensor] = None):
+    """sste_project_pack: beta * S_soft(W) packed 2:4.  Returns (vals, meta)."""
+    O, I, ldw = _matrix(W, 2, "W")
+    if vals is None:
+        vals = torch.empty((O, I // 2), dtype=torch.uint8 if val_dtype == F8E4M3 else torch.int16, device=W.device)
+    if meta is None:
+        meta = torch.empty((O, I // 8), dtype=torch.uint8, device=W.device)
+    _check(library().sste_project_pack(_ptr(W), O, I, ldw, beta, val_dtype, val_scale, _ptr(vals), _ptr(meta),
+                                       _ptr(amax_out), _stream(W)))
+    return vals, meta
+
+
+def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, dtype: int = BF16, x_scale: float = 1.0,
+               w_scale: float = 1.0, Z: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """sste_linear_fwd: Z = (x_scale * w_scale) * X decode(vals, meta)^T, bf16 output."""
+    T, I, ldx = _matrix(X, _esize(dtype), "X")
+    O = vals.shape[0]
+    if Z is None:
+        Z = torch.empty((T, O), dtype=torch.bfloat16, device=X.device)
+    _, _, ldz = _matrix(Z, 2, "Z")
+    _check(library().sste_linear_fwd(_ptr(X), T, I, ldx, dtype, x_scale, _ptr(vals), _ptr(meta), O, w_scale, _ptr(Z), ldz,
+                                     _stream(X)))
+    return Z
+
+
+def wgrad_workspace_bytes(T: int, O: int, I: int, dtype: int = BF16) -> int:
+    return int(library().sste_wgrad_workspace_bytes(T, O, I, dtype))
+
+
+def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtype: int = BF16, dy_scale: float = 1.0,
+                 x_scale: float = 1.0, dW: Optional[torch.Tensor] = None, accumulate: bool = False,
+                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """sste_linear_wgrad: dW (+)= scale * MVUE(dY^T; seed, offset) X, float32 output."""
+    T, O, lddy = _matrix(dY, _esize(dtype), "dY")
+    T2, I, ldx = _matrix(X, _esize(dtype), "X")
+    if T2 != T:
+        raise ValueError("dY and X must have the same number of rows (tokens)")
+    if dW is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dW")
+        dW = torch.empty((O, I), dtype=torch.float32, device=X.device)
+    _, _, lddw = _matrix(dW, 4, "dW")
+    need = wgrad_workspace_bytes(T, O, I, dtype)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(library().sste_linear_wgrad(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(X), I, ldx, x_scale, seed, offset, _ptr(dW),
+                                       lddw, int(bool(accumulate)), _ptr(workspace), ws_bytes, _stream(X)))
+    return dW
+
+
+def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16):
+    """sste_mvue_materialize: MVUE(dY^T) as a packed 2:4 operand.  Returns (vals (O, T/2), meta (O, T/8))."""
+    T, O, lddy = _matrix(dY, _esize(dtype), "dY")
+    vals = torch.empty((O, T // 2), dtype=torch.uint8 if dtype == F8E4M3 else torch.int16, device=dY.device)
+    meta = torch.empty((O, T // 8), dtype=torch.uint8, device=dY.device)
+    _check(library().sste_mvue_materialize(_ptr(dY), T, O, lddy, dtype, seed, offset, _ptr(vals), _ptr(meta), _stream(dY)))
+    return vals, meta
+
+
+def compute_beta(W: torch.Tensor) -> torch.Tensor:
+    """sste_compute_beta: the MSE-optimal scale as a 1-element float32 device tensor."""
+    O, I, ldw = _matrix(W, 2, "W")
+    need = int(library().sste_beta_workspace_bytes(O, I))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=W.device)
+    out = torch.empty(1, dtype=torch.float32, device=W.device)
+    _check(library().sste_compute_beta(_ptr(W), O, I, ldw, _ptr(out), _ptr(ws), ws.numel(), _stream(W)))
+    return out
+
+
+def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor) -> torch.Tensor:
+    """sste_flip_count: number of positions whose recorded state differs (1-element int64 device tensor)."""
+    O, I8, _ = _matrix(meta_a, 1, "meta_a")
+    if tuple(meta_b.shape) != tuple(meta_a.shape) or not meta_a.is_contiguous() or not meta_b.is_contiguous():
+        raise ValueError("metadata arrays must be contiguous and of equal shape")
+    out = torch.empty(1, dtype=torch.int64, device=meta_a.device)
+    _check(library().sste_flip_count(_ptr(meta_a), _ptr(meta_b), O, I8 * 8, _ptr(out), _stream(meta_a)))
+    return out

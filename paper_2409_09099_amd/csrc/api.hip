@@ -1,0 +1,190 @@
+// C ABI of the library: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates, frees or synchronises.
+#include "common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace sste {
+
+static thread_local char g_err[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return status;
+}
+void clear_error() { g_err[0] = 0; }
+
+static uint64_t mix64(uint64_t z) {
+  z ^= z >> 30;
+  z *= 0xBF58476D1CE4E5B9ull;
+  z ^= z >> 27;
+  z *= 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return z;
+}
+
+RngKey derive_key(uint64_t seed, uint64_t offset) {
+  uint64_t k = mix64(seed ^ mix64(offset + 0x9E3779B97F4A7C15ull));
+  RngKey r;
+  r.k0 = (uint32_t)k;
+  r.k1 = (uint32_t)(k >> 32);
+  return r;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool good_scale(float v) { return std::isfinite(v) && v > 0.0f; }
+static bool good_dtype(int d) { return d == SSTE_BF16 || d == SSTE_F8E4M3; }
+static int elems_per_16B(int d) { return d == SSTE_F8E4M3 ? 16 : 8; }
+
+static int hip_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return SSTE_OK;
+  return fail(SSTE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace sste
+
+using namespace sste;
+
+extern "C" {
+
+int sste_version(void) { return 100; }
+
+const char* sste_last_error(void) { return g_err; }
+
+int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype, float val_scale,
+                      void* vals, void* meta, float* amax_out, void* hip_stream) {
+  clear_error();
+  if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "project_pack: negative size O=%lld I=%lld", (long long)O, (long long)I);
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "project_pack: I=%lld is not a multiple of 8 (whole groups of 4, two per metadata byte)", (long long)I);
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "project_pack: unknown val_dtype %d", val_dtype);
+  if (!good_scale(beta)) return fail(SSTE_ERR_VALUE, "project_pack: beta must be finite and > 0");
+  if (!good_scale(val_scale)) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be finite and > 0");
+  if (val_dtype == SSTE_BF16 && val_scale != 1.0f) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be 1 for bf16 values");
+  if (ldw < I) return fail(SSTE_ERR_SHAPE, "project_pack: ldw=%lld < I=%lld", (long long)ldw, (long long)I);
+  if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "project_pack: ldw=%lld is not a multiple of 8", (long long)ldw);
+  bool empty = (O == 0 || I == 0);
+  if (!empty && (!W || !vals || !meta)) return fail(SSTE_ERR_NULL, "project_pack: NULL W, vals or meta");
+  if (!aligned16(W) || !aligned16(vals)) return fail(SSTE_ERR_ALIGN, "project_pack: W and vals must be 16-byte aligned");
+  if (amax_out && (reinterpret_cast<uintptr_t>(amax_out) & 3u)) return fail(SSTE_ERR_ALIGN, "project_pack: amax_out must be 4-byte aligned");
+  return hip_status(launch_project_pack(W, O, I, ldw, beta, val_dtype, val_scale, vals, meta, amax_out, (hipStream_t)hip_stream),
+                    "project_pack launch");
+}
+
+int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale, const void* vals,
+                    const void* meta, int64_t O, float w_scale, void* Z, int64_t ldz, void* hip_stream) {
+  clear_error();
+  if (T < 0 || I < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "linear_fwd: negative size");
+  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_fwd: unknown dtype %d", dtype);
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_fwd: I=%lld is not a multiple of 8", (long long)I);
+  if (!good_scale(x_scale) || !good_scale(w_scale)) return fail(SSTE_ERR_VALUE, "linear_fwd: scales must be finite and > 0");
+  int kmult = dtype == SSTE_F8E4M3 ? 128 : 64;
+  if (I % kmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: I=%lld must be a multiple of %d for this element type", (long long)I, kmult);
+  if (O % 8 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: O=%lld must be a multiple of 8", (long long)O);
+  if (ldx < I || ldz < O) return fail(SSTE_ERR_SHAPE, "linear_fwd: leading dimension smaller than the row length");
+  if (ldx % elems_per_16B(dtype) != 0 || ldz % 8 != 0) return fail(SSTE_ERR_ALIGN, "linear_fwd: ldx / ldz break the 16-byte row rule");
+  bool empty = (T == 0 || O == 0);
+  if (!empty && (!Z || (I > 0 && (!X || !vals || !meta)))) return fail(SSTE_ERR_NULL, "linear_fwd: NULL X, vals, meta or Z");
+  if (!aligned16(X) || !aligned16(vals) || !aligned16(meta) || !aligned16(Z))
+    return fail(SSTE_ERR_ALIGN, "linear_fwd: X, vals, meta and Z must be 16-byte aligned");
+  float scale = x_scale * w_scale;
+  return hip_status(launch_linear_fwd(X, T, I, ldx, dtype, scale, vals, meta, O, Z, ldz, (hipStream_t)hip_stream), "linear_fwd launch");
+}
+
+static int wgrad_shape_check(int64_t T, int64_t O, int64_t I, int dtype, const char* who) {
+  if (T < 0 || O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "%s: negative size", who);
+  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "%s: unknown dtype %d", who, dtype);
+  if (T % 4 != 0) return fail(SSTE_ERR_SHAPE, "%s: T=%lld is not a multiple of 4 (groups of four tokens)", who, (long long)T);
+  int kmult = dtype == SSTE_F8E4M3 ? 128 : 64, nmult = elems_per_16B(dtype);
+  if (T % kmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "%s: T=%lld must be a multiple of %d for this element type", who, (long long)T, kmult);
+  if (O % nmult != 0 || I % nmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "%s: O and I must be multiples of %d", who, nmult);
+  return SSTE_OK;
+}
+
+size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
+  if (wgrad_shape_check(T, O, I, dtype, "wgrad_workspace_bytes") != SSTE_OK) return 0;
+  int s = wgrad_splits(T, O, I, dtype);
+  return s > 1 ? (size_t)s * (size_t)O * (size_t)I * sizeof(float) : 0;
+}
+
+int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
+                      int64_t I, int64_t ldx, float x_scale, uint64_t seed, uint64_t offset, float* dW, int64_t lddw,
+                      int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  int st = wgrad_shape_check(T, O, I, dtype, "linear_wgrad");
+  if (st != SSTE_OK) return st;
+  if (!good_scale(dy_scale) || !good_scale(x_scale)) return fail(SSTE_ERR_VALUE, "linear_wgrad: scales must be finite and > 0");
+  if (accumulate != 0 && accumulate != 1) return fail(SSTE_ERR_VALUE, "linear_wgrad: accumulate must be 0 or 1");
+  if (lddy < O || ldx < I || lddw < I) return fail(SSTE_ERR_SHAPE, "linear_wgrad: leading dimension smaller than the row length");
+  int e16 = elems_per_16B(dtype);
+  if (lddy % e16 != 0 || ldx % e16 != 0 || lddw % 4 != 0) return fail(SSTE_ERR_ALIGN, "linear_wgrad: leading dimensions break the 16-byte row rule");
+  bool empty = (O == 0 || I == 0);
+  if (!empty && (!dW || (T > 0 && (!dY || !X)))) return fail(SSTE_ERR_NULL, "linear_wgrad: NULL dY, X or dW");
+  if (!aligned16(dY) || !aligned16(X) || !aligned16(dW)) return fail(SSTE_ERR_ALIGN, "linear_wgrad: dY, X and dW must be 16-byte aligned");
+  size_t need = sste_wgrad_workspace_bytes(T, O, I, dtype);
+  if (need > 0) {
+    if (!workspace) return fail(SSTE_ERR_WORKSPACE, "linear_wgrad: workspace is NULL, %zu bytes needed", need);
+    if (workspace_bytes < need) return fail(SSTE_ERR_WORKSPACE, "linear_wgrad: workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(SSTE_ERR_ALIGN, "linear_wgrad: workspace must be 16-byte aligned");
+  }
+  float scale = dy_scale * x_scale;
+  if (dtype == SSTE_F8E4M3) scale *= 2.0f;      // the sparsified e4m3 operand is stored halved
+  return hip_status(launch_linear_wgrad(dY, T, O, lddy, dtype, X, I, ldx, scale, derive_key(seed, offset), dW, lddw, accumulate,
+                                        workspace, (hipStream_t)hip_stream),
+                    "linear_wgrad launch");
+}
+
+int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, uint64_t seed, uint64_t offset,
+                          void* vals, void* meta, void* hip_stream) {
+  clear_error();
+  if (T < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: negative size");
+  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "mvue_materialize: unknown dtype %d", dtype);
+  if (T % 8 != 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: T=%lld is not a multiple of 8 (two groups per metadata byte)", (long long)T);
+  if (lddy < O) return fail(SSTE_ERR_SHAPE, "mvue_materialize: lddy < O");
+  bool empty = (T == 0 || O == 0);
+  if (!empty && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "mvue_materialize: NULL dY, vals or meta");
+  if (!aligned16(vals)) return fail(SSTE_ERR_ALIGN, "mvue_materialize: vals must be 16-byte aligned");
+  if (T / 8 > 65535) return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld exceeds 524280", (long long)T);
+  return hip_status(launch_mvue_materialize(dY, T, O, lddy, dtype, derive_key(seed, offset), vals, meta, (hipStream_t)hip_stream),
+                    "mvue_materialize launch");
+}
+
+size_t sste_beta_workspace_bytes(int64_t O, int64_t I) {
+  if (O < 0 || I < 0 || I % 8 != 0) return 0;
+  return beta_workspace_bytes(O, I);
+}
+
+int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "compute_beta: negative size");
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "compute_beta: I=%lld is not a multiple of 8", (long long)I);
+  if (ldw < I) return fail(SSTE_ERR_SHAPE, "compute_beta: ldw < I");
+  if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "compute_beta: ldw is not a multiple of 8");
+  if (!beta_out) return fail(SSTE_ERR_NULL, "compute_beta: beta_out is NULL");
+  if (O * I > 0 && !W) return fail(SSTE_ERR_NULL, "compute_beta: W is NULL");
+  if (!aligned16(W)) return fail(SSTE_ERR_ALIGN, "compute_beta: W must be 16-byte aligned");
+  size_t need = beta_workspace_bytes(O, I);
+  if (!workspace || workspace_bytes < need) return fail(SSTE_ERR_WORKSPACE, "compute_beta: workspace needs %zu bytes", need);
+  if (!aligned16(workspace)) return fail(SSTE_ERR_ALIGN, "compute_beta: workspace must be 16-byte aligned");
+  return hip_status(launch_compute_beta(W, O, I, ldw, beta_out, workspace, (hipStream_t)hip_stream), "compute_beta launch");
+}
+
+int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I, unsigned long long* count_out, void* hip_stream) {
+  clear_error();
+  if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "flip_count: negative size");
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "flip_count: I=%lld is not a multiple of 8", (long long)I);
+  if (!count_out) return fail(SSTE_ERR_NULL, "flip_count: count_out is NULL");
+  int64_t nbytes = O * (I / 8);
+  if (nbytes > 0 && (!meta_a || !meta_b)) return fail(SSTE_ERR_NULL, "flip_count: NULL metadata");
+  if ((reinterpret_cast<uintptr_t>(meta_a) & 3u) || (reinterpret_cast<uintptr_t>(meta_b) & 3u) || (reinterpret_cast<uintptr_t>(count_out) & 7u))
+    return fail(SSTE_ERR_ALIGN, "flip_count: metadata must be 4-byte and count_out 8-byte aligned");
+  return hip_status(launch_flip_count(meta_a, meta_b, nbytes, count_out, (hipStream_t)hip_stream), "flip_count launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+// Shared host/device helpers for the S-STE sparse linear-layer kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/sste.h"
+
+namespace sste {
+
+// ---- host: status + thread-local message -----------------------------------------------------
+int fail(int status, const char* fmt, ...);   // records the message, returns `status`
+void clear_error();
+
+// ---- vector types for MFMA operands -----------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8;
+
+// ---- device bit helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
+
+// float32 -> bf16 pattern, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  __bf16 b = (__bf16)f;
+  uint16_t u;
+  __builtin_memcpy(&u, &b, 2);
+  return u;
+}
+// two floats -> packed bf16 pair (lo in bits 0..15)
+__device__ __forceinline__ uint32_t bf16_rne_pack(float lo, float hi) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  uint32_t u;
+  __builtin_memcpy(&u, &v, 4);
+  return u;
+}
+
+// 16-bit element `idx` (0..3) of the little-endian 64-bit pair {hi:lo}, moved to the top half of
+// a dword with zeros below: the float32 value of that bf16 element.
+__device__ __forceinline__ uint32_t pick16_as_f32bits(uint32_t lo, uint32_t hi, uint32_t idx) {
+  // v_perm_b32: selector bytes 0..3 address `lo`, 4..7 address `hi`, 0x0c yields 0x00
+  uint32_t sel = 0x01000c0cu + idx * 0x02020000u;
+  return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// OCP e4m3 conversions (hardware: v_cvt_f32_fp8 / v_cvt_pk_fp8_f32, OCP flavour on gfx950)
+__device__ __forceinline__ float e4m3_to_f32(uint32_t packed, int byte) {
+  switch (byte) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8(packed, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8(packed, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8(packed, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8(packed, 3);
+  }
+}
+// two floats (already clamped to +-448) -> two e4m3 codes in the low 16 bits
+__device__ __forceinline__ uint32_t e4m3_rne_pack(float lo, float hi) {
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(lo, hi, 0, false) & 0xFFFFu;
+}
+__device__ __forceinline__ float clamp448(float x) { return __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f); }
+
+// ---- host-side launch entry points implemented in the .hip files --------------------------------
+struct RngKey { uint32_t k0, k1; };
+RngKey derive_key(uint64_t seed, uint64_t offset);
+
+hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
+                               float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s);
+hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
+                               hipStream_t s);
+size_t beta_workspace_bytes(int64_t O, int64_t I);
+hipError_t launch_flip_count(const void* a, const void* b, int64_t nbytes, unsigned long long* out, hipStream_t s);
+hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,
+                                   void* vals, void* meta, hipStream_t s);
+hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
+                             const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s);
+int wgrad_splits(int64_t T, int64_t O, int64_t I, int dtype);
+hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
+                               int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,
+                               int accumulate, void* ws, hipStream_t s);
+
+}  // namespace sste

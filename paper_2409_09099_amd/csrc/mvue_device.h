@@ -1,0 +1,98 @@
+// Device code of the 2:4 minimum-variance unbiased estimator (paper Sec. 5.1) and its counter-based
+// random draw.  The rule is stated in full in include/sste.h (sste_mvue_materialize).  Every float
+// operation below is a single IEEE float32 operation in the order written; the translation unit is
+// compiled with -ffp-contract=off so that tau1 = tau0 + h is not fused with tau0 = u * h.
+#pragma once
+#include "common.h"
+
+namespace sste {
+
+// 32-bit draw for a group id: three-round multiply-xorshift hash keyed by (k0, k1).
+__device__ __forceinline__ uint32_t draw_u32(uint32_t k0, uint32_t k1, uint32_t gid_lo, uint32_t gid_hi) {
+  uint32_t x = gid_lo ^ k0;
+  x += gid_hi * 0x9E3779B9u;
+  x ^= x >> 17;
+  x *= 0xED5AD4BBu;
+  x += k1;
+  x ^= x >> 11;
+  x *= 0xAC4C1B51u;
+  x ^= x >> 15;
+  x *= 0x31848BABu;
+  x ^= x >> 14;
+  return x;
+}
+
+struct Sel {
+  float h;        // common magnitude of recorded elements that are not kept as they are
+  uint32_t pos0;  // recorded positions, pos0 < pos1
+  uint32_t pos1;
+};
+
+// Steps 1-4 of the rule on the four magnitudes m0..m3 (all >= 0) and the 32-bit draw x.
+__device__ __forceinline__ Sel mvue_select(float m0, float m1, float m2, float m3, uint32_t x) {
+  float a = fmaxf(m0, m1), b = fminf(m0, m1);
+  float cc = fmaxf(m2, m3), d = fminf(m2, m3);
+  float mx = fmaxf(a, cc), mid = fminf(a, cc);
+  float Lo = (b + d) + mid;
+  float clampv = (Lo == 0.0f) ? mx : Lo;
+  float l0 = fminf(m0, clampv), l1 = fminf(m1, clampv), l2 = fminf(m2, clampv), l3 = fminf(m3, clampv);
+  float P0 = l0;
+  float P1 = P0 + l1;
+  float P2 = P1 + l2;
+  float L = P2 + l3;
+  float h = 0.5f * L;
+  float u = (float)(x >> 8) * 0x1p-24f;     // exact: 24-bit integer times a power of two
+  float tau0 = u * h;
+  float tau1 = tau0 + h;
+  uint32_t i0 = (uint32_t)(P0 <= tau0) + (uint32_t)(P1 <= tau0) + (uint32_t)(P2 <= tau0);
+  uint32_t i1 = (uint32_t)(P0 <= tau1) + (uint32_t)(P1 <= tau1) + (uint32_t)(P2 <= tau1);
+  Sel s;
+  s.h = h;
+  s.pos0 = min(i0, 2u);
+  s.pos1 = min(3u, max(i1, s.pos0 + 1u));
+  return s;
+}
+
+// bf16 group {hi:lo} = (g0 | g1 << 16, g2 | g3 << 16).  Returns the two recorded bf16 values packed
+// (pos0's value in the low half) and writes the metadata nibble pos0 | pos1 << 2.
+__device__ __forceinline__ uint32_t mvue_group_bf16(uint32_t lo, uint32_t hi, uint32_t x, uint32_t& nib) {
+  float m0 = u2f((lo << 16) & 0x7FFFFFFFu), m1 = u2f(lo & 0x7FFF0000u);
+  float m2 = u2f((hi << 16) & 0x7FFFFFFFu), m3 = u2f(hi & 0x7FFF0000u);
+  Sel s = mvue_select(m0, m1, m2, m3, x);
+  uint32_t hq = bf16_rne(s.h);
+  uint32_t out = 0;
+#pragma unroll
+  for (int k = 0; k < 2; k++) {
+    uint32_t p = k ? s.pos1 : s.pos0;
+    uint32_t gb = pick16_as_f32bits(lo, hi, p);          // g_p as float32 bits
+    uint32_t mb = gb & 0x7FFFFFFFu;
+    // keep g_p itself when m_p > h or m_p == 0: (mb - 1) as unsigned >= bits(h) covers both
+    bool own = (mb - 1u) >= f2u(s.h);
+    uint32_t v = own ? (gb >> 16) : (((gb >> 16) & 0x8000u) | hq);
+    out |= v << (16 * k);
+  }
+  nib = s.pos0 | (s.pos1 << 2);
+  return out;
+}
+
+// e4m3 group: the four codes of one group in one dword (g0 in byte 0).  Returns the two recorded
+// codes of theta / 2 in the low 16 bits (pos0's in byte 0).
+__device__ __forceinline__ uint32_t mvue_group_e4m3(uint32_t g, uint32_t x, uint32_t& nib) {
+  uint32_t ga = g & 0x7F7F7F7Fu;
+  float m0 = __builtin_amdgcn_cvt_f32_fp8(ga, 0), m1 = __builtin_amdgcn_cvt_f32_fp8(ga, 1);
+  float m2 = __builtin_amdgcn_cvt_f32_fp8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_fp8(ga, 3);
+  Sel s = mvue_select(m0, m1, m2, m3, x);
+  float mp0 = s.pos0 == 0 ? m0 : (s.pos0 == 1 ? m1 : m2);
+  float mp1 = s.pos1 == 1 ? m1 : (s.pos1 == 2 ? m2 : m3);
+  // stored magnitudes: 0.5 * m_p where g_p is kept as it is, else 0.5 * h; all <= 448
+  bool own0 = (f2u(mp0) - 1u) >= f2u(s.h);
+  bool own1 = (f2u(mp1) - 1u) >= f2u(s.h);
+  float v0 = 0.5f * (own0 ? mp0 : s.h);
+  float v1 = 0.5f * (own1 ? mp1 : s.h);
+  uint32_t q = e4m3_rne_pack(v0, v1);
+  uint32_t s0 = (g >> (8 * s.pos0)) & 0x80u, s1 = (g >> (8 * s.pos1)) & 0x80u;
+  nib = s.pos0 | (s.pos1 << 2);
+  return q | s0 | (s1 << 8);
+}
+
+}  // namespace sste

@@ -1,0 +1,233 @@
+// S(W) = beta * S_soft(W): 2:4 soft-threshold projection (paper Sec. 4.1), frozen scale (Sec. 4.2)
+// and packing into values + 2-bit position metadata, in one streaming pass over W.
+// Also: the MSE-optimal beta reduction of Sec. 4.2 and the flip count of Sec. 3.3.
+//
+// Data movement per weight: 2 B read, 1 B (bf16 values) or 0.5 B (e4m3 values) + 0.125 B written.
+// The kernel is bound by HBM bandwidth; each lane owns one 16-byte chunk (two groups of four), so a
+// wave reads 1 KiB, writes 512 B (256 B) of values and 64 B of metadata, all contiguous.
+#include "common.h"
+
+namespace sste {
+
+struct Proj {
+  float p0, p1;   // beta * (a -/+ t) of the two recorded elements, ascending position order
+  uint32_t nib;   // pos0 | pos1 << 2
+};
+
+// One group {hi:lo} of four bf16.  Order: magnitude field descending, then index ascending.
+__device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float beta) {
+  // key = magnitude << 2 | (3 - index): a larger key ranks first, keys are distinct
+  uint32_t k0 = ((lo & 0x7FFFu) << 2) | 3u;
+  uint32_t k1 = ((lo >> 14) & 0x1FFFCu) | 2u;
+  uint32_t k2 = ((hi & 0x7FFFu) << 2) | 1u;
+  uint32_t k3 = ((hi >> 14) & 0x1FFFCu);
+  // partial sorting network on four distinct keys.  {first, x} partition {a, c} and {y, w} partition
+  // {b, d}; the runner-up is the better of x (loser of the two pair winners) and y (best pair loser),
+  // and the third is the better of the two keys that are left.
+  uint32_t a = max(k0, k1), b = min(k0, k1), c = max(k2, k3), d = min(k2, k3);
+  uint32_t first = max(a, c), x = min(a, c);
+  uint32_t y = max(b, d), w = min(b, d);
+  uint32_t second = max(x, y), z = min(x, y);
+  uint32_t third = max(z, w);
+  uint32_t pa = 3u - (first & 3u), pb = 3u - (second & 3u);
+  uint32_t pos0 = min(pa, pb), pos1 = max(pa, pb);
+  uint32_t tbits = (third >> 2) << 16;              // float32 pattern of t (>= 0)
+  Proj r;
+  uint32_t g0 = pick16_as_f32bits(lo, hi, pos0), g1 = pick16_as_f32bits(lo, hi, pos1);
+  float sd0 = u2f(g0) - u2f(tbits | (g0 & 0x80000000u));    // a - t  or  a + t
+  float sd1 = u2f(g1) - u2f(tbits | (g1 & 0x80000000u));
+  r.p0 = sd0 * beta;
+  r.p1 = sd1 * beta;
+  r.nib = pos0 | (pos1 << 2);
+  return r;
+}
+
+template <bool FP8, bool AMAX>
+__global__ void __launch_bounds__(256)
+k_project_pack(const uint4* __restrict__ W, int64_t n_chunks, int32_t chunks_per_row, int64_t ldw_chunks,
+               float beta, float val_scale, void* __restrict__ vals, uint8_t* __restrict__ meta,
+               uint32_t* __restrict__ amax_bits) {
+  int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  float amax = 0.0f;
+  if (c < n_chunks) {
+    int64_t row = c / chunks_per_row;
+    int64_t col = c - row * chunks_per_row;
+    uint4 w = W[row * ldw_chunks + col];
+    Proj g0 = project_group(w.x, w.y, beta);
+    Proj g1 = project_group(w.z, w.w, beta);
+    if (AMAX) amax = fmaxf(fmaxf(fabsf(g0.p0), fabsf(g0.p1)), fmaxf(fabsf(g1.p0), fabsf(g1.p1)));
+    if (FP8) {
+      uint32_t q0 = e4m3_rne_pack(clamp448(g0.p0 / val_scale), clamp448(g0.p1 / val_scale));
+      uint32_t q1 = e4m3_rne_pack(clamp448(g1.p0 / val_scale), clamp448(g1.p1 / val_scale));
+      ((uint32_t*)vals)[c] = q0 | (q1 << 16);
+    } else {
+      uint2 v;
+      v.x = bf16_rne_pack(g0.p0, g0.p1);
+      v.y = bf16_rne_pack(g1.p0, g1.p1);
+      ((uint2*)vals)[c] = v;
+    }
+    meta[c] = (uint8_t)(g0.nib | (g1.nib << 4));
+  }
+  if (AMAX) {
+    // non-negative floats order like their bit patterns: reduce as unsigned integers
+    uint32_t m = f2u(amax);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
+    __shared__ uint32_t wave_max[4];
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+      atomicMax(amax_bits, m);
+    }
+  }
+}
+
+__global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
+__global__ void k_fill_u64(unsigned long long* p, unsigned long long v) { *p = v; }
+
+hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
+                               float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s) {
+  if (amax_out) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
+  int64_t cpr = I / 8, n = O * cpr;
+  if (n == 0) return hipGetLastError();
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  const uint4* w = (const uint4*)W;
+  uint32_t* ab = (uint32_t*)amax_out;
+  bool fp8 = val_dtype == SSTE_F8E4M3;
+  if (fp8 && amax_out)
+    hipLaunchKernelGGL((k_project_pack<true, true>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+  else if (fp8)
+    hipLaunchKernelGGL((k_project_pack<true, false>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+  else if (amax_out)
+    hipLaunchKernelGGL((k_project_pack<false, true>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+  else
+    hipLaunchKernelGGL((k_project_pack<false, false>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// beta = <w, S_soft(w)> / ||S_soft(w)||^2  (Sec. 4.2).  Exact products in float64, fixed-order sums.
+constexpr int kBetaBlocks = 1024;
+
+__global__ void __launch_bounds__(256)
+k_beta_partial(const uint4* __restrict__ W, int64_t n_chunks, int32_t chunks_per_row, int64_t ldw_chunks,
+               double* __restrict__ partial) {
+  double num = 0.0, den = 0.0;
+  for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (int64_t)gridDim.x * 256) {
+    int64_t row = c / chunks_per_row;
+    int64_t col = c - row * chunks_per_row;
+    uint4 w = W[row * ldw_chunks + col];
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+      uint32_t lo = g ? w.z : w.x, hi = g ? w.w : w.y;
+      Proj p = project_group(lo, hi, 1.0f);         // p = a -/+ t, exact float32 differences
+      uint32_t pos0 = p.nib & 3u, pos1 = p.nib >> 2;
+      double a0 = (double)u2f(pick16_as_f32bits(lo, hi, pos0)), a1 = (double)u2f(pick16_as_f32bits(lo, hi, pos1));
+      double s0 = (double)p.p0, s1 = (double)p.p1;
+      num += a0 * s0 + a1 * s1;
+      den += s0 * s0 + s1 * s1;
+    }
+  }
+  __shared__ double sn[256], sd[256];
+  sn[threadIdx.x] = num;
+  sd[threadIdx.x] = den;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) {
+      sn[threadIdx.x] += sn[threadIdx.x + off];
+      sd[threadIdx.x] += sd[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = sn[0];
+    partial[2 * blockIdx.x + 1] = sd[0];
+  }
+}
+
+__global__ void __launch_bounds__(256) k_beta_final(const double* __restrict__ partial, int nblocks, float* beta_out) {
+  __shared__ double sn[256], sd[256];
+  double num = 0.0, den = 0.0;
+  for (int i = threadIdx.x; i < nblocks; i += 256) {
+    num += partial[2 * i];
+    den += partial[2 * i + 1];
+  }
+  sn[threadIdx.x] = num;
+  sd[threadIdx.x] = den;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) {
+      sn[threadIdx.x] += sn[threadIdx.x + off];
+      sd[threadIdx.x] += sd[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *beta_out = (sd[0] > 0.0) ? (float)(sn[0] / sd[0]) : __builtin_nanf("");
+}
+
+static int beta_blocks(int64_t n_chunks) {
+  int64_t b = (n_chunks + 255) / 256;
+  if (b > kBetaBlocks) b = kBetaBlocks;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+size_t beta_workspace_bytes(int64_t O, int64_t I) { return (size_t)beta_blocks(O * (I / 8)) * 2 * sizeof(double); }
+
+hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
+                               hipStream_t s) {
+  int64_t cpr = I / 8, n = O * cpr;
+  int nb = beta_blocks(n);
+  hipLaunchKernelGGL(k_beta_partial, dim3(nb), dim3(256), 0, s, (const uint4*)W, n, (int32_t)(cpr ? cpr : 1), ldw / 8, (double*)ws);
+  hipLaunchKernelGGL(k_beta_final, dim3(1), dim3(256), 0, s, (const double*)ws, nb, beta_out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Flip count (Sec. 3.3): positions whose recorded / not-recorded state differs between two
+// metadata arrays.  A nibble pos0 | pos1 << 2 expands to the 4-bit mask (1 << pos0) | (1 << pos1).
+__device__ __forceinline__ uint32_t nibble_masks(uint32_t w) {
+  uint32_t out = 0;
+#pragma unroll
+  for (int n = 0; n < 8; n++) {
+    uint32_t nib = (w >> (4 * n)) & 0xFu;
+    uint32_t m = (1u << (nib & 3u)) | (1u << (nib >> 2));
+    out |= m << (4 * n);
+  }
+  return out;
+}
+
+__global__ void __launch_bounds__(256)
+k_flip_count(const uint8_t* __restrict__ a, const uint8_t* __restrict__ b, int64_t nbytes, unsigned long long* out) {
+  unsigned long long cnt = 0;
+  int64_t nwords = nbytes / 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += (int64_t)gridDim.x * 256) {
+    uint32_t wa = ((const uint32_t*)a)[i], wb = ((const uint32_t*)b)[i];
+    cnt += __popc(nibble_masks(wa) ^ nibble_masks(wb));
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    for (int64_t i = nwords * 4; i < nbytes; i++) cnt += __popc(nibble_masks(a[i]) ^ nibble_masks(b[i]));
+  }
+  __shared__ unsigned long long sc[256];
+  sc[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) sc[threadIdx.x] += sc[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && sc[0]) atomicAdd(out, sc[0]);
+}
+
+hipError_t launch_flip_count(const void* a, const void* b, int64_t nbytes, unsigned long long* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(1), 0, s, out, 0ull);
+  if (nbytes > 0) {
+    int64_t blocks = (nbytes / 4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_flip_count, dim3((unsigned)blocks), dim3(256), 0, s, (const uint8_t*)a, (const uint8_t*)b, nbytes, out);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace sste

@@ -1,0 +1,111 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before anything is launched (no GPU needed: no compute call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sste.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2409_09099_amd as pkg
+    return pkg.library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sste_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert {"sste_project_pack", "sste_linear_fwd", "sste_linear_wgrad"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.sste_version() >= 100
+
+
+def test_no_oracle_or_torch_in_the_library_sources():
+    csrc = os.path.join(ROOT, "paper_2409_09099_amd", "csrc")
+    for f in os.listdir(csrc):
+        text = open(os.path.join(csrc, f)).read()
+        assert "oracle" not in text.lower() and "torch" not in text.lower(), f
+    for f in ("binding.py", "__init__.py", "build.py"):
+        text = open(os.path.join(ROOT, "paper_2409_09099_amd", f)).read()
+        assert "import oracle" not in text and "from oracle" not in text, f
+
+
+def _err(lib):
+    return lib.sste_last_error().decode()
+
+
+def test_project_pack_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)      # never dereferenced: validation fails first
+    f = lib.sste_project_pack
+    assert f(fake, -1, 8, 8, 1.0, 0, 1.0, fake, fake, None, None) == 2
+    assert f(fake, 4, 12, 12, 1.0, 0, 1.0, fake, fake, None, None) == 2 and "multiple of 8" in _err(lib)
+    assert f(fake, 4, 16, 8, 1.0, 0, 1.0, fake, fake, None, None) == 2
+    assert f(fake, 4, 16, 20, 1.0, 0, 1.0, fake, fake, None, None) == 3
+    assert f(fake, 4, 16, 16, 1.0, 7, 1.0, fake, fake, None, None) == 4
+    assert f(fake, 4, 16, 16, 0.0, 0, 1.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 16, 16, float("inf"), 0, 1.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 16, 16, 1.0, 0, 2.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 16, 16, 1.0, 1, -1.0, fake, fake, None, None) == 5
+    assert f(None, 4, 16, 16, 1.0, 0, 1.0, fake, fake, None, None) == 1
+    assert f(P(0x1004), 4, 16, 16, 1.0, 0, 1.0, fake, fake, None, None) == 3
+
+
+def test_linear_fwd_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_linear_fwd
+    assert f(fake, -4, 64, 64, 0, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 2
+    assert f(fake, 4, 96, 96, 0, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 7
+    assert f(fake, 4, 64, 64, 1, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 7      # e4m3 needs I % 128 == 0
+    assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 12, 1.0, fake, 16, None) == 7
+    assert f(fake, 4, 64, 32, 0, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 2
+    assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 8, 1.0, fake, 12, None) == 3
+    assert f(fake, 4, 64, 64, 0, -1.0, fake, fake, 8, 1.0, fake, 8, None) == 5
+    assert f(None, 4, 64, 64, 0, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 1
+    assert f(fake, 4, 64, 64, 3, 1.0, fake, fake, 8, 1.0, fake, 8, None) == 4
+
+
+def test_linear_wgrad_validation_and_workspace(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_linear_wgrad
+    args = lambda T=128, O=16, I=16, lddy=16, dtype=0, ldx=16, lddw=16, acc=0, ws=None, wsb=0, dy=fake: (
+        dy, T, O, lddy, dtype, 1.0, fake, I, ldx, 1.0, 1, 2, fake, lddw, acc, ws, wsb, None)
+    assert f(*args(T=102)) == 2          # not whole groups of four tokens
+    assert f(*args(T=100)) == 7          # whole groups, but not a multiple of the k-step
+    assert f(*args(O=12)) == 7
+    assert f(*args(dtype=1, T=128, O=8)) == 7
+    assert f(*args(lddy=8)) == 2
+    assert f(*args(lddw=18)) == 3
+    assert f(*args(acc=2)) == 5
+    assert f(*args(dy=None)) == 1
+    # a problem that needs split partial sums refuses a missing / small workspace
+    need = lib.sste_wgrad_workspace_bytes(8192, 3072, 768, 0)
+    assert need > 0 and need % (3072 * 768 * 4) == 0
+    assert f(*args(T=8192, O=3072, I=768, lddy=3072, ldx=768, lddw=768)) == 6
+    assert f(*args(T=8192, O=3072, I=768, lddy=3072, ldx=768, lddw=768, ws=fake, wsb=need - 1)) == 6
+    assert lib.sste_wgrad_workspace_bytes(512, 256, 1024, 0) == 0
+    assert lib.sste_wgrad_workspace_bytes(100, 256, 1024, 0) == 0
+
+
+def test_other_entry_points_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    assert lib.sste_mvue_materialize(fake, 12, 8, 8, 0, 0, 0, fake, fake, None) == 2
+    assert lib.sste_mvue_materialize(fake, 16, 8, 4, 0, 0, 0, fake, fake, None) == 2
+    assert lib.sste_mvue_materialize(None, 16, 8, 8, 0, 0, 0, fake, fake, None) == 1
+    assert lib.sste_compute_beta(fake, 4, 16, 16, None, fake, 1 << 20, None) == 1
+    assert lib.sste_compute_beta(fake, 4, 16, 16, fake, None, 0, None) == 6
+    assert lib.sste_flip_count(fake, fake, 4, 12, fake, None) == 2
+    assert lib.sste_flip_count(fake, fake, 4, 16, None, None) == 1

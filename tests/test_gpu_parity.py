@@ -1,0 +1,283 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on identical seeded inputs.
+
+Bars: bit-exact for packed values, metadata and the sparsified operand; max |err| / max |ref| <= 1e-2
+(bf16 operands) and <= 6e-2 (e4m3 operands) for the GEMM outputs, both sides using float32-or-better
+accumulation on the same quantised operands.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import formats as F
+from oracle import linear as OL
+from oracle import mvue as OM
+from oracle import projection as OP
+from paper_2409_09099_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 1e-2, "e4m3": 6e-2}
+
+
+@pytest.fixture(scope="module")
+def sste():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2409_09099_amd as lib
+    lib.library()
+    return lib
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.view(dtype) if dtype is not None else t
+
+
+def host(t):
+    return t.detach().cpu().contiguous()
+
+
+def dt(lib, name):
+    return lib.BF16 if name == "bf16" else lib.F8E4M3
+
+
+def bf16_dev(bits):
+    return dev(bits.view(np.int16), torch.bfloat16)
+
+
+def act_dev(codes, dtype):
+    return bf16_dev(codes) if dtype == "bf16" else dev(codes)
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def z_to_f64(Z):
+    return host(Z).view(torch.int16).numpy().view(np.uint16).astype(np.uint32).__lshift__(16).view(np.float32).astype(np.float64)
+
+
+# ------------------------------------------------------------------------------------------ project + pack
+
+def _edge_weights():
+    """Groups that exercise ties, zeros, signed zeros, subnormals, huge values."""
+    rows = [
+        [1, -3, 0.5, 2], [2, -2, 1, 1], [3, 1, 1, 0], [1, 1, 1, 1], [0, 0, 0, 5], [0, 0, 0, 0],
+        [-0.0, 0, -0.0, 0], [-1, -1, -1, -1], [1e-40, -2e-40, 3e-40, 0], [1e38, -3e38, 2e38, 1e-38],
+        [6, 5, -5, 1], [-4, 0.25, -0.5, 8], [1.5, 1.5, -1.5, 0.1], [7, 7, 7, -7.5],
+        [1e-3, 1.0000001e-3, 0.999e-3, -1e-3], [65280, 1, -65280, 3],
+    ]
+    w = np.array(rows, dtype=np.float32).reshape(2, -1)
+    return F.f32_to_bf16_rne(w)
+
+
+@pytest.mark.parametrize("case", ["cfg1", "ragged", "edges", "strided"])
+def test_project_pack_bf16_bit_exact(sste, case):
+    wl = WL.WORKLOADS[1]
+    if case == "cfg1":
+        wb = WL.weight_bits(wl, 0)
+    elif case == "ragged":
+        wb = WL.weight_bits(wl, 0, O=77, I=1048)          # spans several workgroups, ragged tail
+    elif case == "edges":
+        wb = _edge_weights()
+    else:
+        wb = WL.weight_bits(wl, 0, O=33, I=264)
+    beta = np.float32(OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64))) if case != "edges" else np.float32(1.37)
+    if case == "strided":
+        big = torch.zeros((33, 320), dtype=torch.bfloat16, device="cuda")
+        big[:, :264] = bf16_dev(wb)
+        Wd = big[:, :264]
+    else:
+        Wd = bf16_dev(wb)
+    amax = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    vals, meta = sste.project_pack(Wd, float(beta), amax_out=amax)
+    rv, rm, ra = OP.project_pack(wb, beta)
+    assert np.array_equal(host(meta).numpy(), rm)
+    assert np.array_equal(host(vals).numpy().view(np.uint16), rv)
+    assert host(amax).numpy().view(np.uint32)[0] == np.float32(ra).view(np.uint32)
+
+
+@pytest.mark.parametrize("case", ["cfg1", "edges"])
+def test_project_pack_e4m3_bit_exact(sste, case):
+    wl = WL.WORKLOADS[1]
+    wb = WL.weight_bits(wl, 0) if case == "cfg1" else _edge_weights()
+    beta = np.float32(1.4830322)
+    _, _, amax = OP.project_pack(wb, beta)
+    scale = np.float32(amax / np.float32(448.0)) if case == "cfg1" else np.float32(0.37)
+    vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(scale))
+    rv, rm, _ = OP.project_pack(wb, beta, "e4m3", scale)
+    assert np.array_equal(host(meta).numpy(), rm)
+    got = host(vals).numpy()
+    assert np.array_equal(got, rv), np.argwhere(got != rv)[:5]
+
+
+def test_project_pack_empty_and_errors(sste):
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    vals, meta = sste.project_pack(e, 1.0)
+    assert vals.shape == (0, 32) and meta.shape == (0, 8)
+    w = torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.project_pack(w, 1.0, vals=torch.empty((4, 6), dtype=torch.int16, device="cuda"),
+                          meta=torch.empty((4, 2), dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == 2
+    w = torch.zeros((4, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.project_pack(w, float("nan"))
+    assert ei.value.status == 5
+
+
+def test_compute_beta_and_flip_count(sste):
+    wl = WL.WORKLOADS[1]
+    wb = WL.weight_bits(wl, 0)
+    beta = float(host(sste.compute_beta(bf16_dev(wb)))[0])
+    ref = OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64))
+    assert abs(beta - ref) <= 1e-5 * ref
+    assert np.isnan(float(host(sste.compute_beta(torch.ones((4, 16), dtype=torch.bfloat16, device="cuda")))[0]))
+    w2 = WL.weight_update_bits(wb, wl, 0, step=1)
+    _, m1 = sste.project_pack(bf16_dev(wb), beta)
+    _, m2 = sste.project_pack(bf16_dev(w2), beta)
+    got = int(host(sste.flip_count(m1, m2))[0])
+    want = int(np.count_nonzero(OP.structural_mask(host(m1).numpy()) ^ OP.structural_mask(host(m2).numpy())))
+    assert got == want and got > 0
+    assert int(host(sste.flip_count(m1, m1))[0]) == 0
+
+
+# ------------------------------------------------------------------------------------------ MVUE
+
+def _edge_gradients(dtype):
+    g = np.array([[1, 1, 1, 1], [10, 1, 1, 1], [3, 1, 1, 1], [0, 0, 0, 0], [0, 0, 7, 0], [7, 0, 0, 0], [0, 0, 0, -7],
+                  [2, 0, 2, 0], [-1, 2, -3, 4], [1, -8, 2, 1], [1, 2.0 ** -30, 0, 0], [-0.0, 0, -5, 0],
+                  [1e-3, -1e-3, 1e-3, -1e-3], [448, 448, 448, 448], [448, -1, 0.5, 0.25], [3, -3, 1, 0]], dtype=np.float32)
+    cols = g.T                      # (4 tokens, 16 channels): each column is one group
+    cols = np.concatenate([cols, cols[::-1]], axis=0)     # 8 tokens
+    return F.f32_to_bf16_rne(cols) if dtype == "bf16" else F.f32_to_e4m3_rne_sat(cols)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+@pytest.mark.parametrize("case", ["cfg1", "ragged", "edges"])
+def test_mvue_materialize_bit_exact(sste, dtype, case):
+    wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
+    if case == "cfg1":
+        codes, _ = WL.output_gradient(wl, 0, T=512, O=256)
+    elif case == "ragged":
+        codes, _ = WL.output_gradient(wl, 0, T=136, O=333)
+    else:
+        codes = _edge_gradients(dtype)
+    for seed, offset in [(0, 0), (1, 0), (12345678901234567, 99)]:
+        vals, meta = sste.mvue_materialize(act_dev(codes, dtype), seed, offset, dt(sste, dtype))
+        rv, rm = OM.mvue_pack(codes, seed, offset, dtype)
+        gm = host(meta).numpy()
+        assert np.array_equal(gm, rm), (case, seed, np.argwhere(gm != rm)[:5])
+        gv = host(vals).numpy().view(rv.dtype)
+        assert np.array_equal(gv, rv), (case, seed, np.argwhere(gv != rv)[:5])
+
+
+# ------------------------------------------------------------------------------------------ forward GEMM
+
+def _fwd_case(sste, dtype, T, O, I, seed_layer=0):
+    wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
+    wb = WL.weight_bits(wl, seed_layer, O=O, I=I)
+    xc, xs = WL.activations(wl, seed_layer, T=T, I=I)
+    beta = np.float32(1.4830322)
+    if dtype == "bf16":
+        ws = np.float32(1.0)
+        rv, rm, _ = OP.project_pack(wb, beta)
+        vals, meta = sste.project_pack(bf16_dev(wb), float(beta))
+    else:
+        _, _, amax = OP.project_pack(wb, beta)
+        ws = np.float32(max(float(amax), 1e-30) / 448.0)
+        rv, rm, _ = OP.project_pack(wb, beta, "e4m3", ws)
+        vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(ws))
+    Z = sste.linear_fwd(act_dev(xc, dtype), vals, meta, dt(sste, dtype), float(xs), float(ws))
+    ref = OL.linear_fwd(xc, rv, rm, dtype, xs, ws)
+    return z_to_f64(Z), ref
+
+
+@pytest.mark.parametrize("dtype,T,O,I", [
+    ("bf16", 512, 256, 1024),        # the tiny workload
+    ("bf16", 200, 136, 192),         # ragged T and O tails inside one and across two tiles
+    ("bf16", 1, 8, 64),              # single token, one k-step
+    ("bf16", 300, 264, 64),
+    ("e4m3", 512, 256, 1024),
+    ("e4m3", 130, 72, 256),
+])
+def test_linear_fwd_matches_oracle(sste, dtype, T, O, I):
+    got, ref = _fwd_case(sste, dtype, T, O, I)
+    assert got.shape == ref.shape
+    err = rel_err(got, ref)
+    assert err <= TOL[dtype], err
+    # tighter sanity bound: bf16 output rounding (2^-9 of the value) plus float32 accumulation noise
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + np.max(np.abs(ref)) * 1e-4)
+
+
+def test_linear_fwd_empty_and_errors(sste):
+    X = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
+    vals = torch.zeros((8, 32), dtype=torch.int16, device="cuda")
+    meta = torch.full((8, 8), 0x44, dtype=torch.uint8, device="cuda")
+    assert sste.linear_fwd(X, vals, meta).shape == (0, 8)
+    X = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.linear_fwd(X, torch.zeros((8, 48), dtype=torch.int16, device="cuda"), torch.zeros((8, 12), dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == 7
+
+
+# ------------------------------------------------------------------------------------------ weight-gradient GEMM
+
+def _wgrad_case(sste, dtype, T, O, I, seed=3, offset=5, **kw):
+    wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
+    dyc, dys = WL.output_gradient(wl, 0, T=T, O=O)
+    xc, xs = WL.activations(wl, 0, T=T, I=I)
+    dW = sste.linear_wgrad(act_dev(dyc, dtype), act_dev(xc, dtype), seed, offset, dt(sste, dtype), float(dys), float(xs), **kw)
+    ref = OL.linear_wgrad(dyc, xc, seed, offset, dtype, dys, xs)
+    return dW, ref
+
+
+@pytest.mark.parametrize("dtype,T,O,I", [
+    ("bf16", 512, 256, 1024),        # the tiny workload
+    ("bf16", 64, 8, 8),              # one k-step, one partial tile
+    ("bf16", 192, 136, 200),         # ragged O and I tails
+    ("bf16", 4096, 128, 128),        # one tile, token axis split across workgroups
+    ("e4m3", 512, 256, 1024),
+    ("e4m3", 256, 144, 80),
+    ("e4m3", 8192, 128, 128),
+])
+def test_linear_wgrad_matches_oracle(sste, dtype, T, O, I):
+    dW, ref = _wgrad_case(sste, dtype, T, O, I)
+    got = host(dW).numpy().astype(np.float64)
+    assert got.shape == ref.shape
+    err = rel_err(got, ref)
+    assert err <= TOL[dtype], err
+    # the sparse operand is bit-identical on both sides, so only float32 accumulation order differs
+    assert err <= 1e-4, err
+
+
+def test_linear_wgrad_accumulate_and_reproducible(sste):
+    T, O, I = 4096, 128, 256
+    dW1, ref = _wgrad_case(sste, "bf16", T, O, I)
+    dW2, _ = _wgrad_case(sste, "bf16", T, O, I)
+    assert torch.equal(dW1, dW2)                                   # fixed-order split reduction
+    base = torch.full((O, I), 0.5, dtype=torch.float32, device="cuda")
+    dW3, _ = _wgrad_case(sste, "bf16", T, O, I, dW=base, accumulate=True)
+    assert rel_err(host(dW3).numpy().astype(np.float64), ref + 0.5) <= 1e-5
+    # a different seed gives a different estimate of the same dense gradient
+    dW4, ref4 = _wgrad_case(sste, "bf16", T, O, I, seed=4)
+    assert not torch.equal(dW1, dW4)
+    assert rel_err(host(dW4).numpy().astype(np.float64), ref4) <= 1e-4
+
+
+def test_linear_wgrad_strided_output_and_errors(sste):
+    T, O, I = 128, 16, 24
+    big = torch.zeros((O, 40), dtype=torch.float32, device="cuda")
+    dW, ref = _wgrad_case(sste, "bf16", T, O, I, dW=big[:, :I])
+    assert rel_err(host(big[:, :I]).numpy().astype(np.float64), ref) <= 1e-4
+    assert float(big[:, I:].abs().max()) == 0.0
+    dY = torch.zeros((100, 16), dtype=torch.bfloat16, device="cuda")
+    X = torch.zeros((100, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.linear_wgrad(dY, X, 0, 0)
+    assert ei.value.status == 7
+    dY = torch.zeros((102, 16), dtype=torch.bfloat16, device="cuda")
+    X = torch.zeros((102, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.linear_wgrad(dY, X, 0, 0)
+    assert ei.value.status == 2
