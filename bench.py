@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the S-STE 2:4 sparse linear-layer hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+  project + scale + pack of W  ->  forward sparse GEMM  ->  MVUE weight-gradient sparse GEMM.
+The default workload is the GPT-2-124M FFN fc1 layer (W 3072 x 768, 8192 tokens, bf16).
+Prints ONE JSON line.  `value` = dense-equivalent TFLOP/s of forward + weight gradient
+(2 * 2*T*I*O flops per step) over the whole step time, pruning included.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# published MI355X peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_DENSE_TFLOPS = {"bf16": 2500.0, "e4m3": 5000.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload number (1-5); 2 is the headline one")
+    ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
+    ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32):
+    """Times the oracle, as it stands, on one full step of the same workload (host cores)."""
+    import numpy as np
+    from oracle import linear as OL
+    from oracle import projection as OP
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    L = wl.layers[layer]
+    t0 = time.perf_counter()
+    if wl.dtype == "bf16":
+        rv, rm, _ = OP.project_pack(wb, beta32)
+        ws = np.float32(1.0)
+    else:
+        _, _, amax = OP.project_pack(wb, beta32)
+        ws = np.float32(float(amax) / 448.0)
+        rv, rm, _ = OP.project_pack(wb, beta32, "e4m3", ws)
+    t1 = time.perf_counter()
+    OL.linear_fwd(xc, rv, rm, wl.dtype, xs, ws)
+    t2 = time.perf_counter()
+    OL.linear_wgrad(dyc, xc, 0, 0, wl.dtype, dys, xs)
+    t3 = time.perf_counter()
+    flops = 2 * 2.0 * wl.T * L.I * L.O
+    return {
+        "value": flops / (t3 - t0) * 1e-12,
+        "unit": "TFLOP/s",
+        "cores": int(cores),
+        "kind": "oracle",
+        "sample": "one full step of the same workload (project+pack %.2fs, fwd %.2fs, MVUE+wgrad %.2fs)" % (t1 - t0, t2 - t1, t3 - t2),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2409_09099_amd as sste
+    from paper_2409_09099_amd import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    sste.library()
+
+    wl = WL.WORKLOADS[args.config]
+    L = wl.layers[args.layer]
+    T, O, I = wl.T, L.O, L.I
+    fp8 = wl.dtype == "e4m3"
+    dt = sste.F8E4M3 if fp8 else sste.BF16
+    esize = 1 if fp8 else 2
+
+    # ---- seeded synthetic inputs, generated on the host and made resident in HBM before timing
+    wb = WL.weight_bits(wl, args.layer)
+    xc, xs = WL.activations(wl, args.layer)
+    dyc, dys = WL.output_gradient(wl, args.layer)
+
+    def up(a):
+        t = torch.from_numpy(np.ascontiguousarray(a.view(np.int16) if a.dtype == np.uint16 else a)).cuda()
+        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+    W = up(wb)
+    nsets = max(1, args.sets)
+    Xs = [up(xc)] + [up(xc).clone() for _ in range(nsets - 1)]
+    dYs = [up(dyc)] + [up(dyc).clone() for _ in range(nsets - 1)]
+    Zs = [torch.empty((T, O), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+    dWs = [torch.empty((O, I), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    vals = torch.empty((O, I // 2), dtype=torch.uint8 if fp8 else torch.int16, device="cuda")
+    meta = torch.empty((O, I // 8), dtype=torch.uint8, device="cuda")
+    ws_bytes = sste.wgrad_workspace_bytes(T, O, I, dt)
+    wss = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+
+    # beta: computed once from the initial weights, then frozen (paper Sec. 4.2)
+    beta = float(sste.compute_beta(W).cpu()[0])
+    if fp8:
+        amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+        sste.project_pack(W, beta, sste.BF16, 1.0, amax_out=amax)
+        w_scale = float(amax.cpu()[0]) / 448.0
+    else:
+        w_scale = 1.0
+
+    def step(i):
+        s = i % nsets
+        sste.project_pack(W, beta, dt, w_scale, vals=vals, meta=meta)
+        sste.linear_fwd(Xs[s], vals, meta, dt, float(xs), w_scale, Z=Zs[s])
+        sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=dt, dy_scale=float(dys), x_scale=float(xs),
+                          dW=dWs[s], workspace=wss[s])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, every hot kernel bracketed by its own event pair
+    sste.timing_begin(8 * args.steps + 16)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kt = sste.timing_end()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_flops = 2.0 * T * I * O                 # dense-equivalent flops of one GEMM
+    value = 2 * gemm_flops / (ms_per_step * 1e-3) * 1e-12
+
+    def avg_ms(name):
+        ms, n = kt[name]
+        return ms / n if n else float("nan")
+
+    pp_bytes = O * I * (2 + esize / 2 + 0.125)   # algorithmic bytes: read W, write values + metadata
+    kernels = {
+        "project_pack": {"ms": avg_ms("project_pack"), "GB_per_s": pp_bytes / (avg_ms("project_pack") * 1e-3) * 1e-9,
+                         "frac_hbm_peak": pp_bytes / (avg_ms("project_pack") * 1e-3) * 1e-9 / PEAK_HBM_GBS},
+        "fwd": {"ms": avg_ms("fwd"), "dense_equiv_TFLOP_per_s": gemm_flops / (avg_ms("fwd") * 1e-3) * 1e-12},
+        "wgrad": {"ms": avg_ms("wgrad"), "dense_equiv_TFLOP_per_s": gemm_flops / (avg_ms("wgrad") * 1e-3) * 1e-12},
+        "wgrad_reduce": {"ms": avg_ms("wgrad_reduce")},
+    }
+    for k in ("fwd", "wgrad"):
+        kernels[k]["frac_sparse_mfma_peak"] = kernels[k]["dense_equiv_TFLOP_per_s"] / (2 * PEAK_DENSE_TFLOPS[wl.dtype])
+
+    # roofline of the dominant kernel.  The sparse MFMA executes half of the dense-equivalent
+    # multiply-adds: algorithmic flops per launch = T*I*O (I/2 MACs per output element), held against
+    # the published dense MFMA peak of the operand type.
+    dom = max(("project_pack", "fwd", "wgrad"), key=lambda k: kernels[k]["ms"])
+    if dom == "project_pack":
+        achieved = kernels[dom]["GB_per_s"]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    else:
+        achieved = 0.5 * gemm_flops / (kernels[dom]["ms"] * 1e-3) * 1e-12
+        peak = PEAK_DENSE_TFLOPS[wl.dtype]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                    "frac": achieved / peak, "traffic": None}
+    roofline["avg_launch_ms"] = kernels[dom]["ms"]
+
+    out = {
+        "metric": "S-STE 2:4 linear fwd+wgrad TFLOP/s (dense-equivalent, project+pack inside the step)",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype if fp8 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg%d %s layer %s (W %dx%d, %d tokens)" % (wl.cfg, wl.name, L.name, O, I, T),
+                   "buffer_sets": nsets, "wgrad_token_splits": (ws_bytes // (O * I * 4)) if ws_bytes else 1},
+        "frac_sparse_mfma_peak_whole_step": value / (2 * PEAK_DENSE_TFLOPS[wl.dtype]),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.layer, wb, xc, xs, dyc, dys, np.float32(beta))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

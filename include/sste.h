@@ -174,6 +174,24 @@ size_t sste_beta_workspace_bytes(int64_t O, int64_t I);
 int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I,
                     unsigned long long* count_out, void* hip_stream);
 
+/*
+ * Per-kernel timing for benchmarks.  Between sste_timing_begin and sste_timing_end every launch of a
+ * hot-path kernel is bracketed by its own pair of HIP events on the launch stream (events are host
+ * objects; no device memory is allocated).  sste_timing_end waits for the recorded events, adds up
+ * the elapsed milliseconds and the launch counts per kernel into arrays of SSTE_K_COUNT entries
+ * (either may be NULL) and releases the events.  At most `max_launches` launches are recorded; later
+ * ones run untimed.  Timing is process-wide; do not nest.
+ */
+typedef enum {
+  SSTE_K_PROJECT_PACK = 0,   /* projection + scale + pack */
+  SSTE_K_FWD = 1,            /* forward sparse GEMM */
+  SSTE_K_WGRAD = 2,          /* weight-gradient sparse GEMM with the fused estimator */
+  SSTE_K_WGRAD_REDUCE = 3,   /* fixed-order reduction of the token-axis splits */
+  SSTE_K_COUNT = 4
+} sste_kernel_id;
+int sste_timing_begin(int max_launches);
+int sste_timing_end(double* total_ms, int* launches);
+
 /* Message for the most recent non-OK status returned on the calling thread ("" if none). */
 const char* sste_last_error(void);
 

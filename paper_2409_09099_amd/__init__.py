@@ -17,5 +17,7 @@ from .binding import (  # noqa: F401
     linear_wgrad,
     mvue_materialize,
     project_pack,
+    timing_begin,
+    timing_end,
     wgrad_workspace_bytes,
 )

@@ -44,6 +44,10 @@ def library() -> ctypes.CDLL:
     lib.sste_beta_workspace_bytes.argtypes = [i64, i64]
     lib.sste_beta_workspace_bytes.restype = sz
     lib.sste_flip_count.argtypes = [vp, vp, i64, i64, vp, vp]
+    lib.sste_timing_begin.argtypes = [ci]
+    lib.sste_timing_begin.restype = ci
+    lib.sste_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    lib.sste_timing_end.restype = ci
     for name in ("sste_project_pack", "sste_linear_fwd", "sste_linear_wgrad", "sste_mvue_materialize",
                  "sste_compute_beta", "sste_flip_count"):
         getattr(lib, name).restype = ci
@@ -164,3 +168,19 @@ def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor) -> torch.Tensor:
     out = torch.empty(1, dtype=torch.int64, device=meta_a.device)
     _check(library().sste_flip_count(_ptr(meta_a), _ptr(meta_b), O, I8 * 8, _ptr(out), _stream(meta_a)))
     return out
+
+
+KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce")
+
+
+def timing_begin(max_launches: int = 4096) -> None:
+    """sste_timing_begin: bracket every following hot-path kernel launch with its own HIP event pair."""
+    _check(library().sste_timing_begin(max_launches))
+
+
+def timing_end():
+    """sste_timing_end: {kernel name: (total milliseconds, launches)} since timing_begin."""
+    ms = (ctypes.c_double * len(KERNEL_NAMES))()
+    n = (ctypes.c_int * len(KERNEL_NAMES))()
+    _check(library().sste_timing_end(ms, n))
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(KERNEL_NAMES)}

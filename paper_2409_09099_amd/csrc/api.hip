@@ -6,6 +6,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 namespace sste {
 
@@ -19,6 +21,21 @@ int fail(int status, const char* fmt, ...) {
   return status;
 }
 void clear_error() { g_err[0] = 0; }
+
+// ---- per-kernel timing --------------------------------------------------------------------------
+static std::mutex g_timing_mu;
+static bool g_timing_on = false;
+static std::vector<TimingSlot> g_slots;
+static std::vector<int> g_slot_kind;
+static size_t g_slots_used = 0;
+
+TimingSlot* timing_slot(int kind) {
+  if (!g_timing_on) return nullptr;
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  if (!g_timing_on || g_slots_used >= g_slots.size()) return nullptr;
+  g_slot_kind[g_slots_used] = kind;
+  return &g_slots[g_slots_used++];
+}
 
 static uint64_t mix64(uint64_t z) {
   z ^= z >> 30;
@@ -54,6 +71,57 @@ using namespace sste;
 extern "C" {
 
 int sste_version(void) { return 100; }
+
+int sste_timing_begin(int max_launches) {
+  clear_error();
+  if (max_launches <= 0 || max_launches > (1 << 20)) return fail(SSTE_ERR_VALUE, "timing_begin: max_launches out of range");
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  if (g_timing_on) return fail(SSTE_ERR_VALUE, "timing_begin: timing is already on");
+  g_slots.resize((size_t)max_launches);
+  g_slot_kind.assign((size_t)max_launches, -1);
+  for (size_t i = 0; i < g_slots.size(); i++) {
+    hipError_t e = hipEventCreate(&g_slots[i].start);
+    if (e == hipSuccess) e = hipEventCreate(&g_slots[i].stop);
+    if (e != hipSuccess) {
+      g_slots.resize(0);
+      return fail(SSTE_ERR_HIP, "timing_begin: hipEventCreate: %s", hipGetErrorString(e));
+    }
+  }
+  g_slots_used = 0;
+  g_timing_on = true;
+  return SSTE_OK;
+}
+
+int sste_timing_end(double* total_ms, int* launches) {
+  clear_error();
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  if (!g_timing_on) return fail(SSTE_ERR_VALUE, "timing_end: timing is not on");
+  g_timing_on = false;
+  for (int k = 0; k < SSTE_K_COUNT; k++) {
+    if (total_ms) total_ms[k] = 0.0;
+    if (launches) launches[k] = 0;
+  }
+  int status = SSTE_OK;
+  for (size_t i = 0; i < g_slots_used; i++) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(g_slots[i].stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_slots[i].start, g_slots[i].stop);
+    if (e != hipSuccess) { status = fail(SSTE_ERR_HIP, "timing_end: %s", hipGetErrorString(e)); break; }
+    int k = g_slot_kind[i];
+    if (k >= 0 && k < SSTE_K_COUNT) {
+      if (total_ms) total_ms[k] += (double)ms;
+      if (launches) launches[k] += 1;
+    }
+  }
+  for (size_t i = 0; i < g_slots.size(); i++) {
+    (void)hipEventDestroy(g_slots[i].start);
+    (void)hipEventDestroy(g_slots[i].stop);
+  }
+  g_slots.resize(0);
+  g_slot_kind.resize(0);
+  g_slots_used = 0;
+  return status;
+}
 
 const char* sste_last_error(void) { return g_err; }
 

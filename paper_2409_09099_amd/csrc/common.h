@@ -1,6 +1,7 @@
 // Shared host/device helpers for the S-STE sparse linear-layer kernels (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -11,6 +12,19 @@ namespace sste {
 // ---- host: status + thread-local message -----------------------------------------------------
 int fail(int status, const char* fmt, ...);   // records the message, returns `status`
 void clear_error();
+
+// ---- optional per-kernel timing (sste_timing_begin / sste_timing_end) ---------------------------
+// While timing is on, each launch of a hot-path kernel is bracketed by its own pair of HIP events on
+// the launch stream, so the time reported is that kernel's alone.
+struct TimingSlot { hipEvent_t start, stop; };
+TimingSlot* timing_slot(int kind);   // nullptr when timing is off or the event pool is used up
+
+#define SSTE_LAUNCH(kind, kernel, grid, block, stream, ...)                                           \
+  do {                                                                                                \
+    ::sste::TimingSlot* ts_ = ::sste::timing_slot(kind);                                              \
+    if (ts_) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ts_->start, ts_->stop, 0, __VA_ARGS__); \
+    else hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                             \
+  } while (0)
 
 // ---- vector types for MFMA operands -----------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;

@@ -50,45 +50,67 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
     for (int b = 0; b < 4; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   uint4 ra[2], rb[4], rm;
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-  auto load_global = [&](int step) {
+  // Rows past the end of the matrix are read from the last valid row (always mapped memory) and then
+  // zeroed, so the loads need no branch.
+  const uint8_t* pa[2];
+  bool oka[2];
 #pragma unroll
-    for (int r = 0; r < 2; r++) {
-      int c = tid + 256 * r, row = c >> 2, part = c & 3;
-      ra[r] = (o0 + row < O) ? *(const uint4*)(vals + (o0 + row) * vals_row_bytes + (int64_t)step * 64 + part * 16) : zero4;
-    }
-    rm = zero4;
-    if (tid < BM && o0 + tid < O) {
-      const uint8_t* p = meta + (o0 + tid) * meta_row_bytes + (int64_t)step * MB;
-      if (FP8) rm = *(const uint4*)p;
-      else { uint2 v = *(const uint2*)p; rm.x = v.x; rm.y = v.y; }
-    }
+  for (int r = 0; r < 2; r++) {
+    int c = tid + 256 * r, row = c >> 2, part = c & 3;
+    oka[r] = (o0 + row) < O;
+    int64_t rr = oka[r] ? (o0 + row) : (O - 1);
+    pa[r] = vals + rr * vals_row_bytes + part * 16;
+  }
+  const bool okm = (tid < BM) && (o0 + tid < O);
+  const uint8_t* pm = meta + (okm ? (o0 + tid) : (O - 1)) * meta_row_bytes;
+  const uint8_t* pb[4];
+  bool okb[4];
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int c = tid + 256 * r, row = c >> 3, part = c & 7;
-      rb[r] = (t0 + row < T) ? *(const uint4*)(X + (t0 + row) * ldx_bytes + (int64_t)step * 128 + part * 16) : zero4;
-    }
-  };
-  auto store_lds = [&]() {
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-      int c = tid + 256 * r, row = c >> 2, part = c & 3;
-      *(uint4*)(sA + row * A_STRIDE + part * 16) = ra[r];
-    }
-    if (tid < BM) *(uint4*)(sM + tid * M_STRIDE) = rm;
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      int c = tid + 256 * r, row = c >> 3, part = c & 7;
-      *(uint4*)(sB + row * B_STRIDE + part * 16) = rb[r];
-    }
-  };
+  for (int r = 0; r < 4; r++) {
+    int c = tid + 256 * r, row = c >> 3, part = c & 7;
+    okb[r] = (t0 + row) < T;
+    int64_t rr = okb[r] ? (t0 + row) : (T - 1);
+    pb[r] = X + rr * ldx_bytes + part * 16;
+  }
 
-  if (nsteps > 0) load_global(0);
+#define FWD_LOAD_GLOBAL(step)                                                        \
+  do {                                                                               \
+    _Pragma("unroll") for (int r = 0; r < 2; r++) {                                  \
+      uint4 v = *(const uint4*)(pa[r] + (int64_t)(step) * 64);                       \
+      ra[r] = oka[r] ? v : make_uint4(0, 0, 0, 0);                                   \
+    }                                                                                \
+    if (FP8) {                                                                       \
+      uint4 v = *(const uint4*)(pm + (int64_t)(step) * 16);                          \
+      rm = okm ? v : make_uint4(0, 0, 0, 0);                                         \
+    } else {                                                                         \
+      uint2 v = *(const uint2*)(pm + (int64_t)(step) * 8);                           \
+      rm = okm ? make_uint4(v.x, v.y, 0, 0) : make_uint4(0, 0, 0, 0);                \
+    }                                                                                \
+    _Pragma("unroll") for (int r = 0; r < 4; r++) {                                  \
+      uint4 v = *(const uint4*)(pb[r] + (int64_t)(step) * 128);                      \
+      rb[r] = okb[r] ? v : make_uint4(0, 0, 0, 0);                                   \
+    }                                                                                \
+  } while (0)
+
+#define FWD_STORE_LDS()                                                              \
+  do {                                                                               \
+    _Pragma("unroll") for (int r = 0; r < 2; r++) {                                  \
+      int c = tid + 256 * r, row = c >> 2, part = c & 3;                             \
+      *(uint4*)(sA + row * A_STRIDE + part * 16) = ra[r];                            \
+    }                                                                                \
+    if (tid < BM) *(uint4*)(sM + tid * M_STRIDE) = rm;                               \
+    _Pragma("unroll") for (int r = 0; r < 4; r++) {                                  \
+      int c = tid + 256 * r, row = c >> 3, part = c & 7;                             \
+      *(uint4*)(sB + row * B_STRIDE + part * 16) = rb[r];                            \
+    }                                                                                \
+  } while (0)
+
+  if (nsteps > 0) FWD_LOAD_GLOBAL(0);
   for (int step = 0; step < nsteps; step++) {
-    store_lds();
+    FWD_STORE_LDS();
     __syncthreads();
-    if (step + 1 < nsteps) load_global(step + 1);
+    if (step + 1 < nsteps) FWD_LOAD_GLOBAL(step + 1);
 
     uint4 fa[4];
     int fidx[4];
@@ -127,6 +149,9 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
     __syncthreads();
   }
 
+#undef FWD_LOAD_GLOBAL
+#undef FWD_STORE_LDS
+
   // epilogue: lane (j, q) register r of tile (mi, ni) is Z[t][o + r], four consecutive channels
 #pragma unroll
   for (int mi = 0; mi < 4; mi++)
@@ -148,10 +173,10 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   if (T == 0 || O == 0) return hipSuccess;
   dim3 grid((unsigned)((O + BM - 1) / BM), (unsigned)((T + BN - 1) / BN)), block(256);
   if (dtype == SSTE_F8E4M3)
-    hipLaunchKernelGGL((k_linear_fwd<true>), grid, block, 0, s, (const uint8_t*)X, T, I, ldx, (const uint8_t*)vals,
+    SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<true>), grid, block, s, (const uint8_t*)X, T, I, ldx, (const uint8_t*)vals,
                        (const uint8_t*)meta, I / 8, O, scale, (uint16_t*)Z, ldz);
   else
-    hipLaunchKernelGGL((k_linear_fwd<false>), grid, block, 0, s, (const uint8_t*)X, T, I * 2, ldx * 2,
+    SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<false>), grid, block, s, (const uint8_t*)X, T, I * 2, ldx * 2,
                        (const uint8_t*)vals, (const uint8_t*)meta, I / 8, O, scale, (uint16_t*)Z, ldz);
   return hipGetLastError();
 }

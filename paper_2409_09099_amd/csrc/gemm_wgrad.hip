@@ -25,6 +25,9 @@ constexpr int WG_TARGET = 512;   // workgroups wanted in flight (2 per CU)
 constexpr int MAX_SPLITS = 16;
 constexpr int MIN_STEPS_PER_SPLIT = 8;
 
+// component c (compile-time after unrolling) of a uint4
+__device__ __forceinline__ uint32_t comp(const uint4& v, int c) { return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w)); }
+
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
 }  // namespace
@@ -67,63 +70,71 @@ k_linear_wgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   constexpr int XPR = BN * EB / 16;                  // chunks per row: 16 / 8
 
   uint4 rdy[4], rx[XCHUNKS];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-  auto load_global = [&](int64_t step) {
-    int64_t tb = step * BK;
-    bool ok = (o0 + (int64_t)oc * CH) < O;
+  // Columns past the end of the matrix are read from column chunk 0 (always mapped) and then zeroed,
+  // so the loads need no branch.
+  const bool okdy = (o0 + (int64_t)oc * CH) < O;
+  const uint8_t* pdy = dY + (int64_t)(4 * kg) * lddy_bytes + (okdy ? (o0 + (int64_t)oc * CH) : 0) * EB;
+  const uint8_t* px[XCHUNKS];
+  bool okx[XCHUNKS];
 #pragma unroll
-    for (int r = 0; r < 4; r++)
-      rdy[r] = ok ? *(const uint4*)(dY + (tb + 4 * kg + r) * lddy_bytes + (o0 + (int64_t)oc * CH) * EB) : zero4;
-#pragma unroll
-    for (int r = 0; r < XCHUNKS; r++) {
-      int c = tid + 256 * r, row = c / XPR, part = c % XPR;
-      bool okx = (i0 + (int64_t)part * CH) < I;
-      rx[r] = okx ? *(const uint4*)(X + (tb + row) * ldx_bytes + (i0 + (int64_t)part * CH) * EB) : zero4;
-    }
-  };
+  for (int r = 0; r < XCHUNKS; r++) {
+    int c = tid + 256 * r, row = c / XPR, part = c % XPR;
+    okx[r] = (i0 + (int64_t)part * CH) < I;
+    px[r] = X + (int64_t)row * ldx_bytes + (okx[r] ? (i0 + (int64_t)part * CH) : 0) * EB;
+  }
 
-  auto sparsify_and_store = [&](int64_t step) {
-    const uint32_t* r0 = (const uint32_t*)&rdy[0];
-    const uint32_t* r1 = (const uint32_t*)&rdy[1];
-    const uint32_t* r2 = (const uint32_t*)&rdy[2];
-    const uint32_t* r3 = (const uint32_t*)&rdy[3];
-    uint64_t gid_base = (uint64_t)(step * GROUPS + kg) * (uint64_t)O + (uint64_t)(o0 + (int64_t)oc * CH);
-#pragma unroll
-    for (int e = 0; e < CH; e++) {
-      uint64_t gid = gid_base + e;
-      uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));
-      uint32_t nib, v;
-      int row = oc * CH + e;
-      if (FP8) {
-        // byte e of each of the four token rows -> one dword, token 0 in byte 0
-        uint32_t w0 = r0[e >> 2], w1 = r1[e >> 2], w2 = r2[e >> 2], w3 = r3[e >> 2];
-        int sh = 8 * (e & 3);
-        uint32_t g = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24);
-        v = mvue_group_e4m3(g, x, nib);
-        *(uint16_t*)(sA + row * A_STRIDE + 2 * kg) = (uint16_t)v;
-      } else {
-        uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        uint32_t lo = __builtin_amdgcn_perm(r1[e >> 1], r0[e >> 1], sel);
-        uint32_t hi = __builtin_amdgcn_perm(r3[e >> 1], r2[e >> 1], sel);
-        v = mvue_group_bf16(lo, hi, x, nib);
-        *(uint32_t*)(sA + row * A_STRIDE + 4 * kg) = v;
-      }
-      // nibble pre-shifted to its place inside the byte pair: consumers OR neighbouring bytes
-      sM[row * MB_STRIDE + kg] = (uint8_t)(nib << (4 * (kg & 1)));
-    }
-#pragma unroll
-    for (int r = 0; r < XCHUNKS; r++) {
-      int c = tid + 256 * r, row = c / XPR, part = c % XPR;
-      *(uint4*)(sB + row * B_STRIDE + part * 16) = rx[r];
-    }
-  };
+#define WG_LOAD_GLOBAL(step)                                                                  \
+  do {                                                                                        \
+    int64_t tb_ = (int64_t)(step) * BK;                                                       \
+    _Pragma("unroll") for (int r = 0; r < 4; r++) {                                           \
+      uint4 v = *(const uint4*)(pdy + (tb_ + r) * lddy_bytes);                                \
+      rdy[r] = okdy ? v : make_uint4(0, 0, 0, 0);                                             \
+    }                                                                                         \
+    _Pragma("unroll") for (int r = 0; r < XCHUNKS; r++) {                                     \
+      uint4 v = *(const uint4*)(px[r] + tb_ * ldx_bytes);                                     \
+      rx[r] = okx[r] ? v : make_uint4(0, 0, 0, 0);                                            \
+    }                                                                                         \
+  } while (0)
 
-  if (step_begin < step_end) load_global(step_begin);
+  // The estimator on the lane's CH groups (tokens 4 kg .. 4 kg + 3 of CH channels), written to LDS in
+  // the layout the sparse MFMA reads, then the X tile.
+#define WG_SPARSIFY_AND_STORE(step)                                                           \
+  do {                                                                                        \
+    uint64_t gid_base = (uint64_t)((int64_t)(step) * GROUPS + kg) * (uint64_t)O + (uint64_t)(o0 + (int64_t)oc * CH); \
+    _Pragma("unroll") for (int e = 0; e < CH; e++) {                                          \
+      uint64_t gid = gid_base + e;                                                            \
+      uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));            \
+      uint32_t nib, v;                                                                        \
+      int row = oc * CH + e;                                                                  \
+      if (FP8) {                                                                              \
+        uint32_t w0 = comp(rdy[0], e >> 2), w1 = comp(rdy[1], e >> 2);                        \
+        uint32_t w2 = comp(rdy[2], e >> 2), w3 = comp(rdy[3], e >> 2);                        \
+        int sh = 8 * (e & 3);                                                                 \
+        uint32_t g = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24); \
+        v = mvue_group_e4m3(g, x, nib);                                                       \
+        *(uint16_t*)(sA + row * A_STRIDE + 2 * kg) = (uint16_t)v;                             \
+      } else {                                                                                \
+        uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;                                   \
+        uint32_t lo = __builtin_amdgcn_perm(comp(rdy[1], e >> 1), comp(rdy[0], e >> 1), sel); \
+        uint32_t hi = __builtin_amdgcn_perm(comp(rdy[3], e >> 1), comp(rdy[2], e >> 1), sel); \
+        v = mvue_group_bf16(lo, hi, x, nib);                                                  \
+        *(uint32_t*)(sA + row * A_STRIDE + 4 * kg) = v;                                       \
+      }                                                                                       \
+      /* nibble pre-shifted to its place inside the byte pair: consumers OR neighbouring bytes */ \
+      sM[row * MB_STRIDE + kg] = (uint8_t)(nib << (4 * (kg & 1)));                            \
+    }                                                                                         \
+    _Pragma("unroll") for (int r = 0; r < XCHUNKS; r++) {                                     \
+      int c = tid + 256 * r, row = c / XPR, part = c % XPR;                                   \
+      *(uint4*)(sB + row * B_STRIDE + part * 16) = rx[r];                                     \
+    }                                                                                         \
+  } while (0)
+
+  if (step_begin < step_end) WG_LOAD_GLOBAL(step_begin);
   for (int64_t step = step_begin; step < step_end; step++) {
-    sparsify_and_store(step);
+    WG_SPARSIFY_AND_STORE(step);
     __syncthreads();
-    if (step + 1 < step_end) load_global(step + 1);
+    if (step + 1 < step_end) WG_LOAD_GLOBAL(step + 1);
 
     uint4 fa[4];
     int fidx[4];
@@ -184,6 +195,9 @@ k_linear_wgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
     }
     __syncthreads();
   }
+
+#undef WG_LOAD_GLOBAL
+#undef WG_SPARSIFY_AND_STORE
 
   // epilogue: lane (j, q) register r of tile (mi, ni) is element (o + r, i)
   float* dst = out + (int64_t)blockIdx.z * split_stride;
@@ -271,15 +285,15 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
   float k_scale = splits > 1 ? 1.0f : scale;
   int k_acc = splits > 1 ? 0 : accumulate;
   if (fp8)
-    hipLaunchKernelGGL((k_linear_wgrad<true>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
+    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad<true>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
                        ldx * eb, key, sps, k_scale, k_acc, out, ld_out, split_stride);
   else
-    hipLaunchKernelGGL((k_linear_wgrad<false>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
+    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad<false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
                        ldx * eb, key, sps, k_scale, k_acc, out, ld_out, split_stride);
   if (splits > 1) {
     int64_t blocks = (O * (I / 4) + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)ws, splits, O, I, scale,
+    SSTE_LAUNCH(SSTE_K_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)blocks), dim3(256), s, (const float*)ws, splits, O, I, scale,
                        accumulate, dW, lddw);
   }
   return hipGetLastError();

@@ -96,13 +96,13 @@ hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw,
   uint32_t* ab = (uint32_t*)amax_out;
   bool fp8 = val_dtype == SSTE_F8E4M3;
   if (fp8 && amax_out)
-    hipLaunchKernelGGL((k_project_pack<true, true>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, true>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
   else if (fp8)
-    hipLaunchKernelGGL((k_project_pack<true, false>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, false>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
   else if (amax_out)
-    hipLaunchKernelGGL((k_project_pack<false, true>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
   else
-    hipLaunchKernelGGL((k_project_pack<false, false>), grid, block, 0, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
   return hipGetLastError();
 }
 
