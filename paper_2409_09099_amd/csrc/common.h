@@ -80,6 +80,22 @@ __device__ __forceinline__ uint32_t e4m3_rne_pack(float lo, float hi) {
 }
 __device__ __forceinline__ float clamp448(float x) { return __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f); }
 
+// ---- buffer-descriptor loads ---------------------------------------------------------------------
+// A raw buffer descriptor over [base, base + bytes): loads whose offset falls outside return zeros,
+// which replaces per-lane bounds branches at tile edges.  Offsets are 32-bit.
+typedef __amdgpu_buffer_rsrc_t BufferRsrc;
+__device__ __forceinline__ BufferRsrc make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load_b128(BufferRsrc r, uint32_t voffset, uint32_t soffset) {
+  i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voffset, (int)soffset, 0);
+  return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+}
+__device__ __forceinline__ uint2 buffer_load_b64(BufferRsrc r, uint32_t voffset, uint32_t soffset) {
+  i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voffset, (int)soffset, 0);
+  return make_uint2((uint32_t)v[0], (uint32_t)v[1]);
+}
+
 // ---- host-side launch entry points implemented in the .hip files --------------------------------
 struct RngKey { uint32_t k0, k1; };
 RngKey derive_key(uint64_t seed, uint64_t offset);
