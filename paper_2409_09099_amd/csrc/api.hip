@@ -160,6 +160,7 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
   if (!empty && (!Z || (I > 0 && (!X || !vals || !meta)))) return fail(SSTE_ERR_NULL, "linear_fwd: NULL X, vals, meta or Z");
   if (!aligned16(X) || !aligned16(vals) || !aligned16(meta) || !aligned16(Z))
     return fail(SSTE_ERR_ALIGN, "linear_fwd: X, vals, meta and Z must be 16-byte aligned");
+  if (!linear_fwd_supported(T, I, ldx, O, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: a tile of this problem does not fit 32-bit offsets");
   float scale = x_scale * w_scale;
   return hip_status(launch_linear_fwd(X, T, I, ldx, dtype, scale, vals, meta, O, Z, ldz, (hipStream_t)hip_stream), "linear_fwd launch");
 }

@@ -110,6 +110,7 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
                                    void* vals, void* meta, hipStream_t s);
 hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
                              const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s);
+bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
 int wgrad_splits(int64_t T, int64_t O, int64_t I, int dtype);
 hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
                                int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,

@@ -11,12 +11,23 @@
 //   D: lane (j, q) register r holds element (row 4 q + r, col j).
 // In bytes a k-step is the same for both types: 64 B of values + 128 B of X per row.
 //
-// Tiling: a workgroup of 4 waves (2 x 2) computes BM (o) x BN (t); each wave owns MI x NI MFMA tiles.
-// The large shape is 256 x 128 (wave 128 x 64): per sparse MFMA the wave then reads about 540 B from
-// LDS, which keeps the four SIMDs inside the measured LDS read rate (about 220 B/clk per CU for
-// 16-byte reads).  Operands are staged through LDS with a register prefetch of the next k-step.
-// LDS rows are padded to an odd multiple of 32 bytes (96 B for values, 160 B for X): measured
-// conflict-free for the fragment reads (16 rows x 4 adjacent 16-byte pieces per instruction).
+// Tiling: WM x WN waves, each owning 8 x 4 MFMA tiles (128 channels x 64 tokens): per sparse MFMA a
+// wave reads about 540 B of fragments from LDS, inside the measured LDS read rate of the CU.
+// Two shapes are built: 256 x 256 with 8 waves and a 3-stage ring (one workgroup per CU), and
+// 256 x 128 with 4 waves and a 2-stage ring (two workgroups per CU) for problems with few tiles.
+// Operand tiles travel L2 -> LDS directly (buffer_load ... lds, no staging registers) into a ring of
+// NS stages; the loads for k-step s + NS - 1 are issued once the fragments of k-step s have been
+// read.  The vector-memory path of a CU moves 64 B/clk, so a 256 x 256 tile (50 KiB per k-step
+// against 64 sparse MFMAs per SIMD) leaves it about 40 % idle, a 256 x 128 tile almost none.
+// Because the hardware writes the 64 lanes of such a load to consecutive LDS addresses, bank
+// conflicts are avoided by choosing WHICH 16-byte piece each lane fetches: piece c of row r is stored
+// at position c ^ f(r), f(r) = (r / 4) % 4 for the values and (r / 2) % 8 for X, which makes every
+// fragment read (16 rows x one piece) hit 16 different 16-byte bank groups.
+// The loads are written in inline assembly: the compiler otherwise orders every later LDS read
+// behind ALL outstanding LDS-writing loads, which would drain the ring each k-step.  Their
+// completion is tracked by hand with s_waitcnt vmcnt(n) + a workgroup barrier.
+// The epilogue transposes the accumulators through LDS so that each lane stores 16 contiguous bytes
+// and each wave writes whole 256-byte rows of Z.
 // Workgroups are numbered so that each XCD (the chip routes consecutive workgroup ids to its 8 XCDs
 // in turn) works on a contiguous range of tiles, o-tiles fastest: the packed weight stays in that
 // XCD's L2 and an X tile is fetched from HBM once per XCD.
@@ -25,23 +36,59 @@
 namespace sste {
 
 namespace {
-constexpr int A_STRIDE = 96;    // 64 B of packed values + 32 B pad
-constexpr int B_STRIDE = 160;   // 128 B of X + 32 B pad
-constexpr int M_STRIDE = 16;    // metadata bytes per row and k-step: 8 (bf16) or 16 (fp8)
+constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 tokens
+constexpr int EPI_ROW = 272;                      // 128 channels x 2 B + 16 B pad
 constexpr int NUM_XCD = 8;
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+
+// s_waitcnt that constrains only the vector-memory counter (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14; expcnt and lgkmcnt fields left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0F70 | ((N >> 4) << 14));
+}
+
+// 64 lanes x 16 B (or 4 B) from a buffer descriptor straight into LDS at lds_addr + lane * 16 (4)
+__device__ __forceinline__ void dma_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
+}
+__device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
+}
+__device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
+  uint64_t p = (uint64_t)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xFFFFu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
 }  // namespace
 
-template <bool FP8, int MI, int NI>
-__global__ void __launch_bounds__(256, 2)
+template <bool FP8, int WM, int WN, int NS>
+__global__ void __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && NS <= 2) ? 2 : 1)
 k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
              const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t meta_row_bytes,
              int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
-  constexpr int BM = 32 * MI, BN = 32 * NI;      // 2 x 2 waves of MI x NI tiles of 16 x 16
-  constexpr int ACH = BM * 4 / 256;              // 16-byte chunks of packed values per lane and k-step
-  constexpr int BCH = BN * 8 / 256;              // 16-byte chunks of X per lane and k-step
-  __shared__ __align__(16) uint8_t sA[BM * A_STRIDE];
-  __shared__ __align__(16) uint8_t sM[BM * M_STRIDE];
-  __shared__ __align__(16) uint8_t sB[BN * B_STRIDE];
+  constexpr int NW = WM * WN;
+  constexpr int BM = 128 * WM, BN = 64 * WN;
+  constexpr int MB = FP8 ? 16 : 8;                // position bytes per row and k-step
+  constexpr int A_BYTES = BM * 64, B_BYTES = BN * 128, M_BYTES = BM * MB;
+  constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
+  constexpr int EPI_BYTES = NW * 64 * EPI_ROW;
+  constexpr int SMEM = NS * STAGE > EPI_BYTES ? NS * STAGE : EPI_BYTES;
+  constexpr int LA = BM / 16 / NW, LB = BN / 8 / NW, LM = M_BYTES / 256 / NW;   // loads per wave and stage
+  constexpr int LPW = LA + LB + LM;
+  static_assert(LA >= 1 && LB >= 1 && LM >= 1, "tile too small for this many waves");
+  __shared__ __align__(1024) uint8_t smem[SMEM];
 
   // XCD-aware tile order: XCD x owns a contiguous range of logical tiles
   const int bid = blockIdx.x, nblk = gridDim.x;
@@ -51,12 +98,55 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
                                               : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
   const int tm = logical % m_tiles, tn = logical / m_tiles;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
   const int j = lane & 15, q = lane >> 4;
   const int64_t o0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
   const int nsteps = (int)(k_bytes / 128);
   const int64_t vals_row_bytes = k_bytes / 2;
+
+  // buffer descriptors over exactly the valid rows of this tile: rows past the end read as zeros
+  const int rows_a = (int)((O - o0) < BM ? (O - o0) : BM), rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
+  const i32x4 ba = rsrc_words(vals + o0 * vals_row_bytes, (uint32_t)(rows_a * vals_row_bytes));
+  const i32x4 bm = rsrc_words(meta + o0 * meta_row_bytes, (uint32_t)(rows_a * meta_row_bytes));
+  const i32x4 bb = rsrc_words(X + t0 * ldx_bytes, (uint32_t)((rows_b - 1) * ldx_bytes + k_bytes));
+
+  // per-lane source offsets of the direct-to-LDS loads (destination = stage base + load index * 1 KiB
+  // (256 B for the position bits) + lane * 16 (4), fixed by the hardware)
+  uint32_t offa[LA], offb[LB], offm[LM];
+#pragma unroll
+  for (int i = 0; i < LA; i++) {
+    int wl = LA * wave + i;
+    int r = 16 * wl + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
+    offa[i] = (uint32_t)(r * vals_row_bytes + c * 16);
+  }
+#pragma unroll
+  for (int i = 0; i < LB; i++) {
+    int wl = LB * wave + i;
+    int r = 8 * wl + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
+    offb[i] = (uint32_t)(r * ldx_bytes + c * 16);
+  }
+#pragma unroll
+  for (int i = 0; i < LM; i++) {
+    int d = 64 * (LM * wave + i) + lane;          // dword index inside the stage's position bits
+    offm[i] = (uint32_t)((d / (MB / 4)) * meta_row_bytes + 4 * (d % (MB / 4)));
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
+
+  // loads of k-step `step` into ring slot `stg`; past the last k-step the scalar offset is pushed out
+  // of range so that the same number of loads is always in flight (they fetch nothing)
+#define FWD_ISSUE(step, stg)                                                                           \
+  do {                                                                                                 \
+    const bool live_ = (step) < nsteps;                                                                \
+    const uint32_t sa_ = live_ ? (uint32_t)(step) * 64u : 0x40000000u;                                 \
+    const uint32_t sb_ = live_ ? (uint32_t)(step) * 128u : 0x40000000u;                                \
+    const uint32_t sm_ = live_ ? (uint32_t)(step) * (uint32_t)MB : 0x40000000u;                        \
+    const uint32_t base_ = lds0 + (uint32_t)(stg) * STAGE;                                             \
+    _Pragma("unroll") for (int i = 0; i < LA; i++) dma_b128(ba, base_ + (LA * wave + i) * 1024, offa[i], sa_); \
+    _Pragma("unroll") for (int i = 0; i < LB; i++) dma_b128(bb, base_ + A_BYTES + (LB * wave + i) * 1024, offb[i], sb_); \
+    _Pragma("unroll") for (int i = 0; i < LM; i++) dma_b32(bm, base_ + A_BYTES + B_BYTES + (LM * wave + i) * 256, offm[i], sm_); \
+  } while (0)
 
   f32x4 acc[MI][NI];
 #pragma unroll
@@ -64,131 +154,119 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 #pragma unroll
     for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  uint4 ra[ACH], rb[BCH], rm;
+  // per-lane fragment addresses inside a stage
+  const int ra0 = 128 * wm + j;                                          // + 16 mi
+  const uint32_t fa_off = (uint32_t)(ra0 * 64 + ((q ^ ((j >> 2) & 3)) * 16));
+  const uint32_t fm_off = (uint32_t)(A_BYTES + B_BYTES + ra0 * MB + (MB / 4) * q);
+  const int rb0 = 64 * wn + j;                                           // + 16 ni
+  const int cb0 = q ^ ((j >> 1) & 7);
+  const uint32_t fb_off0 = (uint32_t)(A_BYTES + rb0 * 128 + cb0 * 16);
+  const uint32_t fb_off1 = (uint32_t)(A_BYTES + rb0 * 128 + (cb0 ^ 4) * 16);
 
-  // Operand tiles are read through buffer descriptors that cover exactly the valid rows of this
-  // tile: rows past the end of the matrix come back as zeros without a branch.
-  const int rows_a = (int)((O - o0) < BM ? (O - o0) : BM), rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
-  const BufferRsrc ba = make_rsrc(vals + o0 * vals_row_bytes, (uint32_t)(rows_a * vals_row_bytes));
-  const BufferRsrc bm = make_rsrc(meta + o0 * meta_row_bytes, (uint32_t)(rows_a * meta_row_bytes));
-  const BufferRsrc bb = make_rsrc(X + t0 * ldx_bytes, (uint32_t)((rows_b - 1) * ldx_bytes + k_bytes));
-  uint32_t offa[ACH], offb[BCH];
 #pragma unroll
-  for (int r = 0; r < ACH; r++) {
-    int c = tid + 256 * r, row = c >> 2, part = c & 3;
-    offa[r] = (uint32_t)(row * vals_row_bytes + part * 16);
-  }
-  // lanes that own no metadata row point past the end of the descriptor
-  const uint32_t offm = (tid < BM) ? (uint32_t)(tid * meta_row_bytes) : 0x7FFFFF00u;
-#pragma unroll
-  for (int r = 0; r < BCH; r++) {
-    int c = tid + 256 * r, row = c >> 3, part = c & 7;
-    offb[r] = (uint32_t)(row * ldx_bytes + part * 16);
-  }
+  for (int s = 0; s < NS - 1; s++) FWD_ISSUE(s, s);
 
-#define FWD_LOAD_GLOBAL(step)                                                        \
-  do {                                                                               \
-    _Pragma("unroll") for (int r = 0; r < ACH; r++) ra[r] = buffer_load_b128(ba, offa[r], (step) * 64); \
-    if (FP8) rm = buffer_load_b128(bm, offm, (step) * 16);                           \
-    else { uint2 v = buffer_load_b64(bm, offm, (step) * 8); rm = make_uint4(v.x, v.y, 0, 0); } \
-    _Pragma("unroll") for (int r = 0; r < BCH; r++) rb[r] = buffer_load_b128(bb, offb[r], (step) * 128); \
-  } while (0)
-
-#define FWD_STORE_LDS()                                                              \
-  do {                                                                               \
-    _Pragma("unroll") for (int r = 0; r < ACH; r++) {                                \
-      int c = tid + 256 * r, row = c >> 2, part = c & 3;                             \
-      *(uint4*)(sA + row * A_STRIDE + part * 16) = ra[r];                            \
-    }                                                                                \
-    if (tid < BM) *(uint4*)(sM + tid * M_STRIDE) = rm;                               \
-    _Pragma("unroll") for (int r = 0; r < BCH; r++) {                                \
-      int c = tid + 256 * r, row = c >> 3, part = c & 7;                             \
-      *(uint4*)(sB + row * B_STRIDE + part * 16) = rb[r];                            \
-    }                                                                                \
-  } while (0)
-
-  if (nsteps > 0) FWD_LOAD_GLOBAL(0);
+  int stg = 0;
   for (int step = 0; step < nsteps; step++) {
-    FWD_STORE_LDS();
-    __syncthreads();
-    if (step + 1 < nsteps) FWD_LOAD_GLOBAL(step + 1);
-
+    wait_vmcnt<(NS - 2) * LPW>();        // this wave's share of k-step `step` has landed in LDS
+    __syncthreads();                     // ... and everybody else's; slot (step - 1) % NS is free again
+    const uint8_t* sb = smem + stg * STAGE;
     uint4 fb[NI][2];
 #pragma unroll
     for (int ni = 0; ni < NI; ni++) {
-      int row = (16 * NI) * wn + 16 * ni + j;
-      fb[ni][0] = *(const uint4*)(sB + row * B_STRIDE + 16 * q);
-      fb[ni][1] = *(const uint4*)(sB + row * B_STRIDE + 64 + 16 * q);
+      fb[ni][0] = *(const uint4*)(sb + fb_off0 + ni * 2048);
+      fb[ni][1] = *(const uint4*)(sb + fb_off1 + ni * 2048);
+    }
+    uint4 fa[MI];
+    int fidx[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++) {
+      fa[mi] = *(const uint4*)(sb + fa_off + mi * 1024);
+      if (FP8) fidx[mi] = *(const int*)(sb + fm_off + mi * 256);
+      else fidx[mi] = *(const uint16_t*)(sb + fm_off + mi * 128);
+    }
+    {
+      int nstg = stg + NS - 1;
+      if (nstg >= NS) nstg -= NS;
+      FWD_ISSUE(step + NS - 1, nstg);
     }
 #pragma unroll
     for (int mi = 0; mi < MI; mi++) {
-      int row = (16 * MI) * wm + 16 * mi + j;
-      uint4 fa = *(const uint4*)(sA + row * A_STRIDE + 16 * q);
-      int fidx;
-      if (FP8) fidx = *(const int*)(sM + row * M_STRIDE + 4 * q);
-      else fidx = *(const uint16_t*)(sM + row * M_STRIDE + 2 * q);
 #pragma unroll
       for (int ni = 0; ni < NI; ni++) {
         if (FP8) {
           i32x4 av;
           i32x8 bv;
-          __builtin_memcpy(&av, &fa, 16);
+          __builtin_memcpy(&av, &fa[mi], 16);
           __builtin_memcpy(&bv, &fb[ni][0], 32);
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
         } else {
           bf16x8 av;
           bf16x16 bv;
-          __builtin_memcpy(&av, &fa, 16);
+          __builtin_memcpy(&av, &fa[mi], 16);
           __builtin_memcpy(&bv, &fb[ni][0], 32);
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx[mi], 0, 0);
         }
       }
     }
-    __syncthreads();
+    stg = (stg + 1 == NS) ? 0 : stg + 1;
   }
-#undef FWD_LOAD_GLOBAL
-#undef FWD_STORE_LDS
+#undef FWD_ISSUE
 
-  // epilogue: lane (j, q) register r of tile (mi, ni) is Z[t][o + r], four consecutive channels
+  // epilogue: accumulators -> LDS (row = token, the wave's 128 channels contiguous) -> 16-byte stores
+  wait_vmcnt<0>();
+  __syncthreads();
+  uint8_t* eb = smem + wave * (64 * EPI_ROW);
 #pragma unroll
   for (int mi = 0; mi < MI; mi++)
 #pragma unroll
     for (int ni = 0; ni < NI; ni++) {
-      int64_t o = o0 + (16 * MI) * wm + 16 * mi + 4 * q;
-      int64_t t = t0 + (16 * NI) * wn + 16 * ni + j;
-      if (t < T && o < O) {
-        uint2 v;
-        v.x = bf16_rne_pack(acc[mi][ni][0] * scale, acc[mi][ni][1] * scale);
-        v.y = bf16_rne_pack(acc[mi][ni][2] * scale, acc[mi][ni][3] * scale);
-        *(uint2*)(Z + t * ldz + o) = v;
-      }
+      uint2 v;
+      v.x = bf16_rne_pack(acc[mi][ni][0] * scale, acc[mi][ni][1] * scale);
+      v.y = bf16_rne_pack(acc[mi][ni][2] * scale, acc[mi][ni][3] * scale);
+      *(uint2*)(eb + (16 * ni + j) * EPI_ROW + (16 * mi + 4 * q) * 2) = v;
     }
+  // same-wave LDS accesses are ordered; no barrier needed for a wave-private region
+#pragma unroll
+  for (int it = 0; it < 16; it++) {
+    int row = 4 * it + (lane >> 4), chunk = lane & 15;
+    uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
+    int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 8 * chunk;
+    if (t < T && o < O) *(uint4*)(Z + t * ldz + o) = v;
+  }
 }
 
-template <bool FP8, int MI, int NI>
+template <bool FP8, int WM, int WN, int NS>
 static void launch_fwd_cfg(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
                            const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
-  constexpr int BM = 32 * MI, BN = 32 * NI;
+  constexpr int BM = 128 * WM, BN = 64 * WN;
   int m_tiles = (int)((O + BM - 1) / BM), n_tiles = (int)((T + BN - 1) / BN);
-  dim3 grid((unsigned)(m_tiles * n_tiles)), block(256);
+  dim3 grid((unsigned)(m_tiles * n_tiles)), block(64 * WM * WN);
   int64_t eb = FP8 ? 1 : 2;
-  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<FP8, MI, NI>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<FP8, WM, WN, NS>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
               (const uint8_t*)vals, (const uint8_t*)meta, I / 8, O, scale, (uint16_t*)Z, ldz, m_tiles);
+}
+
+bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype) {
+  int64_t eb = dtype == SSTE_F8E4M3 ? 1 : 2;
+  // 32-bit offsets inside a tile, 32-bit tile count
+  if (256 * ldx * eb >= (1ll << 30) || 256 * I * eb >= (1ll << 30)) return false;
+  if (((O + 255) / 256) * ((T + 127) / 128) > 0x7FFFFFFFll) return false;
+  return true;
 }
 
 hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
                              const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
   if (T == 0 || O == 0) return hipSuccess;
-  if (((O + 127) / 128) * ((T + 127) / 128) > 0x7FFFFFFFll) return hipErrorInvalidValue;
-  // large problems use the 256 x 128 tile; small ones keep 128 x 128 so that more workgroups exist
-  bool big = ((O + 255) / 256) * ((T + 127) / 128) >= 512;
   bool fp8 = dtype == SSTE_F8E4M3;
-  if (big) {
-    if (fp8) launch_fwd_cfg<true, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_cfg<false, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+  // 256 x 256 tiles once they fill the 256 CUs several times over, else 256 x 128
+  int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
+  if (big_tiles >= 1024) {
+    if (fp8) launch_fwd_cfg<true, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    else launch_fwd_cfg<false, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   } else {
-    if (fp8) launch_fwd_cfg<true, 4, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_cfg<false, 4, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    if (fp8) launch_fwd_cfg<true, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    else launch_fwd_cfg<false, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   }
   return hipGetLastError();
 }
