@@ -108,8 +108,7 @@ def main():
     dYs = [up(dyc)] + [up(dyc).clone() for _ in range(nsets - 1)]
     Zs = [torch.empty((T, O), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
     dWs = [torch.empty((O, I), dtype=torch.float32, device="cuda") for _ in range(nsets)]
-    vals = torch.empty((O, I // 2), dtype=torch.uint8 if fp8 else torch.int16, device="cuda")
-    meta = torch.empty((O, I // 8), dtype=torch.uint8, device="cuda")
+    vals, meta = sste.packed_buffers(O, I, dt, "cuda")
     ws_bytes = sste.wgrad_workspace_bytes(T, O, I, dt)
     wss = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
 
@@ -125,7 +124,7 @@ def main():
     def step(i):
         s = i % nsets
         sste.project_pack(W, beta, dt, w_scale, vals=vals, meta=meta)
-        sste.linear_fwd(Xs[s], vals, meta, dt, float(xs), w_scale, Z=Zs[s])
+        sste.linear_fwd(Xs[s], vals, meta, O, dt, float(xs), w_scale, Z=Zs[s])
         sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=dt, dy_scale=float(dys), x_scale=float(xs),
                           dW=dWs[s], workspace=wss[s])
 

@@ -23,12 +23,19 @@
  *     for non-finite inputs.
  *
  * Packed 2:4 operand ("vals" + "meta"), the format produced by sste_project_pack and
- * sste_mvue_materialize and consumed by sste_linear_fwd:
- *   vals : R x K/2 elements, row-major.  For each group of 4 consecutive k the two recorded values in
- *          ascending position order.
- *   meta : R x K/8 bytes, row-major.  One nibble per group: pos0 | pos1 << 2 with pos0 < pos1 the
- *          positions (0..3) of the two recorded values inside the group; the even group of a pair
- *          occupies the low nibble of its byte.
+ * sste_mvue_materialize and consumed by sste_linear_fwd.  For an operand with R rows and K dense
+ * columns (groups of 4 along K), each group contributes its two recorded values in ascending position
+ * order and one nibble pos0 | pos1 << 2 (pos0 < pos1 in 0..3).  Both are stored blocked, in the order
+ * the gfx950 sparse matrix instruction consumes them.  Let KS = 64 (bf16) / 128 (e4m3) dense columns
+ * per instruction step, S = K / KS steps, RB = ceil(R / 16) row blocks:
+ *   vals : RB * S blocks of 1024 bytes, block (rb, s) at byte offset (rb * S + s) * 1024.  A block holds
+ *          64 slots of 16 bytes; slot 16 * q + j (q in 0..3, j in 0..15) holds the recorded values of row
+ *          16 * rb + j for dense columns [KS * s + KS/4 * q, KS * s + KS/4 * (q + 1)): 8 bf16 / 16 e4m3.
+ *   meta : RB * S blocks of 128 (bf16) / 256 (e4m3) bytes in the same block order; slot 16 * q + j holds
+ *          2 / 4 bytes: the nibbles of that slot's 4 / 8 groups, group g at bits 4g.
+ * Rows R .. 16 * RB - 1 are padding (sste_project_pack writes them as all-zero rows: values 0, nibbles
+ * 0 | 1 << 2).  Buffer sizes:
+ * vals 16 * RB * K / 2 elements, meta 16 * RB * K / 8 bytes.
  */
 #ifndef SSTE_H
 #define SSTE_H
@@ -69,16 +76,17 @@ typedef enum {
  * RNE_bf16(p); e4m3 values store RNE_e4m3(clamp(p / val_scale, +-448)) with a true float32 division.
  *
  *   W         in   device, bf16, O x I, leading dimension ldw (>= I, multiple of 8)
- *   O, I      in   O >= 0; I >= 0 and a multiple of 8 (whole groups, two per metadata byte)
+ *   O, I      in   O >= 0; I >= 0, a multiple of 4 (whole groups) and of the step KS of val_dtype
  *   beta      in   frozen per-tensor scale, finite and > 0
  *   val_dtype in   SSTE_BF16 or SSTE_F8E4M3: element type of `vals`
  *   val_scale in   finite and > 0; must be 1 for SSTE_BF16
- *   vals      out  device, O x I/2 elements of val_dtype, contiguous rows
- *   meta      out  device, O x I/8 bytes, contiguous rows
+ *   vals      out  device, packed values: 16 * ceil(O/16) * I/2 elements of val_dtype (format above)
+ *   meta      out  device, packed position bits: 16 * ceil(O/16) * I/8 bytes
  *   amax_out  out  device float* or NULL.  If given, receives max |p| over all recorded values
  *                  (before division by val_scale and storage rounding); 0 for an empty matrix.
- * Errors: NULL -> ERR_NULL (W/vals/meta may be NULL only if O*I == 0); bad sizes -> ERR_SHAPE;
- * misalignment -> ERR_ALIGN; bad beta/scale -> ERR_VALUE; bad dtype -> ERR_DTYPE.
+ * Errors: NULL -> ERR_NULL (W/vals/meta may be NULL only if O*I == 0); bad sizes -> ERR_SHAPE; I not a
+ * multiple of KS -> ERR_UNSUPPORTED; misalignment -> ERR_ALIGN; bad beta/scale -> ERR_VALUE; bad dtype ->
+ * ERR_DTYPE.
  */
 int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta,
                       int val_dtype, float val_scale,
@@ -93,7 +101,7 @@ int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float be
  *   T, I, O  in   T >= 0; O >= 0 and a multiple of 8; I a multiple of 64 (bf16) / 128 (e4m3)
  *   dtype    in   element type of X and of vals (both operands share it)
  *   x_scale, w_scale  in  finite, > 0: dequantisation scales (1 for bf16 operands in the paper's setting)
- *   vals, meta  in   packed S(W): O x I/2 and O x I/8 as written by sste_project_pack
+ *   vals, meta  in   packed S(W) (R = O rows, K = I columns) as written by sste_project_pack
  *   Z        out  device, T x O bf16, leading dimension ldz (multiple of 8)
  * Metadata nibbles are trusted to be well formed (pos0 != pos1); malformed ones give an unspecified
  * but memory-safe result.
@@ -147,8 +155,9 @@ size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
  *   k1 = high word; x = (gid & 0xFFFFFFFF) ^ k0; x += (gid >> 32) * 0x9E3779B9; x ^= x >> 17;
  *   x *= 0xED5AD4BB; x += k1; x ^= x >> 11; x *= 0xAC4C1B51; x ^= x >> 15; x *= 0x31848BAB; x ^= x >> 14.
  *
- *   dY    in   device, T x O of `dtype`, leading dimension lddy;  T a multiple of 8, O >= 0
- *   vals  out  device, O x T/2 elements of `dtype`;  meta out: O x T/8 bytes (packed format above, K = T)
+ *   dY    in   device, T x O of `dtype`, leading dimension lddy;  T a multiple of 64 (bf16) / 128 (e4m3)
+ *   vals, meta  out  device, packed format above with R = O rows and K = T columns (padding rows are
+ *              left unwritten)
  */
 int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype,
                           uint64_t seed, uint64_t offset, void* vals, void* meta, void* hip_stream);

@@ -204,6 +204,55 @@ def decode_packed(vals, meta, val_dtype="bf16"):
     return dense.reshape(O, G * 4)
 
 
+# --------------------------------------------------------------------------- device layout
+
+def k_step(val_dtype):
+    """Dense columns covered by one sparse matrix instruction step: 64 (bf16) / 128 (e4m3)."""
+    return 64 if val_dtype == "bf16" else 128
+
+
+def to_fragment_major(vals, meta, val_dtype="bf16"):
+    """Row-major packed (vals (R, K/2), meta (R, K/8)) -> the blocked layout the GPU library stores.
+
+    Pure data movement (no arithmetic).  Rows are padded to a multiple of 16 with the packing of
+    all-zero rows (values 0, nibble 0 | 1 << 2: an all-zero group records positions 0 and 1).  With
+    KS = k_step(val_dtype), RB = ceil(R/16) row blocks and S = K / KS column steps:
+      vals_fm[rb, s, q, j, :]  = the 16 bytes (8 bf16 / 16 e4m3 values) of row 16*rb + j that cover dense
+                                 columns [KS*s + KS/4*q, KS*s + KS/4*(q+1));
+      meta_fm[rb, s, q, j, :]  = the 2 (bf16) / 4 (e4m3) metadata bytes of the same row and columns.
+    Both are returned flattened to 1-D byte-compatible arrays in (rb, s, q, j) order."""
+    vals = np.asarray(vals)
+    meta = np.asarray(meta, dtype=np.uint8)
+    R = vals.shape[0]
+    KS = k_step(val_dtype)
+    K = vals.shape[1] * 2
+    if K % KS != 0:
+        raise ValueError("K must be a multiple of the column step")
+    S = K // KS
+    RB = (R + 15) // 16
+    per = KS // 8                       # values per (row, q): 8 or 16
+    mper = KS // 32                     # metadata bytes per (row, q): 2 or 4
+    vp = np.zeros((RB * 16, K // 2), dtype=vals.dtype)
+    vp[:R] = vals
+    mp = np.full((RB * 16, K // 8), 0x44, dtype=np.uint8)
+    mp[:R] = meta
+    v = vp.reshape(RB, 16, S, 4, per).transpose(0, 2, 3, 1, 4)
+    m = mp.reshape(RB, 16, S, 4, mper).transpose(0, 2, 3, 1, 4)
+    return np.ascontiguousarray(v).reshape(-1), np.ascontiguousarray(m).reshape(-1)
+
+
+def from_fragment_major(vals_fm, meta_fm, R, K, val_dtype="bf16"):
+    """Inverse of ``to_fragment_major``: blocked layout -> row-major (vals (R, K/2), meta (R, K/8))."""
+    KS = k_step(val_dtype)
+    S = K // KS
+    RB = (R + 15) // 16
+    per = KS // 8
+    mper = KS // 32
+    v = np.asarray(vals_fm).reshape(RB, S, 4, 16, per).transpose(0, 3, 1, 2, 4).reshape(RB * 16, K // 2)
+    m = np.asarray(meta_fm, dtype=np.uint8).reshape(RB, S, 4, 16, mper).transpose(0, 3, 1, 2, 4).reshape(RB * 16, K // 8)
+    return np.ascontiguousarray(v[:R]), np.ascontiguousarray(m[:R])
+
+
 def structural_mask(meta):
     """(O, I/8) metadata -> boolean (O, I) mask of the recorded positions."""
     idx0, idx1 = kept_positions(meta)

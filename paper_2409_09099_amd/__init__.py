@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     linear_fwd,
     linear_wgrad,
     mvue_materialize,
+    packed_buffers,
     project_pack,
     timing_begin,
     timing_end,

@@ -88,25 +88,34 @@ def _esize(dtype: int) -> int:
     return 1 if dtype == F8E4M3 else 2
 
 
+def packed_buffers(R: int, K: int, dtype: int, device):
+    """Uninitialised device buffers for a packed 2:4 operand with R rows and K dense columns: the blocked
+    layout pads the rows to a multiple of 16."""
+    rows = (R + 15) // 16 * 16
+    vals = torch.empty((rows, K // 2), dtype=torch.uint8 if dtype == F8E4M3 else torch.int16, device=device)
+    meta = torch.empty((rows, K // 8), dtype=torch.uint8, device=device)
+    return vals, meta
+
+
 def project_pack(W: torch.Tensor, beta: float, val_dtype: int = BF16, val_scale: float = 1.0,
                  vals: Optional[torch.Tensor] = None, meta: Optional[torch.Tensor] = None,
                  amax_out: Optional[torch.Tensor] = None):
     """sste_project_pack: beta * S_soft(W) packed 2:4.  Returns (vals, meta)."""
     O, I, ldw = _matrix(W, 2, "W")
-    if vals is None:
-        vals = torch.empty((O, I // 2), dtype=torch.uint8 if val_dtype == F8E4M3 else torch.int16, device=W.device)
-    if meta is None:
-        meta = torch.empty((O, I // 8), dtype=torch.uint8, device=W.device)
+    if vals is None or meta is None:
+        v, m = packed_buffers(O, I, val_dtype, W.device)
+        vals = v if vals is None else vals
+        meta = m if meta is None else meta
     _check(library().sste_project_pack(_ptr(W), O, I, ldw, beta, val_dtype, val_scale, _ptr(vals), _ptr(meta),
                                        _ptr(amax_out), _stream(W)))
     return vals, meta
 
 
-def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, dtype: int = BF16, x_scale: float = 1.0,
+def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, dtype: int = BF16, x_scale: float = 1.0,
                w_scale: float = 1.0, Z: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """sste_linear_fwd: Z = (x_scale * w_scale) * X decode(vals, meta)^T, bf16 output."""
+    """sste_linear_fwd: Z = (x_scale * w_scale) * X decode(vals, meta)^T, bf16 output.  O = rows of the
+    packed operand (the buffers themselves are padded to a multiple of 16 rows)."""
     T, I, ldx = _matrix(X, _esize(dtype), "X")
-    O = vals.shape[0]
     if Z is None:
         Z = torch.empty((T, O), dtype=torch.bfloat16, device=X.device)
     _, _, ldz = _matrix(Z, 2, "Z")
@@ -144,8 +153,9 @@ def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtyp
 def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16):
     """sste_mvue_materialize: MVUE(dY^T) as a packed 2:4 operand.  Returns (vals (O, T/2), meta (O, T/8))."""
     T, O, lddy = _matrix(dY, _esize(dtype), "dY")
-    vals = torch.empty((O, T // 2), dtype=torch.uint8 if dtype == F8E4M3 else torch.int16, device=dY.device)
-    meta = torch.empty((O, T // 8), dtype=torch.uint8, device=dY.device)
+    vals, meta = packed_buffers(O, T, dtype, dY.device)
+    vals.zero_()
+    meta.zero_()
     _check(library().sste_mvue_materialize(_ptr(dY), T, O, lddy, dtype, seed, offset, _ptr(vals), _ptr(meta), _stream(dY)))
     return vals, meta
 
@@ -160,9 +170,9 @@ def compute_beta(W: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor) -> torch.Tensor:
+def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor, O: int) -> torch.Tensor:
     """sste_flip_count: number of positions whose recorded state differs (1-element int64 device tensor)."""
-    O, I8, _ = _matrix(meta_a, 1, "meta_a")
+    rows, I8, _ = _matrix(meta_a, 1, "meta_a")
     if tuple(meta_b.shape) != tuple(meta_a.shape) or not meta_a.is_contiguous() or not meta_b.is_contiguous():
         raise ValueError("metadata arrays must be contiguous and of equal shape")
     out = torch.empty(1, dtype=torch.int64, device=meta_a.device)

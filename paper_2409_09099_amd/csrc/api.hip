@@ -134,6 +134,8 @@ int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float be
   if (!good_scale(beta)) return fail(SSTE_ERR_VALUE, "project_pack: beta must be finite and > 0");
   if (!good_scale(val_scale)) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be finite and > 0");
   if (val_dtype == SSTE_BF16 && val_scale != 1.0f) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be 1 for bf16 values");
+  if (I % (val_dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
+    return fail(SSTE_ERR_UNSUPPORTED, "project_pack: I=%lld must be a multiple of %d for this value type", (long long)I, val_dtype == SSTE_F8E4M3 ? 128 : 64);
   if (ldw < I) return fail(SSTE_ERR_SHAPE, "project_pack: ldw=%lld < I=%lld", (long long)ldw, (long long)I);
   if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "project_pack: ldw=%lld is not a multiple of 8", (long long)ldw);
   bool empty = (O == 0 || I == 0);
@@ -213,7 +215,9 @@ int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, in
   clear_error();
   if (T < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: negative size");
   if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "mvue_materialize: unknown dtype %d", dtype);
-  if (T % 8 != 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: T=%lld is not a multiple of 8 (two groups per metadata byte)", (long long)T);
+  if (T % 4 != 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: T=%lld is not a multiple of 4 (groups of four tokens)", (long long)T);
+  if (T % (dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
+    return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld must be a multiple of %d for this element type", (long long)T, dtype == SSTE_F8E4M3 ? 128 : 64);
   if (lddy < O) return fail(SSTE_ERR_SHAPE, "mvue_materialize: lddy < O");
   bool empty = (T == 0 || O == 0);
   if (!empty && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "mvue_materialize: NULL dY, vals or meta");
@@ -249,7 +253,7 @@ int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I
   if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "flip_count: negative size");
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "flip_count: I=%lld is not a multiple of 8", (long long)I);
   if (!count_out) return fail(SSTE_ERR_NULL, "flip_count: count_out is NULL");
-  int64_t nbytes = O * (I / 8);
+  int64_t nbytes = ((O + 15) / 16 * 16) * (I / 8);
   if (nbytes > 0 && (!meta_a || !meta_b)) return fail(SSTE_ERR_NULL, "flip_count: NULL metadata");
   if ((reinterpret_cast<uintptr_t>(meta_a) & 3u) || (reinterpret_cast<uintptr_t>(meta_b) & 3u) || (reinterpret_cast<uintptr_t>(count_out) & 7u))
     return fail(SSTE_ERR_ALIGN, "flip_count: metadata must be 4-byte and count_out 8-byte aligned");

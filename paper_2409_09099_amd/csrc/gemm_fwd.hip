@@ -19,10 +19,12 @@
 // NS stages; the loads for k-step s + NS - 1 are issued once the fragments of k-step s have been
 // read.  The vector-memory path of a CU moves 64 B/clk, so a 256 x 256 tile (50 KiB per k-step
 // against 64 sparse MFMAs per SIMD) leaves it about 40 % idle, a 256 x 128 tile almost none.
-// Because the hardware writes the 64 lanes of such a load to consecutive LDS addresses, bank
+// The packed weight is stored in memory in the order the sparse MFMA consumes it (1 KiB blocks of
+// 16 rows x one k-step, one 16-byte slot per lane), so its loads are contiguous and its fragment
+// reads are lane-contiguous.  For X, whose 64 lanes of a load land on consecutive LDS addresses, bank
 // conflicts are avoided by choosing WHICH 16-byte piece each lane fetches: piece c of row r is stored
-// at position c ^ f(r), f(r) = (r / 4) % 4 for the values and (r / 2) % 8 for X, which makes every
-// fragment read (16 rows x one piece) hit 16 different 16-byte bank groups.
+// at position c ^ ((r / 2) % 8), which makes every fragment read (16 rows x one piece) hit 16
+// different 16-byte bank groups.
 // The loads are written in inline assembly: the compiler otherwise orders every later LDS read
 // behind ALL outstanding LDS-writing loads, which would drain the ring each k-step.  Their
 // completion is tracked by hand with s_waitcnt vmcnt(n) + a workgroup barrier.
@@ -76,11 +78,12 @@ __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
 template <bool FP8, int WM, int WN, int NS>
 __global__ void __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && NS <= 2) ? 2 : 1)
 k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
-             const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t meta_row_bytes,
+             const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
              int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
   constexpr int NW = WM * WN;
   constexpr int BM = 128 * WM, BN = 64 * WN;
   constexpr int MB = FP8 ? 16 : 8;                // position bytes per row and k-step
+  constexpr int MBLK = 16 * MB;                   // ... per 16-row block
   constexpr int A_BYTES = BM * 64, B_BYTES = BN * 128, M_BYTES = BM * MB;
   constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
   constexpr int EPI_BYTES = NW * 64 * EPI_ROW;
@@ -104,23 +107,20 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
   const int j = lane & 15, q = lane >> 4;
   const int64_t o0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
   const int nsteps = (int)(k_bytes / 128);
-  const int64_t vals_row_bytes = k_bytes / 2;
 
-  // buffer descriptors over exactly the valid rows of this tile: rows past the end read as zeros
-  const int rows_a = (int)((O - o0) < BM ? (O - o0) : BM), rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
-  const i32x4 ba = rsrc_words(vals + o0 * vals_row_bytes, (uint32_t)(rows_a * vals_row_bytes));
-  const i32x4 bm = rsrc_words(meta + o0 * meta_row_bytes, (uint32_t)(rows_a * meta_row_bytes));
+  // buffer descriptors over exactly the valid part of this tile: what lies past the end reads as zeros
+  const int64_t rblk0 = o0 / 16, rbn = (O + 15) / 16;
+  const int blks_a = (int)((rbn - rblk0) < BM / 16 ? (rbn - rblk0) : BM / 16);
+  const int rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
+  const i32x4 ba = rsrc_words(vals + rblk0 * nsteps * 1024, (uint32_t)(blks_a * nsteps * 1024));
+  const i32x4 bm = rsrc_words(meta + rblk0 * nsteps * MBLK, (uint32_t)(blks_a * nsteps * MBLK));
   const i32x4 bb = rsrc_words(X + t0 * ldx_bytes, (uint32_t)((rows_b - 1) * ldx_bytes + k_bytes));
 
   // per-lane source offsets of the direct-to-LDS loads (destination = stage base + load index * 1 KiB
   // (256 B for the position bits) + lane * 16 (4), fixed by the hardware)
   uint32_t offa[LA], offb[LB], offm[LM];
 #pragma unroll
-  for (int i = 0; i < LA; i++) {
-    int wl = LA * wave + i;
-    int r = 16 * wl + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
-    offa[i] = (uint32_t)(r * vals_row_bytes + c * 16);
-  }
+  for (int i = 0; i < LA; i++) offa[i] = (uint32_t)((LA * wave + i) * nsteps * 1024 + lane * 16);
 #pragma unroll
   for (int i = 0; i < LB; i++) {
     int wl = LB * wave + i;
@@ -130,7 +130,7 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 #pragma unroll
   for (int i = 0; i < LM; i++) {
     int d = 64 * (LM * wave + i) + lane;          // dword index inside the stage's position bits
-    offm[i] = (uint32_t)((d / (MB / 4)) * meta_row_bytes + 4 * (d % (MB / 4)));
+    offm[i] = (uint32_t)((d / (MBLK / 4)) * nsteps * MBLK + 4 * (d % (MBLK / 4)));
   }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
@@ -139,9 +139,9 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 #define FWD_ISSUE(step, stg)                                                                           \
   do {                                                                                                 \
     const bool live_ = (step) < nsteps;                                                                \
-    const uint32_t sa_ = live_ ? (uint32_t)(step) * 64u : 0x40000000u;                                 \
+    const uint32_t sa_ = live_ ? (uint32_t)(step) * 1024u : 0x40000000u;                                 \
     const uint32_t sb_ = live_ ? (uint32_t)(step) * 128u : 0x40000000u;                                \
-    const uint32_t sm_ = live_ ? (uint32_t)(step) * (uint32_t)MB : 0x40000000u;                        \
+    const uint32_t sm_ = live_ ? (uint32_t)(step) * (uint32_t)MBLK : 0x40000000u;                        \
     const uint32_t base_ = lds0 + (uint32_t)(stg) * STAGE;                                             \
     _Pragma("unroll") for (int i = 0; i < LA; i++) dma_b128(ba, base_ + (LA * wave + i) * 1024, offa[i], sa_); \
     _Pragma("unroll") for (int i = 0; i < LB; i++) dma_b128(bb, base_ + A_BYTES + (LB * wave + i) * 1024, offb[i], sb_); \
@@ -155,9 +155,8 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
     for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   // per-lane fragment addresses inside a stage
-  const int ra0 = 128 * wm + j;                                          // + 16 mi
-  const uint32_t fa_off = (uint32_t)(ra0 * 64 + ((q ^ ((j >> 2) & 3)) * 16));
-  const uint32_t fm_off = (uint32_t)(A_BYTES + B_BYTES + ra0 * MB + (MB / 4) * q);
+  const uint32_t fa_off = (uint32_t)(8 * wm * 1024 + lane * 16);          // + 1024 mi
+  const uint32_t fm_off = (uint32_t)(A_BYTES + B_BYTES + 8 * wm * MBLK + lane * (MB / 4));   // + MBLK mi
   const int rb0 = 64 * wn + j;                                           // + 16 ni
   const int cb0 = q ^ ((j >> 1) & 7);
   const uint32_t fb_off0 = (uint32_t)(A_BYTES + rb0 * 128 + cb0 * 16);
@@ -182,8 +181,8 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 #pragma unroll
     for (int mi = 0; mi < MI; mi++) {
       fa[mi] = *(const uint4*)(sb + fa_off + mi * 1024);
-      if (FP8) fidx[mi] = *(const int*)(sb + fm_off + mi * 256);
-      else fidx[mi] = *(const uint16_t*)(sb + fm_off + mi * 128);
+      if (FP8) fidx[mi] = *(const int*)(sb + fm_off + mi * MBLK);
+      else fidx[mi] = *(const uint16_t*)(sb + fm_off + mi * MBLK);
     }
     {
       int nstg = stg + NS - 1;
@@ -244,7 +243,7 @@ static void launch_fwd_cfg(const void* X, int64_t T, int64_t I, int64_t ldx, flo
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(64 * WM * WN);
   int64_t eb = FP8 ? 1 : 2;
   SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<FP8, WM, WN, NS>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
-              (const uint8_t*)vals, (const uint8_t*)meta, I / 8, O, scale, (uint16_t*)Z, ldz, m_tiles);
+              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
 }
 
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype) {

@@ -33,16 +33,22 @@ k_mvue_materialize(const void* __restrict__ dY, int64_t T, int64_t O, int64_t ld
       packed[g] = mvue_group_bf16(lo, hi, x, nib[g]);
     }
   }
-  int64_t Kc = T / 2;                            // values per row
+  // blocked layout of include/sste.h: block (rb, s) of 16 channels x one k-step; slot 16 q + j
+  constexpr int KS = FP8 ? 128 : 64;             // tokens per k-step
+  const int64_t steps = T / KS, t0 = 8 * kp;
+  const int64_t blk = (o / 16) * steps + t0 / KS;
+  const int to = (int)(t0 % KS), q = to / (KS / 4), pi = (to % (KS / 4)) / 8;
+  const int64_t slot = blk * 64 + 16 * q + (o & 15);
   if (FP8) {
-    ((uint32_t*)vals)[(o * Kc + 4 * kp) / 4] = packed[0] | (packed[1] << 16);
+    ((uint32_t*)vals)[slot * 4 + pi] = packed[0] | (packed[1] << 16);
+    meta[slot * 4 + pi] = (uint8_t)(nib[0] | (nib[1] << 4));
   } else {
     uint2 v;
     v.x = packed[0];
     v.y = packed[1];
-    ((uint2*)vals)[(o * Kc + 4 * kp) / 4] = v;
+    ((uint2*)vals)[slot * 2 + pi] = v;
+    meta[slot * 2 + pi] = (uint8_t)(nib[0] | (nib[1] << 4));
   }
-  meta[o * (T / 8) + kp] = (uint8_t)(nib[0] | (nib[1] << 4));
 }
 
 hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,

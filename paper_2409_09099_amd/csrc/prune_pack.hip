@@ -3,8 +3,7 @@
 // Also: the MSE-optimal beta reduction of Sec. 4.2 and the flip count of Sec. 3.3.
 //
 // Data movement per weight: 2 B read, 1 B (bf16 values) or 0.5 B (e4m3 values) + 0.125 B written.
-// The kernel is bound by HBM bandwidth; each lane owns one 16-byte chunk (two groups of four), so a
-// wave reads 1 KiB, writes 512 B (256 B) of values and 64 B of metadata, all contiguous.
+// The kernel is bound by HBM bandwidth.
 #include "common.h"
 
 namespace sste {
@@ -42,31 +41,65 @@ __device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float be
   return r;
 }
 
+// One wave produces one 16-row x one-column-step block of the packed operand in the blocked layout
+// described in include/sste.h: lane (j = lane % 16, q = lane / 16) reads the 16 (bf16 values) or 32
+// (e4m3 values) weights of row 16 rb + j that feed slot q of the sparse matrix instruction, and
+// writes its 16 bytes of values to position lane of the 1 KiB block and its position bits to
+// position lane of the metadata block.  A wave therefore writes 1 KiB + 128 (256) B contiguously
+// and reads whole 128-byte (256-byte) row segments.
 template <bool FP8, bool AMAX>
 __global__ void __launch_bounds__(256)
-k_project_pack(const uint4* __restrict__ W, int64_t n_chunks, int32_t chunks_per_row, int64_t ldw_chunks,
-               float beta, float val_scale, void* __restrict__ vals, uint8_t* __restrict__ meta,
+k_project_pack(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t n_blocks, int64_t ldw_bytes,
+               float beta, float val_scale, uint4* __restrict__ vals, void* __restrict__ meta,
                uint32_t* __restrict__ amax_bits) {
-  int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  constexpr int NG = FP8 ? 8 : 4;                       // groups per lane
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   float amax = 0.0f;
-  if (c < n_chunks) {
-    int64_t row = c / chunks_per_row;
-    int64_t col = c - row * chunks_per_row;
-    uint4 w = W[row * ldw_chunks + col];
-    Proj g0 = project_group(w.x, w.y, beta);
-    Proj g1 = project_group(w.z, w.w, beta);
-    if (AMAX) amax = fmaxf(fmaxf(fabsf(g0.p0), fabsf(g0.p1)), fmaxf(fabsf(g1.p0), fabsf(g1.p1)));
-    if (FP8) {
-      uint32_t q0 = e4m3_rne_pack(clamp448(g0.p0 / val_scale), clamp448(g0.p1 / val_scale));
-      uint32_t q1 = e4m3_rne_pack(clamp448(g1.p0 / val_scale), clamp448(g1.p1 / val_scale));
-      ((uint32_t*)vals)[c] = q0 | (q1 << 16);
+  if (blk < n_blocks) {
+    const int64_t rb = blk / steps;
+    const int32_t s = (int32_t)(blk - rb * steps);
+    const int j = lane & 15, q = lane >> 4;
+    const int64_t row = rb * 16 + j;
+    uint32_t w[2 * NG];
+    if (row < O) {
+      const uint4* src = (const uint4*)(W + row * ldw_bytes + ((int64_t)s * 4 + q) * (NG * 8));
+#pragma unroll
+      for (int c = 0; c < NG / 2; c++) {
+        uint4 v = src[c];
+        w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+      }
     } else {
-      uint2 v;
-      v.x = bf16_rne_pack(g0.p0, g0.p1);
-      v.y = bf16_rne_pack(g1.p0, g1.p1);
-      ((uint2*)vals)[c] = v;
+#pragma unroll
+      for (int c = 0; c < 2 * NG; c++) w[c] = 0;
     }
-    meta[c] = (uint8_t)(g0.nib | (g1.nib << 4));
+    float p[2 * NG];
+    uint32_t nibs = 0;
+#pragma unroll
+    for (int g = 0; g < NG; g++) {
+      Proj r = project_group(w[2 * g], w[2 * g + 1], beta);
+      p[2 * g] = r.p0;
+      p[2 * g + 1] = r.p1;
+      nibs |= r.nib << (4 * g);
+      if (AMAX) amax = fmaxf(amax, fmaxf(fabsf(r.p0), fabsf(r.p1)));
+    }
+    uint4 out;
+    if (FP8) {
+      uint32_t o[4];
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        uint32_t lo = e4m3_rne_pack(clamp448(p[4 * c] / val_scale), clamp448(p[4 * c + 1] / val_scale));
+        uint32_t hi = e4m3_rne_pack(clamp448(p[4 * c + 2] / val_scale), clamp448(p[4 * c + 3] / val_scale));
+        o[c] = lo | (hi << 16);
+      }
+      out = make_uint4(o[0], o[1], o[2], o[3]);
+      ((uint32_t*)meta)[blk * 64 + lane] = nibs;
+    } else {
+      out = make_uint4(bf16_rne_pack(p[0], p[1]), bf16_rne_pack(p[2], p[3]), bf16_rne_pack(p[4], p[5]),
+                       bf16_rne_pack(p[6], p[7]));
+      ((uint16_t*)meta)[blk * 64 + lane] = (uint16_t)nibs;
+    }
+    vals[blk * 64 + lane] = out;
   }
   if (AMAX) {
     // non-negative floats order like their bit patterns: reduce as unsigned integers
@@ -89,20 +122,20 @@ __global__ void k_fill_u64(unsigned long long* p, unsigned long long v) { *p = v
 hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
                                float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s) {
   if (amax_out) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
-  int64_t cpr = I / 8, n = O * cpr;
-  if (n == 0) return hipGetLastError();
-  dim3 grid((unsigned)((n + 255) / 256)), block(256);
-  const uint4* w = (const uint4*)W;
-  uint32_t* ab = (uint32_t*)amax_out;
   bool fp8 = val_dtype == SSTE_F8E4M3;
+  int64_t steps = I / (fp8 ? 128 : 64), n = ((O + 15) / 16) * steps;
+  if (n == 0) return hipGetLastError();
+  dim3 grid((unsigned)((n + 3) / 4)), block(256);
+  const uint8_t* w = (const uint8_t*)W;
+  uint32_t* ab = (uint32_t*)amax_out;
   if (fp8 && amax_out)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, true>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   else if (fp8)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, false>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   else if (amax_out)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   else
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, n, (int32_t)cpr, ldw / 8, beta, val_scale, vals, (uint8_t*)meta, ab);
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   return hipGetLastError();
 }
 

@@ -50,15 +50,17 @@ def test_project_pack_validation(lib):
     f = lib.sste_project_pack
     assert f(fake, -1, 8, 8, 1.0, 0, 1.0, fake, fake, None, None) == 2
     assert f(fake, 4, 12, 12, 1.0, 0, 1.0, fake, fake, None, None) == 2 and "multiple of 8" in _err(lib)
-    assert f(fake, 4, 16, 8, 1.0, 0, 1.0, fake, fake, None, None) == 2
-    assert f(fake, 4, 16, 20, 1.0, 0, 1.0, fake, fake, None, None) == 3
-    assert f(fake, 4, 16, 16, 1.0, 7, 1.0, fake, fake, None, None) == 4
-    assert f(fake, 4, 16, 16, 0.0, 0, 1.0, fake, fake, None, None) == 5
-    assert f(fake, 4, 16, 16, float("inf"), 0, 1.0, fake, fake, None, None) == 5
-    assert f(fake, 4, 16, 16, 1.0, 0, 2.0, fake, fake, None, None) == 5
-    assert f(fake, 4, 16, 16, 1.0, 1, -1.0, fake, fake, None, None) == 5
-    assert f(None, 4, 16, 16, 1.0, 0, 1.0, fake, fake, None, None) == 1
-    assert f(P(0x1004), 4, 16, 16, 1.0, 0, 1.0, fake, fake, None, None) == 3
+    assert f(fake, 4, 64, 8, 1.0, 0, 1.0, fake, fake, None, None) == 2
+    assert f(fake, 4, 64, 68, 1.0, 0, 1.0, fake, fake, None, None) == 3
+    assert f(fake, 4, 64, 64, 1.0, 7, 1.0, fake, fake, None, None) == 4
+    assert f(fake, 4, 64, 64, 0.0, 0, 1.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 64, 64, float("inf"), 0, 1.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 64, 64, 1.0, 0, 2.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 128, 128, 1.0, 1, -1.0, fake, fake, None, None) == 5
+    assert f(fake, 4, 16, 16, 1.0, 0, 1.0, fake, fake, None, None) == 7      # whole groups, but not a whole column step
+    assert f(fake, 4, 64, 64, 1.0, 1, 1.0, fake, fake, None, None) == 7      # e4m3 values need I % 128 == 0
+    assert f(None, 4, 64, 64, 1.0, 0, 1.0, fake, fake, None, None) == 1
+    assert f(P(0x1004), 4, 64, 64, 1.0, 0, 1.0, fake, fake, None, None) == 3
 
 
 def test_linear_fwd_validation(lib):
@@ -102,9 +104,10 @@ def test_linear_wgrad_validation_and_workspace(lib):
 def test_other_entry_points_validation(lib):
     P = ctypes.c_void_p
     fake = P(0x1000)
-    assert lib.sste_mvue_materialize(fake, 12, 8, 8, 0, 0, 0, fake, fake, None) == 2
-    assert lib.sste_mvue_materialize(fake, 16, 8, 4, 0, 0, 0, fake, fake, None) == 2
-    assert lib.sste_mvue_materialize(None, 16, 8, 8, 0, 0, 0, fake, fake, None) == 1
+    assert lib.sste_mvue_materialize(fake, 10, 8, 8, 0, 0, 0, fake, fake, None) == 2
+    assert lib.sste_mvue_materialize(fake, 16, 8, 8, 0, 0, 0, fake, fake, None) == 7
+    assert lib.sste_mvue_materialize(fake, 64, 8, 4, 0, 0, 0, fake, fake, None) == 2
+    assert lib.sste_mvue_materialize(None, 64, 8, 8, 0, 0, 0, fake, fake, None) == 1
     assert lib.sste_compute_beta(fake, 4, 16, 16, None, fake, 1 << 20, None) == 1
     assert lib.sste_compute_beta(fake, 4, 16, 16, fake, None, 0, None) == 6
     assert lib.sste_flip_count(fake, fake, 4, 12, fake, None) == 2

@@ -67,8 +67,9 @@ def _edge_weights():
         [6, 5, -5, 1], [-4, 0.25, -0.5, 8], [1.5, 1.5, -1.5, 0.1], [7, 7, 7, -7.5],
         [1e-3, 1.0000001e-3, 0.999e-3, -1e-3], [65280, 1, -65280, 3],
     ]
-    w = np.array(rows, dtype=np.float32).reshape(2, -1)
-    return F.f32_to_bf16_rne(w)
+    w = np.array(rows, dtype=np.float32).reshape(1, -1)               # 64 weights
+    w = np.concatenate([w, w[:, ::-1]], axis=1)                         # 128: one e4m3 column step
+    return F.f32_to_bf16_rne(np.concatenate([w, -w, w * 0.5], axis=0))
 
 
 @pytest.mark.parametrize("case", ["cfg1", "ragged", "edges", "strided"])
@@ -77,23 +78,24 @@ def test_project_pack_bf16_bit_exact(sste, case):
     if case == "cfg1":
         wb = WL.weight_bits(wl, 0)
     elif case == "ragged":
-        wb = WL.weight_bits(wl, 0, O=77, I=1048)          # spans several workgroups, ragged tail
+        wb = WL.weight_bits(wl, 0, O=77, I=1088)          # spans several workgroups, ragged row tail
     elif case == "edges":
         wb = _edge_weights()
     else:
-        wb = WL.weight_bits(wl, 0, O=33, I=264)
+        wb = WL.weight_bits(wl, 0, O=33, I=256)
     beta = np.float32(OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64))) if case != "edges" else np.float32(1.37)
     if case == "strided":
         big = torch.zeros((33, 320), dtype=torch.bfloat16, device="cuda")
-        big[:, :264] = bf16_dev(wb)
-        Wd = big[:, :264]
+        big[:, :256] = bf16_dev(wb)
+        Wd = big[:, :256]
     else:
         Wd = bf16_dev(wb)
     amax = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
     vals, meta = sste.project_pack(Wd, float(beta), amax_out=amax)
     rv, rm, ra = OP.project_pack(wb, beta)
-    assert np.array_equal(host(meta).numpy(), rm)
-    assert np.array_equal(host(vals).numpy().view(np.uint16), rv)
+    fv, fm = OP.to_fragment_major(rv, rm)
+    assert np.array_equal(host(meta).numpy().reshape(-1), fm)
+    assert np.array_equal(host(vals).numpy().view(np.uint16).reshape(-1), fv)
     assert host(amax).numpy().view(np.uint32)[0] == np.float32(ra).view(np.uint32)
 
 
@@ -106,9 +108,10 @@ def test_project_pack_e4m3_bit_exact(sste, case):
     scale = np.float32(amax / np.float32(448.0)) if case == "cfg1" else np.float32(0.37)
     vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(scale))
     rv, rm, _ = OP.project_pack(wb, beta, "e4m3", scale)
-    assert np.array_equal(host(meta).numpy(), rm)
-    got = host(vals).numpy()
-    assert np.array_equal(got, rv), np.argwhere(got != rv)[:5]
+    fv, fm = OP.to_fragment_major(rv, rm, "e4m3")
+    assert np.array_equal(host(meta).numpy().reshape(-1), fm)
+    got = host(vals).numpy().reshape(-1)
+    assert np.array_equal(got, fv), np.argwhere(got != fv)[:5]
 
 
 def test_project_pack_empty_and_errors(sste):
@@ -117,10 +120,14 @@ def test_project_pack_empty_and_errors(sste):
     assert vals.shape == (0, 32) and meta.shape == (0, 8)
     w = torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(sste.SsteError) as ei:
-        sste.project_pack(w, 1.0, vals=torch.empty((4, 6), dtype=torch.int16, device="cuda"),
-                          meta=torch.empty((4, 2), dtype=torch.uint8, device="cuda"))
+        sste.project_pack(w, 1.0, vals=torch.empty((16, 6), dtype=torch.int16, device="cuda"),
+                          meta=torch.empty((16, 2), dtype=torch.uint8, device="cuda"))
     assert ei.value.status == 2
-    w = torch.zeros((4, 16), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.project_pack(w, 1.0)
+    assert ei.value.status == 7
+    w = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(sste.SsteError) as ei:
         sste.project_pack(w, float("nan"))
     assert ei.value.status == 5
@@ -132,14 +139,16 @@ def test_compute_beta_and_flip_count(sste):
     beta = float(host(sste.compute_beta(bf16_dev(wb)))[0])
     ref = OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64))
     assert abs(beta - ref) <= 1e-5 * ref
-    assert np.isnan(float(host(sste.compute_beta(torch.ones((4, 16), dtype=torch.bfloat16, device="cuda")))[0]))
+    assert np.isnan(float(host(sste.compute_beta(torch.ones((4, 64), dtype=torch.bfloat16, device="cuda")))[0]))
     w2 = WL.weight_update_bits(wb, wl, 0, step=1)
     _, m1 = sste.project_pack(bf16_dev(wb), beta)
     _, m2 = sste.project_pack(bf16_dev(w2), beta)
-    got = int(host(sste.flip_count(m1, m2))[0])
-    want = int(np.count_nonzero(OP.structural_mask(host(m1).numpy()) ^ OP.structural_mask(host(m2).numpy())))
+    got = int(host(sste.flip_count(m1, m2, wb.shape[0]))[0])
+    _, r1, _ = OP.project_pack(wb, np.float32(beta))
+    _, r2, _ = OP.project_pack(w2, np.float32(beta))
+    want = int(np.count_nonzero(OP.structural_mask(r1) ^ OP.structural_mask(r2)))
     assert got == want and got > 0
-    assert int(host(sste.flip_count(m1, m1))[0]) == 0
+    assert int(host(sste.flip_count(m1, m1, wb.shape[0]))[0]) == 0
 
 
 # ------------------------------------------------------------------------------------------ MVUE
@@ -150,6 +159,7 @@ def _edge_gradients(dtype):
                   [1e-3, -1e-3, 1e-3, -1e-3], [448, 448, 448, 448], [448, -1, 0.5, 0.25], [3, -3, 1, 0]], dtype=np.float32)
     cols = g.T                      # (4 tokens, 16 channels): each column is one group
     cols = np.concatenate([cols, cols[::-1]], axis=0)     # 8 tokens
+    cols = np.tile(cols, (16, 1))                         # 128 tokens: one e4m3 column step
     return F.f32_to_bf16_rne(cols) if dtype == "bf16" else F.f32_to_e4m3_rne_sat(cols)
 
 
@@ -160,15 +170,15 @@ def test_mvue_materialize_bit_exact(sste, dtype, case):
     if case == "cfg1":
         codes, _ = WL.output_gradient(wl, 0, T=512, O=256)
     elif case == "ragged":
-        codes, _ = WL.output_gradient(wl, 0, T=136, O=333)
+        codes, _ = WL.output_gradient(wl, 0, T=384, O=333)
     else:
         codes = _edge_gradients(dtype)
     for seed, offset in [(0, 0), (1, 0), (12345678901234567, 99)]:
         vals, meta = sste.mvue_materialize(act_dev(codes, dtype), seed, offset, dt(sste, dtype))
         rv, rm = OM.mvue_pack(codes, seed, offset, dtype)
-        gm = host(meta).numpy()
+        T_, O_ = codes.shape
+        gv, gm = OP.from_fragment_major(host(vals).numpy().view(rv.dtype).reshape(-1), host(meta).numpy().reshape(-1), O_, T_, dtype)
         assert np.array_equal(gm, rm), (case, seed, np.argwhere(gm != rm)[:5])
-        gv = host(vals).numpy().view(rv.dtype)
         assert np.array_equal(gv, rv), (case, seed, np.argwhere(gv != rv)[:5])
 
 
@@ -188,7 +198,7 @@ def _fwd_case(sste, dtype, T, O, I, seed_layer=0):
         ws = np.float32(max(float(amax), 1e-30) / 448.0)
         rv, rm, _ = OP.project_pack(wb, beta, "e4m3", ws)
         vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(ws))
-    Z = sste.linear_fwd(act_dev(xc, dtype), vals, meta, dt(sste, dtype), float(xs), float(ws))
+    Z = sste.linear_fwd(act_dev(xc, dtype), vals, meta, O, dt(sste, dtype), float(xs), float(ws))
     ref = OL.linear_fwd(xc, rv, rm, dtype, xs, ws)
     return z_to_f64(Z), ref
 
@@ -212,12 +222,12 @@ def test_linear_fwd_matches_oracle(sste, dtype, T, O, I):
 
 def test_linear_fwd_empty_and_errors(sste):
     X = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
-    vals = torch.zeros((8, 32), dtype=torch.int16, device="cuda")
-    meta = torch.full((8, 8), 0x44, dtype=torch.uint8, device="cuda")
-    assert sste.linear_fwd(X, vals, meta).shape == (0, 8)
+    vals = torch.zeros((16, 32), dtype=torch.int16, device="cuda")
+    meta = torch.full((16, 8), 0x44, dtype=torch.uint8, device="cuda")
+    assert sste.linear_fwd(X, vals, meta, 8).shape == (0, 8)
     X = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(sste.SsteError) as ei:
-        sste.linear_fwd(X, torch.zeros((8, 48), dtype=torch.int16, device="cuda"), torch.zeros((8, 12), dtype=torch.uint8, device="cuda"))
+        sste.linear_fwd(X, torch.zeros((16, 48), dtype=torch.int16, device="cuda"), torch.zeros((16, 12), dtype=torch.uint8, device="cuda"), 8)
     assert ei.value.status == 7
 
 
