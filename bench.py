@@ -158,14 +158,20 @@ def main():
         "wgrad": {"ms": avg_ms("wgrad"), "dense_equiv_TFLOP_per_s": gemm_flops / (avg_ms("wgrad") * 1e-3) * 1e-12},
         "wgrad_reduce": {"ms": avg_ms("wgrad_reduce")},
     }
+    if kt["mvue_pack"][1]:
+        mv_bytes = T * O * esize * (1 + 0.5 + 0.0625)          # read dY, write packed values + position bits
+        kernels["mvue_pack"] = {"ms": avg_ms("mvue_pack"), "GB_per_s": mv_bytes / (avg_ms("mvue_pack") * 1e-3) * 1e-9,
+                                "frac_hbm_peak": mv_bytes / (avg_ms("mvue_pack") * 1e-3) * 1e-9 / PEAK_HBM_GBS}
+    wgrad_total_ms = sum(kernels[k]["ms"] for k in ("wgrad", "wgrad_reduce", "mvue_pack") if k in kernels and kernels[k]["ms"] == kernels[k]["ms"])
+    kernels["wgrad_all"] = {"ms": wgrad_total_ms, "dense_equiv_TFLOP_per_s": gemm_flops / (wgrad_total_ms * 1e-3) * 1e-12}
     for k in ("fwd", "wgrad"):
         kernels[k]["frac_sparse_mfma_peak"] = kernels[k]["dense_equiv_TFLOP_per_s"] / (2 * PEAK_DENSE_TFLOPS[wl.dtype])
 
     # roofline of the dominant kernel.  The sparse MFMA executes half of the dense-equivalent
     # multiply-adds: algorithmic flops per launch = T*I*O (I/2 MACs per output element), held against
     # the published dense MFMA peak of the operand type.
-    dom = max(("project_pack", "fwd", "wgrad"), key=lambda k: kernels[k]["ms"])
-    if dom == "project_pack":
+    dom = max([k for k in ("project_pack", "fwd", "wgrad", "mvue_pack") if k in kernels], key=lambda k: kernels[k]["ms"])
+    if dom in ("project_pack", "mvue_pack"):
         achieved = kernels[dom]["GB_per_s"]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": achieved / PEAK_HBM_GBS, "traffic": None}

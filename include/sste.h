@@ -128,8 +128,10 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
  *   dW       out  device, O x I float32, leading dimension lddw (multiple of 4)
  *   accumulate in 0: dW is overwritten; 1: the product is added to dW
  *   workspace     device scratch of at least sste_wgrad_workspace_bytes(T, O, I, dtype) bytes, 16-byte
- *                 aligned; holds split-K partial sums that are reduced in a fixed order, so the result
- *                 is bitwise reproducible from run to run.  May be NULL when that size is 0.
+ *                 aligned.  Large problems keep the sparsified operand there (packed, about 0.56 x the
+ *                 bytes of dY) next to the partial sums of the token-axis splits, which are reduced in
+ *                 a fixed order, so the result is bitwise reproducible from run to run.  May be NULL
+ *                 when that size is 0.
  */
 int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
                       const void* X, int64_t I, int64_t ldx, float x_scale,
@@ -194,9 +196,10 @@ int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I
 typedef enum {
   SSTE_K_PROJECT_PACK = 0,   /* projection + scale + pack */
   SSTE_K_FWD = 1,            /* forward sparse GEMM */
-  SSTE_K_WGRAD = 2,          /* weight-gradient sparse GEMM with the fused estimator */
+  SSTE_K_WGRAD = 2,          /* weight-gradient sparse GEMM */
   SSTE_K_WGRAD_REDUCE = 3,   /* fixed-order reduction of the token-axis splits */
-  SSTE_K_COUNT = 4
+  SSTE_K_MVUE_PACK = 4,      /* estimator pre-pass of the weight-gradient path (large problems) */
+  SSTE_K_COUNT = 5
 } sste_kernel_id;
 int sste_timing_begin(int max_launches);
 int sste_timing_end(double* total_ms, int* launches);

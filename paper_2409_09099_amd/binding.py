@@ -180,7 +180,7 @@ def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor, O: int) -> torch.Tens
     return out
 
 
-KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce")
+KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack")
 
 
 def timing_begin(max_launches: int = 4096) -> None:

@@ -179,8 +179,7 @@ static int wgrad_shape_check(int64_t T, int64_t O, int64_t I, int dtype, const c
 
 size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
   if (wgrad_shape_check(T, O, I, dtype, "wgrad_workspace_bytes") != SSTE_OK) return 0;
-  int s = wgrad_splits(T, O, I, dtype);
-  return s > 1 ? (size_t)s * (size_t)O * (size_t)I * sizeof(float) : 0;
+  return wgrad_workspace_bytes(T, O, I, dtype);
 }
 
 int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
@@ -197,6 +196,7 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
   bool empty = (O == 0 || I == 0);
   if (!empty && (!dW || (T > 0 && (!dY || !X)))) return fail(SSTE_ERR_NULL, "linear_wgrad: NULL dY, X or dW");
   if (!aligned16(dY) || !aligned16(X) || !aligned16(dW)) return fail(SSTE_ERR_ALIGN, "linear_wgrad: dY, X and dW must be 16-byte aligned");
+  if (!linear_wgrad_supported(T, O, I, ldx, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_wgrad: this problem does not fit 32-bit tile offsets");
   size_t need = sste_wgrad_workspace_bytes(T, O, I, dtype);
   if (need > 0) {
     if (!workspace) return fail(SSTE_ERR_WORKSPACE, "linear_wgrad: workspace is NULL, %zu bytes needed", need);

@@ -96,6 +96,40 @@ __device__ __forceinline__ uint2 buffer_load_b64(BufferRsrc r, uint32_t voffset,
   return make_uint2((uint32_t)v[0], (uint32_t)v[1]);
 }
 
+// ---- direct-to-LDS loads and hand-tracked completion ------------------------------------------------
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+
+// s_waitcnt that constrains only the vector-memory counter (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14; expcnt and lgkmcnt fields left at "no wait")
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0F70 | ((N >> 4) << 14));
+}
+
+// 64 lanes x 16 B (or 4 B) from a buffer descriptor straight into LDS at lds_addr + lane * 16 (4)
+__device__ __forceinline__ void dma_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
+}
+__device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
+}
+__device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
+  uint64_t p = (uint64_t)base;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xFFFFu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
+}
+
 // ---- host-side launch entry points implemented in the .hip files --------------------------------
 struct RngKey { uint32_t k0, k1; };
 RngKey derive_key(uint64_t seed, uint64_t offset);
@@ -111,7 +145,8 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
                              const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s);
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
-int wgrad_splits(int64_t T, int64_t O, int64_t I, int dtype);
+size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
+bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype);
 hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
                                int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,
                                int accumulate, void* ws, hipStream_t s);

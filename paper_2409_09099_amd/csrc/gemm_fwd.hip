@@ -41,38 +41,6 @@ namespace {
 constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 tokens
 constexpr int EPI_ROW = 272;                      // 128 channels x 2 B + 16 B pad
 constexpr int NUM_XCD = 8;
-typedef __attribute__((address_space(3))) uint8_t lds_u8;
-
-// s_waitcnt that constrains only the vector-memory counter (gfx9 encoding: vmcnt in bits 3:0 and
-// 15:14; expcnt and lgkmcnt fields left at "no wait")
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0F70 | ((N >> 4) << 14));
-}
-
-// 64 lanes x 16 B (or 4 B) from a buffer descriptor straight into LDS at lds_addr + lane * 16 (4)
-__device__ __forceinline__ void dma_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory");
-}
-__device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-               :
-               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory");
-}
-__device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
-  uint64_t p = (uint64_t)base;
-  i32x4 r;
-  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
-  r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xFFFFu));
-  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-  r[3] = 0x00020000;
-  return r;
-}
 }  // namespace
 
 template <bool FP8, int WM, int WN, int NS>

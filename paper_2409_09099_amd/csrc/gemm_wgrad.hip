@@ -1,211 +1,311 @@
-// Weight-gradient GEMM of the S-STE linear layer (paper Sec. 5.1): grad_W = MVUE(grad_Z^T) X.
+// Weight-gradient path of the S-STE linear layer (paper Sec. 5.1): grad_W = MVUE(grad_Z^T) X.
 //
-// MFMA mapping: rows = output channels o, columns = input features i, contraction = tokens t.
-// The sparse operand A = MVUE(dY^T) is never materialised in HBM: every k-step the workgroup loads a
-// [tokens x channels] tile of dY, runs the estimator on groups of four consecutive tokens in
-// registers, and writes packed values + position bits straight into the LDS layout the sparse MFMA
-// reads (row o: 16 bytes per lane quarter).  The random number of a group depends only on
-// (key, group id), so any tiling or split of the token axis gives the same sparsified operand.
-// Operand B = X arrives with the contraction index strided (X is [t][i]); its fragments are read
-// with the transposing LDS load (ds_read_b64_tr_b16 / _b8), which hands each lane 4 (8) consecutive
-// k of one column.
-//
-// Tiling: 128 (o) x 128 (i) per workgroup of 4 waves (2 x 2), k-step of 64 tokens (bf16) / 128 (fp8),
-// token axis split over gridDim.z with partial sums reduced in a fixed order by a second kernel.
+// Large problems run in three kernels on the caller's stream:
+//   1. k_mvue_pack: the estimator is applied once per group of four tokens and the result is written
+//      to the workspace as a packed 2:4 operand in sparse-MFMA fragment order (the format of
+//      include/sste.h with rows = output channels, columns = tokens).  It streams dY once (HBM-bound).
+//   2. k_wgrad_gemm: sparse MFMA GEMM, rows = channels o, columns = input features i, contraction =
+//      tokens, split over the token axis.  The packed operand is loaded like the packed weight of the
+//      forward GEMM; X arrives with the contraction index strided (X is [t][i]) and its fragments are
+//      read with the transposing LDS load (ds_read_b64_tr_b16 / _b8).
+//   3. k_wgrad_reduce: sums the splits in a fixed order (bitwise reproducible) and applies the scale.
+// Why not fuse the estimator into the GEMM's operand load everywhere: it costs about 95 vector
+// instructions per group, and a GEMM tile that is N columns wide re-derives every group I / N times.
+// With a 128-wide tile that is 6 to 40 times per group and the vector pipe, not the matrix pipe or
+// HBM, sets the time (measured: 176 us fused against 60 us here for the 3072 x 768 layer at 8192
+// tokens).  The fused kernel (gemm_wgrad_fused.hip) is kept for small problems, where one launch and no
+// workspace matter more.
 #include "common.h"
 #include "mvue_device.h"
 
 namespace sste {
 
+hipError_t launch_wgrad_fused(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X, int64_t I,
+                              int64_t ldx, RngKey key, int splits, int steps_per_split, float scale, int accumulate,
+                              float* out, int64_t ld_out, int64_t split_stride, hipStream_t s);
+
 namespace {
-constexpr int BM = 128, BN = 128;
-constexpr int A_STRIDE = 80;     // 64 B of packed values per row + pad
-constexpr int MB_STRIDE = 32;    // one metadata byte per group: 16 (bf16) / 32 (fp8) groups per k-step
-constexpr int WG_TARGET = 512;   // workgroups wanted in flight (2 per CU)
-constexpr int MAX_SPLITS = 16;
-constexpr int MIN_STEPS_PER_SPLIT = 8;
-
-// component c (compile-time after unrolling) of a uint4
-__device__ __forceinline__ uint32_t comp(const uint4& v, int c) { return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w)); }
-
+constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 features
+constexpr int NUM_XCD = 8;
+constexpr int NUM_CU = 256;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+
+__device__ __forceinline__ uint32_t comp4(const uint4& v, int c) { return c == 0 ? v.x : (c == 1 ? v.y : (c == 2 ? v.z : v.w)); }
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------------------
+// 1. estimator -> packed operand.  One workgroup: one k-step (64 / 128 tokens) x 128 channels.
 template <bool FP8>
 __global__ void __launch_bounds__(256)
-k_linear_wgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
-               const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, RngKey key,
-               int steps_per_split, float scale, int accumulate,
-               float* __restrict__ out, int64_t ld_out, int64_t split_stride) {
-  constexpr int EB = FP8 ? 1 : 2;               // bytes per element
-  constexpr int BK = FP8 ? 128 : 64;            // tokens per k-step
-  constexpr int B_STRIDE = BN * EB + 32;        // X tile row (one token) + pad
-  constexpr int GROUPS = BK / 4;                // token groups per k-step
-  __shared__ __align__(16) uint8_t sA[BM * A_STRIDE];
-  __shared__ __align__(16) uint8_t sM[BM * MB_STRIDE];
-  __shared__ __align__(16) uint8_t sB[BK * B_STRIDE];
+k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes, RngKey key,
+            uint8_t* __restrict__ vals, uint8_t* __restrict__ meta) {
+  constexpr int EB = FP8 ? 1 : 2;
+  constexpr int KS = FP8 ? 128 : 64;              // tokens per k-step
+  constexpr int GROUPS = KS / 4;                  // 16 / 32 token groups per k-step
+  constexpr int CH = 16 / EB;                     // channels per 16-byte chunk: 8 / 16
+  constexpr int OC = 128 / CH;                    // chunks across the 128 channels: 16 / 8
+  constexpr int GPQ = GROUPS / 4;                 // groups per lane quarter: 4 / 8
+  constexpr int MBLK = FP8 ? 256 : 128;           // metadata bytes per block
+  __shared__ __align__(16) uint8_t sV[8 * 1024];
+  __shared__ __align__(16) uint8_t sN[128 * GROUPS];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int j = lane & 15, q = lane >> 4;
-  const int64_t o0 = (int64_t)blockIdx.x * BM, i0 = (int64_t)blockIdx.y * BN;
-  const int64_t total_steps = T / BK;
-  const int64_t step_begin = (int64_t)blockIdx.z * steps_per_split;
-  int64_t step_end = step_begin + steps_per_split;
-  if (step_end > total_steps) step_end = total_steps;
+  const int tid = threadIdx.x;
+  const int kg = tid / OC, oc = tid % OC;
+  const int64_t s = blockIdx.y, steps = T / KS;
+  const int64_t o0 = (int64_t)blockIdx.x * 128;
+  const int64_t och = o0 + (int64_t)oc * CH;
 
-  f32x4 acc[4][4];
+  uint4 rdy[4];
+  if (och < O) {
+    const uint8_t* p = dY + (s * KS + 4 * kg) * lddy_bytes + och * EB;
 #pragma unroll
-  for (int a = 0; a < 4; a++)
+    for (int r = 0; r < 4; r++) rdy[r] = *(const uint4*)(p + r * lddy_bytes);
+  } else {
 #pragma unroll
-    for (int b = 0; b < 4; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-  // dY tile: a lane owns 4 tokens (one group) x 16 bytes of channels (8 bf16 / 16 fp8 channels)
-  constexpr int OC = BM * EB / 16;              // 16-byte channel chunks per tile row: 16 (bf16) / 8 (fp8)
-  const int kg = tid / OC, oc = tid % OC;       // kg in [0, GROUPS): 256 / OC == GROUPS for both types
-  constexpr int CH = 16 / EB;                   // channels per chunk
-  // X tile: BK rows of BN * EB bytes
-  constexpr int XCHUNKS = BK * BN * EB / 16 / 256;   // 16-byte chunks per lane: 4 (bf16) / 4 (fp8)
-  constexpr int XPR = BN * EB / 16;                  // chunks per row: 16 / 8
-
-  uint4 rdy[4], rx[XCHUNKS];
-
-  // Columns past the end of the matrix are read from column chunk 0 (always mapped) and then zeroed,
-  // so the loads need no branch.
-  const bool okdy = (o0 + (int64_t)oc * CH) < O;
-  const uint8_t* pdy = dY + (int64_t)(4 * kg) * lddy_bytes + (okdy ? (o0 + (int64_t)oc * CH) : 0) * EB;
-  const uint8_t* px[XCHUNKS];
-  bool okx[XCHUNKS];
-#pragma unroll
-  for (int r = 0; r < XCHUNKS; r++) {
-    int c = tid + 256 * r, row = c / XPR, part = c % XPR;
-    okx[r] = (i0 + (int64_t)part * CH) < I;
-    px[r] = X + (int64_t)row * ldx_bytes + (okx[r] ? (i0 + (int64_t)part * CH) : 0) * EB;
+    for (int r = 0; r < 4; r++) rdy[r] = make_uint4(0, 0, 0, 0);
   }
-
-#define WG_LOAD_GLOBAL(step)                                                                  \
-  do {                                                                                        \
-    int64_t tb_ = (int64_t)(step) * BK;                                                       \
-    _Pragma("unroll") for (int r = 0; r < 4; r++) {                                           \
-      uint4 v = *(const uint4*)(pdy + (tb_ + r) * lddy_bytes);                                \
-      rdy[r] = okdy ? v : make_uint4(0, 0, 0, 0);                                             \
-    }                                                                                         \
-    _Pragma("unroll") for (int r = 0; r < XCHUNKS; r++) {                                     \
-      uint4 v = *(const uint4*)(px[r] + tb_ * ldx_bytes);                                     \
-      rx[r] = okx[r] ? v : make_uint4(0, 0, 0, 0);                                            \
-    }                                                                                         \
-  } while (0)
-
-  // The estimator on the lane's CH groups (tokens 4 kg .. 4 kg + 3 of CH channels), written to LDS in
-  // the layout the sparse MFMA reads, then the X tile.
-#define WG_SPARSIFY_AND_STORE(step)                                                           \
-  do {                                                                                        \
-    uint64_t gid_base = (uint64_t)((int64_t)(step) * GROUPS + kg) * (uint64_t)O + (uint64_t)(o0 + (int64_t)oc * CH); \
-    _Pragma("unroll") for (int e = 0; e < CH; e++) {                                          \
-      uint64_t gid = gid_base + e;                                                            \
-      uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));            \
-      uint32_t nib, v;                                                                        \
-      int row = oc * CH + e;                                                                  \
-      if (FP8) {                                                                              \
-        uint32_t w0 = comp(rdy[0], e >> 2), w1 = comp(rdy[1], e >> 2);                        \
-        uint32_t w2 = comp(rdy[2], e >> 2), w3 = comp(rdy[3], e >> 2);                        \
-        int sh = 8 * (e & 3);                                                                 \
-        uint32_t g = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24); \
-        v = mvue_group_e4m3(g, x, nib);                                                       \
-        *(uint16_t*)(sA + row * A_STRIDE + 2 * kg) = (uint16_t)v;                             \
-      } else {                                                                                \
-        uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;                                   \
-        uint32_t lo = __builtin_amdgcn_perm(comp(rdy[1], e >> 1), comp(rdy[0], e >> 1), sel); \
-        uint32_t hi = __builtin_amdgcn_perm(comp(rdy[3], e >> 1), comp(rdy[2], e >> 1), sel); \
-        v = mvue_group_bf16(lo, hi, x, nib);                                                  \
-        *(uint32_t*)(sA + row * A_STRIDE + 4 * kg) = v;                                       \
-      }                                                                                       \
-      /* nibble pre-shifted to its place inside the byte pair: consumers OR neighbouring bytes */ \
-      sM[row * MB_STRIDE + kg] = (uint8_t)(nib << (4 * (kg & 1)));                            \
-    }                                                                                         \
-    _Pragma("unroll") for (int r = 0; r < XCHUNKS; r++) {                                     \
-      int c = tid + 256 * r, row = c / XPR, part = c % XPR;                                   \
-      *(uint4*)(sB + row * B_STRIDE + part * 16) = rx[r];                                     \
-    }                                                                                         \
-  } while (0)
-
-  if (step_begin < step_end) WG_LOAD_GLOBAL(step_begin);
-  for (int64_t step = step_begin; step < step_end; step++) {
-    WG_SPARSIFY_AND_STORE(step);
-    __syncthreads();
-    if (step + 1 < step_end) WG_LOAD_GLOBAL(step + 1);
-
-    uint4 fa[4];
-    int fidx[4];
+  const uint64_t gid_base = (uint64_t)(s * GROUPS + kg) * (uint64_t)O + (uint64_t)och;
+  const int q = kg / GPQ, g = kg % GPQ;
 #pragma unroll
-    for (int mi = 0; mi < 4; mi++) {
-      int row = 64 * wm + 16 * mi + j;
-      fa[mi] = *(const uint4*)(sA + row * A_STRIDE + 16 * q);
+  for (int e = 0; e < CH; e++) {
+    uint64_t gid = gid_base + e;
+    uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));
+    uint32_t nib, v;
+    int c = oc * CH + e;                           // channel inside the tile
+    uint8_t* slot = sV + (c >> 4) * 1024 + (16 * q + (c & 15)) * 16;
+    if (FP8) {
+      uint32_t w0 = comp4(rdy[0], e >> 2), w1 = comp4(rdy[1], e >> 2), w2 = comp4(rdy[2], e >> 2), w3 = comp4(rdy[3], e >> 2);
+      int sh = 8 * (e & 3);
+      uint32_t gw = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24);
+      v = mvue_group_e4m3(gw, x, nib);
+      *(uint16_t*)(slot + 2 * g) = (uint16_t)v;
+    } else {
+      uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      uint32_t lo = __builtin_amdgcn_perm(comp4(rdy[1], e >> 1), comp4(rdy[0], e >> 1), sel);
+      uint32_t hi = __builtin_amdgcn_perm(comp4(rdy[3], e >> 1), comp4(rdy[2], e >> 1), sel);
+      v = mvue_group_bf16(lo, hi, x, nib);
+      *(uint32_t*)(slot + 4 * g) = v;
+    }
+    sN[c * GROUPS + kg] = (uint8_t)(nib << (4 * (kg & 1)));   // pre-shifted: neighbours are OR-ed below
+  }
+  __syncthreads();
+
+  const int64_t rb0 = o0 / 16, rbn = (O + 15) / 16;
+#pragma unroll
+  for (int it = 0; it < 2; it++) {
+    int ci = tid + 256 * it, rb = ci >> 6, sl = ci & 63;     // block and slot inside the tile
+    if (rb0 + rb < rbn) {
+      int64_t blk = (rb0 + rb) * steps + s;
+      *(uint4*)(vals + blk * 1024 + sl * 16) = *(const uint4*)(sV + ci * 16);
+      int c = rb * 16 + (sl & 15), qq = sl >> 4;
       if (FP8) {
-        // 8 groups per lane: bytes b0..b7, odd ones pre-shifted by 4
-        uint2 w = *(const uint2*)(sM + row * MB_STRIDE + 8 * q);
+        uint2 w = *(const uint2*)(sN + c * GROUPS + 8 * qq);
         uint32_t a = w.x | (w.x >> 8), b = w.y | (w.y >> 8);
-        fidx[mi] = (int)((a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u));
+        uint32_t idx = (a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u);
+        *(uint32_t*)(meta + blk * MBLK + sl * 4) = idx;
       } else {
-        uint32_t w = *(const uint32_t*)(sM + row * MB_STRIDE + 4 * q);
+        uint32_t w = *(const uint32_t*)(sN + c * GROUPS + 4 * qq);
         uint32_t a = w | (w >> 8);
-        fidx[mi] = (int)((a & 0xFFu) | ((a >> 8) & 0xFF00u));
+        *(uint16_t*)(meta + blk * MBLK + sl * 2) = (uint16_t)((a & 0xFFu) | ((a >> 8) & 0xFF00u));
       }
     }
+  }
+}
+
+static void launch_mvue_pack(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key, void* vals,
+                             void* meta, hipStream_t s, int timed_kind) {
+  bool fp8 = dtype == SSTE_F8E4M3;
+  int ks = fp8 ? 128 : 64;
+  dim3 grid((unsigned)((O + 127) / 128), (unsigned)(T / ks)), block(256);
+  if (fp8) {
+    if (timed_kind >= 0) SSTE_LAUNCH(timed_kind, (k_mvue_pack<true>), grid, block, s, (const uint8_t*)dY, T, O, lddy, key, (uint8_t*)vals, (uint8_t*)meta);
+    else hipLaunchKernelGGL((k_mvue_pack<true>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy, key, (uint8_t*)vals, (uint8_t*)meta);
+  } else {
+    if (timed_kind >= 0) SSTE_LAUNCH(timed_kind, (k_mvue_pack<false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, key, (uint8_t*)vals, (uint8_t*)meta);
+    else hipLaunchKernelGGL((k_mvue_pack<false>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy * 2, key, (uint8_t*)vals, (uint8_t*)meta);
+  }
+}
+
+hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,
+                                   void* vals, void* meta, hipStream_t s) {
+  if (T == 0 || O == 0) return hipSuccess;
+  launch_mvue_pack(dY, T, O, lddy, dtype, key, vals, meta, s, -1);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// 2. sparse GEMM on the packed operand.  256 (o) x 256 (i) per workgroup of 8 waves (2 x 4), 3-stage ring.
+template <bool FP8, int NS>
+__global__ void __launch_bounds__(512, 1)
+k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t O, int64_t total_steps,
+             const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, int steps_per_split, float scale,
+             int accumulate, float* __restrict__ out, int64_t ld_out, int64_t split_stride, int m_tiles, int n_tiles) {
+  constexpr int WM = 2, WN = 4, NW = 8;
+  constexpr int BM = 256, BN = 256;
+  constexpr int EB = FP8 ? 1 : 2;
+  constexpr int KS = FP8 ? 128 : 64;              // tokens per k-step
+  constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
+  constexpr int ROWB = BN * EB;                   // bytes of one token row of the X tile: 512 / 256
+  constexpr int A_BYTES = BM * 64, B_BYTES = KS * ROWB, M_BYTES = BM * MB;
+  constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
+  constexpr int LA = BM / 16 / NW, LB = B_BYTES / 1024 / NW, LM = M_BYTES / 256 / NW;
+  constexpr int LPW = LA + LB + LM;
+  constexpr int RPL = 1024 / ROWB;                // token rows per 1 KiB load: 2 / 4
+  constexpr int CPR = ROWB / 16;                  // 16-byte chunks per row: 32 / 16
+  __shared__ __align__(1024) uint8_t smem[NS * STAGE];
+
+  // tile order: XCD x owns a contiguous range of (tile, split) units, channel tiles fastest
+  const int bid = blockIdx.x, nblk = gridDim.x;
+  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
+  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
+  const int logical = (rem == 0 || xcd < rem) ? xcd * per_xcd + slot
+                                              : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+  const int tiles = m_tiles * n_tiles;
+  const int z = logical / tiles, tile = logical % tiles;
+  const int tm = tile % m_tiles, tn = tile / m_tiles;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t o0 = (int64_t)tm * BM, i0 = (int64_t)tn * BN;
+  const int64_t step_begin = (int64_t)z * steps_per_split;
+  int64_t step_end = step_begin + steps_per_split;
+  if (step_end > total_steps) step_end = total_steps;
+  const int nsteps = (int)(step_end - step_begin);
+
+  const int64_t rblk0 = o0 / 16, rbn = (O + 15) / 16;
+  const int blks_a = (int)((rbn - rblk0) < BM / 16 ? (rbn - rblk0) : BM / 16);
+  const i32x4 ba = rsrc_words(vals + (rblk0 * total_steps + step_begin) * 1024, (uint32_t)((blks_a * total_steps - step_begin) * 1024));
+  const i32x4 bm = rsrc_words(meta + (rblk0 * total_steps + step_begin) * MBLK, (uint32_t)((blks_a * total_steps - step_begin) * MBLK));
+  const int cols_b = (int)((I - i0) < BN ? (I - i0) : BN);
+  const i32x4 bb = rsrc_words(X + step_begin * KS * ldx_bytes + i0 * EB, (uint32_t)(((int64_t)nsteps * KS - 1) * ldx_bytes + cols_b * EB));
+
+  uint32_t offa[LA], offb[LB], offm[LM];
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++) {
-      int n0 = 64 * wn + 16 * ni;
-      uint2 piece[4];
+  for (int i = 0; i < LA; i++) offa[i] = (uint32_t)((LA * wave + i) * total_steps * 1024 + lane * 16);
+#pragma unroll
+  for (int i = 0; i < LB; i++) {
+    int wl = LB * wave + i;
+    int r = RPL * wl + lane / CPR, cs = lane % CPR;          // token row inside the k-step, stored chunk
+    int c = FP8 ? (cs ^ (r & 15)) : ((((cs >> 1) ^ (r & 15)) << 1) | (cs & 1));   // source chunk
+    // chunks past the last feature column must read as zeros: push them out of the descriptor
+    offb[i] = (c * 16 < cols_b * EB) ? (uint32_t)(r * ldx_bytes + c * 16) : 0x80000000u;
+  }
+#pragma unroll
+  for (int i = 0; i < LM; i++) {
+    int d = 64 * (LM * wave + i) + lane;
+    offm[i] = (uint32_t)((d / (MBLK / 4)) * total_steps * MBLK + 4 * (d % (MBLK / 4)));
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
+
+#define WG_ISSUE(step, stg)                                                                            \
+  do {                                                                                                 \
+    const bool live_ = (step) < nsteps;                                                                \
+    const uint32_t sa_ = live_ ? (uint32_t)(step) * 1024u : 0x40000000u;                               \
+    const uint32_t sb_ = live_ ? (uint32_t)((step) * KS * ldx_bytes) : 0x40000000u;                    \
+    const uint32_t sm_ = live_ ? (uint32_t)(step) * (uint32_t)MBLK : 0x40000000u;                      \
+    const uint32_t base_ = lds0 + (uint32_t)(stg) * STAGE;                                             \
+    _Pragma("unroll") for (int i = 0; i < LA; i++) dma_b128(ba, base_ + (LA * wave + i) * 1024, offa[i], sa_); \
+    _Pragma("unroll") for (int i = 0; i < LB; i++) dma_b128(bb, base_ + A_BYTES + (LB * wave + i) * 1024, offb[i], sb_); \
+    _Pragma("unroll") for (int i = 0; i < LM; i++) dma_b32(bm, base_ + A_BYTES + B_BYTES + (LM * wave + i) * 256, offm[i], sm_); \
+  } while (0)
+
+  f32x4 acc[MI][NI];
+#pragma unroll
+  for (int a = 0; a < MI; a++)
+#pragma unroll
+    for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const uint32_t fa_off = (uint32_t)(8 * wm * 1024 + lane * 16);
+  const uint32_t fm_off = (uint32_t)(A_BYTES + B_BYTES + 8 * wm * MBLK + lane * (MB / 4));
+  // transposing reads of X: piece r of tile ni covers tokens k0 .. k0 + 3 (bf16) / k0 .. k0 + 7 (fp8)
+  uint32_t fb_off[4];
+#pragma unroll
+  for (int r = 0; r < 4; r++) {
+    if (FP8) {
+      int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
+      int c = (64 * wn) / 16;                                   // + ni
+      fb_off[r] = (uint32_t)(A_BYTES + row * ROWB + ((c ^ (row & 15)) * 16) + 8 * (j & 1));
+    } else {
+      int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
+      int p = (64 * wn) / 16;                                   // + ni   (32-byte pair index)
+      fb_off[r] = (uint32_t)(A_BYTES + row * ROWB + ((p ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+    }
+  }
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; s++) WG_ISSUE(s, s);
+
+  int stg = 0;
+  for (int step = 0; step < nsteps; step++) {
+    wait_vmcnt<(NS - 2) * LPW>();
+    __syncthreads();
+    const uint8_t* sb = smem + stg * STAGE;
+    uint2 fb[NI][4];
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++)
 #pragma unroll
       for (int r = 0; r < 4; r++) {
+        // tile ni shifts the (swizzled) chunk / pair index by ni: XOR-ing ni into the stored index
+        // equals adding it because the base index 4 wn has its two low bits clear
         if (FP8) {
-          // piece r holds 8 consecutive tokens: k0 = 16 q + 8 (r & 1) + 64 (r >> 1);
-          // source lane s of the 16-lane block addresses row k0 + s / 2, columns n0 + 8 (s % 2) ..
-          int k0 = 16 * q + 8 * (r & 1) + 64 * (r >> 1);
-          const uint8_t* p = sB + (k0 + (j >> 1)) * B_STRIDE + (n0 + 8 * (j & 1));
+          int row_lo = (16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1)) & 15;
+          (void)row_lo;
+          const uint8_t* p = sb + (fb_off[r] ^ (uint32_t)(ni * 16));
           i32x2 t = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)p);
-          piece[r].x = (uint32_t)t[0];
-          piece[r].y = (uint32_t)t[1];
+          fb[ni][r] = make_uint2((uint32_t)t[0], (uint32_t)t[1]);
         } else {
-          // piece r holds 4 consecutive tokens: k0 = 8 q + 4 (r & 1) + 32 (r >> 1);
-          // source lane s addresses row k0 + s / 4, columns n0 + 4 (s % 4) ..
-          int k0 = 8 * q + 4 * (r & 1) + 32 * (r >> 1);
-          const uint8_t* p = sB + (k0 + (j >> 2)) * B_STRIDE + (n0 + 4 * (j & 3)) * 2;
+          const uint8_t* p = sb + (fb_off[r] ^ (uint32_t)(ni * 32));
           bf16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-          __builtin_memcpy(&piece[r], &t, 8);
+          __builtin_memcpy(&fb[ni][r], &t, 8);
         }
       }
+    uint4 fa[MI];
+    int fidx[MI];
 #pragma unroll
-      for (int mi = 0; mi < 4; mi++) {
+    for (int mi = 0; mi < MI; mi++) {
+      fa[mi] = *(const uint4*)(sb + fa_off + mi * 1024);
+      if (FP8) fidx[mi] = *(const int*)(sb + fm_off + mi * MBLK);
+      else fidx[mi] = *(const uint16_t*)(sb + fm_off + mi * MBLK);
+    }
+    {
+      int nstg = stg + NS - 1;
+      if (nstg >= NS) nstg -= NS;
+      WG_ISSUE(step + NS - 1, nstg);
+    }
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++) {
         if (FP8) {
           i32x4 av;
           i32x8 bv;
           __builtin_memcpy(&av, &fa[mi], 16);
-          __builtin_memcpy(&bv, &piece[0], 32);
+          __builtin_memcpy(&bv, &fb[ni][0], 32);
           acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
         } else {
           bf16x8 av;
           bf16x16 bv;
           __builtin_memcpy(&av, &fa[mi], 16);
-          __builtin_memcpy(&bv, &piece[0], 32);
+          __builtin_memcpy(&bv, &fb[ni][0], 32);
           acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx[mi], 0, 0);
         }
       }
     }
-    __syncthreads();
+    stg = (stg + 1 == NS) ? 0 : stg + 1;
   }
-
-#undef WG_LOAD_GLOBAL
-#undef WG_SPARSIFY_AND_STORE
+#undef WG_ISSUE
+  wait_vmcnt<0>();
 
   // epilogue: lane (j, q) register r of tile (mi, ni) is element (o + r, i)
-  float* dst = out + (int64_t)blockIdx.z * split_stride;
+  float* dst = out + (int64_t)z * split_stride;
 #pragma unroll
-  for (int mi = 0; mi < 4; mi++)
+  for (int mi = 0; mi < MI; mi++)
 #pragma unroll
-    for (int ni = 0; ni < 4; ni++) {
-      int64_t o = o0 + 64 * wm + 16 * mi + 4 * q;
+    for (int ni = 0; ni < NI; ni++) {
+      int64_t o = o0 + 128 * wm + 16 * mi + 4 * q;
       int64_t i = i0 + 64 * wn + 16 * ni + j;
       if (i < I) {
 #pragma unroll
@@ -220,7 +320,8 @@ k_linear_wgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
     }
 }
 
-// out[o][i] = scale * sum_z ws[z][o][i]  (+ out[o][i]); z ascending: a fixed order.
+// ---------------------------------------------------------------------------------------------------------
+// 3. out[o][i] = scale * sum_z ws[z][o][i]  (+ out[o][i]); z ascending: a fixed order.
 __global__ void __launch_bounds__(256)
 k_wgrad_reduce(const float* __restrict__ ws, int splits, int64_t O, int64_t I, float scale, int accumulate,
                float* __restrict__ dW, int64_t lddw) {
@@ -248,16 +349,60 @@ k_zero_rows(float* __restrict__ dW, int64_t O, int64_t I, int64_t lddw) {
   }
 }
 
-int wgrad_splits(int64_t T, int64_t O, int64_t I, int dtype) {
-  int bk = (dtype == SSTE_F8E4M3) ? 128 : 64;
-  int64_t steps = T / bk;
-  int64_t tiles = ((O + BM - 1) / BM) * ((I + BN - 1) / BN);
-  if (tiles <= 0 || steps <= 0) return 1;
-  int64_t s = (WG_TARGET + tiles - 1) / tiles;
-  if (s > steps / MIN_STEPS_PER_SPLIT) s = steps / MIN_STEPS_PER_SPLIT;
-  if (s > MAX_SPLITS) s = MAX_SPLITS;
+// ---------------------------------------------------------------------------------------------------------
+// host: path choice, split choice, workspace layout
+struct WgradPlan {
+  bool packed;          // true: estimator pre-pass + GEMM on the packed operand; false: fused kernel
+  int splits;           // token-axis splits
+  int steps_per_split;
+  size_t vals_bytes, meta_bytes, partial_bytes;   // workspace sections (each a multiple of 256)
+};
+
+static size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
+static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
+  WgradPlan p{};
+  bool fp8 = dtype == SSTE_F8E4M3;
+  int ks = fp8 ? 128 : 64;
+  int64_t steps = T / ks;
+  // the pre-pass pays off once the GEMM tiles would re-derive each group several times and the problem
+  // is large enough to fill the chip; everything else runs the fused kernel
+  p.packed = (T >= 2048) && (O >= 256) && (I >= 256) && ((T * ((O + 15) / 16 * 16)) < (1ll << 40));
+  if (steps <= 0) {
+    p.splits = 1;
+    p.steps_per_split = 1;
+    return p;
+  }
+  int64_t tile = p.packed ? 256 : 128;
+  int64_t tiles = ((O + tile - 1) / tile) * ((I + tile - 1) / tile);
+  int64_t target = p.packed ? NUM_CU : 2 * NUM_CU;
+  int64_t s = p.packed ? target / tiles : (target + tiles - 1) / tiles;
+  if (s > steps / 8) s = steps / 8;
+  if (s > 32) s = 32;
   if (s < 1) s = 1;
-  return (int)s;
+  int64_t sps = (steps + s - 1) / s;
+  s = (steps + sps - 1) / sps;                        // no empty split
+  p.splits = (int)s;
+  p.steps_per_split = (int)sps;
+  if (p.packed) {
+    int64_t rows = (O + 15) / 16 * 16;
+    p.vals_bytes = round256((size_t)rows * (size_t)(T / 2) * (fp8 ? 1 : 2));
+    p.meta_bytes = round256((size_t)rows * (size_t)(T / 8));
+  }
+  p.partial_bytes = s > 1 ? round256((size_t)s * (size_t)O * (size_t)I * sizeof(float)) : 0;
+  return p;
+}
+
+size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
+  WgradPlan p = wgrad_plan(T, O, I, dtype);
+  return p.vals_bytes + p.meta_bytes + p.partial_bytes;
+}
+
+bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype) {
+  int64_t eb = dtype == SSTE_F8E4M3 ? 1 : 2;
+  if (T * ldx * eb >= (1ll << 31)) return wgrad_plan(T, O, I, dtype).packed ? false : true;   // 32-bit offsets in the GEMM
+  if (((O + 127) / 128) * ((I + 127) / 128) * 32 > 0x7FFFFFFFll) return false;
+  return true;
 }
 
 hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
@@ -265,8 +410,8 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
                                int accumulate, void* ws, hipStream_t s) {
   if (O == 0 || I == 0) return hipSuccess;
   bool fp8 = dtype == SSTE_F8E4M3;
-  int bk = fp8 ? 128 : 64, eb = fp8 ? 1 : 2;
-  int64_t steps = T / bk;
+  int ks = fp8 ? 128 : 64, eb = fp8 ? 1 : 2;
+  int64_t steps = T / ks;
   if (steps == 0) {
     if (!accumulate) {
       int64_t blocks = (O * I + 255) / 256;
@@ -275,26 +420,36 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
     }
     return hipGetLastError();
   }
-  int splits = wgrad_splits(T, O, I, dtype);
-  int sps = (int)((steps + splits - 1) / splits);
-  splits = (int)((steps + sps - 1) / sps);            // drop empty tail splits
-  dim3 grid((unsigned)((O + BM - 1) / BM), (unsigned)((I + BN - 1) / BN), (unsigned)splits), block(256);
-  float* out = splits > 1 ? (float*)ws : dW;
-  int64_t ld_out = splits > 1 ? I : lddw;
-  int64_t split_stride = splits > 1 ? O * I : 0;
-  float k_scale = splits > 1 ? 1.0f : scale;
-  int k_acc = splits > 1 ? 0 : accumulate;
-  if (fp8)
-    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad<true>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
-                       ldx * eb, key, sps, k_scale, k_acc, out, ld_out, split_stride);
-  else
-    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad<false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
-                       ldx * eb, key, sps, k_scale, k_acc, out, ld_out, split_stride);
-  if (splits > 1) {
+  WgradPlan p = wgrad_plan(T, O, I, dtype);
+  uint8_t* wsb = (uint8_t*)ws;
+  float* partial = (float*)(wsb + p.vals_bytes + p.meta_bytes);
+  float* out = p.splits > 1 ? partial : dW;
+  int64_t ld_out = p.splits > 1 ? I : lddw;
+  int64_t split_stride = p.splits > 1 ? O * I : 0;
+  float k_scale = p.splits > 1 ? 1.0f : scale;
+  int k_acc = p.splits > 1 ? 0 : accumulate;
+  if (p.packed) {
+    uint8_t* vals = wsb;
+    uint8_t* meta = wsb + p.vals_bytes;
+    launch_mvue_pack(dY, T, O, lddy, dtype, key, vals, meta, s, SSTE_K_MVUE_PACK);
+    int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((I + 255) / 256);
+    dim3 grid((unsigned)(m_tiles * n_tiles * p.splits)), block(512);
+    if (fp8)
+      SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<true, 3>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
+                  (const uint8_t*)X, I, ldx * eb, p.steps_per_split, k_scale, k_acc, out, ld_out, split_stride, m_tiles, n_tiles);
+    else
+      SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<false, 3>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
+                  (const uint8_t*)X, I, ldx * eb, p.steps_per_split, k_scale, k_acc, out, ld_out, split_stride, m_tiles, n_tiles);
+  } else {
+    hipError_t e = launch_wgrad_fused(dY, T, O, lddy, dtype, X, I, ldx, key, p.splits, p.steps_per_split, k_scale, k_acc,
+                                      out, ld_out, split_stride, s);
+    if (e != hipSuccess) return e;
+  }
+  if (p.splits > 1) {
     int64_t blocks = (O * (I / 4) + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    SSTE_LAUNCH(SSTE_K_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)blocks), dim3(256), s, (const float*)ws, splits, O, I, scale,
-                       accumulate, dW, lddw);
+    SSTE_LAUNCH(SSTE_K_WGRAD_REDUCE, k_wgrad_reduce, dim3((unsigned)blocks), dim3(256), s, (const float*)partial, p.splits, O, I,
+                scale, accumulate, dW, lddw);
   }
   return hipGetLastError();
 }

@@ -94,7 +94,7 @@ def test_linear_wgrad_validation_and_workspace(lib):
     assert f(*args(dy=None)) == 1
     # a problem that needs split partial sums refuses a missing / small workspace
     need = lib.sste_wgrad_workspace_bytes(8192, 3072, 768, 0)
-    assert need > 0 and need % (3072 * 768 * 4) == 0
+    assert need >= 2 * 3072 * 768 * 4
     assert f(*args(T=8192, O=3072, I=768, lddy=3072, ldx=768, lddw=768)) == 6
     assert f(*args(T=8192, O=3072, I=768, lddy=3072, ldx=768, lddw=768, ws=fake, wsb=need - 1)) == 6
     assert lib.sste_wgrad_workspace_bytes(512, 256, 1024, 0) == 0

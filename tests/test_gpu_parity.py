@@ -247,9 +247,12 @@ def _wgrad_case(sste, dtype, T, O, I, seed=3, offset=5, **kw):
     ("bf16", 64, 8, 8),              # one k-step, one partial tile
     ("bf16", 192, 136, 200),         # ragged O and I tails
     ("bf16", 4096, 128, 128),        # one tile, token axis split across workgroups
+    ("bf16", 2048, 264, 328),        # estimator pre-pass + packed GEMM, ragged channel and feature tails
+    ("bf16", 4096, 512, 256),        # pre-pass path, several tiles and splits
     ("e4m3", 512, 256, 1024),
     ("e4m3", 256, 144, 80),
     ("e4m3", 8192, 128, 128),
+    ("e4m3", 2048, 272, 320),        # pre-pass path, ragged tails
 ])
 def test_linear_wgrad_matches_oracle(sste, dtype, T, O, I):
     dW, ref = _wgrad_case(sste, dtype, T, O, I)
