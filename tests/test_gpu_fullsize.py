@@ -1,0 +1,134 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times.
+
+The packed weight is compared bit for bit in full (the oracle packs a whole layer in about a second).
+For the GEMMs the oracle computes sampled outputs one by one from the definition: a forward sample is
+the float64 dot product of one activation row with one decoded weight row; a weight-gradient sample is
+the float64 dot product of one sparsified gradient column (the oracle's own estimator on that column,
+same seed / offset / group ids) with one activation column.  The sparsified operand itself is compared
+bit for bit on sampled channels.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import formats as F
+from oracle import mvue as OM
+from oracle import projection as OP
+from oracle import rng as OR
+from paper_2409_09099_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 1e-2, "e4m3": 6e-2}
+CASES = [(2, 0), (3, 0), (3, 1), (4, 0), (4, 1), (4, 2), (4, 3), (5, 0), (5, 2), (5, 3)]
+
+
+@pytest.fixture(scope="module")
+def sste():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2409_09099_amd as lib
+    lib.library()
+    return lib
+
+
+def up(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(a.view(np.int16))).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def decode(codes, dtype):
+    return (F.bf16_to_f32(codes) if dtype == "bf16" else F.e4m3_to_f32(codes)).astype(np.float64)
+
+
+def oracle_theta_column(dy_codes, o, seed, offset, dtype):
+    """The oracle's sparsified gradient for channel o as a dense (T,) float64 vector of stored values."""
+    T, O = dy_codes.shape
+    g = dy_codes[:, o].reshape(T // 4, 4)
+    gids = np.arange(T // 4, dtype=np.uint64) * np.uint64(O) + np.uint64(o)
+    u = OR.uniform24(seed, offset, gids)
+    vals, nib = OM.mvue_groups_bits(g, u, dtype)
+    v = decode(vals, dtype)
+    theta = np.zeros((T // 4, 4))
+    rows = np.arange(T // 4)
+    theta[rows, nib & 3] = v[:, 0]
+    theta[rows, nib >> 2] = v[:, 1]
+    return theta.reshape(T), vals, nib
+
+
+@pytest.mark.parametrize("cfg,layer", CASES)
+def test_full_size_layer(sste, cfg, layer):
+    wl = WL.WORKLOADS[cfg]
+    L = wl.layers[layer]
+    T, O, I, dtype = wl.T, L.O, L.I, wl.dtype
+    dt = sste.BF16 if dtype == "bf16" else sste.F8E4M3
+    rs = np.random.default_rng(100 * cfg + layer)
+    print(f"cfg {cfg} layer {L.name}: T={T} O={O} I={I} {dtype}", flush=True)
+
+    wb = WL.weight_bits(wl, layer)
+    xc, xs = WL.activations(wl, layer)
+    dyc, dys = WL.output_gradient(wl, layer)
+    W, X, dY = up(wb), up(xc), up(dyc)
+
+    # ---- beta and project + pack: whole layer, bit for bit
+    beta = float(sste.compute_beta(W).cpu()[0])
+    beta_ref = OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64))
+    assert abs(beta - beta_ref) <= 1e-5 * beta_ref
+    assert 1.45 < beta_ref < 1.52                       # i.i.d. Gaussian weights
+    beta32 = np.float32(beta_ref)
+    if dtype == "bf16":
+        ws = np.float32(1.0)
+        rv, rm, _ = OP.project_pack(wb, beta32)
+    else:
+        _, _, amax = OP.project_pack(wb, beta32)
+        ws = np.float32(float(amax) / 448.0)
+        rv, rm, _ = OP.project_pack(wb, beta32, "e4m3", ws)
+    vals, meta = sste.project_pack(W, float(beta32), dt, float(ws))
+    fv, fm = OP.to_fragment_major(rv, rm, dtype)
+    assert np.array_equal(vals.cpu().numpy().view(rv.dtype).reshape(-1), fv)
+    assert np.array_equal(meta.cpu().numpy().reshape(-1), fm)
+
+    # ---- forward: sampled outputs from the definition
+    Z = sste.linear_fwd(X, vals, meta, O, dt, float(xs), float(ws))
+    Wd = OP.decode_packed(rv, rm, dtype)
+    Xf = decode(xc, dtype)
+    ts = np.concatenate([rs.integers(0, T, 60), [0, T - 1, 127, 128]])
+    os_ = np.concatenate([rs.integers(0, O, 60), [0, O - 1, 255, 256]])
+    ref = np.einsum("ni,ni->n", Xf[ts], Wd[os_]) * float(np.float32(xs)) * float(np.float32(ws))
+    got = Z[torch.from_numpy(ts).cuda(), torch.from_numpy(os_).cuda()].float().cpu().numpy().astype(np.float64)
+    zmax = float(Z.float().abs().max())
+    assert np.max(np.abs(got - ref)) <= TOL[dtype] * zmax, (np.max(np.abs(got - ref)), zmax)
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-4 * zmax       # bf16 output rounding
+    # every output row / column block was written: no stale memory in the result
+    assert torch.isfinite(Z.float()).all()
+
+    # ---- sparsified operand on sampled channels, bit for bit
+    seed, offset = cfg, 7
+    tv, tm = sste.mvue_materialize(dY, seed, offset, dt)
+    gv, gm = OP.from_fragment_major(tv.cpu().numpy().view(rv.dtype).reshape(-1), tm.cpu().numpy().reshape(-1), O, T, dtype)
+    chans = np.concatenate([rs.integers(0, O, 12), [0, O - 1]])
+    thetas = {}
+    for o in chans:
+        theta, ovals, onib = oracle_theta_column(dyc, int(o), seed, offset, dtype)
+        thetas[int(o)] = theta
+        assert np.array_equal(gv[o].reshape(-1, 2), ovals), o
+        nib_gpu = np.stack([gm[o] & 0xF, gm[o] >> 4], axis=1).reshape(-1)
+        assert np.array_equal(nib_gpu, onib), o
+
+    # ---- weight gradient: sampled outputs from the definition
+    dW = sste.linear_wgrad(dY, X, seed, offset, dt, float(dys), float(xs))
+    scale = float(np.float32(dys)) * float(np.float32(xs)) * (2.0 if dtype == "e4m3" else 1.0)
+    dmax = float(dW.abs().max())
+    worst = 0.0
+    for o in chans:
+        cols = np.concatenate([rs.integers(0, I, 6), [0, I - 1]])
+        ref = (thetas[int(o)] @ Xf[:, cols]) * scale
+        got = dW[int(o)].cpu().numpy().astype(np.float64)[cols]
+        worst = max(worst, float(np.max(np.abs(got - ref))))
+    assert worst <= TOL[dtype] * dmax, (worst, dmax)
+    assert worst <= 1e-4 * dmax                       # identical sparse operand: only fp32 summation order differs
+    assert torch.isfinite(dW).all()
+    # run-to-run bitwise reproducible (fixed-order split reduction)
+    dW2 = sste.linear_wgrad(dY, X, seed, offset, dt, float(dys), float(xs))
+    assert torch.equal(dW, dW2)
