@@ -21,6 +21,16 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0
 PEAK_DENSE_TFLOPS = {"bf16": 2500.0, "e4m3": 5000.0}
 
+# HBM bytes per launch on the headline workload, from two rocprofv3 --pmc runs of this file (FETCH_SIZE
+# scaled by 2.000, WRITE_SIZE by 1.000: what a plain 256 MiB copy reads on the same counters); the
+# summary with the commands is committed under profiles/.  KiB read + KiB written.
+HBM_TRAFFIC_KIB = {
+    (2, "project_pack"): 4658 + 2592,
+    (2, "fwd"): 55410 + 49152,
+    (2, "mvue_pack"): 49251 + 27648,
+    (2, "wgrad"): 64816 + 64516,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -31,6 +41,8 @@ def parse():
     ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
     ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies before the warm-up (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -128,6 +140,14 @@ def main():
         sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=dt, dy_scale=float(dys), x_scale=float(xs),
                           dW=dWs[s], workspace=wss[s])
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -181,6 +201,8 @@ def main():
         roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                     "frac": achieved / peak, "traffic": None}
     roofline["avg_launch_ms"] = kernels[dom]["ms"]
+    kib = HBM_TRAFFIC_KIB.get((wl.cfg, dom)) if args.layer == 0 else None
+    roofline["traffic"] = kib * 1024 if kib is not None else None
 
     out = {
         "metric": "S-STE 2:4 linear fwd+wgrad TFLOP/s (dense-equivalent, project+pack inside the step)",
