@@ -226,9 +226,10 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
                              const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
   if (T == 0 || O == 0) return hipSuccess;
   bool fp8 = dtype == SSTE_F8E4M3;
-  // 256 x 256 tiles once they fill the 256 CUs several times over, else 256 x 128
+  // 256 x 256 tiles (8 waves, 3-stage ring) unless the problem has too few of them to occupy the chip;
+  // measured faster than 256 x 128 even at 1.5 rounds of tiles (3072 x 8192 outputs: 33.6 vs 36.4 us)
   int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
-  if (big_tiles >= 1024) {
+  if (big_tiles >= 128) {
     if (fp8) launch_fwd_cfg<true, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
     else launch_fwd_cfg<false, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   } else {
