@@ -199,8 +199,217 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
     int row = 4 * it + (lane >> 4), chunk = lane & 15;
     uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
     int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 8 * chunk;
-    if (t < T && o < O) *(uint4*)(Z + t * ldz + o) = v;
+    if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
   }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Software-pipelined 256 x 256 variant (8 waves, 2 x 4).  The kernel above alternates, workgroup-wide,
+// between a phase that reads fragments from LDS and a phase that issues MFMAs; here the three pipes
+// (vector memory, LDS, matrix) run side by side within a k-step:
+//   * X fragments are double-buffered in registers: while the 32 MFMAs of k-step s run on one set, the
+//     set for k-step s + 1 is read from LDS, one 16-byte piece per group of four MFMAs;
+//   * packed-weight fragments roll through a two-deep register buffer, one row block ahead of its use;
+//   * the direct-to-LDS loads of a k-step are spread over the groups instead of issued in one burst.
+// Weight and X tiles live in separate three-slot rings because their LDS lifetimes differ: X of
+// k-step s is consumed during k-step s - 1, the weight tile of k-step s during s - 1 (row block 0)
+// and s.  At the single barrier of k-step s the tiles of s + 1 must have landed; the loads issued
+// during s are the weight tile of s + 2 and the X tile of s + 3.
+template <bool FP8>
+__global__ void __launch_bounds__(512, 1)
+k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
+                  const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
+  constexpr int WM = 2, WN = 4, NW = 8, BM = 256, BN = 256, NR = 3;
+  constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
+  constexpr int A_BYTES = BM * 64, M_BYTES = BM * MB, ASTAGE = A_BYTES + M_BYTES, BSTAGE = BN * 128;
+  constexpr int EPI_BYTES = NW * 64 * EPI_ROW;
+  constexpr int RING = NR * (ASTAGE + BSTAGE);
+  constexpr int SMEM = RING > EPI_BYTES ? RING : EPI_BYTES;
+  constexpr int LA = BM / 16 / NW, LB = BN / 8 / NW, LM = M_BYTES / 256 / NW;   // 2, 4, 1 (2 for fp8)
+  static_assert(LA == 2 && LB == 4 && (LM == 1 || LM == 2), "issue schedule below assumes these counts");
+  __shared__ __align__(1024) uint8_t smem[SMEM];
+  uint8_t* const smemA = smem;
+  uint8_t* const smemB = smem + NR * ASTAGE;
+
+  const int bid = blockIdx.x, nblk = gridDim.x;
+  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
+  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
+  const int logical = (rem == 0 || xcd < rem) ? xcd * per_xcd + slot
+                                              : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+  const int tm = logical % m_tiles, tn = logical / m_tiles;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t o0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
+  const int nsteps = (int)(k_bytes / 128);
+
+  const int64_t rblk0 = o0 / 16, rbn = (O + 15) / 16;
+  const int blks_a = (int)((rbn - rblk0) < BM / 16 ? (rbn - rblk0) : BM / 16);
+  const int rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
+  const i32x4 ba = rsrc_words(vals + rblk0 * nsteps * 1024, (uint32_t)(blks_a * nsteps * 1024));
+  const i32x4 bm = rsrc_words(meta + rblk0 * nsteps * MBLK, (uint32_t)(blks_a * nsteps * MBLK));
+  const i32x4 bb = rsrc_words(X + t0 * ldx_bytes, (uint32_t)((rows_b - 1) * ldx_bytes + k_bytes));
+
+  uint32_t offa[LA], offb[LB], offm[LM];
+#pragma unroll
+  for (int i = 0; i < LA; i++) offa[i] = (uint32_t)((LA * wave + i) * nsteps * 1024 + lane * 16);
+#pragma unroll
+  for (int i = 0; i < LB; i++) {
+    int wl = LB * wave + i;
+    int r = 8 * wl + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
+    offb[i] = (uint32_t)(r * ldx_bytes + c * 16);
+  }
+#pragma unroll
+  for (int i = 0; i < LM; i++) {
+    int d = 64 * (LM * wave + i) + lane;
+    offm[i] = (uint32_t)((d / (MBLK / 4)) * nsteps * MBLK + 4 * (d % (MBLK / 4)));
+  }
+  const uint32_t ldsA = (uint32_t)(uintptr_t)(lds_u8*)smemA;
+  const uint32_t ldsB = (uint32_t)(uintptr_t)(lds_u8*)smemB;
+  constexpr uint32_t DEAD = 0x40000000u;            // scalar offset past every descriptor: the load fetches nothing
+
+#define PIPE_DMA_A(i, step, slot_)                                                                        \
+  dma_b128(ba, ldsA + (uint32_t)(slot_) * ASTAGE + (LA * wave + (i)) * 1024, offa[i],                     \
+           (step) < nsteps ? (uint32_t)(step) * 1024u : DEAD)
+#define PIPE_DMA_M(i, step, slot_)                                                                        \
+  dma_b32(bm, ldsA + (uint32_t)(slot_) * ASTAGE + A_BYTES + (LM * wave + (i)) * 256, offm[i],             \
+          (step) < nsteps ? (uint32_t)(step) * (uint32_t)MBLK : DEAD)
+#define PIPE_DMA_B(i, step, slot_)                                                                        \
+  dma_b128(bb, ldsB + (uint32_t)(slot_) * BSTAGE + (LB * wave + (i)) * 1024, offb[i],                     \
+           (step) < nsteps ? (uint32_t)(step) * 128u : DEAD)
+
+  f32x4 acc[MI][NI];
+#pragma unroll
+  for (int a = 0; a < MI; a++)
+#pragma unroll
+    for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const uint32_t fa_off = (uint32_t)(8 * wm * 1024 + lane * 16);                    // + 1024 mi
+  const uint32_t fm_off = (uint32_t)(A_BYTES + 8 * wm * MBLK + lane * (MB / 4));      // + MBLK mi
+  const int rb0 = 64 * wn + j;                                                      // + 16 ni
+  const int cb0 = q ^ ((j >> 1) & 7);
+  const uint32_t fb_off0 = (uint32_t)(rb0 * 128 + cb0 * 16);
+  const uint32_t fb_off1 = (uint32_t)(rb0 * 128 + (cb0 ^ 4) * 16);
+
+  // prologue: weight tiles 0, 1 and X tiles 0, 1, 2 in flight, in the order the barriers expect
+#pragma unroll
+  for (int i = 0; i < LA; i++) PIPE_DMA_A(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < LM; i++) PIPE_DMA_M(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < LA; i++) PIPE_DMA_A(i, 1, 1);
+#pragma unroll
+  for (int i = 0; i < LM; i++) PIPE_DMA_M(i, 1, 1);
+#pragma unroll
+  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 1, 1);
+#pragma unroll
+  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 2, 2);
+
+  uint4 fb0[NI][2], fb1[NI][2];       // X fragments: current / next k-step, roles swap every k-step
+  uint4 fa[2];                        // packed-weight fragment of row block mi in fa[mi % 2]
+  int fidx[2];
+  wait_vmcnt<LA + LM + 2 * LB>();     // tiles of k-step 0 have landed
+  __syncthreads();
+#pragma unroll
+  for (int ni = 0; ni < NI; ni++) {
+    fb0[ni][0] = *(const uint4*)(smemB + fb_off0 + ni * 2048);
+    fb0[ni][1] = *(const uint4*)(smemB + fb_off1 + ni * 2048);
+  }
+  fa[0] = *(const uint4*)(smemA + fa_off);
+  if (FP8) fidx[0] = *(const int*)(smemA + fm_off);
+  else fidx[0] = *(const uint16_t*)(smemA + fm_off);
+
+  int s0 = 0, s1 = 1, s2 = 2;         // ring slots of k-steps step, step + 1, step + 2 (both rings)
+
+  // one k-step: MFMAs on BC, next X fragments into BX
+#define PIPE_STEP(BC, BX)                                                                                 \
+  do {                                                                                                    \
+    wait_vmcnt<LB>();                 /* all but the newest X tile: k-step step + 1 has landed */          \
+    __syncthreads();                  /* ... for every wave; slots of step - 1 (weights) and step (X) are free */ \
+    const uint8_t* pa = smemA + s0 * ASTAGE;                                                              \
+    const uint8_t* pa1 = smemA + s1 * ASTAGE;                                                             \
+    const uint8_t* pb1 = smemB + s1 * BSTAGE;                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < MI; mi++) {                                                   \
+      const uint8_t* an = mi < MI - 1 ? pa + (mi + 1) * 1024 : pa1;                                       \
+      const uint8_t* mn = mi < MI - 1 ? pa + (mi + 1) * MBLK : pa1;                                       \
+      fa[(mi + 1) & 1] = *(const uint4*)(an + fa_off);                                                    \
+      if (FP8) fidx[(mi + 1) & 1] = *(const int*)(mn + fm_off);                                           \
+      else fidx[(mi + 1) & 1] = *(const uint16_t*)(mn + fm_off);                                          \
+      BX[mi >> 1][mi & 1] = *(const uint4*)(pb1 + ((mi & 1) ? fb_off1 : fb_off0) + (mi >> 1) * 2048);     \
+      if (mi == 0) PIPE_DMA_A(0, step + 2, s2);                                                           \
+      if (mi == 1) PIPE_DMA_A(1, step + 2, s2);                                                           \
+      if (mi == 2) { _Pragma("unroll") for (int i = 0; i < LM; i++) PIPE_DMA_M(i, step + 2, s2); }        \
+      if (mi >= 3 && mi < 3 + LB) PIPE_DMA_B(mi - 3, step + 3, s0);                                       \
+      _Pragma("unroll") for (int ni = 0; ni < NI; ni++) {                                                 \
+        if (FP8) {                                                                                        \
+          i32x4 av;                                                                                       \
+          i32x8 bv;                                                                                       \
+          __builtin_memcpy(&av, &fa[mi & 1], 16);                                                         \
+          __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+        } else {                                                                                          \
+          bf16x8 av;                                                                                      \
+          bf16x16 bv;                                                                                     \
+          __builtin_memcpy(&av, &fa[mi & 1], 16);                                                         \
+          __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+        }                                                                                                 \
+      }                                                                                                   \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
+    const int t_ = s0;                                                                                    \
+    s0 = s1;                                                                                              \
+    s1 = s2;                                                                                              \
+    s2 = t_;                                                                                              \
+  } while (0)
+
+  int step = 0;
+  for (; step + 1 < nsteps; step += 2) {
+    PIPE_STEP(fb0, fb1);
+    step++;
+    PIPE_STEP(fb1, fb0);
+    step--;
+  }
+  if (step < nsteps) PIPE_STEP(fb0, fb1);
+#undef PIPE_STEP
+#undef PIPE_DMA_A
+#undef PIPE_DMA_M
+#undef PIPE_DMA_B
+
+  wait_vmcnt<0>();
+  __syncthreads();
+  uint8_t* eb = smem + wave * (64 * EPI_ROW);
+#pragma unroll
+  for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+    for (int ni = 0; ni < NI; ni++) {
+      uint2 v;
+      v.x = bf16_rne_pack(acc[mi][ni][0] * scale, acc[mi][ni][1] * scale);
+      v.y = bf16_rne_pack(acc[mi][ni][2] * scale, acc[mi][ni][3] * scale);
+      *(uint2*)(eb + (16 * ni + j) * EPI_ROW + (16 * mi + 4 * q) * 2) = v;
+    }
+#pragma unroll
+  for (int it = 0; it < 16; it++) {
+    int row = 4 * it + (lane >> 4), chunk = lane & 15;
+    uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
+    int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 8 * chunk;
+    if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
+  }
+}
+
+template <bool FP8>
+static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
+                            const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
+  int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((T + 255) / 256);
+  dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
+  int64_t eb = FP8 ? 1 : 2;
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
 }
 
 template <bool FP8, int WM, int WN, int NS>
@@ -230,8 +439,8 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   // measured faster than 256 x 128 even at 1.5 rounds of tiles (3072 x 8192 outputs: 33.6 vs 36.4 us)
   int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
   if (big_tiles >= 128) {
-    if (fp8) launch_fwd_cfg<true, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_cfg<false, 2, 4, 3>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    if (fp8) launch_fwd_pipe<true>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    else launch_fwd_pipe<false>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   } else {
     if (fp8) launch_fwd_cfg<true, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
     else launch_fwd_cfg<false, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
