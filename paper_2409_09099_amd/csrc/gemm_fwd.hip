@@ -204,30 +204,44 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Software-pipelined 256 x 256 variant (8 waves, 2 x 4).  The kernel above alternates, workgroup-wide,
-// between a phase that reads fragments from LDS and a phase that issues MFMAs; here the three pipes
-// (vector memory, LDS, matrix) run side by side within a k-step:
-//   * X fragments are double-buffered in registers: while the 32 MFMAs of k-step s run on one set, the
-//     set for k-step s + 1 is read from LDS, one 16-byte piece per group of four MFMAs;
+// Software-pipelined variant: 8 waves (2 x 4), each owning MI_ x NI_ MFMA tiles, so a workgroup covers
+// 32 MI_ channels x 64 NI_ tokens (256 x 256, 192 x 256, ...).  The kernel above alternates,
+// workgroup-wide, between a phase that reads fragments from LDS and a phase that issues MFMAs; here the
+// three pipes (vector memory, LDS, matrix) run side by side within a k-step:
+//   * X fragments are double-buffered in registers: while the MFMAs of k-step s run on one set, the
+//     set for k-step s + 1 is read from LDS, spread over the groups of NI_ MFMAs;
 //   * packed-weight fragments roll through a two-deep register buffer, one row block ahead of its use;
 //   * the direct-to-LDS loads of a k-step are spread over the groups instead of issued in one burst.
 // Weight and X tiles live in separate three-slot rings because their LDS lifetimes differ: X of
 // k-step s is consumed during k-step s - 1, the weight tile of k-step s during s - 1 (row block 0)
 // and s.  At the single barrier of k-step s the tiles of s + 1 must have landed; the loads issued
 // during s are the weight tile of s + 2 and the X tile of s + 3.
-template <bool FP8>
+// Every wave issues the same number of loads per k-step (the counts in s_waitcnt are compile-time
+// constants); where the tile has fewer 1 KiB blocks than 8 waves x loads, the surplus loads address
+// blocks past the end of the tile's buffer descriptor and fetch nothing.
+namespace {
+// MFMA group (0 .. groups-1) in which item idx of n evenly spread items is issued
+constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
+}  // namespace
+
+template <bool FP8, int MI_, int NI_>
 __global__ void __launch_bounds__(512, 1)
 k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
                   const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
                   int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
-  constexpr int WM = 2, WN = 4, NW = 8, BM = 256, BN = 256, NR = 3;
+  constexpr int WN = 4, NW = 8, BM = 32 * MI_, BN = 64 * NI_, NR = 3;
   constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
-  constexpr int A_BYTES = BM * 64, M_BYTES = BM * MB, ASTAGE = A_BYTES + M_BYTES, BSTAGE = BN * 128;
-  constexpr int EPI_BYTES = NW * 64 * EPI_ROW;
+  constexpr int LA = (BM / 16 + NW - 1) / NW;                    // weight blocks (1 KiB) per wave and k-step
+  constexpr int LM = (BM * MB / 256 + NW - 1) / NW;              // 256-byte pieces of position bits
+  constexpr int LB = NI_;                                        // 8-token slabs (1 KiB) of X
+  constexpr int A_BYTES = NW * LA * 1024, M_BYTES = NW * LM * 256;
+  constexpr int ASTAGE = A_BYTES + M_BYTES, BSTAGE = BN * 128;
+  constexpr int EROW = 32 * MI_ + 16;                            // epilogue row: the wave's channels + pad
+  constexpr int EPI_BYTES = NW * 16 * NI_ * EROW;
   constexpr int RING = NR * (ASTAGE + BSTAGE);
   constexpr int SMEM = RING > EPI_BYTES ? RING : EPI_BYTES;
-  constexpr int LA = BM / 16 / NW, LB = BN / 8 / NW, LM = M_BYTES / 256 / NW;   // 2, 4, 1 (2 for fp8)
-  static_assert(LA == 2 && LB == 4 && (LM == 1 || LM == 2), "issue schedule below assumes these counts");
+  constexpr int NLOAD = LA + LM + LB;                            // issue order inside a k-step: A.., M.., B..
+  constexpr int NPIECE = 2 * NI_;                                // 16-byte pieces of the next X fragments
   __shared__ __align__(1024) uint8_t smem[SMEM];
   uint8_t* const smemA = smem;
   uint8_t* const smemB = smem + NR * ASTAGE;
@@ -271,52 +285,49 @@ k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int
   const uint32_t ldsB = (uint32_t)(uintptr_t)(lds_u8*)smemB;
   constexpr uint32_t DEAD = 0x40000000u;            // scalar offset past every descriptor: the load fetches nothing
 
-#define PIPE_DMA_A(i, step, slot_)                                                                        \
-  dma_b128(ba, ldsA + (uint32_t)(slot_) * ASTAGE + (LA * wave + (i)) * 1024, offa[i],                     \
-           (step) < nsteps ? (uint32_t)(step) * 1024u : DEAD)
-#define PIPE_DMA_M(i, step, slot_)                                                                        \
-  dma_b32(bm, ldsA + (uint32_t)(slot_) * ASTAGE + A_BYTES + (LM * wave + (i)) * 256, offm[i],             \
-          (step) < nsteps ? (uint32_t)(step) * (uint32_t)MBLK : DEAD)
-#define PIPE_DMA_B(i, step, slot_)                                                                        \
-  dma_b128(bb, ldsB + (uint32_t)(slot_) * BSTAGE + (LB * wave + (i)) * 1024, offb[i],                     \
-           (step) < nsteps ? (uint32_t)(step) * 128u : DEAD)
+  // load number n (0 .. NLOAD-1) of this wave for weight k-step sa -> slot slot_a, X k-step sb -> slot slot_b
+#define PIPE_LOAD(n, sa, slot_a, sb, slot_b)                                                              \
+  do {                                                                                                    \
+    if ((n) < LA)                                                                                         \
+      dma_b128(ba, ldsA + (uint32_t)(slot_a) * ASTAGE + (LA * wave + (n)) * 1024, offa[(n) < LA ? (n) : 0], \
+               (sa) < nsteps ? (uint32_t)(sa) * 1024u : DEAD);                                            \
+    else if ((n) < LA + LM)                                                                               \
+      dma_b32(bm, ldsA + (uint32_t)(slot_a) * ASTAGE + A_BYTES + (LM * wave + ((n) - LA)) * 256,          \
+              offm[((n) >= LA && (n) < LA + LM) ? (n) - LA : 0],                                          \
+              (sa) < nsteps ? (uint32_t)(sa) * (uint32_t)MBLK : DEAD);                                    \
+    else                                                                                                  \
+      dma_b128(bb, ldsB + (uint32_t)(slot_b) * BSTAGE + (LB * wave + ((n) - LA - LM)) * 1024,             \
+               offb[(n) >= LA + LM ? (n) - LA - LM : 0], (sb) < nsteps ? (uint32_t)(sb) * 128u : DEAD);   \
+  } while (0)
 
-  f32x4 acc[MI][NI];
+  f32x4 acc[MI_][NI_];
 #pragma unroll
-  for (int a = 0; a < MI; a++)
+  for (int a = 0; a < MI_; a++)
 #pragma unroll
-    for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < NI_; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const uint32_t fa_off = (uint32_t)(8 * wm * 1024 + lane * 16);                    // + 1024 mi
-  const uint32_t fm_off = (uint32_t)(A_BYTES + 8 * wm * MBLK + lane * (MB / 4));      // + MBLK mi
-  const int rb0 = 64 * wn + j;                                                      // + 16 ni
+  const uint32_t fa_off = (uint32_t)(MI_ * wm * 1024 + lane * 16);                  // + 1024 mi
+  const uint32_t fm_off = (uint32_t)(A_BYTES + MI_ * wm * MBLK + lane * (MB / 4));  // + MBLK mi
+  const int rb0 = 16 * NI_ * wn + j;                                                // + 16 ni
   const int cb0 = q ^ ((j >> 1) & 7);
   const uint32_t fb_off0 = (uint32_t)(rb0 * 128 + cb0 * 16);
   const uint32_t fb_off1 = (uint32_t)(rb0 * 128 + (cb0 ^ 4) * 16);
 
   // prologue: weight tiles 0, 1 and X tiles 0, 1, 2 in flight, in the order the barriers expect
 #pragma unroll
-  for (int i = 0; i < LA; i++) PIPE_DMA_A(i, 0, 0);
+  for (int n = 0; n < NLOAD; n++) PIPE_LOAD(n, 0, 0, 0, 0);
 #pragma unroll
-  for (int i = 0; i < LM; i++) PIPE_DMA_M(i, 0, 0);
+  for (int n = 0; n < NLOAD; n++) PIPE_LOAD(n, 1, 1, 1, 1);
 #pragma unroll
-  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 0, 0);
-#pragma unroll
-  for (int i = 0; i < LA; i++) PIPE_DMA_A(i, 1, 1);
-#pragma unroll
-  for (int i = 0; i < LM; i++) PIPE_DMA_M(i, 1, 1);
-#pragma unroll
-  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 1, 1);
-#pragma unroll
-  for (int i = 0; i < LB; i++) PIPE_DMA_B(i, 2, 2);
+  for (int n = LA + LM; n < NLOAD; n++) PIPE_LOAD(n, 0, 0, 2, 2);
 
-  uint4 fb0[NI][2], fb1[NI][2];       // X fragments: current / next k-step, roles swap every k-step
+  uint4 fb0[NI_][2], fb1[NI_][2];     // X fragments: current / next k-step, roles swap every k-step
   uint4 fa[2];                        // packed-weight fragment of row block mi in fa[mi % 2]
   int fidx[2];
   wait_vmcnt<LA + LM + 2 * LB>();     // tiles of k-step 0 have landed
   __syncthreads();
 #pragma unroll
-  for (int ni = 0; ni < NI; ni++) {
+  for (int ni = 0; ni < NI_; ni++) {
     fb0[ni][0] = *(const uint4*)(smemB + fb_off0 + ni * 2048);
     fb0[ni][1] = *(const uint4*)(smemB + fb_off1 + ni * 2048);
   }
@@ -334,18 +345,18 @@ k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int
     const uint8_t* pa = smemA + s0 * ASTAGE;                                                              \
     const uint8_t* pa1 = smemA + s1 * ASTAGE;                                                             \
     const uint8_t* pb1 = smemB + s1 * BSTAGE;                                                             \
-    _Pragma("unroll") for (int mi = 0; mi < MI; mi++) {                                                   \
-      const uint8_t* an = mi < MI - 1 ? pa + (mi + 1) * 1024 : pa1;                                       \
-      const uint8_t* mn = mi < MI - 1 ? pa + (mi + 1) * MBLK : pa1;                                       \
+    _Pragma("unroll") for (int mi = 0; mi < MI_; mi++) {                                                  \
+      const uint8_t* an = mi < MI_ - 1 ? pa + (mi + 1) * 1024 : pa1;                                      \
+      const uint8_t* mn = mi < MI_ - 1 ? pa + (mi + 1) * MBLK : pa1;                                      \
       fa[(mi + 1) & 1] = *(const uint4*)(an + fa_off);                                                    \
       if (FP8) fidx[(mi + 1) & 1] = *(const int*)(mn + fm_off);                                           \
       else fidx[(mi + 1) & 1] = *(const uint16_t*)(mn + fm_off);                                          \
-      BX[mi >> 1][mi & 1] = *(const uint4*)(pb1 + ((mi & 1) ? fb_off1 : fb_off0) + (mi >> 1) * 2048);     \
-      if (mi == 0) PIPE_DMA_A(0, step + 2, s2);                                                           \
-      if (mi == 1) PIPE_DMA_A(1, step + 2, s2);                                                           \
-      if (mi == 2) { _Pragma("unroll") for (int i = 0; i < LM; i++) PIPE_DMA_M(i, step + 2, s2); }        \
-      if (mi >= 3 && mi < 3 + LB) PIPE_DMA_B(mi - 3, step + 3, s0);                                       \
-      _Pragma("unroll") for (int ni = 0; ni < NI; ni++) {                                                 \
+      _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
+        if (spread(pc, NPIECE, MI_) == mi)                                                                \
+          BX[pc >> 1][pc & 1] = *(const uint4*)(pb1 + ((pc & 1) ? fb_off1 : fb_off0) + (pc >> 1) * 2048); \
+      _Pragma("unroll") for (int n = 0; n < NLOAD; n++)                                                   \
+        if (spread(n, NLOAD, MI_) == mi) PIPE_LOAD(n, step + 2, s2, step + 3, s0);                        \
+      _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
         if (FP8) {                                                                                        \
           i32x4 av;                                                                                       \
           i32x8 bv;                                                                                       \
@@ -377,38 +388,44 @@ k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int
   }
   if (step < nsteps) PIPE_STEP(fb0, fb1);
 #undef PIPE_STEP
-#undef PIPE_DMA_A
-#undef PIPE_DMA_M
-#undef PIPE_DMA_B
+#undef PIPE_LOAD
 
+  // epilogue: accumulators -> LDS (row = token, the wave's 16 MI_ channels contiguous) -> 16-byte stores
   wait_vmcnt<0>();
   __syncthreads();
-  uint8_t* eb = smem + wave * (64 * EPI_ROW);
+  uint8_t* eb = smem + wave * (16 * NI_ * EROW);
 #pragma unroll
-  for (int mi = 0; mi < MI; mi++)
+  for (int mi = 0; mi < MI_; mi++)
 #pragma unroll
-    for (int ni = 0; ni < NI; ni++) {
+    for (int ni = 0; ni < NI_; ni++) {
       uint2 v;
       v.x = bf16_rne_pack(acc[mi][ni][0] * scale, acc[mi][ni][1] * scale);
       v.y = bf16_rne_pack(acc[mi][ni][2] * scale, acc[mi][ni][3] * scale);
-      *(uint2*)(eb + (16 * ni + j) * EPI_ROW + (16 * mi + 4 * q) * 2) = v;
+      *(uint2*)(eb + (16 * ni + j) * EROW + (16 * mi + 4 * q) * 2) = v;
     }
+  // same-wave LDS accesses are ordered; no barrier needed for a wave-private region
+  constexpr int CHUNKS = 2 * MI_;                                // 16-byte chunks per token row
+  constexpr int NCH = 16 * NI_ * CHUNKS;
 #pragma unroll
-  for (int it = 0; it < 16; it++) {
-    int row = 4 * it + (lane >> 4), chunk = lane & 15;
-    uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
-    int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 8 * chunk;
-    if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
+  for (int it = 0; it < (NCH + 63) / 64; it++) {
+    int c = 64 * it + lane;
+    if (c < NCH) {
+      int row = c / CHUNKS, chunk = c % CHUNKS;
+      uint4 v = *(const uint4*)(eb + row * EROW + chunk * 16);
+      int64_t t = t0 + 16 * NI_ * wn + row, o = o0 + 16 * MI_ * wm + 8 * chunk;
+      if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
+    }
   }
 }
 
-template <bool FP8>
+template <bool FP8, int MI_, int NI_>
 static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
                             const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
-  int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((T + 255) / 256);
+  constexpr int BM = 32 * MI_, BN = 64 * NI_;
+  int m_tiles = (int)((O + BM - 1) / BM), n_tiles = (int)((T + BN - 1) / BN);
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
   int64_t eb = FP8 ? 1 : 2;
-  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8, MI_, NI_>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
               (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
 }
 
@@ -439,8 +456,8 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   // measured faster than 256 x 128 even at 1.5 rounds of tiles (3072 x 8192 outputs: 33.6 vs 36.4 us)
   int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
   if (big_tiles >= 128) {
-    if (fp8) launch_fwd_pipe<true>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_pipe<false>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    if (fp8) launch_fwd_pipe<true, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    else launch_fwd_pipe<false, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   } else {
     if (fp8) launch_fwd_cfg<true, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
     else launch_fwd_cfg<false, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);

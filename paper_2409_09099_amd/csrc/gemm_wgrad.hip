@@ -25,7 +25,6 @@ hipError_t launch_wgrad_fused(const void* dY, int64_t T, int64_t O, int64_t lddy
                               float* out, int64_t ld_out, int64_t split_stride, hipStream_t s);
 
 namespace {
-constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 features
 constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
@@ -135,25 +134,42 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 2. sparse GEMM on the packed operand.  256 (o) x 256 (i) per workgroup of 8 waves (2 x 4), 3-stage ring.
-template <bool FP8, int NS>
+// 2. sparse GEMM on the packed operand.  8 waves (2 x 4), each owning MI_ x NI_ MFMA tiles: a workgroup
+// covers 32 MI_ channels x 64 NI_ features (256 x 256, 192 x 192, ...) over one split of the token axis.
+// Same software pipeline as the forward GEMM: X fragments double-buffered in registers and read one
+// k-step ahead, packed fragments rolling one row block ahead, direct-to-LDS loads spread over the MFMA
+// groups, separate three-slot rings for the two operands, one barrier per k-step.
+// X tile in LDS: one row per token, 512 B (bf16: 256 features) or 256 B (fp8) whatever the tile width;
+// narrower tiles leave the tail of each row unused.  32-byte feature pair p (bf16) / 16-byte chunk c
+// (fp8) of token row r is stored at position p ^ (r % 16): the transposing reads below, which gather
+// 4 (8) token rows x 16 features per 16 lanes, then hit distinct banks.
+namespace {
+constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
+}  // namespace
+
+template <bool FP8, int MI_, int NI_>
 __global__ void __launch_bounds__(512, 1)
 k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t O, int64_t total_steps,
              const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, int steps_per_split, float scale,
              int accumulate, float* __restrict__ out, int64_t ld_out, int64_t split_stride, int m_tiles, int n_tiles) {
-  constexpr int WM = 2, WN = 4, NW = 8;
-  constexpr int BM = 256, BN = 256;
+  constexpr int WN = 4, NW = 8, NR = 3;
+  constexpr int BM = 32 * MI_, BN = 64 * NI_;
   constexpr int EB = FP8 ? 1 : 2;
   constexpr int KS = FP8 ? 128 : 64;              // tokens per k-step
   constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
-  constexpr int ROWB = BN * EB;                   // bytes of one token row of the X tile: 512 / 256
-  constexpr int A_BYTES = BM * 64, B_BYTES = KS * ROWB, M_BYTES = BM * MB;
-  constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
-  constexpr int LA = BM / 16 / NW, LB = B_BYTES / 1024 / NW, LM = M_BYTES / 256 / NW;
-  constexpr int LPW = LA + LB + LM;
+  constexpr int ROWB = 256 * EB;                  // LDS bytes per token row: 512 / 256
+  constexpr int LA = (BM / 16 + NW - 1) / NW;     // packed blocks (1 KiB) per wave and k-step
+  constexpr int LM = (BM * MB / 256 + NW - 1) / NW;
+  constexpr int BSTAGE = KS * ROWB;               // 32 KiB
+  constexpr int LB = BSTAGE / 1024 / NW;          // 4
+  constexpr int A_BYTES = NW * LA * 1024, M_BYTES = NW * LM * 256, ASTAGE = A_BYTES + M_BYTES;
+  constexpr int NLOAD = LA + LM + LB;             // issue order inside a k-step: A.., M.., B..
+  constexpr int NPIECE = 4 * NI_;                 // 8-byte pieces of the next X fragments
   constexpr int RPL = 1024 / ROWB;                // token rows per 1 KiB load: 2 / 4
   constexpr int CPR = ROWB / 16;                  // 16-byte chunks per row: 32 / 16
-  __shared__ __align__(1024) uint8_t smem[NS * STAGE];
+  __shared__ __align__(1024) uint8_t smem[NR * (ASTAGE + BSTAGE)];
+  uint8_t* const smemA = smem;
+  uint8_t* const smemB = smem + NR * ASTAGE;
 
   // tile order: XCD x owns a contiguous range of (tile, split) units, channel tiles fastest
   const int bid = blockIdx.x, nblk = gridDim.x;
@@ -182,131 +198,163 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
   const int cols_b = (int)((I - i0) < BN ? (I - i0) : BN);
   const i32x4 bb = rsrc_words(X + step_begin * KS * ldx_bytes + i0 * EB, (uint32_t)(((int64_t)nsteps * KS - 1) * ldx_bytes + cols_b * EB));
 
+  // Packed blocks past the tile's last one must fetch nothing although the descriptor (which runs to
+  // the end of the tile's last block row) may still cover their offsets: push them out of range.
   uint32_t offa[LA], offb[LB], offm[LM];
 #pragma unroll
-  for (int i = 0; i < LA; i++) offa[i] = (uint32_t)((LA * wave + i) * total_steps * 1024 + lane * 16);
+  for (int i = 0; i < LA; i++)
+    offa[i] = (LA * wave + i) < blks_a ? (uint32_t)((LA * wave + i) * total_steps * 1024 + lane * 16) : 0x80000000u;
 #pragma unroll
   for (int i = 0; i < LB; i++) {
     int wl = LB * wave + i;
     int r = RPL * wl + lane / CPR, cs = lane % CPR;          // token row inside the k-step, stored chunk
     int c = FP8 ? (cs ^ (r & 15)) : ((((cs >> 1) ^ (r & 15)) << 1) | (cs & 1));   // source chunk
-    // chunks past the last feature column must read as zeros: push them out of the descriptor
+    // chunks past the last feature column of the tile must read as zeros
     offb[i] = (c * 16 < cols_b * EB) ? (uint32_t)(r * ldx_bytes + c * 16) : 0x80000000u;
   }
 #pragma unroll
   for (int i = 0; i < LM; i++) {
     int d = 64 * (LM * wave + i) + lane;
-    offm[i] = (uint32_t)((d / (MBLK / 4)) * total_steps * MBLK + 4 * (d % (MBLK / 4)));
+    int blk = d / (MBLK / 4);
+    offm[i] = blk < blks_a ? (uint32_t)(blk * total_steps * MBLK + 4 * (d % (MBLK / 4))) : 0x80000000u;
   }
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
+  const uint32_t ldsA = (uint32_t)(uintptr_t)(lds_u8*)smemA;
+  const uint32_t ldsB = (uint32_t)(uintptr_t)(lds_u8*)smemB;
+  constexpr uint32_t DEAD = 0x40000000u;
 
-#define WG_ISSUE(step, stg)                                                                            \
-  do {                                                                                                 \
-    const bool live_ = (step) < nsteps;                                                                \
-    const uint32_t sa_ = live_ ? (uint32_t)(step) * 1024u : 0x40000000u;                               \
-    const uint32_t sb_ = live_ ? (uint32_t)((step) * KS * ldx_bytes) : 0x40000000u;                    \
-    const uint32_t sm_ = live_ ? (uint32_t)(step) * (uint32_t)MBLK : 0x40000000u;                      \
-    const uint32_t base_ = lds0 + (uint32_t)(stg) * STAGE;                                             \
-    _Pragma("unroll") for (int i = 0; i < LA; i++) dma_b128(ba, base_ + (LA * wave + i) * 1024, offa[i], sa_); \
-    _Pragma("unroll") for (int i = 0; i < LB; i++) dma_b128(bb, base_ + A_BYTES + (LB * wave + i) * 1024, offb[i], sb_); \
-    _Pragma("unroll") for (int i = 0; i < LM; i++) dma_b32(bm, base_ + A_BYTES + B_BYTES + (LM * wave + i) * 256, offm[i], sm_); \
+#define WG_LOAD(n, sa, slot_a, sb, slot_b)                                                                \
+  do {                                                                                                    \
+    if ((n) < LA)                                                                                         \
+      dma_b128(ba, ldsA + (uint32_t)(slot_a) * ASTAGE + (LA * wave + (n)) * 1024, offa[(n) < LA ? (n) : 0], \
+               (sa) < nsteps ? (uint32_t)(sa) * 1024u : DEAD);                                            \
+    else if ((n) < LA + LM)                                                                               \
+      dma_b32(bm, ldsA + (uint32_t)(slot_a) * ASTAGE + A_BYTES + (LM * wave + ((n) - LA)) * 256,          \
+              offm[((n) >= LA && (n) < LA + LM) ? (n) - LA : 0],                                          \
+              (sa) < nsteps ? (uint32_t)(sa) * (uint32_t)MBLK : DEAD);                                    \
+    else                                                                                                  \
+      dma_b128(bb, ldsB + (uint32_t)(slot_b) * BSTAGE + (LB * wave + ((n) - LA - LM)) * 1024,             \
+               offb[(n) >= LA + LM ? (n) - LA - LM : 0],                                                  \
+               (sb) < nsteps ? (uint32_t)((sb) * KS * ldx_bytes) : DEAD);                                 \
   } while (0)
 
-  f32x4 acc[MI][NI];
+  f32x4 acc[MI_][NI_];
 #pragma unroll
-  for (int a = 0; a < MI; a++)
+  for (int a = 0; a < MI_; a++)
 #pragma unroll
-    for (int b = 0; b < NI; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < NI_; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const uint32_t fa_off = (uint32_t)(8 * wm * 1024 + lane * 16);
-  const uint32_t fm_off = (uint32_t)(A_BYTES + B_BYTES + 8 * wm * MBLK + lane * (MB / 4));
+  const uint32_t fa_off = (uint32_t)(MI_ * wm * 1024 + lane * 16);
+  const uint32_t fm_off = (uint32_t)(A_BYTES + MI_ * wm * MBLK + lane * (MB / 4));
   // transposing reads of X: piece r of tile ni covers tokens k0 .. k0 + 3 (bf16) / k0 .. k0 + 7 (fp8)
-  uint32_t fb_off[4];
+  uint32_t fb_off[NI_][4];
 #pragma unroll
-  for (int r = 0; r < 4; r++) {
-    if (FP8) {
-      int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
-      int c = (64 * wn) / 16;                                   // + ni
-      fb_off[r] = (uint32_t)(A_BYTES + row * ROWB + ((c ^ (row & 15)) * 16) + 8 * (j & 1));
-    } else {
-      int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
-      int p = (64 * wn) / 16;                                   // + ni   (32-byte pair index)
-      fb_off[r] = (uint32_t)(A_BYTES + row * ROWB + ((p ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
-    }
-  }
-
+  for (int ni = 0; ni < NI_; ni++)
 #pragma unroll
-  for (int s = 0; s < NS - 1; s++) WG_ISSUE(s, s);
-
-  int stg = 0;
-  for (int step = 0; step < nsteps; step++) {
-    wait_vmcnt<(NS - 2) * LPW>();
-    __syncthreads();
-    const uint8_t* sb = smem + stg * STAGE;
-    uint2 fb[NI][4];
-#pragma unroll
-    for (int ni = 0; ni < NI; ni++)
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        // tile ni shifts the (swizzled) chunk / pair index by ni: XOR-ing ni into the stored index
-        // equals adding it because the base index 4 wn has its two low bits clear
-        if (FP8) {
-          int row_lo = (16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1)) & 15;
-          (void)row_lo;
-          const uint8_t* p = sb + (fb_off[r] ^ (uint32_t)(ni * 16));
-          i32x2 t = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)p);
-          fb[ni][r] = make_uint2((uint32_t)t[0], (uint32_t)t[1]);
-        } else {
-          const uint8_t* p = sb + (fb_off[r] ^ (uint32_t)(ni * 32));
-          bf16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-          __builtin_memcpy(&fb[ni][r], &t, 8);
-        }
-      }
-    uint4 fa[MI];
-    int fidx[MI];
-#pragma unroll
-    for (int mi = 0; mi < MI; mi++) {
-      fa[mi] = *(const uint4*)(sb + fa_off + mi * 1024);
-      if (FP8) fidx[mi] = *(const int*)(sb + fm_off + mi * MBLK);
-      else fidx[mi] = *(const uint16_t*)(sb + fm_off + mi * MBLK);
-    }
-    {
-      int nstg = stg + NS - 1;
-      if (nstg >= NS) nstg -= NS;
-      WG_ISSUE(step + NS - 1, nstg);
-    }
-#pragma unroll
-    for (int mi = 0; mi < MI; mi++) {
-#pragma unroll
-      for (int ni = 0; ni < NI; ni++) {
-        if (FP8) {
-          i32x4 av;
-          i32x8 bv;
-          __builtin_memcpy(&av, &fa[mi], 16);
-          __builtin_memcpy(&bv, &fb[ni][0], 32);
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
-        } else {
-          bf16x8 av;
-          bf16x16 bv;
-          __builtin_memcpy(&av, &fa[mi], 16);
-          __builtin_memcpy(&bv, &fb[ni][0], 32);
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx[mi], 0, 0);
-        }
+    for (int r = 0; r < 4; r++) {
+      int p = NI_ * wn + ni;                                      // feature pair (bf16) / chunk (fp8) of the tile
+      if (FP8) {
+        int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
+        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ (row & 15)) * 16) + 8 * (j & 1));
+      } else {
+        int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
+        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
       }
     }
-    stg = (stg + 1 == NS) ? 0 : stg + 1;
+
+#define WG_READ_B(dst, base, pc)                                                                          \
+  do {                                                                                                    \
+    const uint8_t* p_ = (base) + fb_off[(pc) >> 2][(pc) & 3];                                             \
+    if (FP8) {                                                                                            \
+      i32x2 t_ = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)p_);                                  \
+      dst[(pc) >> 2][(pc) & 3] = make_uint2((uint32_t)t_[0], (uint32_t)t_[1]);                            \
+    } else {                                                                                              \
+      bf16x4 t_ = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p_);                              \
+      __builtin_memcpy(&dst[(pc) >> 2][(pc) & 3], &t_, 8);                                                \
+    }                                                                                                     \
+  } while (0)
+
+  // prologue: packed tiles 0, 1 and X tiles 0, 1, 2 in flight, in the order the barriers expect
+#pragma unroll
+  for (int n = 0; n < NLOAD; n++) WG_LOAD(n, 0, 0, 0, 0);
+#pragma unroll
+  for (int n = 0; n < NLOAD; n++) WG_LOAD(n, 1, 1, 1, 1);
+#pragma unroll
+  for (int n = LA + LM; n < NLOAD; n++) WG_LOAD(n, 0, 0, 2, 2);
+
+  uint2 fb0[NI_][4], fb1[NI_][4];     // X fragments: current / next k-step, roles swap every k-step
+  uint4 fa[2];                        // packed fragment of row block mi in fa[mi % 2]
+  int fidx[2];
+  wait_vmcnt<LA + LM + 2 * LB>();     // tiles of k-step 0 have landed
+  __syncthreads();
+#pragma unroll
+  for (int pc = 0; pc < NPIECE; pc++) WG_READ_B(fb0, smemB, pc);
+  fa[0] = *(const uint4*)(smemA + fa_off);
+  if (FP8) fidx[0] = *(const int*)(smemA + fm_off);
+  else fidx[0] = *(const uint16_t*)(smemA + fm_off);
+
+  int s0 = 0, s1 = 1, s2 = 2;         // ring slots of k-steps step, step + 1, step + 2 (both rings)
+
+#define WG_STEP(BC, BX)                                                                                   \
+  do {                                                                                                    \
+    wait_vmcnt<LB>();                 /* all but the newest X tile: k-step step + 1 has landed */          \
+    __syncthreads();                  /* ... for every wave; slots of step - 1 (packed) and step (X) are free */ \
+    const uint8_t* pa = smemA + s0 * ASTAGE;                                                              \
+    const uint8_t* pa1 = smemA + s1 * ASTAGE;                                                             \
+    const uint8_t* pb1 = smemB + s1 * BSTAGE;                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < MI_; mi++) {                                                  \
+      const uint8_t* an = mi < MI_ - 1 ? pa + (mi + 1) * 1024 : pa1;                                      \
+      const uint8_t* mn = mi < MI_ - 1 ? pa + (mi + 1) * MBLK : pa1;                                      \
+      fa[(mi + 1) & 1] = *(const uint4*)(an + fa_off);                                                    \
+      if (FP8) fidx[(mi + 1) & 1] = *(const int*)(mn + fm_off);                                           \
+      else fidx[(mi + 1) & 1] = *(const uint16_t*)(mn + fm_off);                                          \
+      _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
+        if (spread(pc, NPIECE, MI_) == mi) WG_READ_B(BX, pb1, pc);                                        \
+      _Pragma("unroll") for (int n = 0; n < NLOAD; n++)                                                   \
+        if (spread(n, NLOAD, MI_) == mi) WG_LOAD(n, step + 2, s2, step + 3, s0);                          \
+      _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
+        if (FP8) {                                                                                        \
+          i32x4 av;                                                                                       \
+          i32x8 bv;                                                                                       \
+          __builtin_memcpy(&av, &fa[mi & 1], 16);                                                         \
+          __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+        } else {                                                                                          \
+          bf16x8 av;                                                                                      \
+          bf16x16 bv;                                                                                     \
+          __builtin_memcpy(&av, &fa[mi & 1], 16);                                                         \
+          __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
+          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+        }                                                                                                 \
+      }                                                                                                   \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
+    const int t_ = s0;                                                                                    \
+    s0 = s1;                                                                                              \
+    s1 = s2;                                                                                              \
+    s2 = t_;                                                                                              \
+  } while (0)
+
+  int step = 0;
+  for (; step + 1 < nsteps; step += 2) {
+    WG_STEP(fb0, fb1);
+    step++;
+    WG_STEP(fb1, fb0);
+    step--;
   }
-#undef WG_ISSUE
+  if (step < nsteps) WG_STEP(fb0, fb1);
+#undef WG_STEP
+#undef WG_READ_B
+#undef WG_LOAD
   wait_vmcnt<0>();
 
   // epilogue: lane (j, q) register r of tile (mi, ni) is element (o + r, i)
   float* dst = out + (int64_t)z * split_stride;
 #pragma unroll
-  for (int mi = 0; mi < MI; mi++)
+  for (int mi = 0; mi < MI_; mi++)
 #pragma unroll
-    for (int ni = 0; ni < NI; ni++) {
-      int64_t o = o0 + 128 * wm + 16 * mi + 4 * q;
-      int64_t i = i0 + 64 * wn + 16 * ni + j;
+    for (int ni = 0; ni < NI_; ni++) {
+      int64_t o = o0 + 16 * MI_ * wm + 16 * mi + 4 * q;
+      int64_t i = i0 + 16 * NI_ * wn + 16 * ni + j;
       if (i < I) {
 #pragma unroll
         for (int r = 0; r < 4; r++) {
@@ -350,15 +398,35 @@ k_zero_rows(float* __restrict__ dW, int64_t O, int64_t I, int64_t lddw) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// host: path choice, split choice, workspace layout
+// host: path choice, tile and split choice, workspace layout
 struct WgradPlan {
   bool packed;          // true: estimator pre-pass + GEMM on the packed operand; false: fused kernel
+  int mi, ni;           // MFMA tiles per wave of the packed GEMM (workgroup tile 32 mi x 64 ni)
   int splits;           // token-axis splits
   int steps_per_split;
   size_t vals_bytes, meta_bytes, partial_bytes;   // workspace sections (each a multiple of 256)
 };
 
 static size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
+// Time model (microseconds) behind the tile / split choice of the packed GEMM, fitted to timings of the
+// 3072 x 768 (8192 tokens) and 5120 x 1280 (16384 tokens) layers.  One workgroup per CU; a k-step costs
+// about 0.34 + 0.0175 per MFMA tile of the wave (0.90 for 8 x 4, 0.66 for 6 x 3), a workgroup about 4 us
+// of ramp-up and drain, and the split partials are written once and read once at 5.5 TB/s.  The model
+// only has to rank a handful of candidates; it is within 10 % of the measurements it was fitted to.
+static double wgrad_model_us(int64_t O, int64_t I, int64_t steps, int mi, int ni, int64_t s, int64_t* sps_out) {
+  int64_t bm = 32 * mi, bn = 64 * ni;
+  int64_t tiles = ((O + bm - 1) / bm) * ((I + bn - 1) / bn);
+  int64_t sps = (steps + s - 1) / s;
+  int64_t splits = (steps + sps - 1) / sps;
+  int64_t rounds = (tiles * splits + NUM_CU - 1) / NUM_CU;
+  double t_step = 0.34 + 0.0175 * mi * ni;
+  double t = (double)rounds * ((double)sps * t_step + 4.0);
+  double out_bytes = (double)O * (double)I * 4.0;
+  if (splits > 1) t += 2.0 + (double)(2 * splits + 1) * out_bytes / 5.5e6;
+  *sps_out = sps;
+  return t;
+}
 
 static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   WgradPlan p{};
@@ -368,29 +436,74 @@ static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   // the pre-pass pays off once the GEMM tiles would re-derive each group several times and the problem
   // is large enough to fill the chip; everything else runs the fused kernel
   p.packed = (T >= 2048) && (O >= 256) && (I >= 256) && ((T * ((O + 15) / 16 * 16)) < (1ll << 40));
+  p.mi = 8;
+  p.ni = 4;
   if (steps <= 0) {
     p.splits = 1;
     p.steps_per_split = 1;
     return p;
   }
-  int64_t tile = p.packed ? 256 : 128;
-  int64_t tiles = ((O + tile - 1) / tile) * ((I + tile - 1) / tile);
-  int64_t target = p.packed ? NUM_CU : 2 * NUM_CU;
-  int64_t s = p.packed ? target / tiles : (target + tiles - 1) / tiles;
-  if (s > steps / 8) s = steps / 8;
-  if (s > 32) s = 32;
-  if (s < 1) s = 1;
-  int64_t sps = (steps + s - 1) / s;
-  s = (steps + sps - 1) / sps;                        // no empty split
-  p.splits = (int)s;
-  p.steps_per_split = (int)sps;
   if (p.packed) {
+    static const int shapes[4][2] = {{8, 4}, {6, 3}, {8, 3}, {6, 4}};
+    double best = 1e30;
+    for (int k = 0; k < 4; k++) {
+      int64_t smax = steps / 8 < 32 ? steps / 8 : 32;
+      if (smax < 1) smax = 1;
+      for (int64_t s = 1; s <= smax; s++) {
+        int64_t sps;
+        double t = wgrad_model_us(O, I, steps, shapes[k][0], shapes[k][1], s, &sps);
+        if (t < best) {
+          best = t;
+          p.mi = shapes[k][0];
+          p.ni = shapes[k][1];
+          p.steps_per_split = (int)sps;
+          p.splits = (int)((steps + sps - 1) / sps);
+        }
+      }
+    }
     int64_t rows = (O + 15) / 16 * 16;
     p.vals_bytes = round256((size_t)rows * (size_t)(T / 2) * (fp8 ? 1 : 2));
     p.meta_bytes = round256((size_t)rows * (size_t)(T / 8));
+  } else {
+    int64_t tiles = ((O + 127) / 128) * ((I + 127) / 128);
+    int64_t s = (2 * NUM_CU + tiles - 1) / tiles;
+    if (s > steps / 8) s = steps / 8;
+    if (s > 32) s = 32;
+    if (s < 1) s = 1;
+    int64_t sps = (steps + s - 1) / s;
+    p.splits = (int)((steps + sps - 1) / sps);                // no empty split
+    p.steps_per_split = (int)sps;
   }
-  p.partial_bytes = s > 1 ? round256((size_t)s * (size_t)O * (size_t)I * sizeof(float)) : 0;
+  p.partial_bytes = p.splits > 1 ? round256((size_t)p.splits * (size_t)O * (size_t)I * sizeof(float)) : 0;
   return p;
+}
+
+template <bool FP8, int MI_, int NI_>
+static void launch_wgrad_gemm_cfg(const void* vals, const void* meta, int64_t O, int64_t steps, const void* X, int64_t I,
+                                  int64_t ldx_bytes, int splits, int steps_per_split, float scale, int accumulate,
+                                  float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
+  int m_tiles = (int)((O + 32 * MI_ - 1) / (32 * MI_)), n_tiles = (int)((I + 64 * NI_ - 1) / (64 * NI_));
+  dim3 grid((unsigned)(m_tiles * n_tiles * splits)), block(512);
+  SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<FP8, MI_, NI_>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
+              (const uint8_t*)X, I, ldx_bytes, steps_per_split, scale, accumulate, out, ld_out, split_stride, m_tiles, n_tiles);
+}
+
+static void launch_wgrad_gemm(bool fp8, int mi, int ni, const void* vals, const void* meta, int64_t O, int64_t steps,
+                              const void* X, int64_t I, int64_t ldx_bytes, int splits, int steps_per_split, float scale,
+                              int accumulate, float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
+#define WG_CASE(F, M, N)                                                                                       \
+  if (fp8 == F && mi == M && ni == N)                                                                          \
+    return launch_wgrad_gemm_cfg<F, M, N>(vals, meta, O, steps, X, I, ldx_bytes, splits, steps_per_split, scale, \
+                                          accumulate, out, ld_out, split_stride, s)
+  WG_CASE(false, 8, 4);
+  WG_CASE(false, 6, 3);
+  WG_CASE(false, 8, 3);
+  WG_CASE(false, 6, 4);
+  WG_CASE(true, 8, 4);
+  WG_CASE(true, 6, 3);
+  WG_CASE(true, 8, 3);
+  WG_CASE(true, 6, 4);
+#undef WG_CASE
 }
 
 size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
@@ -432,14 +545,8 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
     uint8_t* vals = wsb;
     uint8_t* meta = wsb + p.vals_bytes;
     launch_mvue_pack(dY, T, O, lddy, dtype, key, vals, meta, s, SSTE_K_MVUE_PACK);
-    int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((I + 255) / 256);
-    dim3 grid((unsigned)(m_tiles * n_tiles * p.splits)), block(512);
-    if (fp8)
-      SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<true, 3>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
-                  (const uint8_t*)X, I, ldx * eb, p.steps_per_split, k_scale, k_acc, out, ld_out, split_stride, m_tiles, n_tiles);
-    else
-      SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<false, 3>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
-                  (const uint8_t*)X, I, ldx * eb, p.steps_per_split, k_scale, k_acc, out, ld_out, split_stride, m_tiles, n_tiles);
+    launch_wgrad_gemm(fp8, p.mi, p.ni, vals, meta, O, steps, X, I, ldx * eb, p.splits, p.steps_per_split, k_scale, k_acc, out,
+                      ld_out, split_stride, s);
   } else {
     hipError_t e = launch_wgrad_fused(dY, T, O, lddy, dtype, X, I, ldx, key, p.splits, p.steps_per_split, k_scale, k_acc,
                                       out, ld_out, split_stride, s);
