@@ -160,6 +160,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kt = sste.timing_end() if not args.no_kernel_timing else {k: (float("nan"), 1) for k in sste.binding.KERNEL_NAMES}
@@ -214,6 +215,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / args.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -60,8 +60,12 @@ __device__ __forceinline__ uint32_t bf16_rne_pack(float lo, float hi) {
 // 16-bit element `idx` (0..3) of the little-endian 64-bit pair {hi:lo}, moved to the top half of
 // a dword with zeros below: the float32 value of that bf16 element.
 __device__ __forceinline__ uint32_t pick16_as_f32bits(uint32_t lo, uint32_t hi, uint32_t idx) {
-  // v_perm_b32: selector bytes 0..3 address `lo`, 4..7 address `hi`, 0x0c yields 0x00
-  uint32_t sel = 0x01000c0cu + idx * 0x02020000u;
+  // v_perm_b32: selector bytes 0..3 address `lo`, 4..7 address `hi`, 0x0c yields 0x00.
+  // selector = 0x01000c0c + idx * 0x02020000.  Written as two shift-or/add instructions: the compiler
+  // turns any C spelling of it back into a 32-bit multiply, which runs at quarter rate.
+  uint32_t t, sel;
+  asm("v_lshl_or_b32 %0, %1, 8, %1" : "=v"(t) : "v"(idx));
+  asm("v_lshl_add_u32 %0, %1, 17, %2" : "=v"(sel) : "v"(t), "s"(0x01000c0cu));
   return __builtin_amdgcn_perm(hi, lo, sel);
 }
 

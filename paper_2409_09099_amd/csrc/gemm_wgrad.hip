@@ -65,11 +65,13 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     for (int r = 0; r < 4; r++) rdy[r] = make_uint4(0, 0, 0, 0);
   }
   const uint64_t gid_base = (uint64_t)(s * GROUPS + kg) * (uint64_t)O + (uint64_t)och;
+  const uint32_t gid_lo0 = (uint32_t)gid_base, gid_hi0 = (uint32_t)(gid_base >> 32);
+  const uint32_t hi_term0 = gid_hi0 * 0x9E3779B9u, hi_term1 = (gid_hi0 + 1u) * 0x9E3779B9u;
   const int q = kg / GPQ, g = kg % GPQ;
 #pragma unroll
   for (int e = 0; e < CH; e++) {
-    uint64_t gid = gid_base + e;
-    uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));
+    uint32_t gid_lo = gid_lo0 + (uint32_t)e;                 // group id gid_base + e: low word, carry into the high word
+    uint32_t x = draw_u32_pre(key.k0, key.k1, gid_lo, gid_lo < gid_lo0 ? hi_term1 : hi_term0);
     uint32_t nib, v;
     int c = oc * CH + e;                           // channel inside the tile
     uint8_t* slot = sV + (c >> 4) * 1024 + (16 * q + (c & 15)) * 16;
@@ -444,9 +446,9 @@ static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
     return p;
   }
   if (p.packed) {
-    static const int shapes[4][2] = {{8, 4}, {6, 3}, {8, 3}, {6, 4}};
+    static const int shapes[3][2] = {{8, 4}, {6, 3}, {8, 3}};
     double best = 1e30;
-    for (int k = 0; k < 4; k++) {
+    for (int k = 0; k < 3; k++) {
       int64_t smax = steps / 8 < 32 ? steps / 8 : 32;
       if (smax < 1) smax = 1;
       for (int64_t s = 1; s <= smax; s++) {
@@ -498,11 +500,9 @@ static void launch_wgrad_gemm(bool fp8, int mi, int ni, const void* vals, const 
   WG_CASE(false, 8, 4);
   WG_CASE(false, 6, 3);
   WG_CASE(false, 8, 3);
-  WG_CASE(false, 6, 4);
   WG_CASE(true, 8, 4);
   WG_CASE(true, 6, 3);
   WG_CASE(true, 8, 3);
-  WG_CASE(true, 6, 4);
 #undef WG_CASE
 }
 

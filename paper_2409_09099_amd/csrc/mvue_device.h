@@ -7,10 +7,12 @@
 
 namespace sste {
 
-// 32-bit draw for a group id: three-round multiply-xorshift hash keyed by (k0, k1).
-__device__ __forceinline__ uint32_t draw_u32(uint32_t k0, uint32_t k1, uint32_t gid_lo, uint32_t gid_hi) {
+// 32-bit draw for a group id: three-round multiply-xorshift hash keyed by (k0, k1).  hi_term is the
+// high word of the group id times 0x9E3779B9, which callers that walk consecutive ids hoist out of
+// their loops.
+__device__ __forceinline__ uint32_t draw_u32_pre(uint32_t k0, uint32_t k1, uint32_t gid_lo, uint32_t hi_term) {
   uint32_t x = gid_lo ^ k0;
-  x += gid_hi * 0x9E3779B9u;
+  x += hi_term;
   x ^= x >> 17;
   x *= 0xED5AD4BBu;
   x += k1;
@@ -21,6 +23,9 @@ __device__ __forceinline__ uint32_t draw_u32(uint32_t k0, uint32_t k1, uint32_t 
   x ^= x >> 14;
   return x;
 }
+__device__ __forceinline__ uint32_t draw_u32(uint32_t k0, uint32_t k1, uint32_t gid_lo, uint32_t gid_hi) {
+  return draw_u32_pre(k0, k1, gid_lo, gid_hi * 0x9E3779B9u);
+}
 
 struct Sel {
   float h;        // common magnitude of recorded elements that are not kept as they are
@@ -28,14 +33,18 @@ struct Sel {
   uint32_t pos1;
 };
 
-// Steps 1-4 of the rule on the four magnitudes m0..m3 (all >= 0) and the 32-bit draw x.
-__device__ __forceinline__ Sel mvue_select(float m0, float m1, float m2, float m3, uint32_t x) {
-  float a = fmaxf(m0, m1), b = fminf(m0, m1);
-  float cc = fmaxf(m2, m3), d = fminf(m2, m3);
-  float mx = fmaxf(a, cc), mid = fminf(a, cc);
-  float Lo = (b + d) + mid;
-  float clampv = (Lo == 0.0f) ? mx : Lo;
-  float l0 = fminf(m0, clampv), l1 = fminf(m1, clampv), l2 = fminf(m2, clampv), l3 = fminf(m3, clampv);
+// Steps 1-4 of the rule on the four magnitudes m0..m3 (all >= 0, finite) and the 32-bit draw x.
+// Non-negative floats order like their bit patterns, so minima, maxima and comparisons are taken on
+// the bits as unsigned integers (same results, and no NaN canonicalisation instructions); sums and
+// products are float32 operations.
+__device__ __forceinline__ Sel mvue_select(float m0f, float m1f, float m2f, float m3f, uint32_t x) {
+  uint32_t m0 = f2u(m0f), m1 = f2u(m1f), m2 = f2u(m2f), m3 = f2u(m3f);
+  uint32_t a = max(m0, m1), b = min(m0, m1);
+  uint32_t cc = max(m2, m3), d = min(m2, m3);
+  uint32_t mx = max(a, cc), mid = min(a, cc);
+  float Lo = (u2f(b) + u2f(d)) + u2f(mid);
+  uint32_t clampv = (f2u(Lo) == 0u) ? mx : f2u(Lo);      // Lo is a sum of non-negative terms: +0 or positive
+  float l0 = u2f(min(m0, clampv)), l1 = u2f(min(m1, clampv)), l2 = u2f(min(m2, clampv)), l3 = u2f(min(m3, clampv));
   float P0 = l0;
   float P1 = P0 + l1;
   float P2 = P1 + l2;
@@ -44,8 +53,9 @@ __device__ __forceinline__ Sel mvue_select(float m0, float m1, float m2, float m
   float u = (float)(x >> 8) * 0x1p-24f;     // exact: 24-bit integer times a power of two
   float tau0 = u * h;
   float tau1 = tau0 + h;
-  uint32_t i0 = (uint32_t)(P0 <= tau0) + (uint32_t)(P1 <= tau0) + (uint32_t)(P2 <= tau0);
-  uint32_t i1 = (uint32_t)(P0 <= tau1) + (uint32_t)(P1 <= tau1) + (uint32_t)(P2 <= tau1);
+  uint32_t p0 = f2u(P0), p1 = f2u(P1), p2 = f2u(P2), t0 = f2u(tau0), t1 = f2u(tau1);
+  uint32_t i0 = (uint32_t)(p0 <= t0) + (uint32_t)(p1 <= t0) + (uint32_t)(p2 <= t0);
+  uint32_t i1 = (uint32_t)(p0 <= t1) + (uint32_t)(p1 <= t1) + (uint32_t)(p2 <= t1);
   Sel s;
   s.h = h;
   s.pos0 = min(i0, 2u);
