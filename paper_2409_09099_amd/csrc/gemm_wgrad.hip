@@ -46,8 +46,12 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
   constexpr int OC = 128 / CH;                    // chunks across the 128 channels: 16 / 8
   constexpr int GPQ = GROUPS / 4;                 // groups per lane quarter: 4 / 8
   constexpr int MBLK = FP8 ? 256 : 128;           // metadata bytes per block
-  __shared__ __align__(16) uint8_t sV[8 * 1024];
-  __shared__ __align__(16) uint8_t sN[128 * GROUPS];
+  // LDS staging, padded against bank conflicts: the lanes of a wave write the same slot of 8 different
+  // blocks (1040-byte block pitch puts them 4 banks apart) and the same group of 8 or 16 different
+  // channels (a pitch of GROUPS + 4 bytes spreads those over the banks).
+  constexpr int VPITCH = 1024 + 16, NPITCH = GROUPS + 4;
+  __shared__ __align__(16) uint8_t sV[8 * VPITCH];
+  __shared__ __align__(16) uint8_t sN[128 * NPITCH];
 
   const int tid = threadIdx.x;
   const int kg = tid / OC, oc = tid % OC;
@@ -74,7 +78,7 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     uint32_t x = draw_u32_pre(key.k0, key.k1, gid_lo, gid_lo < gid_lo0 ? hi_term1 : hi_term0);
     uint32_t nib, v;
     int c = oc * CH + e;                           // channel inside the tile
-    uint8_t* slot = sV + (c >> 4) * 1024 + (16 * q + (c & 15)) * 16;
+    uint8_t* slot = sV + (c >> 4) * VPITCH + (16 * q + (c & 15)) * 16;
     if (FP8) {
       uint32_t w0 = comp4(rdy[0], e >> 2), w1 = comp4(rdy[1], e >> 2), w2 = comp4(rdy[2], e >> 2), w3 = comp4(rdy[3], e >> 2);
       int sh = 8 * (e & 3);
@@ -88,7 +92,7 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
       v = mvue_group_bf16(lo, hi, x, nib);
       *(uint32_t*)(slot + 4 * g) = v;
     }
-    sN[c * GROUPS + kg] = (uint8_t)(nib << (4 * (kg & 1)));   // pre-shifted: neighbours are OR-ed below
+    sN[c * NPITCH + kg] = (uint8_t)(nib << (4 * (kg & 1)));   // pre-shifted: neighbours are OR-ed below
   }
   __syncthreads();
 
@@ -98,15 +102,15 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     int ci = tid + 256 * it, rb = ci >> 6, sl = ci & 63;     // block and slot inside the tile
     if (rb0 + rb < rbn) {
       int64_t blk = (rb0 + rb) * steps + s;
-      store_stream_b128(vals + blk * 1024 + sl * 16, *(const uint4*)(sV + ci * 16));
+      store_stream_b128(vals + blk * 1024 + sl * 16, *(const uint4*)(sV + rb * VPITCH + sl * 16));
       int c = rb * 16 + (sl & 15), qq = sl >> 4;
       if (FP8) {
-        uint2 w = *(const uint2*)(sN + c * GROUPS + 8 * qq);
-        uint32_t a = w.x | (w.x >> 8), b = w.y | (w.y >> 8);
+        uint32_t wx = *(const uint32_t*)(sN + c * NPITCH + 8 * qq), wy = *(const uint32_t*)(sN + c * NPITCH + 8 * qq + 4);
+        uint32_t a = wx | (wx >> 8), b = wy | (wy >> 8);
         uint32_t idx = (a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u);
         store_stream_b32(meta + blk * MBLK + sl * 4, idx);
       } else {
-        uint32_t w = *(const uint32_t*)(sN + c * GROUPS + 4 * qq);
+        uint32_t w = *(const uint32_t*)(sN + c * NPITCH + 4 * qq);
         uint32_t a = w | (w >> 8);
         store_stream_b16(meta + blk * MBLK + sl * 2, (uint16_t)((a & 0xFFu) | ((a >> 8) & 0xFF00u)));
       }
