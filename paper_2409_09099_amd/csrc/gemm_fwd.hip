@@ -41,6 +41,15 @@ namespace {
 constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 tokens
 constexpr int EPI_ROW = 272;                      // 128 channels x 2 B + 16 B pad
 constexpr int NUM_XCD = 8;
+constexpr int NUM_CU = 256;
+
+// The chip hands consecutive workgroup ids to its 8 XCDs in turn; this numbering gives each XCD a
+// contiguous range of logical numbers instead.
+__device__ __forceinline__ int xcd_contiguous(int bid, int nblk) {
+  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
+  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
+  return (rem == 0 || xcd < rem) ? xcd * per_xcd + slot : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+}
 }  // namespace
 
 template <bool FP8, int WM, int WN, int NS>
@@ -224,11 +233,22 @@ namespace {
 constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
 }  // namespace
 
+// LDS bytes one tile of the pipelined kernel needs (rings, reused by the epilogue)
 template <bool FP8, int MI_, int NI_>
-__global__ void __launch_bounds__(512, 1)
-k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
-                  const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
-                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
+constexpr int fwd_pipe_smem() {
+  constexpr int NW = 8, NR = 3, MB = FP8 ? 16 : 8;
+  constexpr int LA = (32 * MI_ / 16 + NW - 1) / NW, LM = (32 * MI_ * MB / 256 + NW - 1) / NW;
+  constexpr int RING = NR * (NW * LA * 1024 + NW * LM * 256 + 64 * NI_ * 128);
+  constexpr int EPI = NW * 16 * NI_ * (32 * MI_ + 16);
+  return RING > EPI ? RING : EPI;
+}
+
+// One output tile: channels [o0, o0 + 32 MI_) x tokens [t0, t0 + 64 NI_).  `smem` is the workgroup's LDS.
+template <bool FP8, int MI_, int NI_>
+__device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes,
+                                              int64_t ldx_bytes, const uint8_t* __restrict__ vals,
+                                              const uint8_t* __restrict__ meta, int64_t O, float scale,
+                                              uint16_t* __restrict__ Z, int64_t ldz, int64_t o0, int64_t t0) {
   constexpr int WN = 4, NW = 8, BM = 32 * MI_, BN = 64 * NI_, NR = 3;
   constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
   constexpr int LA = (BM / 16 + NW - 1) / NW;                    // weight blocks (1 KiB) per wave and k-step
@@ -237,27 +257,17 @@ k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int
   constexpr int A_BYTES = NW * LA * 1024, M_BYTES = NW * LM * 256;
   constexpr int ASTAGE = A_BYTES + M_BYTES, BSTAGE = BN * 128;
   constexpr int EROW = 32 * MI_ + 16;                            // epilogue row: the wave's channels + pad
-  constexpr int EPI_BYTES = NW * 16 * NI_ * EROW;
-  constexpr int RING = NR * (ASTAGE + BSTAGE);
-  constexpr int SMEM = RING > EPI_BYTES ? RING : EPI_BYTES;
   constexpr int NLOAD = LA + LM + LB;                            // issue order inside a k-step: A.., M.., B..
   constexpr int NPIECE = 2 * NI_;                                // 16-byte pieces of the next X fragments
-  __shared__ __align__(1024) uint8_t smem[SMEM];
+  static_assert(NR * (ASTAGE + BSTAGE) <= fwd_pipe_smem<FP8, MI_, NI_>() && NW * 16 * NI_ * EROW <= fwd_pipe_smem<FP8, MI_, NI_>(),
+                "LDS size helper out of step with the tile layout");
   uint8_t* const smemA = smem;
   uint8_t* const smemB = smem + NR * ASTAGE;
-
-  const int bid = blockIdx.x, nblk = gridDim.x;
-  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
-  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-  const int logical = (rem == 0 || xcd < rem) ? xcd * per_xcd + slot
-                                              : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
-  const int tm = logical % m_tiles, tn = logical / m_tiles;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
   const int j = lane & 15, q = lane >> 4;
-  const int64_t o0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
   const int nsteps = (int)(k_bytes / 128);
 
   const int64_t rblk0 = o0 / 16, rbn = (O + 15) / 16;
@@ -418,6 +428,46 @@ k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int
   }
 }
 
+// One tile shape for the whole grid.  Workgroups are numbered so that each XCD works on a contiguous
+// range of tiles, o-tiles fastest.
+template <bool FP8, int MI_, int NI_>
+__global__ void __launch_bounds__(512, 1)
+k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
+                  const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
+  __shared__ __align__(1024) uint8_t smem[fwd_pipe_smem<FP8, MI_, NI_>()];
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tm = logical % m_tiles, tn = logical / m_tiles;
+  fwd_pipe_tile<FP8, MI_, NI_>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * (32 * MI_),
+                               (int64_t)tn * (64 * NI_));
+}
+
+// Two tile shapes in one grid, for layers whose 256 x 256 tiles fill the CUs a whole number of times plus
+// a remainder of at most half a round: the first n_big workgroups take 256 x 256 tiles, the rest take
+// the remaining tiles as 256 x 128 halves.  The last round then has twice as many, half as long
+// workgroups instead of leaving more than half of the CUs idle for a full tile time.
+template <bool FP8>
+__global__ void __launch_bounds__(512, 1)
+k_linear_fwd_dual(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
+                  const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
+                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles, int n_big) {
+  __shared__ __align__(1024) uint8_t smem[fwd_pipe_smem<FP8, 8, 4>()];
+  static_assert(fwd_pipe_smem<FP8, 8, 2>() <= fwd_pipe_smem<FP8, 8, 4>(), "the half tile fits in the full tile's LDS");
+  const int bid = blockIdx.x;
+  if (bid < n_big) {
+    const int logical = xcd_contiguous(bid, n_big);
+    const int tm = logical % m_tiles, tn = logical / m_tiles;
+    fwd_pipe_tile<FP8, 8, 4>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * 256, (int64_t)tn * 256);
+  } else {
+    const int h = xcd_contiguous(bid - n_big, (int)gridDim.x - n_big);      // half-tile number
+    const int tile = n_big + (h >> 1);
+    const int tm = tile % m_tiles, tn = tile / m_tiles;
+    const int64_t t0 = (int64_t)tn * 256 + 128 * (h & 1);
+    if (t0 >= T) return;                       // second half of a ragged last token tile: nothing to do
+    fwd_pipe_tile<FP8, 8, 2>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * 256, t0);
+  }
+}
+
 template <bool FP8, int MI_, int NI_>
 static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
                             const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
@@ -427,6 +477,17 @@ static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, fl
   int64_t eb = FP8 ? 1 : 2;
   SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8, MI_, NI_>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
               (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
+}
+
+template <bool FP8>
+static void launch_fwd_dual(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
+                            const void* meta, int64_t O, void* Z, int64_t ldz, int n_big, hipStream_t s) {
+  int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((T + 255) / 256);
+  int n_small = 2 * (m_tiles * n_tiles - n_big);
+  dim3 grid((unsigned)(n_big + n_small)), block(512);
+  int64_t eb = FP8 ? 1 : 2;
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_dual<FP8>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles, n_big);
 }
 
 template <bool FP8, int WM, int WN, int NS>
@@ -455,7 +516,13 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   // 256 x 256 tiles (8 waves, 3-stage ring) unless the problem has too few of them to occupy the chip;
   // measured faster than 256 x 128 even at 1.5 rounds of tiles (3072 x 8192 outputs: 33.6 vs 36.4 us)
   int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
-  if (big_tiles >= 128) {
+  int64_t rem = big_tiles % NUM_CU;
+  if (big_tiles > NUM_CU && rem > 0 && rem <= NUM_CU / 2) {
+    // whole rounds of 256 x 256 tiles, then the remainder as twice as many 256 x 128 tiles
+    int n_big = (int)(big_tiles - rem);
+    if (fp8) launch_fwd_dual<true>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, n_big, s);
+    else launch_fwd_dual<false>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, n_big, s);
+  } else if (big_tiles >= 128) {
     if (fp8) launch_fwd_pipe<true, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
     else launch_fwd_pipe<false, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
   } else {

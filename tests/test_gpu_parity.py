@@ -210,6 +210,12 @@ def _fwd_case(sste, dtype, T, O, I, seed_layer=0):
     ("bf16", 300, 264, 64),
     ("e4m3", 512, 256, 1024),
     ("e4m3", 130, 72, 256),
+    # pipelined 256 x 256 kernel (128 .. 256 tiles), ragged token and channel tails
+    ("bf16", 16424, 520, 128),
+    ("e4m3", 16424, 520, 128),
+    # two tile shapes in one grid (262 tiles: 256 full + 12 halves), last token tile 64 rows: its second half is empty
+    ("bf16", 33344, 264, 64),
+    ("e4m3", 33344, 264, 128),
 ])
 def test_linear_fwd_matches_oracle(sste, dtype, T, O, I):
     got, ref = _fwd_case(sste, dtype, T, O, I)
