@@ -300,3 +300,36 @@ def test_linear_wgrad_strided_output_and_errors(sste):
     with pytest.raises(sste.SsteError) as ei:
         sste.linear_wgrad(dY, X, 0, 0)
     assert ei.value.status == 2
+
+
+# ------------------------------------------------------------------------------------------ strided operands, large-problem kernels
+
+def test_large_kernels_with_strided_operands(sste):
+    """X, dY, Z and dW are views into wider buffers (leading dimension > row length) at sizes that take the
+    pipelined forward kernel and the pre-pass + packed GEMM of the weight gradient; the padding columns of the
+    outputs must stay untouched."""
+    T, O, I = 16448, 520, 320
+    wl = WL.WORKLOADS[1]
+    wb = WL.weight_bits(wl, 0, O=O, I=I)
+    xc, xs = WL.activations(wl, 0, T=T, I=I)
+    dyc, dys = WL.output_gradient(wl, 0, T=T, O=O)
+    beta = np.float32(1.4830322)
+    rv, rm, _ = OP.project_pack(wb, beta)
+    vals, meta = sste.project_pack(bf16_dev(wb), float(beta))
+
+    Xbig = torch.full((T, I + 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    Xbig[:, :I] = act_dev(xc, "bf16")
+    dYbig = torch.full((T, O + 24), 3.0, dtype=torch.bfloat16, device="cuda")
+    dYbig[:, :O] = act_dev(dyc, "bf16")
+    Zbig = torch.full((T, O + 8), -5.0, dtype=torch.bfloat16, device="cuda")
+    dWbig = torch.full((O, I + 12), 9.0, dtype=torch.float32, device="cuda")
+
+    sste.linear_fwd(Xbig[:, :I], vals, meta, O, sste.BF16, float(xs), 1.0, Z=Zbig[:, :O])
+    ref = OL.linear_fwd(xc, rv, rm, "bf16", xs, np.float32(1.0))
+    assert rel_err(z_to_f64(Zbig[:, :O]), ref) <= TOL["bf16"]
+    assert float((Zbig[:, O:].float() + 5.0).abs().max()) == 0.0
+
+    sste.linear_wgrad(dYbig[:, :O], Xbig[:, :I], 11, 2, sste.BF16, float(dys), float(xs), dW=dWbig[:, :I])
+    refw = OL.linear_wgrad(dyc, xc, 11, 2, "bf16", dys, xs)
+    assert rel_err(host(dWbig[:, :I]).numpy().astype(np.float64), refw) <= 1e-4
+    assert float((dWbig[:, I:] - 9.0).abs().max()) == 0.0
