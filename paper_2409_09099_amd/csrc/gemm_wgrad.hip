@@ -81,8 +81,10 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     uint8_t* slot = sV + (c >> 4) * VPITCH + (16 * q + (c & 15)) * 16;
     if (FP8) {
       uint32_t w0 = comp4(rdy[0], e >> 2), w1 = comp4(rdy[1], e >> 2), w2 = comp4(rdy[2], e >> 2), w3 = comp4(rdy[3], e >> 2);
-      int sh = 8 * (e & 3);
-      uint32_t gw = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24);
+      // byte e % 4 of the four token rows -> one dword (token 0 in byte 0): three byte permutes
+      const uint32_t bsel = (uint32_t)(e & 3) | ((uint32_t)(4 + (e & 3)) << 8) | 0x0c0c0000u;
+      uint32_t t01 = __builtin_amdgcn_perm(w1, w0, bsel), t23 = __builtin_amdgcn_perm(w3, w2, bsel);
+      uint32_t gw = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
       v = mvue_group_e4m3(gw, x, nib);
       *(uint16_t*)(slot + 2 * g) = (uint16_t)v;
     } else {

@@ -92,15 +92,16 @@ __device__ __forceinline__ uint32_t mvue_group_e4m3(uint32_t g, uint32_t x, uint
   float m0 = __builtin_amdgcn_cvt_f32_fp8(ga, 0), m1 = __builtin_amdgcn_cvt_f32_fp8(ga, 1);
   float m2 = __builtin_amdgcn_cvt_f32_fp8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_fp8(ga, 3);
   Sel s = mvue_select(m0, m1, m2, m3, x);
-  float mp0 = s.pos0 == 0 ? m0 : (s.pos0 == 1 ? m1 : m2);
-  float mp1 = s.pos1 == 1 ? m1 : (s.pos1 == 2 ? m2 : m3);
+  // recorded elements: shift their code down to byte 0 (the conversion reads byte 0 only)
+  uint32_t sh0 = s.pos0 << 3, sh1 = s.pos1 << 3;
+  float mp0 = __builtin_amdgcn_cvt_f32_fp8(ga >> sh0, 0), mp1 = __builtin_amdgcn_cvt_f32_fp8(ga >> sh1, 0);
   // stored magnitudes: 0.5 * m_p where g_p is kept as it is, else 0.5 * h; all <= 448
   bool own0 = (f2u(mp0) - 1u) >= f2u(s.h);
   bool own1 = (f2u(mp1) - 1u) >= f2u(s.h);
   float v0 = 0.5f * (own0 ? mp0 : s.h);
   float v1 = 0.5f * (own1 ? mp1 : s.h);
   uint32_t q = e4m3_rne_pack(v0, v1);
-  uint32_t s0 = (g >> (8 * s.pos0)) & 0x80u, s1 = (g >> (8 * s.pos1)) & 0x80u;
+  uint32_t s0 = (g >> sh0) & 0x80u, s1 = (g >> sh1) & 0x80u;
   nib = s.pos0 | (s.pos1 << 2);
   return q | s0 | (s1 << 8);
 }
