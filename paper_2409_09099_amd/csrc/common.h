@@ -134,22 +134,17 @@ __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
   return r;
 }
 
-// Streaming (non-temporal) stores for outputs that the writing kernel never reads back: they leave the
-// L2 to the operands that are re-read, and no pile of dirty lines is left to flush when the kernel ends
-// (measured on the 5120 x 1280 forward GEMM at 16384 tokens: 142 -> 113 us).
+// Streaming (non-temporal) store for a final output that no kernel of the path reads again (Z): it
+// leaves the L2 to the operands that are re-read, and no pile of dirty lines is left to flush when the
+// kernel ends (measured on the 5120 x 1280 forward GEMM at 16384 tokens: 142 -> 113 us).  Intermediate
+// results that the next kernel consumes (the packed estimator operand, the split partial sums) are
+// stored normally: written with this hint they come back from HBM instead of the cache hierarchy and
+// the consumer runs 15 % slower.
 __device__ __forceinline__ void store_stream_b128(void* p, uint4 v) {
   i32x4 t;
   __builtin_memcpy(&t, &v, 16);
   __builtin_nontemporal_store(t, (i32x4*)p);
 }
-__device__ __forceinline__ void store_stream_b128(void* p, float4 v) {
-  f32x4 t;
-  __builtin_memcpy(&t, &v, 16);
-  __builtin_nontemporal_store(t, (f32x4*)p);
-}
-__device__ __forceinline__ void store_stream_b32(void* p, uint32_t v) { __builtin_nontemporal_store(v, (uint32_t*)p); }
-__device__ __forceinline__ void store_stream_b16(void* p, uint16_t v) { __builtin_nontemporal_store(v, (uint16_t*)p); }
-__device__ __forceinline__ void store_stream_f32(float* p, float v) { __builtin_nontemporal_store(v, p); }
 
 // ---- host-side launch entry points implemented in the .hip files --------------------------------
 struct RngKey { uint32_t k0, k1; };

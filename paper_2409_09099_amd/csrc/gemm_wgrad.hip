@@ -104,17 +104,17 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     int ci = tid + 256 * it, rb = ci >> 6, sl = ci & 63;     // block and slot inside the tile
     if (rb0 + rb < rbn) {
       int64_t blk = (rb0 + rb) * steps + s;
-      store_stream_b128(vals + blk * 1024 + sl * 16, *(const uint4*)(sV + rb * VPITCH + sl * 16));
+      *(uint4*)(vals + blk * 1024 + sl * 16) = *(const uint4*)(sV + rb * VPITCH + sl * 16);
       int c = rb * 16 + (sl & 15), qq = sl >> 4;
       if (FP8) {
         uint32_t wx = *(const uint32_t*)(sN + c * NPITCH + 8 * qq), wy = *(const uint32_t*)(sN + c * NPITCH + 8 * qq + 4);
         uint32_t a = wx | (wx >> 8), b = wy | (wy >> 8);
         uint32_t idx = (a & 0xFFu) | ((a >> 8) & 0xFF00u) | ((b & 0xFFu) << 16) | ((b << 8) & 0xFF000000u);
-        store_stream_b32(meta + blk * MBLK + sl * 4, idx);
+        *(uint32_t*)(meta + blk * MBLK + sl * 4) = idx;
       } else {
         uint32_t w = *(const uint32_t*)(sN + c * NPITCH + 4 * qq);
         uint32_t a = w | (w >> 8);
-        store_stream_b16(meta + blk * MBLK + sl * 2, (uint16_t)((a & 0xFFu) | ((a >> 8) & 0xFF00u)));
+        *(uint16_t*)(meta + blk * MBLK + sl * 2) = (uint16_t)((a & 0xFFu) | ((a >> 8) & 0xFF00u));
       }
     }
   }
