@@ -26,9 +26,9 @@ PEAK_DENSE_TFLOPS = {"bf16": 2500.0, "e4m3": 5000.0}
 # summary with the commands is committed under profiles/.  KiB read + KiB written.
 HBM_TRAFFIC_KIB = {
     (2, "project_pack"): 4658 + 2592,
-    (2, "fwd"): 37630 + 49502,
-    (2, "mvue_pack"): 49234 + 27648,
-    (2, "wgrad"): 67784 + 36888,
+    (2, "fwd"): 42320 + 49225,
+    (2, "mvue_pack"): 49246 + 27648,
+    (2, "wgrad"): 67784 + 36882,
 }
 
 
@@ -236,7 +236,7 @@ def main():
         "dtype": wl.dtype if fp8 else "bf16",
         "data": "synthetic",
         "config": {"workload": "cfg%d %s layer %s (W %dx%d, %d tokens)" % (wl.cfg, wl.name, L.name, O, I, T),
-                   "buffer_sets": nsets, "wgrad_token_splits": (ws_bytes // (O * I * 4)) if ws_bytes else 1},
+                   "buffer_sets": nsets, "wgrad_workspace_bytes": int(ws_bytes)},
         "frac_sparse_mfma_peak_whole_step": value / (2 * PEAK_DENSE_TFLOPS[wl.dtype]),
         "kernels": kernels,
         "roofline": roofline,
