@@ -145,6 +145,11 @@ __device__ __forceinline__ void store_stream_b128(void* p, uint4 v) {
   __builtin_memcpy(&t, &v, 16);
   __builtin_nontemporal_store(t, (i32x4*)p);
 }
+__device__ __forceinline__ void store_stream_b128(void* p, float4 v) {
+  f32x4 t;
+  __builtin_memcpy(&t, &v, 16);
+  __builtin_nontemporal_store(t, (f32x4*)p);
+}
 
 // ---- host-side launch entry points implemented in the .hip files --------------------------------
 struct RngKey { uint32_t k0, k1; };

@@ -63,7 +63,10 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
   if (och < O) {
     const uint8_t* p = dY + (s * KS + 4 * kg) * lddy_bytes + och * EB;
 #pragma unroll
-    for (int r = 0; r < 4; r++) rdy[r] = *(const uint4*)(p + r * lddy_bytes);
+    for (int r = 0; r < 4; r++) {
+      i32x4 t = __builtin_nontemporal_load((const i32x4*)(p + r * lddy_bytes));
+      rdy[r] = make_uint4((uint32_t)t[0], (uint32_t)t[1], (uint32_t)t[2], (uint32_t)t[3]);
+    }
   } else {
 #pragma unroll
     for (int r = 0; r < 4; r++) rdy[r] = make_uint4(0, 0, 0, 0);
@@ -384,15 +387,17 @@ k_wgrad_reduce(const float* __restrict__ ws, int splits, int64_t O, int64_t I, f
   int64_t n4 = O * (I / 4);
   for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n4; c += (int64_t)gridDim.x * 256) {
     int64_t row = c / (I / 4), col = (c - row * (I / 4)) * 4;
-    float4 s = *(const float4*)(ws + row * I + col);
+    f32x4 s0 = __builtin_nontemporal_load((const f32x4*)(ws + row * I + col));
+    float4 s = make_float4(s0[0], s0[1], s0[2], s0[3]);
     for (int z = 1; z < splits; z++) {
-      float4 v = *(const float4*)(ws + (int64_t)z * O * I + row * I + col);
+      f32x4 v0 = __builtin_nontemporal_load((const f32x4*)(ws + (int64_t)z * O * I + row * I + col));
+      float4 v = make_float4(v0[0], v0[1], v0[2], v0[3]);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
     float4* p = (float4*)(dW + row * lddw + col);
     float4 r = make_float4(s.x * scale, s.y * scale, s.z * scale, s.w * scale);
     if (accumulate) { float4 d = *p; r.x += d.x; r.y += d.y; r.z += d.z; r.w += d.w; }
-    *p = r;
+    store_stream_b128(p, r);
   }
 }
 
