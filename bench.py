@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
     ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prune-model", action="store_true",
+                    help="skip the whole-model re-projection measurement (144 weight tensors of GPT-2-774M, 2.2 GB)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with events (debug)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies before the warm-up (reference for HBM byte counters)")
@@ -78,6 +80,42 @@ def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32):
         "cores": int(cores),
         "kind": "oracle",
         "sample": "one full step of the same workload (project+pack %.2fs, fwd %.2fs, MVUE+wgrad %.2fs)" % (t1 - t0, t2 - t1, t3 - t2),
+    }
+
+
+def prune_model(sste, torch, iters=20):
+    """Re-projection + packing of every sparse linear layer of GPT-2-774M (36 blocks x QKV, attention
+    projection, fc1, fc2 = 144 distinct bf16 tensors, 1.4 GB read: larger than the Infinity Cache), the
+    per-iteration work workload 4 models, as ONE multi-tensor launch and as 144 single launches."""
+    shapes = [(3840, 1280), (1280, 1280), (5120, 1280), (1280, 5120)] * 36
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4000)
+    Ws = [(torch.randn(s, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16) for s in shapes]
+    weights = sum(o * i for o, i in shapes)
+    algo_bytes = weights * 3.125                           # 2 B read + 1 B values + 0.125 B positions per weight
+    batch = sste.PackBatch(Ws, [1.48] * len(Ws), sste.BF16)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters
+
+    def singles():
+        for W, v, m in zip(Ws, batch.vals, batch.metas):
+            sste.project_pack(W, 1.48, sste.BF16, 1.0, vals=v, meta=m)
+
+    ms_batch = timed(batch.launch)
+    ms_single = timed(singles)
+    return {
+        "tensors": len(shapes), "weights": weights, "algorithmic_bytes": algo_bytes,
+        "one_launch": {"ms": ms_batch, "GB_per_s": algo_bytes / ms_batch * 1e-6, "frac_hbm_peak": algo_bytes / ms_batch * 1e-6 / PEAK_HBM_GBS},
+        "launch_per_tensor": {"ms": ms_single, "GB_per_s": algo_bytes / ms_single * 1e-6,
+                              "frac_hbm_peak": algo_bytes / ms_single * 1e-6 / PEAK_HBM_GBS},
     }
 
 
@@ -241,6 +279,8 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if not args.no_prune_model:
+        out["prune_pack_model"] = prune_model(sste, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.layer, wb, xc, xs, dyc, dys, np.float32(beta))
     print(json.dumps(out))

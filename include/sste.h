@@ -93,6 +93,45 @@ int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float be
                       void* vals, void* meta, float* amax_out, void* hip_stream);
 
 /*
+ * Projection + scale + pack of MANY weight tensors in one launch (the per-iteration re-projection of
+ * every sparse layer of a model, Sec. 4: S(W) is recomputed from the dense weights in every iteration).
+ * Single layers are small enough that a launch per tensor is dominated by launch latency; one grid
+ * over all tensors streams at memory bandwidth.  The arithmetic, the rounding and the packed format of
+ * every tensor are exactly those of sste_project_pack.
+ *
+ * Two calls, so that the launch itself touches no host memory and allocates nothing:
+ *   sste_project_pack_batch_prepare  (host only) validates the items and writes a table of
+ *       n_items * SSTE_PACK_TABLE_ITEM_BYTES bytes into HOST memory `table_host`, and the total number
+ *       of 16-row x one-step blocks into *total_blocks_out.  The caller copies the table to device
+ *       memory (16-byte aligned) once; it stays valid as long as the pointers and shapes do.
+ *   sste_project_pack_batch  enqueues one kernel that processes all items of the DEVICE copy of the
+ *       table.  n_items, total_blocks and val_dtype must be the values given to / returned by prepare.
+ *
+ *   items     in   host array; per item: W (device, bf16, O x I, leading dimension ldw), vals and meta
+ *                  (device, sized as for sste_project_pack), O, I, ldw, beta, val_scale -- each with the
+ *                  meaning and the constraints of the same-named argument of sste_project_pack.
+ *                  Items with O * I == 0 are allowed and produce nothing.
+ * Errors (prepare): as sste_project_pack, reported for the first offending item; n_items < 0 -> ERR_SHAPE.
+ * Errors (launch): NULL table with n_items > 0 -> ERR_NULL; misaligned table -> ERR_ALIGN; negative
+ * counts -> ERR_SHAPE; bad dtype -> ERR_DTYPE.  The table's contents are not re-validated.
+ */
+typedef struct sste_pack_item {
+  const void* W;
+  void* vals;
+  void* meta;
+  int64_t O, I, ldw;
+  float beta;
+  float val_scale;
+} sste_pack_item;
+
+#define SSTE_PACK_TABLE_ITEM_BYTES 64
+
+int sste_project_pack_batch_prepare(const sste_pack_item* items, int n_items, int val_dtype,
+                                    void* table_host, int64_t* total_blocks_out);
+int sste_project_pack_batch(const void* table_device, int n_items, int64_t total_blocks, int val_dtype,
+                            void* hip_stream);
+
+/*
  * Forward GEMM with a 2:4-sparse weight operand (Sec. 5.1: Z_l = X_l S(W_l)^T).
  *
  *   Z = (x_scale * w_scale) * X * decode(vals, meta)^T,  float32 accumulation, Z stored as bf16 (RNE).

@@ -9,6 +9,7 @@ cannot be loaded.
 from .binding import (  # noqa: F401
     BF16,
     F8E4M3,
+    PackBatch,
     SsteError,
     compute_beta,
     flip_count,

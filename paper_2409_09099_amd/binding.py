@@ -35,6 +35,8 @@ def library() -> ctypes.CDLL:
     lib.sste_version.restype = ci
     lib.sste_last_error.restype = ctypes.c_char_p
     lib.sste_project_pack.argtypes = [vp, i64, i64, i64, f32, ci, f32, vp, vp, vp, vp]
+    lib.sste_project_pack_batch_prepare.argtypes = [vp, ci, ci, vp, ctypes.POINTER(i64)]
+    lib.sste_project_pack_batch.argtypes = [vp, ci, i64, ci, vp]
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
     lib.sste_wgrad_workspace_bytes.argtypes = [i64, i64, i64, ci]
@@ -48,8 +50,8 @@ def library() -> ctypes.CDLL:
     lib.sste_timing_begin.restype = ci
     lib.sste_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.sste_timing_end.restype = ci
-    for name in ("sste_project_pack", "sste_linear_fwd", "sste_linear_wgrad", "sste_mvue_materialize",
-                 "sste_compute_beta", "sste_flip_count"):
+    for name in ("sste_project_pack", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd",
+                 "sste_linear_wgrad", "sste_mvue_materialize", "sste_compute_beta", "sste_flip_count"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -109,6 +111,49 @@ def project_pack(W: torch.Tensor, beta: float, val_dtype: int = BF16, val_scale:
     _check(library().sste_project_pack(_ptr(W), O, I, ldw, beta, val_dtype, val_scale, _ptr(vals), _ptr(meta),
                                        _ptr(amax_out), _stream(W)))
     return vals, meta
+
+
+class _PackItem(ctypes.Structure):
+    """sste_pack_item of include/sste.h."""
+    _fields_ = [("W", ctypes.c_void_p), ("vals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
+                ("O", ctypes.c_int64), ("I", ctypes.c_int64), ("ldw", ctypes.c_int64),
+                ("beta", ctypes.c_float), ("val_scale", ctypes.c_float)]
+
+
+PACK_TABLE_ITEM_BYTES = 64
+
+
+class PackBatch:
+    """A prepared sste_project_pack_batch: the device table plus the tensors it points to.  `launch()`
+    re-projects and re-packs every tensor in one kernel; call it again whenever the weights changed."""
+
+    def __init__(self, Ws, betas, val_dtype: int = BF16, val_scales=None, vals=None, metas=None):
+        n = len(Ws)
+        if len(betas) != n:
+            raise ValueError("one beta per tensor")
+        val_scales = [1.0] * n if val_scales is None else list(val_scales)
+        self.Ws, self.val_dtype = list(Ws), val_dtype
+        self.vals, self.metas = [], []
+        items = (_PackItem * max(n, 1))()
+        for k, W in enumerate(self.Ws):
+            O, I, ldw = _matrix(W, 2, "W")
+            v, m = (vals[k], metas[k]) if vals is not None and metas is not None else packed_buffers(O, I, val_dtype, W.device)
+            self.vals.append(v)
+            self.metas.append(m)
+            items[k] = _PackItem(_ptr(W), _ptr(v), _ptr(m), O, I, ldw, float(betas[k]), float(val_scales[k]))
+        table_host = torch.zeros(max(n, 1) * PACK_TABLE_ITEM_BYTES, dtype=torch.uint8)
+        total = ctypes.c_int64(0)
+        _check(library().sste_project_pack_batch_prepare(ctypes.cast(items, ctypes.c_void_p), n, val_dtype,
+                                                         ctypes.c_void_p(table_host.data_ptr()), ctypes.byref(total)))
+        self.n, self.total_blocks = n, int(total.value)
+        self.device = self.Ws[0].device if n else torch.device("cuda")
+        self.table = table_host.to(self.device)
+
+    def launch(self):
+        """sste_project_pack_batch on the current stream of the tensors' device."""
+        _check(library().sste_project_pack_batch(_ptr(self.table), self.n, self.total_blocks, self.val_dtype,
+                                                 _stream(self.table)))
+        return self.vals, self.metas
 
 
 def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, dtype: int = BF16, x_scale: float = 1.0,

@@ -125,25 +125,93 @@ int sste_timing_end(double* total_ms, int* launches) {
 
 const char* sste_last_error(void) { return g_err; }
 
+// Per-item argument checks shared by the single-tensor and the batch entry points.
+static int check_pack_args(const char* who, const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
+                           float val_scale, const void* vals, const void* meta) {
+  if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "%s: negative size O=%lld I=%lld", who, (long long)O, (long long)I);
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "%s: I=%lld is not a multiple of 8 (whole groups of 4, two per metadata byte)", who, (long long)I);
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "%s: unknown val_dtype %d", who, val_dtype);
+  if (!good_scale(beta)) return fail(SSTE_ERR_VALUE, "%s: beta must be finite and > 0", who);
+  if (!good_scale(val_scale)) return fail(SSTE_ERR_VALUE, "%s: val_scale must be finite and > 0", who);
+  if (val_dtype == SSTE_BF16 && val_scale != 1.0f) return fail(SSTE_ERR_VALUE, "%s: val_scale must be 1 for bf16 values", who);
+  if (I % (val_dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
+    return fail(SSTE_ERR_UNSUPPORTED, "%s: I=%lld must be a multiple of %d for this value type", who, (long long)I, val_dtype == SSTE_F8E4M3 ? 128 : 64);
+  if (ldw < I) return fail(SSTE_ERR_SHAPE, "%s: ldw=%lld < I=%lld", who, (long long)ldw, (long long)I);
+  if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "%s: ldw=%lld is not a multiple of 8", who, (long long)ldw);
+  bool empty = (O == 0 || I == 0);
+  if (!empty && (!W || !vals || !meta)) return fail(SSTE_ERR_NULL, "%s: NULL W, vals or meta", who);
+  if (!aligned16(W) || !aligned16(vals)) return fail(SSTE_ERR_ALIGN, "%s: W and vals must be 16-byte aligned", who);
+  return SSTE_OK;
+}
+
+// device-side table item of sste_project_pack_batch; must match PackTableItem in prune_pack.hip
+struct PackTableItemHost {
+  const void* W;
+  void* vals;
+  void* meta;
+  int64_t O;
+  int64_t ldw_bytes;
+  int64_t first_block;
+  int32_t steps;
+  float beta;
+  float val_scale;
+  int32_t pad;
+};
+static_assert(sizeof(PackTableItemHost) == SSTE_PACK_TABLE_ITEM_BYTES, "table item size is part of the C ABI");
+
 int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype, float val_scale,
                       void* vals, void* meta, float* amax_out, void* hip_stream) {
   clear_error();
-  if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "project_pack: negative size O=%lld I=%lld", (long long)O, (long long)I);
-  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "project_pack: I=%lld is not a multiple of 8 (whole groups of 4, two per metadata byte)", (long long)I);
-  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "project_pack: unknown val_dtype %d", val_dtype);
-  if (!good_scale(beta)) return fail(SSTE_ERR_VALUE, "project_pack: beta must be finite and > 0");
-  if (!good_scale(val_scale)) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be finite and > 0");
-  if (val_dtype == SSTE_BF16 && val_scale != 1.0f) return fail(SSTE_ERR_VALUE, "project_pack: val_scale must be 1 for bf16 values");
-  if (I % (val_dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
-    return fail(SSTE_ERR_UNSUPPORTED, "project_pack: I=%lld must be a multiple of %d for this value type", (long long)I, val_dtype == SSTE_F8E4M3 ? 128 : 64);
-  if (ldw < I) return fail(SSTE_ERR_SHAPE, "project_pack: ldw=%lld < I=%lld", (long long)ldw, (long long)I);
-  if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "project_pack: ldw=%lld is not a multiple of 8", (long long)ldw);
-  bool empty = (O == 0 || I == 0);
-  if (!empty && (!W || !vals || !meta)) return fail(SSTE_ERR_NULL, "project_pack: NULL W, vals or meta");
-  if (!aligned16(W) || !aligned16(vals)) return fail(SSTE_ERR_ALIGN, "project_pack: W and vals must be 16-byte aligned");
+  int st = check_pack_args("project_pack", W, O, I, ldw, beta, val_dtype, val_scale, vals, meta);
+  if (st != SSTE_OK) return st;
   if (amax_out && (reinterpret_cast<uintptr_t>(amax_out) & 3u)) return fail(SSTE_ERR_ALIGN, "project_pack: amax_out must be 4-byte aligned");
   return hip_status(launch_project_pack(W, O, I, ldw, beta, val_dtype, val_scale, vals, meta, amax_out, (hipStream_t)hip_stream),
                     "project_pack launch");
+}
+
+int sste_project_pack_batch_prepare(const sste_pack_item* items, int n_items, int val_dtype, void* table_host,
+                                    int64_t* total_blocks_out) {
+  clear_error();
+  if (n_items < 0) return fail(SSTE_ERR_SHAPE, "project_pack_batch_prepare: n_items=%d", n_items);
+  if (!total_blocks_out || (n_items > 0 && (!items || !table_host)))
+    return fail(SSTE_ERR_NULL, "project_pack_batch_prepare: NULL items, table_host or total_blocks_out");
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "project_pack_batch_prepare: unknown val_dtype %d", val_dtype);
+  PackTableItemHost* out = (PackTableItemHost*)table_host;
+  int64_t blocks = 0;
+  for (int i = 0; i < n_items; i++) {
+    const sste_pack_item& it = items[i];
+    char who[64];
+    snprintf(who, sizeof who, "project_pack_batch_prepare item %d", i);
+    int st = check_pack_args(who, it.W, it.O, it.I, it.ldw, it.beta, val_dtype, it.val_scale, it.vals, it.meta);
+    if (st != SSTE_OK) return st;
+    int64_t steps = it.I / (val_dtype == SSTE_F8E4M3 ? 128 : 64);
+    if (steps > 0x7FFFFFFFll) return fail(SSTE_ERR_UNSUPPORTED, "%s: I too large", who);
+    PackTableItemHost t{};
+    t.W = it.W;
+    t.vals = it.vals;
+    t.meta = it.meta;
+    t.O = it.O;
+    t.ldw_bytes = it.ldw * 2;
+    t.first_block = blocks;
+    t.steps = (int32_t)(steps > 0 ? steps : 1);       // an empty item owns no block; the divisor only has to be non-zero
+    t.beta = it.beta;
+    t.val_scale = it.val_scale;
+    out[i] = t;
+    blocks += ((it.O + 15) / 16) * steps;
+  }
+  *total_blocks_out = blocks;
+  return SSTE_OK;
+}
+
+int sste_project_pack_batch(const void* table_device, int n_items, int64_t total_blocks, int val_dtype, void* hip_stream) {
+  clear_error();
+  if (n_items < 0 || total_blocks < 0) return fail(SSTE_ERR_SHAPE, "project_pack_batch: negative count");
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "project_pack_batch: unknown val_dtype %d", val_dtype);
+  if (n_items > 0 && !table_device) return fail(SSTE_ERR_NULL, "project_pack_batch: NULL table");
+  if (!aligned16(table_device)) return fail(SSTE_ERR_ALIGN, "project_pack_batch: the table must be 16-byte aligned");
+  if ((total_blocks + 3) / 4 > 0x7FFFFFFFll) return fail(SSTE_ERR_UNSUPPORTED, "project_pack_batch: too many blocks for one grid");
+  return hip_status(launch_project_pack_batch(table_device, n_items, total_blocks, val_dtype, (hipStream_t)hip_stream),
+                    "project_pack_batch launch");
 }
 
 int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale, const void* vals,

@@ -47,60 +47,70 @@ __device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float be
 // writes its 16 bytes of values to position lane of the 1 KiB block and its position bits to
 // position lane of the metadata block.  A wave therefore writes 1 KiB + 128 (256) B contiguously
 // and reads whole 128-byte (256-byte) row segments.
+//
+// Block `blk` (row block rb = blk / steps, column step s = blk % steps) of one tensor, by one wave.
+// Returns the largest |p| this lane recorded (only computed when AMAX).
+template <bool FP8, bool AMAX>
+__device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t blk,
+                                               int64_t ldw_bytes, float beta, float val_scale,
+                                               uint4* __restrict__ vals, void* __restrict__ meta, int lane) {
+  constexpr int NG = FP8 ? 8 : 4;                       // groups per lane
+  float amax = 0.0f;
+  const int64_t rb = blk / steps;
+  const int32_t s = (int32_t)(blk - rb * steps);
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t row = rb * 16 + j;
+  uint32_t w[2 * NG];
+  if (row < O) {
+    const uint4* src = (const uint4*)(W + row * ldw_bytes + ((int64_t)s * 4 + q) * (NG * 8));
+#pragma unroll
+    for (int c = 0; c < NG / 2; c++) {
+      uint4 v = src[c];
+      w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 2 * NG; c++) w[c] = 0;
+  }
+  float p[2 * NG];
+  uint32_t nibs = 0;
+#pragma unroll
+  for (int g = 0; g < NG; g++) {
+    Proj r = project_group(w[2 * g], w[2 * g + 1], beta);
+    p[2 * g] = r.p0;
+    p[2 * g + 1] = r.p1;
+    nibs |= r.nib << (4 * g);
+    if (AMAX) amax = fmaxf(amax, fmaxf(fabsf(r.p0), fabsf(r.p1)));
+  }
+  uint4 out;
+  if (FP8) {
+    uint32_t o[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      uint32_t lo = e4m3_rne_pack(clamp448(p[4 * c] / val_scale), clamp448(p[4 * c + 1] / val_scale));
+      uint32_t hi = e4m3_rne_pack(clamp448(p[4 * c + 2] / val_scale), clamp448(p[4 * c + 3] / val_scale));
+      o[c] = lo | (hi << 16);
+    }
+    out = make_uint4(o[0], o[1], o[2], o[3]);
+    ((uint32_t*)meta)[blk * 64 + lane] = nibs;
+  } else {
+    out = make_uint4(bf16_rne_pack(p[0], p[1]), bf16_rne_pack(p[2], p[3]), bf16_rne_pack(p[4], p[5]),
+                     bf16_rne_pack(p[6], p[7]));
+    ((uint16_t*)meta)[blk * 64 + lane] = (uint16_t)nibs;
+  }
+  vals[blk * 64 + lane] = out;
+  return amax;
+}
+
 template <bool FP8, bool AMAX>
 __global__ void __launch_bounds__(256)
 k_project_pack(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t n_blocks, int64_t ldw_bytes,
                float beta, float val_scale, uint4* __restrict__ vals, void* __restrict__ meta,
                uint32_t* __restrict__ amax_bits) {
-  constexpr int NG = FP8 ? 8 : 4;                       // groups per lane
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   float amax = 0.0f;
-  if (blk < n_blocks) {
-    const int64_t rb = blk / steps;
-    const int32_t s = (int32_t)(blk - rb * steps);
-    const int j = lane & 15, q = lane >> 4;
-    const int64_t row = rb * 16 + j;
-    uint32_t w[2 * NG];
-    if (row < O) {
-      const uint4* src = (const uint4*)(W + row * ldw_bytes + ((int64_t)s * 4 + q) * (NG * 8));
-#pragma unroll
-      for (int c = 0; c < NG / 2; c++) {
-        uint4 v = src[c];
-        w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < 2 * NG; c++) w[c] = 0;
-    }
-    float p[2 * NG];
-    uint32_t nibs = 0;
-#pragma unroll
-    for (int g = 0; g < NG; g++) {
-      Proj r = project_group(w[2 * g], w[2 * g + 1], beta);
-      p[2 * g] = r.p0;
-      p[2 * g + 1] = r.p1;
-      nibs |= r.nib << (4 * g);
-      if (AMAX) amax = fmaxf(amax, fmaxf(fabsf(r.p0), fabsf(r.p1)));
-    }
-    uint4 out;
-    if (FP8) {
-      uint32_t o[4];
-#pragma unroll
-      for (int c = 0; c < 4; c++) {
-        uint32_t lo = e4m3_rne_pack(clamp448(p[4 * c] / val_scale), clamp448(p[4 * c + 1] / val_scale));
-        uint32_t hi = e4m3_rne_pack(clamp448(p[4 * c + 2] / val_scale), clamp448(p[4 * c + 3] / val_scale));
-        o[c] = lo | (hi << 16);
-      }
-      out = make_uint4(o[0], o[1], o[2], o[3]);
-      ((uint32_t*)meta)[blk * 64 + lane] = nibs;
-    } else {
-      out = make_uint4(bf16_rne_pack(p[0], p[1]), bf16_rne_pack(p[2], p[3]), bf16_rne_pack(p[4], p[5]),
-                       bf16_rne_pack(p[6], p[7]));
-      ((uint16_t*)meta)[blk * 64 + lane] = (uint16_t)nibs;
-    }
-    vals[blk * 64 + lane] = out;
-  }
+  if (blk < n_blocks) amax = project_block<FP8, AMAX>(W, O, steps, blk, ldw_bytes, beta, val_scale, vals, meta, lane);
   if (AMAX) {
     // non-negative floats order like their bit patterns: reduce as unsigned integers
     uint32_t m = f2u(amax);
@@ -114,6 +124,38 @@ k_project_pack(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t 
       atomicMax(amax_bits, m);
     }
   }
+}
+
+// Many tensors in one grid: wave w of the grid takes global block w; the table (sorted by first_block)
+// says which tensor that block belongs to.  64 bytes per item, layout shared with api.hip.
+struct PackTableItem {
+  const uint8_t* W;
+  uint4* vals;
+  void* meta;
+  int64_t O;
+  int64_t ldw_bytes;
+  int64_t first_block;
+  int32_t steps;
+  float beta;
+  float val_scale;
+  int32_t pad;
+};
+static_assert(sizeof(PackTableItem) == 64, "table item size is part of the C ABI (SSTE_PACK_TABLE_ITEM_BYTES)");
+
+template <bool FP8>
+__global__ void __launch_bounds__(256)
+k_project_pack_batch(const PackTableItem* __restrict__ table, int n_items, int64_t total_blocks) {
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  if (blk >= total_blocks) return;
+  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (table[mid].first_block <= blk) lo = mid;
+    else hi = mid - 1;
+  }
+  const PackTableItem it = table[lo];
+  project_block<FP8, false>(it.W, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.beta, it.val_scale, it.vals, it.meta, lane);
 }
 
 __global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
@@ -136,6 +178,16 @@ hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw,
     SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   else
     SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
+  return hipGetLastError();
+}
+
+hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t total_blocks, int val_dtype, hipStream_t s) {
+  if (n_items == 0 || total_blocks == 0) return hipSuccess;
+  dim3 grid((unsigned)((total_blocks + 3) / 4)), block(256);
+  if (val_dtype == SSTE_F8E4M3)
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack_batch<true>), grid, block, s, (const PackTableItem*)table, n_items, total_blocks);
+  else
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack_batch<false>), grid, block, s, (const PackTableItem*)table, n_items, total_blocks);
   return hipGetLastError();
 }
 

@@ -112,3 +112,43 @@ def test_other_entry_points_validation(lib):
     assert lib.sste_compute_beta(fake, 4, 16, 16, fake, None, 0, None) == 6
     assert lib.sste_flip_count(fake, fake, 4, 12, fake, None) == 2
     assert lib.sste_flip_count(fake, fake, 4, 16, None, None) == 1
+
+
+def test_project_pack_batch_prepare(lib):
+    """Host-only half of the batch call: validation per item, block counts and the table layout."""
+    import struct
+    from paper_2409_09099_amd.binding import _PackItem, PACK_TABLE_ITEM_BYTES
+    P = ctypes.c_void_p
+    prep = lib.sste_project_pack_batch_prepare
+    total = ctypes.c_int64(-1)
+    items = (_PackItem * 3)(
+        _PackItem(0x10000, 0x20000, 0x30000, 40, 128, 136, 1.5, 1.0),       # 3 row blocks x 2 steps = 6 blocks
+        _PackItem(None, None, None, 0, 64, 64, 1.0, 1.0),                   # empty item: no blocks
+        _PackItem(0x40000, 0x50000, 0x60000, 16, 64, 64, 2.0, 1.0))         # 1 block
+    table = ctypes.create_string_buffer(3 * PACK_TABLE_ITEM_BYTES)
+    assert prep(ctypes.cast(items, P), 3, 0, ctypes.cast(table, P), ctypes.byref(total)) == 0, _err(lib)
+    assert total.value == 7
+    rows = [struct.unpack_from("<QQQqqqiffi", table.raw, k * PACK_TABLE_ITEM_BYTES) for k in range(3)]
+    # (W, vals, meta, O, ldw_bytes, first_block, steps, beta, val_scale, pad)
+    assert rows[0][:7] == (0x10000, 0x20000, 0x30000, 40, 272, 0, 2) and rows[0][7] == 1.5
+    assert rows[1][3] == 0 and rows[1][5] == 6
+    assert rows[2][:7] == (0x40000, 0x50000, 0x60000, 16, 128, 6, 1)
+    # errors name the first offending item
+    items[2].I = 96
+    assert prep(ctypes.cast(items, P), 3, 0, ctypes.cast(table, P), ctypes.byref(total)) == 7 and "item 2" in _err(lib)
+    items[2].I = 64
+    items[0].beta = 0.0
+    assert prep(ctypes.cast(items, P), 3, 0, ctypes.cast(table, P), ctypes.byref(total)) == 5 and "item 0" in _err(lib)
+    items[0].beta = 1.5
+    assert prep(ctypes.cast(items, P), 3, 1, ctypes.cast(table, P), ctypes.byref(total)) == 7      # e4m3 needs I % 128 == 0
+    assert prep(ctypes.cast(items, P), 3, 9, ctypes.cast(table, P), ctypes.byref(total)) == 4
+    assert prep(ctypes.cast(items, P), -1, 0, ctypes.cast(table, P), ctypes.byref(total)) == 2
+    assert prep(ctypes.cast(items, P), 3, 0, None, ctypes.byref(total)) == 1
+    assert prep(None, 0, 0, None, ctypes.byref(total)) == 0 and total.value == 0
+    # launch half: argument checks only (no kernel is enqueued for an empty table)
+    launch = lib.sste_project_pack_batch
+    assert launch(None, 0, 0, 0, None) == 0
+    assert launch(None, 2, 5, 0, None) == 1
+    assert launch(P(0x1004), 2, 5, 0, None) == 3
+    assert launch(P(0x1000), -2, 5, 0, None) == 2
+    assert launch(P(0x1000), 2, 5, 5, None) == 4

@@ -114,6 +114,41 @@ def test_project_pack_e4m3_bit_exact(sste, case):
     assert np.array_equal(got, fv), np.argwhere(got != fv)[:5]
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+def test_project_pack_batch_bit_exact(sste, dtype):
+    """Many tensors in one launch: every tensor's packed form is the oracle's, bit for bit (shapes with a
+    ragged row tail, a strided tensor, an empty tensor and the edge-case groups among them)."""
+    wl = WL.WORKLOADS[1]
+    shapes = [(256, 1024), (77, 1152), (16, 128), (0, 128), (33, 256), (40, 384)]
+    wbs = [WL.weight_bits(wl, k % len(wl.layers), O=O, I=I) if O else np.zeros((0, I), dtype=np.uint16)
+           for k, (O, I) in enumerate(shapes)] + [_edge_weights()]
+    betas = [np.float32(1.25 + 0.125 * k) for k in range(len(wbs))]
+    scales = [np.float32(1.0)] * len(wbs) if dtype == "bf16" else [np.float32(0.004 * (k + 1)) for k in range(len(wbs))]
+    Ws = []
+    for k, wb in enumerate(wbs):
+        if k == 4:                                        # a view into a wider buffer
+            big = torch.zeros((wb.shape[0], wb.shape[1] + 64), dtype=torch.bfloat16, device="cuda")
+            big[:, :wb.shape[1]] = bf16_dev(wb)
+            Ws.append(big[:, :wb.shape[1]])
+        elif wb.shape[0] == 0:
+            Ws.append(torch.empty((0, wb.shape[1]), dtype=torch.bfloat16, device="cuda"))
+        else:
+            Ws.append(bf16_dev(wb))
+    batch = sste.PackBatch(Ws, [float(b) for b in betas], dt(sste, dtype), [float(x) for x in scales])
+    for rep in range(2):                                  # the table is reusable
+        for v, m in zip(batch.vals, batch.metas):
+            v.fill_(0x55)
+            m.fill_(0xAA)
+        vals, metas = batch.launch()
+        for k, wb in enumerate(wbs):
+            if wb.shape[0] == 0:
+                continue
+            rv, rm, _ = OP.project_pack(wb, betas[k]) if dtype == "bf16" else OP.project_pack(wb, betas[k], "e4m3", scales[k])
+            fv, fm = OP.to_fragment_major(rv, rm, dtype)
+            assert np.array_equal(host(metas[k]).numpy().reshape(-1), fm), k
+            assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv), k
+
+
 def test_project_pack_empty_and_errors(sste):
     e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     vals, meta = sste.project_pack(e, 1.0)
