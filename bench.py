@@ -279,6 +279,17 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if wl.cfg == 4:
+        # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta;
+        # the fraction of positions whose kept / pruned state changes (flip rate, paper Sec. 3.3) is a sanity number
+        flips, w_bits = [], wb
+        v_prev, m_prev = sste.project_pack(up(w_bits), beta, dt, w_scale)
+        for k in range(10):
+            w_bits = WL.weight_update_bits(w_bits, wl, args.layer, k)
+            v_new, m_new = sste.project_pack(up(w_bits), beta, dt, w_scale)
+            flips.append(int(sste.flip_count(m_prev, m_new, O).cpu()[0]) / float(O * I))
+            m_prev = m_new
+        out["flip_rate_per_step"] = flips
     if not args.no_prune_model:
         out["prune_pack_model"] = prune_model(sste, torch)
     if not args.no_cpu_baseline:
