@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
     ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-context", action="store_true",
+                    help="also time the vendor dense bf16 GEMM (torch.matmul) on the same shapes: context, not the product")
     ap.add_argument("--no-prune-model", action="store_true",
                     help="skip the whole-model re-projection measurement (144 weight tensors of GPT-2-774M, 2.2 GB)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with events (debug)")
@@ -279,6 +281,21 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if args.dense_context and not fp8:
+        # what the vendor's dense GEMM reaches on the same layer (forward Z = X W^T; weight gradient dY^T X)
+        def dense_us(fn, iters=50):
+            for i in range(5):
+                fn(i)
+            torch.cuda.synchronize()
+            d0 = time.perf_counter()
+            for i in range(iters):
+                fn(i)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - d0) / iters * 1e6
+        f_us = dense_us(lambda i: torch.matmul(Xs[i % nsets], W.t(), out=Zs[i % nsets]))
+        w_us = dense_us(lambda i: torch.matmul(dYs[i % nsets].t(), Xs[i % nsets]))
+        out["dense_context"] = {"library": "torch.matmul (bf16 in, bf16 out)", "fwd_us": f_us, "fwd_TFLOP_per_s": gemm_flops / f_us * 1e-6,
+                                "wgrad_us": w_us, "wgrad_TFLOP_per_s": gemm_flops / w_us * 1e-6}
     if wl.cfg == 4:
         # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta;
         # the fraction of positions whose kept / pruned state changes (flip rate, paper Sec. 3.3) is a sanity number
