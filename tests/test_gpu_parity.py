@@ -368,3 +368,48 @@ def test_large_kernels_with_strided_operands(sste):
     refw = OL.linear_wgrad(dyc, xc, 11, 2, "bf16", dys, xs)
     assert rel_err(host(dWbig[:, :I]).numpy().astype(np.float64), refw) <= 1e-4
     assert float((dWbig[:, I:] - 9.0).abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------------------------------ HIP graph capture
+
+def test_step_under_graph_capture_replays_bit_exact(sste):
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    memset nodes), so a whole step can be captured into a HIP graph.  Every replay must reproduce the eager
+    result bit for bit, with eager work and synchronisations between the replays."""
+    T, O, I = 4096, 512, 256                       # takes the estimator pre-pass + packed GEMM + reduction
+    wl = WL.WORKLOADS[1]
+    W = bf16_dev(WL.weight_bits(wl, 0, O=O, I=I))
+    X = bf16_dev(WL.activations(wl, 0, T=T, I=I)[0])
+    dY = bf16_dev(WL.output_gradient(wl, 0, T=T, O=O)[0])
+    beta = 1.4830322
+    vals, meta = sste.packed_buffers(O, I, sste.BF16, "cuda")
+    Z = torch.empty((T, O), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((O, I), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(sste.wgrad_workspace_bytes(T, O, I, sste.BF16), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sste.project_pack(W, beta, vals=vals, meta=meta)
+        sste.linear_fwd(X, vals, meta, O, Z=Z)
+        sste.linear_wgrad(dY, X, 5, 9, dW=dW, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (vals, meta, Z, dW)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(4):
+        for t in (vals, meta, Z, dW, ws):
+            t.view(torch.uint8).fill_(0x3C + rep)  # eager work between replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((vals, meta, Z, dW), ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), rep
