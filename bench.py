@@ -26,9 +26,9 @@ PEAK_DENSE_TFLOPS = {"bf16": 2500.0, "e4m3": 5000.0}
 # summary with the commands is committed under profiles/.  KiB read + KiB written.
 HBM_TRAFFIC_KIB = {
     (2, "project_pack"): 4658 + 2592,
-    (2, "fwd"): 42320 + 49225,
+    (2, "fwd"): 42304 + 49211,
     (2, "mvue_pack"): 49246 + 27648,
-    (2, "wgrad"): 67784 + 36882,
+    (2, "wgrad"): 67784 + 36887,
 }
 
 
