@@ -1,11 +1,12 @@
-"""The sparse linear layer of Sec. 5.1: Z = X S(W)^T and grad_W = MVUE(grad_Z^T) X.
+"""The sparse linear layer of Sec. 5.1: Z = X S(W)^T, grad_W = MVUE(grad_Z^T) X and grad_X = grad_Z S(W).
 
 Test infrastructure only (see the package header).  Both products are the plain definitions,
 evaluated in float64 on exactly the quantised operands the storage formats hold (bf16 or e4m3
 decoded without error), so the only difference to a finite-precision GEMM is accumulation
 rounding.  Pinned (tests/test_oracle_linear.py): a pure-Python triple loop on tiny shapes,
 linearity, and -- for the weight gradient -- convergence of the mean over seeds to the dense
-product grad_Z^T X.
+product grad_Z^T X; the input gradient is pinned by its own loop and by the adjoint identity
+<grad_Z, X S(W)^T> = <grad_Z S(W), X> that ties it to the forward product.
 """
 import numpy as np
 
@@ -67,3 +68,26 @@ def linear_wgrad_dense(dy_codes, x_codes, dtype="bf16", dy_scale=1.0, x_scale=1.
     dY = decode_activations(dy_codes, dtype)
     X = decode_activations(x_codes, dtype)
     return (dY.T @ X) * (np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale)))
+
+
+def linear_dgrad(dy_codes, vals, meta, dtype="bf16", dy_scale=1.0, w_scale=1.0):
+    """grad_X = (dy_scale * w_scale) * grad_Z . decode(vals, meta)   in float64 (Sec. 5.1: the input
+    gradient is the dense product with the projected weight; it is not sparsified).  dY: (T, O),
+    result (T, I)."""
+    dY = decode_activations(dy_codes, dtype)
+    Wd = projection.decode_packed(vals, meta, dtype)                # (O, I)
+    return (dY @ Wd) * (np.float64(np.float32(dy_scale)) * np.float64(np.float32(w_scale)))
+
+
+def linear_dgrad_loops(dY, Wd):
+    """Triple loop dX[t][i] = sum_o dY[t][o] Wd[o][i] for tiny shapes (pure Python floats)."""
+    T, O = dY.shape
+    I = Wd.shape[1]
+    dX = [[0.0] * I for _ in range(T)]
+    for t in range(T):
+        for i in range(I):
+            acc = 0.0
+            for o in range(O):
+                acc += float(dY[t][o]) * float(Wd[o][i])
+            dX[t][i] = acc
+    return np.array(dX, dtype=np.float64)

@@ -99,3 +99,37 @@ def test_wgrad_e4m3_doubles_the_stored_half_theta():
     half_theta = P.decode_packed(vals, meta, "e4m3").T
     want = (half_theta.T @ F.e4m3_to_f32(x).astype(np.float64)) * 2 * 0.5 * 0.25
     assert np.allclose(dW, want, rtol=1e-13)
+
+
+def test_dgrad_against_triple_loop_and_shape():
+    rng = np.random.default_rng(7)
+    wb = _bf16(rng, (8, 16), 0.02)                  # O = 8, I = 16
+    dyb = _bf16(rng, (12, 8), 1e-3)                 # T = 12
+    vals, meta, _ = P.project_pack(wb, 1.5)
+    dX = Lin.linear_dgrad(dyb, vals, meta)
+    Wd = P.decode_packed(vals, meta)
+    dY = F.bf16_to_f32(dyb).astype(np.float64)
+    assert dX.shape == (12, 16)                     # a transposed weight or a wrong contraction axis fails here
+    assert np.allclose(dX, Lin.linear_dgrad_loops(dY, Wd), rtol=1e-13, atol=1e-22)
+    # a zero in S(W) column i for every channel gives a zero input gradient there: the 2:4 structure shows
+    pruned_everywhere = np.all(Wd == 0.0, axis=0)
+    assert np.all(dX[:, pruned_everywhere] == 0.0)
+    assert np.allclose(Lin.linear_dgrad(dyb, vals, meta, dy_scale=0.25, w_scale=8.0), 2.0 * dX)
+
+
+def test_dgrad_is_the_adjoint_of_the_forward_product():
+    """<dY, X S(W)^T> = <dY S(W), X> for any X, dY: ties the input gradient to the forward oracle."""
+    rng = np.random.default_rng(8)
+    for dtype, wscale in (("bf16", 1.0), ("e4m3", 0.0002)):
+        wb = _bf16(rng, (24, 32), 0.02)
+        vals, meta, _ = P.project_pack(wb, 1.4, dtype, np.float32(wscale))
+        if dtype == "bf16":
+            x, dy = _bf16(rng, (10, 32), 1.0), _bf16(rng, (10, 24), 1e-3)
+        else:
+            x = F.f32_to_e4m3_rne_sat((rng.standard_normal((10, 32)) * 40).astype(np.float32))
+            dy = F.f32_to_e4m3_rne_sat((rng.standard_normal((10, 24)) * 40).astype(np.float32))
+        Z = Lin.linear_fwd(x, vals, meta, dtype, x_scale=1.0, w_scale=wscale)
+        dX = Lin.linear_dgrad(dy, vals, meta, dtype, dy_scale=1.0, w_scale=wscale)
+        lhs = np.sum(Lin.decode_activations(dy, dtype) * Z)
+        rhs = np.sum(dX * Lin.decode_activations(x, dtype))
+        assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), abs(rhs))
