@@ -178,6 +178,26 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
                       float* dW, int64_t lddw, int accumulate,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Input gradient (Sec. 5.1: grad_X_l = grad_Z_l S(W_l); the paper keeps this product dense).
+ *
+ *   dX = (dy_scale * w_scale) * dY * decode(vals, meta),  float32 accumulation, dX stored as bf16 (RNE).
+ *
+ *   dY       in   device, T x O of `dtype`, leading dimension lddy
+ *   T, O, I  in   T >= 0; O >= 0 and a multiple of 8; I a multiple of 64
+ *   dtype    in   SSTE_BF16 (element type of dY and of vals).  SSTE_F8E4M3 -> ERR_UNSUPPORTED.
+ *   dy_scale, w_scale  in  finite, > 0
+ *   vals, meta  in   packed S(W) (R = O rows, K = I columns) as written by sste_project_pack; rows past O
+ *                    up to the next multiple of 16 must be the padding that call writes
+ *   dX       out  device, T x I bf16, leading dimension lddx (multiple of 8); O == 0 gives zeros
+ * The packed weight is expanded to dense-with-zeros on its way into on-chip memory; nothing is
+ * written besides dX.
+ * Errors: as sste_linear_fwd, with the roles of X / Z taken by dY / dX.
+ */
+int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                      const void* vals, const void* meta, int64_t I, float w_scale,
+                      void* dX, int64_t lddx, void* hip_stream);
+
 /* Bytes of scratch sste_linear_wgrad needs for this problem (0 if it needs none; 0 on bad arguments). */
 size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 
@@ -238,7 +258,8 @@ typedef enum {
   SSTE_K_WGRAD = 2,          /* weight-gradient sparse GEMM */
   SSTE_K_WGRAD_REDUCE = 3,   /* fixed-order reduction of the token-axis splits */
   SSTE_K_MVUE_PACK = 4,      /* estimator pre-pass of the weight-gradient path (large problems) */
-  SSTE_K_COUNT = 5
+  SSTE_K_DGRAD = 5,          /* input-gradient dense GEMM */
+  SSTE_K_COUNT = 6
 } sste_kernel_id;
 int sste_timing_begin(int max_launches);
 int sste_timing_end(double* total_ms, int* launches);

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     compute_beta,
     flip_count,
     library,
+    linear_dgrad,
     linear_fwd,
     linear_wgrad,
     mvue_materialize,

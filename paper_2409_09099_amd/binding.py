@@ -38,6 +38,7 @@ def library() -> ctypes.CDLL:
     lib.sste_project_pack_batch_prepare.argtypes = [vp, ci, ci, vp, ctypes.POINTER(i64)]
     lib.sste_project_pack_batch.argtypes = [vp, ci, i64, ci, vp]
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
+    lib.sste_linear_dgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
     lib.sste_wgrad_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.sste_wgrad_workspace_bytes.restype = sz
@@ -50,7 +51,7 @@ def library() -> ctypes.CDLL:
     lib.sste_timing_begin.restype = ci
     lib.sste_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.sste_timing_end.restype = ci
-    for name in ("sste_project_pack", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd",
+    for name in ("sste_project_pack", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd", "sste_linear_dgrad",
                  "sste_linear_wgrad", "sste_mvue_materialize", "sste_compute_beta", "sste_flip_count"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -169,6 +170,19 @@ def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, 
     return Z
 
 
+def linear_dgrad(dY: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, I: int, dtype: int = BF16, dy_scale: float = 1.0,
+                 w_scale: float = 1.0, dX: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """sste_linear_dgrad: dX = (dy_scale * w_scale) * dY decode(vals, meta), bf16 output.  I = dense columns of
+    the packed operand."""
+    T, O, lddy = _matrix(dY, _esize(dtype), "dY")
+    if dX is None:
+        dX = torch.empty((T, I), dtype=torch.bfloat16, device=dY.device)
+    _, _, lddx = _matrix(dX, 2, "dX")
+    _check(library().sste_linear_dgrad(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(vals), _ptr(meta), I, w_scale, _ptr(dX),
+                                       lddx, _stream(dY)))
+    return dX
+
+
 def wgrad_workspace_bytes(T: int, O: int, I: int, dtype: int = BF16) -> int:
     return int(library().sste_wgrad_workspace_bytes(T, O, I, dtype))
 
@@ -225,7 +239,7 @@ def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor, O: int) -> torch.Tens
     return out
 
 
-KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack")
+KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack", "dgrad")
 
 
 def timing_begin(max_launches: int = 4096) -> None:

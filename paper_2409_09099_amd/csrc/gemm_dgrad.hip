@@ -1,0 +1,280 @@
+// Input gradient of the S-STE linear layer (paper Sec. 5.1): grad_X = grad_Z S(W).  The paper keeps this
+// product dense (only grad_Z is sparsified, and only for the weight gradient), so it runs on the dense
+// matrix instruction; what it shares with the forward pass is the packed weight, which is decoded to
+// dense-with-zeros on its way into LDS instead of being kept a second time in memory.
+//
+// MFMA mapping: grad_X^T = S(W)^T grad_Z^T.  Rows = input features i, columns = tokens t, contraction
+// k = output channels o.  v_mfma_f32_16x16x32_bf16: A lane (row i = lane % 16, q = lane / 16) holds
+// k = 8q .. 8q+7, B lane (col j, q) the same k range of its column, D lane (j, q) register r is
+// element (4q + r, j).  A 64-channel k-step takes two instructions per tile (k 0..31 and 32..63).
+//   B operand = grad_Z tile: token rows with 64 channels (128 B) contiguous -- the same tile, swizzle
+//     and 16-byte fragment reads as X in the forward GEMM; direct-to-LDS loads into a two-slot ring.
+//   A operand = S(W) tile: 64 channels x 256 features.  Each wave loads two 1 KiB blocks of packed
+//     values plus their position bits into registers, expands every group of four (two values, two
+//     2-bit positions -> four bf16) and writes dense rows [channel][feature] into a three-slot LDS
+//     ring, in the layout and swizzle the weight-gradient GEMM uses for X (512-byte rows, 32-byte
+//     feature pair p of row r at position p ^ (r % 16)).  The contraction index is strided there, so
+//     the fragments are read with the transposing LDS load (ds_read_b64_tr_b16).
+// Pipeline per k-step s: wait for everything issued during s - 1 (grad_Z tile s + 1 in LDS, packed
+// blocks s + 2 in registers), barrier, decode blocks s + 2 into LDS, then eight groups of MFMAs during
+// which the grad_Z fragments of s + 1 are read (register double buffer), the S(W) fragments roll one
+// row block ahead, the grad_Z tile s + 2 is requested and, last, the packed blocks s + 3 are loaded.
+// Loads get one k-step (about 2000 clocks here) to complete; that keeps the LDS at exactly 160 KiB.
+// Epilogue as in the forward GEMM: transposed through LDS, 16-byte streaming stores of bf16 rows.
+#include "common.h"
+
+namespace sste {
+
+namespace {
+constexpr int NUM_XCD = 8;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+__device__ __forceinline__ int xcd_contiguous(int bid, int nblk) {
+  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
+  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
+  return (rem == 0 || xcd < rem) ? xcd * per_xcd + slot : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+}
+constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
+
+// One group of a packed 2:4 operand -> its four dense bf16: w = value0 | value1 << 16 (ascending
+// positions), nib = pos0 | pos1 << 2 with pos0 < pos1.  lo holds positions 0, 1; hi positions 2, 3.
+__device__ __forceinline__ void expand_group(uint32_t w, uint32_t nib, uint32_t& lo, uint32_t& hi) {
+  const uint32_t pos0 = nib & 3u, pos1 = nib >> 2;
+  const uint32_t v0 = w & 0xFFFFu, v0h = w << 16, v1 = w >> 16, v1h = w & 0xFFFF0000u;
+  lo = (pos0 == 0u ? v0 : 0u) | (pos0 == 1u ? v0h : 0u) | (pos1 == 1u ? v1h : 0u);
+  hi = (pos0 == 2u ? v0 : 0u) | (pos1 == 2u ? v1 : 0u) | (pos1 == 3u ? v1h : 0u);
+}
+}  // namespace
+
+__global__ void __launch_bounds__(512, 1)
+k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
+               const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
+               float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
+  constexpr int WN = 4, NW = 8, MI_ = 8, NI_ = 4;
+  constexpr int BM = 256, BN = 256;                 // features x tokens per workgroup
+  constexpr int ASLOT = 64 * 512;                   // decoded S(W): 64 channels x 256 features bf16
+  constexpr int BSLOT = BN * 128;                   // grad_Z: 256 tokens x 64 channels bf16
+  constexpr int NRA = 3, NRB = 2;
+  constexpr int LB = BSLOT / 1024 / NW;             // direct-to-LDS loads per wave and k-step: 4
+  constexpr int EROW = 32 * MI_ + 16;
+  constexpr int NPIECE = 2 * NI_;
+  static_assert(NRA * ASLOT + NRB * BSLOT <= 160 * 1024 && NW * 16 * NI_ * EROW <= NRA * ASLOT + NRB * BSLOT, "LDS budget");
+  __shared__ __align__(1024) uint8_t smem[NRA * ASLOT + NRB * BSLOT];
+  uint8_t* const smemA = smem;
+  uint8_t* const smemB = smem + NRA * ASLOT;
+
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tm = logical % m_tiles, tn = logical / m_tiles;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t i0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
+  const int nsteps = (int)((O + 63) / 64);
+  const int64_t rbn = (O + 15) / 16;
+
+  // grad_Z tile: exactly the valid rows and channels; what lies outside reads as zeros
+  const int rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
+  const i32x4 bb = rsrc_words(dY + t0 * lddy_bytes, (uint32_t)((rows_b - 1) * lddy_bytes + O * 2));
+  uint32_t offb[LB];
+#pragma unroll
+  for (int i = 0; i < LB; i++) {
+    int wl = LB * wave + i;
+    int r = 8 * wl + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
+    offb[i] = (uint32_t)(r * lddy_bytes + c * 16);
+  }
+  const uint32_t ldsB = (uint32_t)(uintptr_t)(lds_u8*)smemB;
+  constexpr uint32_t DEAD = 0x40000000u;
+
+  // packed S(W): this wave's two blocks of a k-step are (row block 4 s + rbl, column step 4 tm + csl)
+  const BufferRsrc rv = make_rsrc(vals, (uint32_t)(rbn * isteps * 1024));
+  const BufferRsrc rm = make_rsrc(meta, (uint32_t)(rbn * isteps * 128));
+  uint32_t pv_off[2], pm_off[2], dec_off[2];
+#pragma unroll
+  for (int e = 0; e < 2; e++) {
+    const int blkid = 2 * wave + e, rbl = blkid >> 2, csl = blkid & 3;
+    const int cs = 4 * tm + csl;
+    const bool live = cs < isteps;                  // column steps past the last feature: nothing to fetch
+    pv_off[e] = live ? (uint32_t)((rbl * isteps + cs) * 1024 + lane * 16) : 0x80000000u;
+    pm_off[e] = live ? (uint32_t)((rbl * isteps + cs) * 128 + lane * 2) : 0x80000000u;
+    const int row = 16 * rbl + j, p = 4 * csl + q;
+    dec_off[e] = (uint32_t)(row * 512 + ((p ^ (row & 15)) * 32));
+  }
+  uint4 pk[2];
+  uint32_t pmeta[2];
+#define DG_LOAD_PACKED(step)                                                                              \
+  do {                                                                                                    \
+    const uint32_t sv_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 1024u;                                \
+    const uint32_t sm_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 128u;                                 \
+    _Pragma("unroll") for (int e = 0; e < 2; e++) {                                                       \
+      /* row blocks past the last one (tail of the channel axis, k-steps past the end) fetch nothing */    \
+      const bool live_ = 4 * (int64_t)(step) + ((2 * wave + e) >> 2) < rbn;                               \
+      pk[e] = buffer_load_b128(rv, live_ ? pv_off[e] : 0x80000000u, live_ ? sv_ : 0u);                    \
+      pmeta[e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
+                                                                         (int)(live_ ? sm_ : 0u), 0);    \
+    }                                                                                                     \
+  } while (0)
+#define DG_DECODE(slot_)                                                                                  \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int e = 0; e < 2; e++) {                                                       \
+      uint32_t d_[8];                                                                                     \
+      expand_group(pk[e].x, pmeta[e] & 15u, d_[0], d_[1]);                                                \
+      expand_group(pk[e].y, (pmeta[e] >> 4) & 15u, d_[2], d_[3]);                                         \
+      expand_group(pk[e].z, (pmeta[e] >> 8) & 15u, d_[4], d_[5]);                                         \
+      expand_group(pk[e].w, pmeta[e] >> 12, d_[6], d_[7]);                                                \
+      uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
+      *(uint4*)dst_ = make_uint4(d_[0], d_[1], d_[2], d_[3]);                                             \
+      *(uint4*)(dst_ + 16) = make_uint4(d_[4], d_[5], d_[6], d_[7]);                                      \
+    }                                                                                                     \
+  } while (0)
+#define DG_DMA_B(i, step, slot_)                                                                          \
+  dma_b128(bb, ldsB + (uint32_t)(slot_) * BSLOT + (LB * wave + (i)) * 1024, offb[i],                      \
+           (step) < nsteps ? (uint32_t)(step) * 128u : DEAD)
+
+  f32x4 acc[MI_][NI_];
+#pragma unroll
+  for (int a = 0; a < MI_; a++)
+#pragma unroll
+    for (int b = 0; b < NI_; b++) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // fragment addresses.  S(W): transposing reads, piece r covers channels 8q + 4 (r & 1) + 32 (r >> 1) .. + 3
+  // of the 16 features of row block mi; the feature pair index 8 wm + mi enters through the XOR below
+  // (mi only touches the low three bits of the pair position).
+  uint32_t fa_off[4];
+#pragma unroll
+  for (int r = 0; r < 4; r++) {
+    int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
+    fa_off[r] = (uint32_t)(row * 512 + (((8 * wm) ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+  }
+  const int rb0 = 16 * NI_ * wn + j;
+  const int cb0 = q ^ ((j >> 1) & 7);
+  const uint32_t fb_off0 = (uint32_t)(rb0 * 128 + cb0 * 16);
+  const uint32_t fb_off1 = (uint32_t)(rb0 * 128 + (cb0 ^ 4) * 16);
+
+#define DG_READ_A(dst, base, mi_)                                                                         \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int r = 0; r < 4; r++) {                                                       \
+      bf16x4 t_ = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)((base) + (fa_off[r] ^ (uint32_t)((mi_) * 32)))); \
+      __builtin_memcpy(&dst[r], &t_, 8);                                                                  \
+    }                                                                                                     \
+  } while (0)
+
+  // prologue: grad_Z tiles 0 and 1 requested, S(W) tiles 0 and 1 decoded, packed blocks of k-step 2 in registers
+#pragma unroll
+  for (int i = 0; i < LB; i++) DG_DMA_B(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < LB; i++) DG_DMA_B(i, 1, 1);
+  DG_LOAD_PACKED(0);
+  DG_DECODE(0);
+  DG_LOAD_PACKED(1);
+  DG_DECODE(1);
+  DG_LOAD_PACKED(2);
+
+  uint4 fb0[NI_][2], fb1[NI_][2];     // grad_Z fragments: current / next k-step
+  uint2 fa[2][4];                     // S(W) fragments of row block mi in fa[mi % 2]
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int ni = 0; ni < NI_; ni++) {
+    fb0[ni][0] = *(const uint4*)(smemB + fb_off0 + ni * 2048);
+    fb0[ni][1] = *(const uint4*)(smemB + fb_off1 + ni * 2048);
+  }
+  DG_READ_A(fa[0], smemA, 0);
+
+  int a0 = 0, a1 = 1, a2 = 2;         // S(W) ring slots of k-steps step, step + 1, step + 2
+  int b1 = 1;                         // grad_Z ring slot of k-step step + 1 (step + 2 goes to the other one)
+
+#define DG_STEP(BC, BX)                                                                                   \
+  do {                                                                                                    \
+    wait_vmcnt<0>();                  /* everything issued during the previous k-step has arrived */      \
+    __syncthreads();                  /* ... for every wave; S(W) slot a2 and grad_Z slot 1 - b1 are free */ \
+    DG_DECODE(a2);                                                                                        \
+    const uint8_t* pa = smemA + a0 * ASLOT;                                                               \
+    const uint8_t* pa1 = smemA + a1 * ASLOT;                                                              \
+    const uint8_t* pb1 = smemB + b1 * BSLOT;                                                              \
+    _Pragma("unroll") for (int mi = 0; mi < MI_; mi++) {                                                  \
+      if (mi < MI_ - 1) DG_READ_A(fa[(mi + 1) & 1], pa, mi + 1);                                          \
+      else DG_READ_A(fa[(mi + 1) & 1], pa1, 0);                                                           \
+      _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
+        if (spread(pc, NPIECE, MI_) == mi)                                                                \
+          BX[pc >> 1][pc & 1] = *(const uint4*)(pb1 + ((pc & 1) ? fb_off1 : fb_off0) + (pc >> 1) * 2048); \
+      _Pragma("unroll") for (int n = 0; n < LB; n++)                                                      \
+        if (n == mi) DG_DMA_B(n, step + 2, 1 - b1);                                                       \
+      if (mi == MI_ - 1) DG_LOAD_PACKED(step + 3);                                                        \
+      _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
+        bf16x8 av0, av1, bv0, bv1;                                                                        \
+        __builtin_memcpy(&av0, &fa[mi & 1][0], 16);                                                       \
+        __builtin_memcpy(&av1, &fa[mi & 1][2], 16);                                                       \
+        __builtin_memcpy(&bv0, &BC[ni][0], 16);                                                           \
+        __builtin_memcpy(&bv1, &BC[ni][1], 16);                                                           \
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av0, bv0, acc[mi][ni], 0, 0, 0);            \
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av1, bv1, acc[mi][ni], 0, 0, 0);            \
+      }                                                                                                   \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
+    const int t_ = a0;                                                                                    \
+    a0 = a1;                                                                                              \
+    a1 = a2;                                                                                              \
+    a2 = t_;                                                                                              \
+    b1 = 1 - b1;                                                                                          \
+  } while (0)
+
+  int step = 0;
+  for (; step + 1 < nsteps; step += 2) {
+    DG_STEP(fb0, fb1);
+    step++;
+    DG_STEP(fb1, fb0);
+    step--;
+  }
+  if (step < nsteps) DG_STEP(fb0, fb1);
+#undef DG_STEP
+#undef DG_READ_A
+#undef DG_DMA_B
+#undef DG_DECODE
+#undef DG_LOAD_PACKED
+
+  // epilogue: accumulators -> LDS (row = token, the wave's 128 features contiguous) -> 16-byte stores
+  wait_vmcnt<0>();
+  __syncthreads();
+  uint8_t* eb = smem + wave * (16 * NI_ * EROW);
+#pragma unroll
+  for (int mi = 0; mi < MI_; mi++)
+#pragma unroll
+    for (int ni = 0; ni < NI_; ni++) {
+      uint2 v;
+      v.x = bf16_rne_pack(acc[mi][ni][0] * scale, acc[mi][ni][1] * scale);
+      v.y = bf16_rne_pack(acc[mi][ni][2] * scale, acc[mi][ni][3] * scale);
+      *(uint2*)(eb + (16 * ni + j) * EROW + (16 * mi + 4 * q) * 2) = v;
+    }
+  constexpr int CHUNKS = 2 * MI_, NCH = 16 * NI_ * CHUNKS;
+#pragma unroll
+  for (int it = 0; it < (NCH + 63) / 64; it++) {
+    int c = 64 * it + lane;
+    if (c < NCH) {
+      int row = c / CHUNKS, chunk = c % CHUNKS;
+      uint4 v = *(const uint4*)(eb + row * EROW + chunk * 16);
+      int64_t t = t0 + 16 * NI_ * wn + row, i = i0 + 16 * MI_ * wm + 8 * chunk;
+      if (t < T && i < I) store_stream_b128(dX + t * lddx + i, v);
+    }
+  }
+}
+
+bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype) {
+  if (dtype != SSTE_BF16) return false;                                   // e4m3 operands: not built
+  if (256 * lddy * 2 >= (1ll << 30)) return false;                        // 32-bit offsets inside a grad_Z tile
+  if (((O + 15) / 16 * 16) * I >= (1ll << 31)) return false;              // packed operand addressed with 32-bit offsets
+  if (((I + 255) / 256) * ((T + 255) / 256) > 0x7FFFFFFFll) return false;
+  return true;
+}
+
+hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, float scale, const void* vals,
+                               const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s) {
+  if (T == 0 || I == 0) return hipSuccess;
+  int m_tiles = (int)((I + 255) / 256), n_tiles = (int)((T + 255) / 256);
+  dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
+  SSTE_LAUNCH(SSTE_K_DGRAD, k_linear_dgrad, grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
+              (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
+  return hipGetLastError();
+}
+
+}  // namespace sste

@@ -413,3 +413,59 @@ def test_step_under_graph_capture_replays_bit_exact(sste):
         torch.cuda.synchronize()
         for got, want in zip((vals, meta, Z, dW), ref):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), rep
+
+
+# ------------------------------------------------------------------------------------------ input gradient
+
+@pytest.mark.parametrize("T,O,I", [
+    (512, 256, 1024),          # the tiny workload's shapes
+    (300, 264, 320),           # ragged token tile, channel count not a multiple of the 64-channel k-step, ragged feature tile
+    (1, 8, 64),                # single token, one partial k-step
+    (1000, 520, 384),          # several k-steps, two feature tiles
+    (8, 0, 64),                # no channels: zeros
+])
+def test_linear_dgrad_matches_oracle(sste, T, O, I):
+    wl = WL.WORKLOADS[1]
+    beta = np.float32(1.4830322)
+    dyc, dys = WL.output_gradient(wl, 0, T=T, O=max(O, 8))
+    dyc = dyc[:, :O]
+    if O:
+        wb = WL.weight_bits(wl, 0, O=O, I=I)
+        rv, rm, _ = OP.project_pack(wb, beta)
+        vals, meta = sste.project_pack(bf16_dev(wb), float(beta))
+        ref = OL.linear_dgrad(dyc, rv, rm, "bf16", dys, np.float32(1.0))
+        dY = bf16_dev(np.ascontiguousarray(dyc))
+    else:
+        vals, meta = sste.packed_buffers(0, I, sste.BF16, "cuda")
+        ref = np.zeros((T, I))
+        dY = torch.zeros((T, 8), dtype=torch.bfloat16, device="cuda")[:, :0]      # no channels, valid row pitch
+    dX = torch.full((T, I), 7.0, dtype=torch.bfloat16, device="cuda")
+    sste.linear_dgrad(dY, vals, meta, I, sste.BF16, float(dys), 1.0, dX=dX)
+    got = z_to_f64(dX)
+    if O == 0:
+        assert np.all(got == 0.0)
+        return
+    assert rel_err(got, ref) <= TOL["bf16"]
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + np.max(np.abs(ref)) * 1e-4)
+
+
+def test_linear_dgrad_strided_and_errors(sste):
+    T, O, I = 260, 72, 128
+    wl = WL.WORKLOADS[1]
+    wb = WL.weight_bits(wl, 0, O=O, I=I)
+    dyc, dys = WL.output_gradient(wl, 0, T=T, O=O)
+    rv, rm, _ = OP.project_pack(wb, np.float32(1.25))
+    vals, meta = sste.project_pack(bf16_dev(wb), 1.25)
+    dYbig = torch.full((T, O + 24), 3.0, dtype=torch.bfloat16, device="cuda")
+    dYbig[:, :O] = bf16_dev(dyc)
+    dXbig = torch.full((T, I + 8), -5.0, dtype=torch.bfloat16, device="cuda")
+    sste.linear_dgrad(dYbig[:, :O], vals, meta, I, sste.BF16, float(dys), 1.0, dX=dXbig[:, :I])
+    ref = OL.linear_dgrad(dyc, rv, rm, "bf16", dys, np.float32(1.0))
+    assert rel_err(z_to_f64(dXbig[:, :I]), ref) <= TOL["bf16"]
+    assert float((dXbig[:, I:].float() + 5.0).abs().max()) == 0.0
+    with pytest.raises(sste.SsteError) as ei:          # e4m3 operands are not built for this product
+        sste.linear_dgrad(torch.zeros((T, 80), dtype=torch.uint8, device="cuda"), vals, meta, I, sste.F8E4M3)
+    assert ei.value.status == 7
+    with pytest.raises(sste.SsteError) as ei:
+        sste.linear_dgrad(dYbig[:, :O], vals, meta, 96)
+    assert ei.value.status == 7
