@@ -281,6 +281,21 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if not fp8:
+        # the layer's third GEMM, grad_X = grad_Z S(W): dense by the paper's choice, not part of `value`
+        dXs = [torch.empty((T, I), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+        for i in range(5):
+            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, dt, float(dys), w_scale, dX=dXs[i % nsets])
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(args.steps):
+            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, dt, float(dys), w_scale, dX=dXs[i % nsets])
+        torch.cuda.synchronize()
+        dg_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        out_dgrad = {"ms": dg_ms, "TFLOP_per_s": gemm_flops / (dg_ms * 1e-3) * 1e-12, "frac_dense_mfma_peak": gemm_flops / (dg_ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
+        del dXs
+    else:
+        out_dgrad = None
     if args.dense_context and not fp8:
         # what the vendor's dense GEMM reaches on the same layer (forward Z = X W^T; weight gradient dY^T X)
         def dense_us(fn, iters=50):
@@ -296,6 +311,8 @@ def main():
         w_us = dense_us(lambda i: torch.matmul(dYs[i % nsets].t(), Xs[i % nsets]))
         out["dense_context"] = {"library": "torch.matmul (bf16 in, bf16 out)", "fwd_us": f_us, "fwd_TFLOP_per_s": gemm_flops / f_us * 1e-6,
                                 "wgrad_us": w_us, "wgrad_TFLOP_per_s": gemm_flops / w_us * 1e-6}
+    if out_dgrad is not None:
+        out["dgrad_dense"] = out_dgrad
     if wl.cfg == 4:
         # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta;
         # the fraction of positions whose kept / pruned state changes (flip rate, paper Sec. 3.3) is a sanity number

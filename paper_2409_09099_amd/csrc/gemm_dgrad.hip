@@ -46,16 +46,17 @@ __device__ __forceinline__ void expand_group(uint32_t w, uint32_t nib, uint32_t&
 }
 }  // namespace
 
+template <int NI_>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
                float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
-  constexpr int WN = 4, NW = 8, MI_ = 8, NI_ = 4;
-  constexpr int BM = 256, BN = 256;                 // features x tokens per workgroup
+  constexpr int WN = 4, NW = 8, MI_ = 8;
+  constexpr int BM = 256, BN = 64 * NI_;            // features x tokens per workgroup (256 x 256 or 256 x 128)
   constexpr int ASLOT = 64 * 512;                   // decoded S(W): 64 channels x 256 features bf16
-  constexpr int BSLOT = BN * 128;                   // grad_Z: 256 tokens x 64 channels bf16
+  constexpr int BSLOT = BN * 128;                   // grad_Z: BN tokens x 64 channels bf16
   constexpr int NRA = 3, NRB = 2;
-  constexpr int LB = BSLOT / 1024 / NW;             // direct-to-LDS loads per wave and k-step: 4
+  constexpr int LB = BSLOT / 1024 / NW;             // direct-to-LDS loads per wave and k-step: 4 / 2
   constexpr int EROW = 32 * MI_ + 16;
   constexpr int NPIECE = 2 * NI_;
   static_assert(NRA * ASLOT + NRB * BSLOT <= 160 * 1024 && NW * 16 * NI_ * EROW <= NRA * ASLOT + NRB * BSLOT, "LDS budget");
@@ -102,6 +103,7 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   }
   uint4 pk[2];
   uint32_t pmeta[2];
+  uint32_t dec[8];                    // one block row being expanded: 16 dense bf16
 #define DG_LOAD_PACKED(step)                                                                              \
   do {                                                                                                    \
     const uint32_t sv_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 1024u;                                \
@@ -114,18 +116,20 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
                                                                          (int)(live_ ? sm_ : 0u), 0);    \
     }                                                                                                     \
   } while (0)
+// expansion of group g of block e into the staging registers; after the fourth group the 32 bytes are written
+#define DG_DECODE_PIECE(slot_, e, g)                                                                      \
+  do {                                                                                                    \
+    const uint32_t w_ = (g) == 0 ? pk[e].x : (g) == 1 ? pk[e].y : (g) == 2 ? pk[e].z : pk[e].w;           \
+    expand_group(w_, (pmeta[e] >> (4 * (g))) & 15u, dec[2 * (g)], dec[2 * (g) + 1]);                      \
+    if ((g) == 3) {                                                                                       \
+      uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
+      *(uint4*)dst_ = make_uint4(dec[0], dec[1], dec[2], dec[3]);                                         \
+      *(uint4*)(dst_ + 16) = make_uint4(dec[4], dec[5], dec[6], dec[7]);                                  \
+    }                                                                                                     \
+  } while (0)
 #define DG_DECODE(slot_)                                                                                  \
   do {                                                                                                    \
-    _Pragma("unroll") for (int e = 0; e < 2; e++) {                                                       \
-      uint32_t d_[8];                                                                                     \
-      expand_group(pk[e].x, pmeta[e] & 15u, d_[0], d_[1]);                                                \
-      expand_group(pk[e].y, (pmeta[e] >> 4) & 15u, d_[2], d_[3]);                                         \
-      expand_group(pk[e].z, (pmeta[e] >> 8) & 15u, d_[4], d_[5]);                                         \
-      expand_group(pk[e].w, pmeta[e] >> 12, d_[6], d_[7]);                                                \
-      uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
-      *(uint4*)dst_ = make_uint4(d_[0], d_[1], d_[2], d_[3]);                                             \
-      *(uint4*)(dst_ + 16) = make_uint4(d_[4], d_[5], d_[6], d_[7]);                                      \
-    }                                                                                                     \
+    _Pragma("unroll") for (int d_ = 0; d_ < 8; d_++) DG_DECODE_PIECE(slot_, d_ >> 2, d_ & 3);             \
   } while (0)
 #define DG_DMA_B(i, step, slot_)                                                                          \
   dma_b128(bb, ldsB + (uint32_t)(slot_) * BSLOT + (LB * wave + (i)) * 1024, offb[i],                      \
@@ -188,11 +192,13 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   do {                                                                                                    \
     wait_vmcnt<0>();                  /* everything issued during the previous k-step has arrived */      \
     __syncthreads();                  /* ... for every wave; S(W) slot a2 and grad_Z slot 1 - b1 are free */ \
-    DG_DECODE(a2);                                                                                        \
+    /* the 256 x 256 tile has no registers to spare for an expansion in flight across the MFMA groups */ \
+    if (NI_ == 4) DG_DECODE(a2);                                                                          \
     const uint8_t* pa = smemA + a0 * ASLOT;                                                               \
     const uint8_t* pa1 = smemA + a1 * ASLOT;                                                              \
     const uint8_t* pb1 = smemB + b1 * BSLOT;                                                              \
     _Pragma("unroll") for (int mi = 0; mi < MI_; mi++) {                                                  \
+      if (NI_ != 4) DG_DECODE_PIECE(a2, mi >> 2, mi & 3);   /* blocks of k-step step + 2 -> dense, a group per MFMA group */ \
       if (mi < MI_ - 1) DG_READ_A(fa[(mi + 1) & 1], pa, mi + 1);                                          \
       else DG_READ_A(fa[(mi + 1) & 1], pa1, 0);                                                           \
       _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
@@ -231,6 +237,7 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
 #undef DG_READ_A
 #undef DG_DMA_B
 #undef DG_DECODE
+#undef DG_DECODE_PIECE
 #undef DG_LOAD_PACKED
 
   // epilogue: accumulators -> LDS (row = token, the wave's 128 features contiguous) -> 16-byte stores
@@ -270,10 +277,18 @@ bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int d
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, float scale, const void* vals,
                                const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s) {
   if (T == 0 || I == 0) return hipSuccess;
-  int m_tiles = (int)((I + 255) / 256), n_tiles = (int)((T + 255) / 256);
+  int m_tiles = (int)((I + 255) / 256);
+  // 256 x 256 tiles unless they leave a quarter or more of the CUs without work in the only round
+  int64_t big = (int64_t)m_tiles * ((T + 255) / 256);
+  bool half = big < 192;
+  int n_tiles = (int)((T + (half ? 127 : 255)) / (half ? 128 : 256));
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
-  SSTE_LAUNCH(SSTE_K_DGRAD, k_linear_dgrad, grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
-              (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
+  if (half)
+    SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<2>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
+                (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
+  else
+    SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<4>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
+                (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
   return hipGetLastError();
 }
 
