@@ -152,3 +152,21 @@ def test_project_pack_batch_prepare(lib):
     assert launch(P(0x1004), 2, 5, 0, None) == 3
     assert launch(P(0x1000), -2, 5, 0, None) == 2
     assert launch(P(0x1000), 2, 5, 5, None) == 4
+
+
+def test_linear_dgrad_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_linear_dgrad
+    f.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float, P, P, ctypes.c_int64,
+                  ctypes.c_float, P, ctypes.c_int64, P]
+    assert f(fake, -4, 64, 64, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 2
+    assert f(fake, 4, 64, 64, 1, 1.0, fake, fake, 128, 1.0, fake, 128, None) == 7      # e4m3 operands are not built
+    assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 96, 1.0, fake, 96, None) == 7        # I must be a multiple of 64
+    assert f(fake, 4, 60, 64, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 7        # O must be a multiple of 8
+    assert f(fake, 4, 64, 32, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 2        # lddy < O
+    assert f(fake, 4, 64, 68, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 3        # lddy breaks the 16-byte row rule
+    assert f(fake, 4, 64, 64, 0, 0.0, fake, fake, 64, 1.0, fake, 64, None) == 5
+    assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 1
+    assert f(fake, 4, 64, 64, 5, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 4
+    assert f(fake, 0, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 0         # no tokens: nothing to do

@@ -103,6 +103,19 @@ def test_full_size_layer(sste, cfg, layer):
     # every output row / column block was written: no stale memory in the result
     assert torch.isfinite(Z.float()).all()
 
+    # ---- input gradient (dense by the paper's choice; bf16 workloads only): sampled outputs from the definition
+    if dtype == "bf16":
+        dX = sste.linear_dgrad(dY, vals, meta, I, dt, float(dys), float(ws))
+        dYf = decode(dyc, dtype)
+        ts = np.concatenate([rs.integers(0, T, 60), [0, T - 1, 127, 128, 255, 256]])
+        is_ = np.concatenate([rs.integers(0, I, 60), [0, I - 1, 255, 256 % I, 63, 64]])
+        ref = np.einsum("no,on->n", dYf[ts], Wd[:, is_]) * float(np.float32(dys)) * float(np.float32(ws))
+        got = dX[torch.from_numpy(ts).cuda(), torch.from_numpy(is_).cuda()].float().cpu().numpy().astype(np.float64)
+        xmax = float(dX.float().abs().max())
+        assert np.max(np.abs(got - ref)) <= TOL[dtype] * xmax, (np.max(np.abs(got - ref)), xmax)
+        assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-4 * xmax
+        assert torch.isfinite(dX.float()).all()
+
     # ---- sparsified operand on sampled channels, bit for bit
     seed, offset = cfg, 7
     tv, tm = sste.mvue_materialize(dY, seed, offset, dt)
