@@ -101,35 +101,35 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
     const int row = 16 * rbl + j, p = 4 * csl + q;
     dec_off[e] = (uint32_t)(row * 512 + ((p ^ (row & 15)) * 32));
   }
-  uint4 pk[2];
-  uint32_t pmeta[2];
+  uint4 pk[2], pk2[2];                // packed blocks in flight / being expanded (second set: 256 x 128 tile only)
+  uint32_t pmeta[2], pmeta2[2];
   uint32_t dec[8];                    // one block row being expanded: 16 dense bf16
-#define DG_LOAD_PACKED(step)                                                                              \
+#define DG_LOAD_PACKED(step, PK, PM)                                                                            \
   do {                                                                                                    \
     const uint32_t sv_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 1024u;                                \
     const uint32_t sm_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 128u;                                 \
     _Pragma("unroll") for (int e = 0; e < 2; e++) {                                                       \
       /* row blocks past the last one (tail of the channel axis, k-steps past the end) fetch nothing */    \
       const bool live_ = 4 * (int64_t)(step) + ((2 * wave + e) >> 2) < rbn;                               \
-      pk[e] = buffer_load_b128(rv, live_ ? pv_off[e] : 0x80000000u, live_ ? sv_ : 0u);                    \
-      pmeta[e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
+      PK[e] = buffer_load_b128(rv, live_ ? pv_off[e] : 0x80000000u, live_ ? sv_ : 0u);                    \
+      PM[e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
                                                                          (int)(live_ ? sm_ : 0u), 0);    \
     }                                                                                                     \
   } while (0)
 // expansion of group g of block e into the staging registers; after the fourth group the 32 bytes are written
-#define DG_DECODE_PIECE(slot_, e, g)                                                                      \
+#define DG_DECODE_PIECE(slot_, e, g, PK, PM)                                                                    \
   do {                                                                                                    \
-    const uint32_t w_ = (g) == 0 ? pk[e].x : (g) == 1 ? pk[e].y : (g) == 2 ? pk[e].z : pk[e].w;           \
-    expand_group(w_, (pmeta[e] >> (4 * (g))) & 15u, dec[2 * (g)], dec[2 * (g) + 1]);                      \
+    const uint32_t w_ = (g) == 0 ? PK[e].x : (g) == 1 ? PK[e].y : (g) == 2 ? PK[e].z : PK[e].w;           \
+    expand_group(w_, (PM[e] >> (4 * (g))) & 15u, dec[2 * (g)], dec[2 * (g) + 1]);                         \
     if ((g) == 3) {                                                                                       \
       uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
       *(uint4*)dst_ = make_uint4(dec[0], dec[1], dec[2], dec[3]);                                         \
       *(uint4*)(dst_ + 16) = make_uint4(dec[4], dec[5], dec[6], dec[7]);                                  \
     }                                                                                                     \
   } while (0)
-#define DG_DECODE(slot_)                                                                                  \
+#define DG_DECODE(slot_, PK, PM)                                                                             \
   do {                                                                                                    \
-    _Pragma("unroll") for (int d_ = 0; d_ < 8; d_++) DG_DECODE_PIECE(slot_, d_ >> 2, d_ & 3);             \
+    _Pragma("unroll") for (int d_ = 0; d_ < 8; d_++) DG_DECODE_PIECE(slot_, d_ >> 2, d_ & 3, PK, PM);     \
   } while (0)
 #define DG_DMA_B(i, step, slot_)                                                                          \
   dma_b128(bb, ldsB + (uint32_t)(slot_) * BSLOT + (LB * wave + (i)) * 1024, offb[i],                      \
@@ -168,11 +168,11 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   for (int i = 0; i < LB; i++) DG_DMA_B(i, 0, 0);
 #pragma unroll
   for (int i = 0; i < LB; i++) DG_DMA_B(i, 1, 1);
-  DG_LOAD_PACKED(0);
-  DG_DECODE(0);
-  DG_LOAD_PACKED(1);
-  DG_DECODE(1);
-  DG_LOAD_PACKED(2);
+  DG_LOAD_PACKED(0, pk, pmeta);
+  DG_DECODE(0, pk, pmeta);
+  DG_LOAD_PACKED(1, pk, pmeta);
+  DG_DECODE(1, pk, pmeta);
+  DG_LOAD_PACKED(2, pk, pmeta);
 
   uint4 fb0[NI_][2], fb1[NI_][2];     // grad_Z fragments: current / next k-step
   uint2 fa[2][4];                     // S(W) fragments of row block mi in fa[mi % 2]
@@ -188,17 +188,21 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   int a0 = 0, a1 = 1, a2 = 2;         // S(W) ring slots of k-steps step, step + 1, step + 2
   int b1 = 1;                         // grad_Z ring slot of k-step step + 1 (step + 2 goes to the other one)
 
-#define DG_STEP(BC, BX)                                                                                   \
+#define DG_STEP(BC, BX, PKC, PMC, PKN, PMN)                                                                                 \
   do {                                                                                                    \
     wait_vmcnt<0>();                  /* everything issued during the previous k-step has arrived */      \
     __syncthreads();                  /* ... for every wave; S(W) slot a2 and grad_Z slot 1 - b1 are free */ \
     /* the 256 x 256 tile has no registers to spare for an expansion in flight across the MFMA groups */ \
-    if (NI_ == 4) DG_DECODE(a2);                                                                          \
+    if (NI_ == 4) DG_DECODE(a2, PKC, PMC);                                                                \
     const uint8_t* pa = smemA + a0 * ASLOT;                                                               \
     const uint8_t* pa1 = smemA + a1 * ASLOT;                                                              \
     const uint8_t* pb1 = smemB + b1 * BSLOT;                                                              \
     _Pragma("unroll") for (int mi = 0; mi < MI_; mi++) {                                                  \
-      if (NI_ != 4) DG_DECODE_PIECE(a2, mi >> 2, mi & 3);   /* blocks of k-step step + 2 -> dense, a group per MFMA group */ \
+      if (NI_ != 4) DG_DECODE_PIECE(a2, mi >> 2, mi & 3, PKC, PMC);   /* blocks of k-step step + 2 -> dense, a group per MFMA group */ \
+      /* next packed blocks: into the second register set at once (256 x 128), or into the same one    */ \
+      /* at the end of the k-step (256 x 256: a load in flight across the groups would spill)           */ \
+      if (NI_ != 4 && mi == 0) DG_LOAD_PACKED(step + 3, PKN, PMN);                                        \
+      if (NI_ == 4 && mi == MI_ - 1) DG_LOAD_PACKED(step + 3, PKC, PMC);                                  \
       if (mi < MI_ - 1) DG_READ_A(fa[(mi + 1) & 1], pa, mi + 1);                                          \
       else DG_READ_A(fa[(mi + 1) & 1], pa1, 0);                                                           \
       _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
@@ -206,7 +210,6 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
           BX[pc >> 1][pc & 1] = *(const uint4*)(pb1 + ((pc & 1) ? fb_off1 : fb_off0) + (pc >> 1) * 2048); \
       _Pragma("unroll") for (int n = 0; n < LB; n++)                                                      \
         if (n == mi) DG_DMA_B(n, step + 2, 1 - b1);                                                       \
-      if (mi == MI_ - 1) DG_LOAD_PACKED(step + 3);                                                        \
       _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
         bf16x8 av0, av1, bv0, bv1;                                                                        \
         __builtin_memcpy(&av0, &fa[mi & 1][0], 16);                                                       \
@@ -227,12 +230,22 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
 
   int step = 0;
   for (; step + 1 < nsteps; step += 2) {
-    DG_STEP(fb0, fb1);
-    step++;
-    DG_STEP(fb1, fb0);
-    step--;
+    if (NI_ == 4) {
+      DG_STEP(fb0, fb1, pk, pmeta, pk, pmeta);
+      step++;
+      DG_STEP(fb1, fb0, pk, pmeta, pk, pmeta);
+      step--;
+    } else {
+      DG_STEP(fb0, fb1, pk, pmeta, pk2, pmeta2);
+      step++;
+      DG_STEP(fb1, fb0, pk2, pmeta2, pk, pmeta);
+      step--;
+    }
   }
-  if (step < nsteps) DG_STEP(fb0, fb1);
+  if (step < nsteps) {
+    if (NI_ == 4) DG_STEP(fb0, fb1, pk, pmeta, pk, pmeta);
+    else DG_STEP(fb0, fb1, pk, pmeta, pk2, pmeta2);
+  }
 #undef DG_STEP
 #undef DG_READ_A
 #undef DG_DMA_B
