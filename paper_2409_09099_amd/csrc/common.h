@@ -134,6 +134,18 @@ __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
   return r;
 }
 
+// The chip hands consecutive workgroup ids to its 8 XCDs in turn; this numbering gives each XCD a
+// contiguous range of logical numbers instead, so that the workgroups sharing an L2 work on
+// neighbouring tiles.
+__device__ __forceinline__ int xcd_contiguous(int bid, int nblk) {
+  constexpr int XCDS = 8;
+  const int per_xcd = (nblk + XCDS - 1) / XCDS, rem = nblk % XCDS;
+  const int xcd = bid % XCDS, slot = bid / XCDS;
+  return (rem == 0 || xcd < rem) ? xcd * per_xcd + slot : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+}
+// MFMA group (0 .. groups-1) in which item idx of n evenly spread items is issued
+constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
+
 // Streaming (non-temporal) store for a final output that no kernel of the path reads again (Z): it
 // leaves the L2 to the operands that are re-read, and no pile of dirty lines is left to flush when the
 // kernel ends (measured on the 5120 x 1280 forward GEMM at 16384 tokens: 142 -> 113 us).  Intermediate

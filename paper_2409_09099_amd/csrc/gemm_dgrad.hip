@@ -26,15 +26,7 @@
 namespace sste {
 
 namespace {
-constexpr int NUM_XCD = 8;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
-__device__ __forceinline__ int xcd_contiguous(int bid, int nblk) {
-  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
-  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-  return (rem == 0 || xcd < rem) ? xcd * per_xcd + slot : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
-}
-constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
 
 // One group of a packed 2:4 operand -> its four dense bf16: w = value0 | value1 << 16 (ascending
 // positions), nib = pos0 | pos1 << 2 with pos0 < pos1.  lo holds positions 0, 1; hi positions 2, 3.

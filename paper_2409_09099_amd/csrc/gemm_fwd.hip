@@ -11,14 +11,19 @@
 //   D: lane (j, q) register r holds element (row 4 q + r, col j).
 // In bytes a k-step is the same for both types: 64 B of values + 128 B of X per row.
 //
-// Tiling: WM x WN waves, each owning 8 x 4 MFMA tiles (128 channels x 64 tokens): per sparse MFMA a
-// wave reads about 540 B of fragments from LDS, inside the measured LDS read rate of the CU.
-// Two shapes are built: 256 x 256 with 8 waves and a 3-stage ring (one workgroup per CU), and
-// 256 x 128 with 4 waves and a 2-stage ring (two workgroups per CU) for problems with few tiles.
-// Operand tiles travel L2 -> LDS directly (buffer_load ... lds, no staging registers) into a ring of
-// NS stages; the loads for k-step s + NS - 1 are issued once the fragments of k-step s have been
-// read.  The vector-memory path of a CU moves 64 B/clk, so a 256 x 256 tile (50 KiB per k-step
-// against 64 sparse MFMAs per SIMD) leaves it about 40 % idle, a 256 x 128 tile almost none.
+// Tiling: every wave owns a grid of 16 x 16 MFMA tiles (8 x 4 = 128 channels x 64 tokens in the main
+// shape): per sparse MFMA it reads about 540 B of fragments from LDS, inside the LDS read rate of the CU.
+// Three kernels share the operand layouts:
+//   k_linear_fwd        the first, phase-structured kernel (fragment reads, then loads, then MFMAs);
+//                       kept as 256 x 128 / 4 waves / 2-stage ring, two workgroups per CU, for layers
+//                       with fewer than 128 tiles of 256 x 256;
+//   k_linear_fwd_pipe   software-pipelined 256 x 256 tiles, 8 waves, one workgroup per CU (below);
+//   k_linear_fwd_dual   the same tile code for 256 x 256 and 256 x 128 tiles in one grid, for layers
+//                       whose last round of 256 x 256 tiles would fill at most half of the CUs.
+// Operand tiles travel L2 -> LDS directly (buffer_load ... lds, no staging registers) into rings of
+// LDS slots.  What limits all of them is the L1 of the CU: it keeps 64 line requests in flight, and a
+// request takes 400 - 500 clocks under load, so a CU receives about 20 B/clk (measured; a 256 x 256
+// k-step needs 50 KiB per 1024 MFMA clocks).
 // The packed weight is stored in memory in the order the sparse MFMA consumes it (1 KiB blocks of
 // 16 rows x one k-step, one 16-byte slot per lane), so its loads are contiguous and its fragment
 // reads are lane-contiguous.  For X, whose 64 lanes of a load land on consecutive LDS addresses, bank
@@ -40,16 +45,8 @@ namespace sste {
 namespace {
 constexpr int MI = 8, NI = 4;                     // MFMA tiles per wave: 128 channels x 64 tokens
 constexpr int EPI_ROW = 272;                      // 128 channels x 2 B + 16 B pad
-constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 
-// The chip hands consecutive workgroup ids to its 8 XCDs in turn; this numbering gives each XCD a
-// contiguous range of logical numbers instead.
-__device__ __forceinline__ int xcd_contiguous(int bid, int nblk) {
-  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
-  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-  return (rem == 0 || xcd < rem) ? xcd * per_xcd + slot : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
-}
 }  // namespace
 
 template <bool FP8, int WM, int WN, int NS>
@@ -71,11 +68,7 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
   __shared__ __align__(1024) uint8_t smem[SMEM];
 
   // XCD-aware tile order: XCD x owns a contiguous range of logical tiles
-  const int bid = blockIdx.x, nblk = gridDim.x;
-  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
-  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-  const int logical = (rem == 0 || xcd < rem) ? xcd * per_xcd + slot
-                                              : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tm = logical % m_tiles, tn = logical / m_tiles;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -228,10 +221,6 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
 // Every wave issues the same number of loads per k-step (the counts in s_waitcnt are compile-time
 // constants); where the tile has fewer 1 KiB blocks than 8 waves x loads, the surplus loads address
 // blocks past the end of the tile's buffer descriptor and fetch nothing.
-namespace {
-// MFMA group (0 .. groups-1) in which item idx of n evenly spread items is issued
-constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
-}  // namespace
 
 // LDS bytes one tile of the pipelined kernel needs (rings, reused by the epilogue)
 template <bool FP8, int MI_, int NI_>

@@ -25,7 +25,6 @@ hipError_t launch_wgrad_fused(const void* dY, int64_t T, int64_t O, int64_t lddy
                               float* out, int64_t ld_out, int64_t split_stride, hipStream_t s);
 
 namespace {
-constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
@@ -154,9 +153,6 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 // narrower tiles leave the tail of each row unused.  32-byte feature pair p (bf16) / 16-byte chunk c
 // (fp8) of token row r is stored at position p ^ (r % 16): the transposing reads below, which gather
 // 4 (8) token rows x 16 features per 16 lanes, then hit distinct banks.
-namespace {
-constexpr int spread(int idx, int n, int groups) { return idx * groups / n; }
-}  // namespace
 
 template <bool FP8, int MI_, int NI_>
 __global__ void __launch_bounds__(512, 1)
@@ -183,11 +179,7 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
   uint8_t* const smemB = smem + NR * ASTAGE;
 
   // tile order: XCD x owns a contiguous range of (tile, split) units, channel tiles fastest
-  const int bid = blockIdx.x, nblk = gridDim.x;
-  const int per_xcd = (nblk + NUM_XCD - 1) / NUM_XCD, rem = nblk % NUM_XCD;
-  const int xcd = bid % NUM_XCD, slot = bid / NUM_XCD;
-  const int logical = (rem == 0 || xcd < rem) ? xcd * per_xcd + slot
-                                              : rem * per_xcd + (xcd - rem) * (per_xcd - 1) + slot;
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tiles = m_tiles * n_tiles;
   const int z = logical / tiles, tile = logical % tiles;
   const int tm = tile % m_tiles, tn = tile / m_tiles;
