@@ -167,7 +167,10 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   DG_LOAD_PACKED(2, pk, pmeta);
 
   uint4 fb0[NI_][2], fb1[NI_][2];     // grad_Z fragments: current / next k-step
-  uint2 fa[2][4];                     // S(W) fragments of row block mi in fa[mi % 2]
+  // S(W) fragments roll AD row blocks ahead of their use (two where registers allow: the 256 x 128 tile
+  // issues only four MFMAs per group, too few to cover an LDS round trip); block mi lives in fa[mi % AB]
+  constexpr int AD = NI_ == 2 ? 2 : 1, AB = 2 * AD;
+  uint2 fa[AB][4];
   wait_vmcnt<0>();
   __syncthreads();
 #pragma unroll
@@ -175,7 +178,8 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
     fb0[ni][0] = *(const uint4*)(smemB + fb_off0 + ni * 2048);
     fb0[ni][1] = *(const uint4*)(smemB + fb_off1 + ni * 2048);
   }
-  DG_READ_A(fa[0], smemA, 0);
+#pragma unroll
+  for (int b = 0; b < AD; b++) DG_READ_A(fa[b], smemA, b);
 
   int a0 = 0, a1 = 1, a2 = 2;         // S(W) ring slots of k-steps step, step + 1, step + 2
   int b1 = 1;                         // grad_Z ring slot of k-step step + 1 (step + 2 goes to the other one)
@@ -195,8 +199,8 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
       /* at the end of the k-step (256 x 256: a load in flight across the groups would spill)           */ \
       if (NI_ != 4 && mi == 0) DG_LOAD_PACKED(step + 3, PKN, PMN);                                        \
       if (NI_ == 4 && mi == MI_ - 1) DG_LOAD_PACKED(step + 3, PKC, PMC);                                  \
-      if (mi < MI_ - 1) DG_READ_A(fa[(mi + 1) & 1], pa, mi + 1);                                          \
-      else DG_READ_A(fa[(mi + 1) & 1], pa1, 0);                                                           \
+      if (mi + AD < MI_) DG_READ_A(fa[(mi + AD) & (AB - 1)], pa, mi + AD);                                \
+      else DG_READ_A(fa[(mi + AD) & (AB - 1)], pa1, mi + AD - MI_);                                       \
       _Pragma("unroll") for (int pc = 0; pc < NPIECE; pc++)                                               \
         if (spread(pc, NPIECE, MI_) == mi)                                                                \
           BX[pc >> 1][pc & 1] = *(const uint4*)(pb1 + ((pc & 1) ? fb_off1 : fb_off0) + (pc >> 1) * 2048); \
@@ -204,8 +208,8 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
         if (n == mi) DG_DMA_B(n, step + 2, 1 - b1);                                                       \
       _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
         bf16x8 av0, av1, bv0, bv1;                                                                        \
-        __builtin_memcpy(&av0, &fa[mi & 1][0], 16);                                                       \
-        __builtin_memcpy(&av1, &fa[mi & 1][2], 16);                                                       \
+        __builtin_memcpy(&av0, &fa[mi & (AB - 1)][0], 16);                                                       \
+        __builtin_memcpy(&av1, &fa[mi & (AB - 1)][2], 16);                                                       \
         __builtin_memcpy(&bv0, &BC[ni][0], 16);                                                           \
         __builtin_memcpy(&bv1, &BC[ni][1], 16);                                                           \
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av0, bv0, acc[mi][ni], 0, 0, 0);            \
