@@ -31,10 +31,11 @@ typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 // One group of a packed 2:4 operand -> its four dense bf16: w = value0 | value1 << 16 (ascending
 // positions), nib = pos0 | pos1 << 2 with pos0 < pos1.  lo holds positions 0, 1; hi positions 2, 3.
 __device__ __forceinline__ void expand_group(uint32_t w, uint32_t nib, uint32_t& lo, uint32_t& hi) {
-  const uint32_t pos0 = nib & 3u, pos1 = nib >> 2;
-  const uint32_t v0 = w & 0xFFFFu, v0h = w << 16, v1 = w >> 16, v1h = w & 0xFFFF0000u;
-  lo = (pos0 == 0u ? v0 : 0u) | (pos0 == 1u ? v0h : 0u) | (pos1 == 1u ? v1h : 0u);
-  hi = (pos0 == 2u ? v0 : 0u) | (pos1 == 2u ? v1 : 0u) | (pos1 == 3u ? v1h : 0u);
+  // each value shifted to its 16-bit position inside the 64-bit group: two 64-bit shifts and an OR
+  // (a third of the instructions of per-position selects)
+  const uint64_t d = ((uint64_t)(w & 0xFFFFu) << ((nib & 3u) << 4)) | ((uint64_t)(w >> 16) << ((nib & 12u) << 2));
+  lo = (uint32_t)d;
+  hi = (uint32_t)(d >> 32);
 }
 }  // namespace
 
