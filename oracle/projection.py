@@ -15,6 +15,8 @@ Math layer (float64) -- the paper's definitions written out:
 Bit-spec layer (float32 + integers) -- the rounding sequence a bf16 / e4m3 packed operand forces:
   * ``project_pack``     S(w) = beta * S_soft(w) on bf16 inputs -> (values, 2-bit metadata, amax);
   * ``decode_packed``    packed (values, metadata) -> dense-with-zeros matrix;
+  * ``sgd_step``         Sec. 2, Eq. (7): the dense weight moves by -alpha * gradient of the sparse
+                         weight; ``sgd_project_pack`` is that step followed by ``project_pack``;
   * ``kept_positions``   metadata -> the two recorded positions per group.
 
 Readings taken where the paper is silent (all restated in the design notes of the repository):
@@ -26,6 +28,10 @@ Readings taken where the paper is silent (all restated in the design notes of th
   * rounding: sd = a -/+ t in float32, p = sd * beta in float32 (beta a float32 input),
     bf16 path: value = RNE_bf16(p); e4m3 path: q = p / val_scale (float32 division), clamp to
     +-448, value = RNE_e4m3(q).  amax = max |p| over recorded values (float32).
+
+  * the step of Eq. (7): step = alpha * g in float32, w' = w - step in float32 (two roundings, no
+    fused multiply-add); a bf16 dense weight stores RNE_bf16(w') and is projected from that; a
+    float32 dense weight stores w' and is projected from RNE_bf16(w').
 
 Pinned (tests/test_oracle_projection.py): worked groups, the appendix's sorted form, the 2:4
 invariant, idempotence (projection), homogeneity, the 2-delta continuity bound of the Theorem 1
@@ -180,6 +186,34 @@ def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
     nib = (idx0 | (idx1 << 2)).astype(np.uint8).reshape(O, I // 8, 2)
     meta = (nib[:, :, 0] | (nib[:, :, 1] << 4)).astype(np.uint8)
     return vals, meta, np.float32(amax)
+
+
+def sgd_step(w, g, alpha, master="bf16"):
+    """Eq. (7): w_{k+1} = w_k - alpha_k * g, with g the gradient taken at the sparse weight.
+
+    w : (O, I) uint16 bf16 patterns (master="bf16") or float32 values (master="f32");
+    g : (O, I) float32.  Returns (w_next in the storage of w, bf16 patterns the projection reads).
+    """
+    g32 = np.asarray(g, dtype=np.float32)
+    a32 = np.float32(alpha)
+    if master == "bf16":
+        w32 = formats.bf16_to_f32(np.asarray(w, dtype=np.uint16))
+    elif master == "f32":
+        w32 = np.asarray(w, dtype=np.float32)
+    else:
+        raise ValueError("master must be 'bf16' or 'f32'")
+    step = (a32 * g32).astype(np.float32)
+    nxt = (w32 - step).astype(np.float32)
+    bits = formats.f32_to_bf16_rne(nxt).reshape(nxt.shape)
+    return (bits if master == "bf16" else nxt), bits
+
+
+def sgd_project_pack(w, g, alpha, beta, master="bf16", val_dtype="bf16", val_scale=1.0):
+    """One iteration's weight side (Sec. 2, steps 3 then 1): update the dense weight with Eq. (7),
+    then S(w) = beta * S_soft(w) of the new weight, packed.  Returns (w_next, vals, meta)."""
+    w_next, bits = sgd_step(w, g, alpha, master)
+    vals, meta, _ = project_pack(bits, beta, val_dtype, val_scale)
+    return w_next, vals, meta
 
 
 def kept_positions(meta):

@@ -194,3 +194,52 @@ def test_tie_break_rule_exhaustive_small_alphabet():
         _, meta, _ = P.project_pack(wb, 1.0)
         nib = int(meta[0, 0]) & 0xF
         assert [nib & 3, nib >> 2] == want, (combo, nib)
+
+
+def test_sgd_step_hand_values_and_library_cast():
+    """Eq. (7) with the stated rounding sequence: hand-worked bf16 ties, alpha = 0, and PyTorch's
+    CPU float32 arithmetic + bfloat16 cast as an independent implementation."""
+    import torch
+    one = np.array([[0x3F80]], dtype=np.uint16)                       # 1.0
+    # 1 - 2^-9 lies midway between the bf16 neighbours 1 - 2^-8 and 1: ties-to-even gives 1.0
+    nxt, bits = P.sgd_step(one, np.array([[1.0]], np.float32), 2.0 ** -9)
+    assert nxt[0, 0] == 0x3F80 and bits[0, 0] == 0x3F80
+    # 1 - 2^-8 is a bf16 number (0x3F7F)
+    nxt, _ = P.sgd_step(one, np.array([[1.0]], np.float32), 2.0 ** -8)
+    assert nxt[0, 0] == 0x3F7F
+    # sign: a positive gradient lowers the weight, a negative one raises it (1 + 2^-7 = 0x3F81)
+    nxt, _ = P.sgd_step(one, np.array([[-1.0]], np.float32), 2.0 ** -7)
+    assert nxt[0, 0] == 0x3F81
+    # a float32 dense weight keeps the unrounded step; the projection sees the rounded one
+    nxt, bits = P.sgd_step(np.array([[1.0]], np.float32), np.array([[1.0]], np.float32), 2.0 ** -9, master="f32")
+    assert nxt.dtype == np.float32 and nxt[0, 0] == np.float32(1.0 - 2.0 ** -9) and bits[0, 0] == 0x3F80
+    rng = np.random.default_rng(5)
+    w = rng.normal(0, 0.02, (16, 64)).astype(np.float32)
+    wb = F.f32_to_bf16_rne(w).reshape(w.shape)
+    g = rng.normal(0, 1e-3, (16, 64)).astype(np.float32)
+    same, _ = P.sgd_step(wb, g, 0.0)
+    assert np.array_equal(same, wb)
+    for alpha in (1e-2, 0.37, 3.0):
+        nxt, bits = P.sgd_step(wb, g, alpha)
+        tw = torch.from_numpy(wb.view(np.int16)).view(torch.bfloat16)
+        ref = (tw.float() - torch.tensor(alpha, dtype=torch.float32) * torch.from_numpy(g)).to(torch.bfloat16)
+        assert np.array_equal(nxt, ref.view(torch.int16).numpy().view(np.uint16))
+        nf, bf = P.sgd_step(w, g, alpha, master="f32")
+        reff = torch.from_numpy(w) - torch.tensor(alpha, dtype=torch.float32) * torch.from_numpy(g)
+        assert np.array_equal(nf, reff.numpy())
+        assert np.array_equal(bf, reff.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+def test_sgd_project_pack_is_step_then_projection_of_the_definition():
+    """The fused call equals the float64 definition applied to the stepped weight: decode(pack) is
+    RNE_bf16(beta * S_soft(w')) with w' the stored next weight."""
+    rng = np.random.default_rng(6)
+    w = F.f32_to_bf16_rne(rng.normal(0, 0.02, (8, 64)).astype(np.float32)).reshape(8, 64)
+    g = rng.normal(0, 1e-2, (8, 64)).astype(np.float32)
+    w_next, vals, meta = P.sgd_project_pack(w, g, 0.5, 1.25)
+    assert not np.array_equal(w_next, w)
+    dense = P.decode_packed(vals, meta)
+    want = 1.25 * P.soft_threshold(F.bf16_to_f32(w_next).astype(np.float64))
+    got = dense.astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -8 + 1e-30)
+    assert np.array_equal(got != 0, want != 0)
