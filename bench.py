@@ -113,12 +113,25 @@ def prune_model(sste, torch, iters=20):
 
     ms_batch = timed(batch.launch)
     ms_single = timed(singles)
-    return {
+    out = {
         "tensors": len(shapes), "weights": weights, "algorithmic_bytes": algo_bytes,
         "one_launch": {"ms": ms_batch, "GB_per_s": algo_bytes / ms_batch * 1e-6, "frac_hbm_peak": algo_bytes / ms_batch * 1e-6 / PEAK_HBM_GBS},
         "launch_per_tensor": {"ms": ms_single, "GB_per_s": algo_bytes / ms_single * 1e-6,
                               "frac_hbm_peak": algo_bytes / ms_single * 1e-6 / PEAK_HBM_GBS},
     }
+    # The dense-weight step fused with the re-projection, one launch for all 144 tensors: W and the
+    # float32 gradient are read, W is written back, the packed form is written.  alpha = 0 keeps the
+    # weights where they are over the repetitions.
+    Gs = [torch.randn(s, generator=g, device="cuda", dtype=torch.float32) * 1e-4 for s in shapes]
+    for master, wbytes in (("bf16", 2), ("f32", 4)):
+        Wm = Ws if master == "bf16" else [W.float() for W in Ws]
+        upd_bytes = weights * (2 * wbytes + 4 + 1.125)
+        ub = sste.UpdateBatch(Wm, Gs, [1.48] * len(Wm), sste.BF16, vals=batch.vals, metas=batch.metas)
+        ms = timed(lambda: ub.launch(0.0))
+        out["update_fused_" + master] = {"ms": ms, "algorithmic_bytes": upd_bytes, "GB_per_s": upd_bytes / ms * 1e-6,
+                                         "frac_hbm_peak": upd_bytes / ms * 1e-6 / PEAK_HBM_GBS}
+        del Wm, ub
+    return out
 
 
 def main():

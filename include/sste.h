@@ -61,7 +61,8 @@ typedef enum {
 
 typedef enum {
   SSTE_BF16 = 0,   /* bfloat16 */
-  SSTE_F8E4M3 = 1  /* OCP FP8 e4m3fn: bias 7, max 448, no infinity */
+  SSTE_F8E4M3 = 1, /* OCP FP8 e4m3fn: bias 7, max 448, no infinity */
+  SSTE_F32 = 2     /* float32: accepted only where an argument's description says so */
 } sste_dtype;
 
 /*
@@ -130,6 +131,65 @@ int sste_project_pack_batch_prepare(const sste_pack_item* items, int n_items, in
                                     void* table_host, int64_t* total_blocks_out);
 int sste_project_pack_batch(const void* table_device, int n_items, int64_t total_blocks, int val_dtype,
                             void* hip_stream);
+
+/*
+ * Dense-weight update fused with the projection of the updated weight (Sec. 2: each iteration prunes
+ * the dense weight, takes the gradient at the sparse weight and updates the DENSE weight with it,
+ * Eq. (7): w_{k+1} = w_k - alpha_k * g_k; Sec. 4: the pruning is S(w) = beta * S_soft(w)).
+ * One pass over W: reads W and G, writes W back in place and writes the packed S(W_{k+1}), instead of
+ * an update pass followed by sste_project_pack.
+ *
+ * Rounding: step = alpha * g and w' = w - step are single float32 operations (no fused multiply-add).
+ * w_dtype SSTE_BF16: W stores RNE_bf16(w') and the projection reads that.  w_dtype SSTE_F32: W stores
+ * w' and the projection reads RNE_bf16(w').  From there on the arithmetic and the packed format are
+ * exactly those of sste_project_pack.
+ *
+ *   W         in/out device, bf16 or float32 (w_dtype), O x I, leading dimension ldw (>= I; a multiple
+ *                    of 8 for bf16, of 4 for float32); updated in place
+ *   w_dtype   in     SSTE_BF16 or SSTE_F32
+ *   G         in     device, float32, O x I, leading dimension ldg (>= I, multiple of 4): the weight
+ *                    gradient as sste_linear_wgrad writes it; must not overlap W
+ *   alpha     in     learning rate, finite (any sign; 0 re-projects W unchanged)
+ *   beta, val_dtype, val_scale, vals, meta, O, I: as for sste_project_pack
+ * Errors: as sste_project_pack; bad w_dtype -> ERR_DTYPE; non-finite alpha -> ERR_VALUE; NULL G with
+ * O * I > 0 -> ERR_NULL; G or W not 16-byte aligned, bad ldw / ldg -> ERR_ALIGN / ERR_SHAPE.
+ */
+int sste_sgd_project_pack(void* W, int w_dtype, int64_t O, int64_t I, int64_t ldw,
+                          const float* G, int64_t ldg, float alpha, float beta,
+                          int val_dtype, float val_scale, void* vals, void* meta, void* hip_stream);
+
+/*
+ * The same update + projection + pack for MANY weight tensors in one launch (every sparse layer of a
+ * model once per iteration), arranged like sste_project_pack_batch: prepare validates on the host and
+ * writes a table for the caller to copy to the device once; the launch reads only the device table.
+ * The learning rate alpha is an argument of the launch, since it changes from iteration to iteration.
+ * All tensors of one table share w_dtype and val_dtype.  Per tensor the result is exactly that of
+ * sste_sgd_project_pack.
+ *
+ *   items     in   host array; per item W, G, vals, meta (device), O, I, ldw, ldg, beta, val_scale, each
+ *                  as the same-named argument of sste_sgd_project_pack.  Empty items produce nothing.
+ *   table_host     HOST memory of n_items * SSTE_UPDATE_TABLE_ITEM_BYTES bytes
+ *   table_device   the caller's DEVICE copy of it, 16-byte aligned
+ * Errors (prepare): as sste_sgd_project_pack, for the first offending item.  Errors (launch): NULL or
+ * misaligned table, negative counts, bad dtypes, non-finite alpha.  The table's contents are not
+ * re-validated.
+ */
+typedef struct sste_update_item {
+  void* W;
+  const float* G;
+  void* vals;
+  void* meta;
+  int64_t O, I, ldw, ldg;
+  float beta;
+  float val_scale;
+} sste_update_item;
+
+#define SSTE_UPDATE_TABLE_ITEM_BYTES 80
+
+int sste_sgd_project_pack_batch_prepare(const sste_update_item* items, int n_items, int w_dtype, int val_dtype,
+                                        void* table_host, int64_t* total_blocks_out);
+int sste_sgd_project_pack_batch(const void* table_device, int n_items, int64_t total_blocks, int w_dtype,
+                                int val_dtype, float alpha, void* hip_stream);
 
 /*
  * Forward GEMM with a 2:4-sparse weight operand (Sec. 5.1: Z_l = X_l S(W_l)^T).
@@ -259,7 +319,8 @@ typedef enum {
   SSTE_K_WGRAD_REDUCE = 3,   /* fixed-order reduction of the token-axis splits */
   SSTE_K_MVUE_PACK = 4,      /* estimator pre-pass of the weight-gradient path (large problems) */
   SSTE_K_DGRAD = 5,          /* input-gradient dense GEMM */
-  SSTE_K_COUNT = 6
+  SSTE_K_SGD_PROJECT_PACK = 6, /* dense-weight update fused with projection + pack */
+  SSTE_K_COUNT = 7
 } sste_kernel_id;
 int sste_timing_begin(int max_launches);
 int sste_timing_end(double* total_ms, int* launches);

@@ -9,8 +9,10 @@ cannot be loaded.
 from .binding import (  # noqa: F401
     BF16,
     F8E4M3,
+    F32,
     PackBatch,
     SsteError,
+    UpdateBatch,
     compute_beta,
     flip_count,
     library,
@@ -20,6 +22,7 @@ from .binding import (  # noqa: F401
     mvue_materialize,
     packed_buffers,
     project_pack,
+    sgd_project_pack,
     timing_begin,
     timing_end,
     wgrad_workspace_bytes,

@@ -7,6 +7,7 @@ import torch
 
 BF16 = 0
 F8E4M3 = 1
+F32 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsste.so")
@@ -35,6 +36,9 @@ def library() -> ctypes.CDLL:
     lib.sste_version.restype = ci
     lib.sste_last_error.restype = ctypes.c_char_p
     lib.sste_project_pack.argtypes = [vp, i64, i64, i64, f32, ci, f32, vp, vp, vp, vp]
+    lib.sste_sgd_project_pack.argtypes = [vp, ci, i64, i64, i64, vp, i64, f32, f32, ci, f32, vp, vp, vp]
+    lib.sste_sgd_project_pack_batch_prepare.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(i64)]
+    lib.sste_sgd_project_pack_batch.argtypes = [vp, ci, i64, ci, ci, f32, vp]
     lib.sste_project_pack_batch_prepare.argtypes = [vp, ci, ci, vp, ctypes.POINTER(i64)]
     lib.sste_project_pack_batch.argtypes = [vp, ci, i64, ci, vp]
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
@@ -51,7 +55,7 @@ def library() -> ctypes.CDLL:
     lib.sste_timing_begin.restype = ci
     lib.sste_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.sste_timing_end.restype = ci
-    for name in ("sste_project_pack", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd", "sste_linear_dgrad",
+    for name in ("sste_project_pack", "sste_sgd_project_pack", "sste_sgd_project_pack_batch_prepare", "sste_sgd_project_pack_batch", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd", "sste_linear_dgrad",
                  "sste_linear_wgrad", "sste_mvue_materialize", "sste_compute_beta", "sste_flip_count"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -114,6 +118,24 @@ def project_pack(W: torch.Tensor, beta: float, val_dtype: int = BF16, val_scale:
     return vals, meta
 
 
+def sgd_project_pack(W: torch.Tensor, G: torch.Tensor, alpha: float, beta: float, val_dtype: int = BF16,
+                     val_scale: float = 1.0, vals: Optional[torch.Tensor] = None, meta: Optional[torch.Tensor] = None):
+    """sste_sgd_project_pack: W <- W - alpha * G in place (W bf16 or float32), then beta * S_soft(W)
+    packed 2:4.  Returns (vals, meta)."""
+    w_f32 = W.dtype == torch.float32
+    O, I, ldw = _matrix(W, 4 if w_f32 else 2, "W")
+    Og, Ig, ldg = _matrix(G, 4, "G")
+    if (Og, Ig) != (O, I) or G.dtype != torch.float32:
+        raise ValueError("G must be a float32 matrix of W's shape")
+    if vals is None or meta is None:
+        v, m = packed_buffers(O, I, val_dtype, W.device)
+        vals = v if vals is None else vals
+        meta = m if meta is None else meta
+    _check(library().sste_sgd_project_pack(_ptr(W), F32 if w_f32 else BF16, O, I, ldw, _ptr(G), ldg, alpha, beta,
+                                           val_dtype, val_scale, _ptr(vals), _ptr(meta), _stream(W)))
+    return vals, meta
+
+
 class _PackItem(ctypes.Structure):
     """sste_pack_item of include/sste.h."""
     _fields_ = [("W", ctypes.c_void_p), ("vals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
@@ -154,6 +176,56 @@ class PackBatch:
         """sste_project_pack_batch on the current stream of the tensors' device."""
         _check(library().sste_project_pack_batch(_ptr(self.table), self.n, self.total_blocks, self.val_dtype,
                                                  _stream(self.table)))
+        return self.vals, self.metas
+
+
+class _UpdateItem(ctypes.Structure):
+    """sste_update_item of include/sste.h."""
+    _fields_ = [("W", ctypes.c_void_p), ("G", ctypes.c_void_p), ("vals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
+                ("O", ctypes.c_int64), ("I", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldg", ctypes.c_int64),
+                ("beta", ctypes.c_float), ("val_scale", ctypes.c_float)]
+
+
+UPDATE_TABLE_ITEM_BYTES = 80
+
+
+class UpdateBatch:
+    """A prepared sste_sgd_project_pack_batch: `launch(alpha)` applies W <- W - alpha * G to every
+    tensor in place and re-projects and re-packs it, in one kernel."""
+
+    def __init__(self, Ws, Gs, betas, val_dtype: int = BF16, val_scales=None, vals=None, metas=None):
+        n = len(Ws)
+        if len(betas) != n or len(Gs) != n:
+            raise ValueError("one gradient and one beta per tensor")
+        val_scales = [1.0] * n if val_scales is None else list(val_scales)
+        self.Ws, self.Gs, self.val_dtype = list(Ws), list(Gs), val_dtype
+        w_f32 = n > 0 and self.Ws[0].dtype == torch.float32
+        self.w_dtype = F32 if w_f32 else BF16
+        self.vals, self.metas = [], []
+        items = (_UpdateItem * max(n, 1))()
+        for k, (W, G) in enumerate(zip(self.Ws, self.Gs)):
+            if (W.dtype == torch.float32) != w_f32:
+                raise ValueError("all dense weights of one table have the same type")
+            O, I, ldw = _matrix(W, 4 if w_f32 else 2, "W")
+            Og, Ig, ldg = _matrix(G, 4, "G")
+            if (Og, Ig) != (O, I) or G.dtype != torch.float32:
+                raise ValueError("G must be a float32 matrix of W's shape")
+            v, m = (vals[k], metas[k]) if vals is not None and metas is not None else packed_buffers(O, I, val_dtype, W.device)
+            self.vals.append(v)
+            self.metas.append(m)
+            items[k] = _UpdateItem(_ptr(W), _ptr(G), _ptr(v), _ptr(m), O, I, ldw, ldg, float(betas[k]), float(val_scales[k]))
+        table_host = torch.zeros(max(n, 1) * UPDATE_TABLE_ITEM_BYTES, dtype=torch.uint8)
+        total = ctypes.c_int64(0)
+        _check(library().sste_sgd_project_pack_batch_prepare(ctypes.cast(items, ctypes.c_void_p), n, self.w_dtype, val_dtype,
+                                                             ctypes.c_void_p(table_host.data_ptr()), ctypes.byref(total)))
+        self.n, self.total_blocks = n, int(total.value)
+        self.device = self.Ws[0].device if n else torch.device("cuda")
+        self.table = table_host.to(self.device)
+
+    def launch(self, alpha: float):
+        """sste_sgd_project_pack_batch on the current stream of the tensors' device."""
+        _check(library().sste_sgd_project_pack_batch(_ptr(self.table), self.n, self.total_blocks, self.w_dtype,
+                                                     self.val_dtype, alpha, _stream(self.table)))
         return self.vals, self.metas
 
 
@@ -239,7 +311,7 @@ def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor, O: int) -> torch.Tens
     return out
 
 
-KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack", "dgrad")
+KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack", "dgrad", "sgd_project_pack")
 
 
 def timing_begin(max_launches: int = 4096) -> None:

@@ -127,7 +127,7 @@ const char* sste_last_error(void) { return g_err; }
 
 // Per-item argument checks shared by the single-tensor and the batch entry points.
 static int check_pack_args(const char* who, const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
-                           float val_scale, const void* vals, const void* meta) {
+                           float val_scale, const void* vals, const void* meta, int ldw_multiple = 8) {
   if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "%s: negative size O=%lld I=%lld", who, (long long)O, (long long)I);
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "%s: I=%lld is not a multiple of 8 (whole groups of 4, two per metadata byte)", who, (long long)I);
   if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "%s: unknown val_dtype %d", who, val_dtype);
@@ -137,7 +137,7 @@ static int check_pack_args(const char* who, const void* W, int64_t O, int64_t I,
   if (I % (val_dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
     return fail(SSTE_ERR_UNSUPPORTED, "%s: I=%lld must be a multiple of %d for this value type", who, (long long)I, val_dtype == SSTE_F8E4M3 ? 128 : 64);
   if (ldw < I) return fail(SSTE_ERR_SHAPE, "%s: ldw=%lld < I=%lld", who, (long long)ldw, (long long)I);
-  if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "%s: ldw=%lld is not a multiple of 8", who, (long long)ldw);
+  if (ldw % ldw_multiple != 0) return fail(SSTE_ERR_ALIGN, "%s: ldw=%lld is not a multiple of %d", who, (long long)ldw, ldw_multiple);
   bool empty = (O == 0 || I == 0);
   if (!empty && (!W || !vals || !meta)) return fail(SSTE_ERR_NULL, "%s: NULL W, vals or meta", who);
   if (!aligned16(W) || !aligned16(vals)) return fail(SSTE_ERR_ALIGN, "%s: W and vals must be 16-byte aligned", who);
@@ -167,6 +167,98 @@ int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float be
   if (amax_out && (reinterpret_cast<uintptr_t>(amax_out) & 3u)) return fail(SSTE_ERR_ALIGN, "project_pack: amax_out must be 4-byte aligned");
   return hip_status(launch_project_pack(W, O, I, ldw, beta, val_dtype, val_scale, vals, meta, amax_out, (hipStream_t)hip_stream),
                     "project_pack launch");
+}
+
+static int check_update_args(const char* who, const void* W, int w_dtype, int64_t O, int64_t I, int64_t ldw, const float* G,
+                             int64_t ldg, float beta, int val_dtype, float val_scale, const void* vals, const void* meta) {
+  if (w_dtype != SSTE_BF16 && w_dtype != SSTE_F32) return fail(SSTE_ERR_DTYPE, "%s: w_dtype %d is neither bf16 nor float32", who, w_dtype);
+  int st = check_pack_args(who, W, O, I, ldw, beta, val_dtype, val_scale, vals, meta, w_dtype == SSTE_F32 ? 4 : 8);
+  if (st != SSTE_OK) return st;
+  if (ldg < I) return fail(SSTE_ERR_SHAPE, "%s: ldg=%lld < I=%lld", who, (long long)ldg, (long long)I);
+  if (ldg % 4 != 0) return fail(SSTE_ERR_ALIGN, "%s: ldg=%lld is not a multiple of 4", who, (long long)ldg);
+  if (O > 0 && I > 0 && !G) return fail(SSTE_ERR_NULL, "%s: NULL G", who);
+  if (!aligned16(G)) return fail(SSTE_ERR_ALIGN, "%s: G must be 16-byte aligned", who);
+  return SSTE_OK;
+}
+
+int sste_sgd_project_pack(void* W, int w_dtype, int64_t O, int64_t I, int64_t ldw, const float* G, int64_t ldg, float alpha,
+                          float beta, int val_dtype, float val_scale, void* vals, void* meta, void* hip_stream) {
+  clear_error();
+  int st = check_update_args("sgd_project_pack", W, w_dtype, O, I, ldw, G, ldg, beta, val_dtype, val_scale, vals, meta);
+  if (st != SSTE_OK) return st;
+  if (!std::isfinite(alpha)) return fail(SSTE_ERR_VALUE, "sgd_project_pack: alpha must be finite");
+  return hip_status(launch_sgd_project_pack(W, w_dtype == SSTE_F32, O, I, ldw, G, ldg, alpha, beta, val_dtype, val_scale, vals, meta,
+                                            (hipStream_t)hip_stream),
+                    "sgd_project_pack launch");
+}
+
+// device-side table item of sste_sgd_project_pack_batch; must match UpdateTableItem in prune_pack.hip
+struct UpdateTableItemHost {
+  void* W;
+  const float* G;
+  void* vals;
+  void* meta;
+  int64_t O;
+  int64_t ldw_bytes;
+  int64_t ldg;
+  int64_t first_block;
+  int32_t steps;
+  float beta;
+  float val_scale;
+  int32_t pad;
+};
+static_assert(sizeof(UpdateTableItemHost) == SSTE_UPDATE_TABLE_ITEM_BYTES, "table item size is part of the C ABI");
+
+int sste_sgd_project_pack_batch_prepare(const sste_update_item* items, int n_items, int w_dtype, int val_dtype, void* table_host,
+                                        int64_t* total_blocks_out) {
+  clear_error();
+  if (n_items < 0) return fail(SSTE_ERR_SHAPE, "sgd_project_pack_batch_prepare: n_items=%d", n_items);
+  if (!total_blocks_out || (n_items > 0 && (!items || !table_host)))
+    return fail(SSTE_ERR_NULL, "sgd_project_pack_batch_prepare: NULL items, table_host or total_blocks_out");
+  if (w_dtype != SSTE_BF16 && w_dtype != SSTE_F32) return fail(SSTE_ERR_DTYPE, "sgd_project_pack_batch_prepare: w_dtype %d is neither bf16 nor float32", w_dtype);
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "sgd_project_pack_batch_prepare: unknown val_dtype %d", val_dtype);
+  UpdateTableItemHost* out = (UpdateTableItemHost*)table_host;
+  int64_t blocks = 0;
+  for (int i = 0; i < n_items; i++) {
+    const sste_update_item& it = items[i];
+    char who[64];
+    snprintf(who, sizeof who, "sgd_project_pack_batch_prepare item %d", i);
+    int st = check_update_args(who, it.W, w_dtype, it.O, it.I, it.ldw, it.G, it.ldg, it.beta, val_dtype, it.val_scale, it.vals, it.meta);
+    if (st != SSTE_OK) return st;
+    int64_t steps = it.I / (val_dtype == SSTE_F8E4M3 ? 128 : 64);
+    if (steps > 0x7FFFFFFFll) return fail(SSTE_ERR_UNSUPPORTED, "%s: I too large", who);
+    UpdateTableItemHost t{};
+    t.W = it.W;
+    t.G = it.G;
+    t.vals = it.vals;
+    t.meta = it.meta;
+    t.O = it.O;
+    t.ldw_bytes = it.ldw * (w_dtype == SSTE_F32 ? 4 : 2);
+    t.ldg = it.ldg;
+    t.first_block = blocks;
+    t.steps = (int32_t)(steps > 0 ? steps : 1);       // an empty item owns no block; the divisor only has to be non-zero
+    t.beta = it.beta;
+    t.val_scale = it.val_scale;
+    out[i] = t;
+    blocks += ((it.O + 15) / 16) * steps;
+  }
+  *total_blocks_out = blocks;
+  return SSTE_OK;
+}
+
+int sste_sgd_project_pack_batch(const void* table_device, int n_items, int64_t total_blocks, int w_dtype, int val_dtype, float alpha,
+                                void* hip_stream) {
+  clear_error();
+  if (n_items < 0 || total_blocks < 0) return fail(SSTE_ERR_SHAPE, "sgd_project_pack_batch: negative count");
+  if (w_dtype != SSTE_BF16 && w_dtype != SSTE_F32) return fail(SSTE_ERR_DTYPE, "sgd_project_pack_batch: w_dtype %d is neither bf16 nor float32", w_dtype);
+  if (!good_dtype(val_dtype)) return fail(SSTE_ERR_DTYPE, "sgd_project_pack_batch: unknown val_dtype %d", val_dtype);
+  if (!std::isfinite(alpha)) return fail(SSTE_ERR_VALUE, "sgd_project_pack_batch: alpha must be finite");
+  if (n_items > 0 && !table_device) return fail(SSTE_ERR_NULL, "sgd_project_pack_batch: NULL table");
+  if (!aligned16(table_device)) return fail(SSTE_ERR_ALIGN, "sgd_project_pack_batch: the table must be 16-byte aligned");
+  if ((total_blocks + 3) / 4 > 0x7FFFFFFFll) return fail(SSTE_ERR_UNSUPPORTED, "sgd_project_pack_batch: too many blocks for one grid");
+  return hip_status(launch_sgd_project_pack_batch(table_device, n_items, total_blocks, w_dtype == SSTE_F32, val_dtype, alpha,
+                                                  (hipStream_t)hip_stream),
+                    "sgd_project_pack_batch launch");
 }
 
 int sste_project_pack_batch_prepare(const sste_pack_item* items, int n_items, int val_dtype, void* table_host,

@@ -169,6 +169,11 @@ RngKey derive_key(uint64_t seed, uint64_t offset);
 
 hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
                                float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s);
+hipError_t launch_sgd_project_pack(void* W, bool w_f32, int64_t O, int64_t I, int64_t ldw, const float* G, int64_t ldg,
+                                   float alpha, float beta, int val_dtype, float val_scale, void* vals, void* meta,
+                                   hipStream_t s);
+hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t total_blocks, bool w_f32, int val_dtype,
+                                         float alpha, hipStream_t s);
 hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t total_blocks, int val_dtype, hipStream_t s);
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype);
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, float scale, const void* vals,

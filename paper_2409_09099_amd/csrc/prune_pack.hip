@@ -1,6 +1,7 @@
 // S(W) = beta * S_soft(W): 2:4 soft-threshold projection (paper Sec. 4.1), frozen scale (Sec. 4.2)
 // and packing into values + 2-bit position metadata, in one streaming pass over W.
-// Also: the MSE-optimal beta reduction of Sec. 4.2 and the flip count of Sec. 3.3.
+// Also: the same pass fused with the dense-weight step of Eq. (7), the MSE-optimal beta reduction of
+// Sec. 4.2 and the flip count of Sec. 3.3.
 //
 // Data movement per weight: 2 B read, 1 B (bf16 values) or 0.5 B (e4m3 values) + 0.125 B written.
 // The kernel is bound by HBM bandwidth.
@@ -50,28 +51,13 @@ __device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float be
 //
 // Block `blk` (row block rb = blk / steps, column step s = blk % steps) of one tensor, by one wave.
 // Returns the largest |p| this lane recorded (only computed when AMAX).
+// The lane's weights (bf16 pairs, w[2g] and w[2g+1] = group g) -> its slot of block `blk`.
 template <bool FP8, bool AMAX>
-__device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t blk,
-                                               int64_t ldw_bytes, float beta, float val_scale,
-                                               uint4* __restrict__ vals, void* __restrict__ meta, int lane) {
+__device__ __forceinline__ float project_store(const uint32_t (&w)[FP8 ? 16 : 8], int64_t blk, float beta,
+                                               float val_scale, uint4* __restrict__ vals, void* __restrict__ meta,
+                                               int lane) {
   constexpr int NG = FP8 ? 8 : 4;                       // groups per lane
   float amax = 0.0f;
-  const int64_t rb = blk / steps;
-  const int32_t s = (int32_t)(blk - rb * steps);
-  const int j = lane & 15, q = lane >> 4;
-  const int64_t row = rb * 16 + j;
-  uint32_t w[2 * NG];
-  if (row < O) {
-    const uint4* src = (const uint4*)(W + row * ldw_bytes + ((int64_t)s * 4 + q) * (NG * 8));
-#pragma unroll
-    for (int c = 0; c < NG / 2; c++) {
-      uint4 v = src[c];
-      w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
-    }
-  } else {
-#pragma unroll
-    for (int c = 0; c < 2 * NG; c++) w[c] = 0;
-  }
   float p[2 * NG];
   uint32_t nibs = 0;
 #pragma unroll
@@ -100,6 +86,139 @@ __device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, in
   }
   vals[blk * 64 + lane] = out;
   return amax;
+}
+
+template <bool FP8, bool AMAX>
+__device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t blk,
+                                               int64_t ldw_bytes, float beta, float val_scale,
+                                               uint4* __restrict__ vals, void* __restrict__ meta, int lane) {
+  constexpr int NG = FP8 ? 8 : 4;
+  const int64_t rb = blk / steps;
+  const int32_t s = (int32_t)(blk - rb * steps);
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t row = rb * 16 + j;
+  uint32_t w[2 * NG];
+  if (row < O) {
+    const uint4* src = (const uint4*)(W + row * ldw_bytes + ((int64_t)s * 4 + q) * (NG * 8));
+#pragma unroll
+    for (int c = 0; c < NG / 2; c++) {
+      uint4 v = src[c];
+      w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 2 * NG; c++) w[c] = 0;
+  }
+  return project_store<FP8, AMAX>(w, blk, beta, val_scale, vals, meta, lane);
+}
+
+// Dense-weight step of Eq. (7) fused with the projection of the new weight (Sec. 2: update the dense
+// weight with the gradient taken at the sparse weight, then prune it again): one pass reads W and the
+// gradient, writes W back and writes the packed S(W).  step = alpha * g and w' = w - step are single
+// float32 operations.  A bf16 dense weight stores RNE_bf16(w') and is projected from it; a float32
+// dense weight stores w' and is projected from RNE_bf16(w').  Same block-per-wave mapping as above.
+// Per weight: 2 + 4 B read, 2 B written (bf16 weight; 4 + 4, 4 for float32) + the packed bytes.
+template <bool FP8, bool F32>
+__device__ __forceinline__ void sgd_block(uint8_t* W, const float* __restrict__ G, int64_t O, int32_t steps, int64_t blk,
+                                          int64_t ldw_bytes, int64_t ldg, float alpha, float beta, float val_scale,
+                                          uint4* __restrict__ vals, void* __restrict__ meta, int lane) {
+  constexpr int NG = FP8 ? 8 : 4;
+  const int64_t rb = blk / steps;
+  const int32_t s = (int32_t)(blk - rb * steps);
+  const int j = lane & 15, q = lane >> 4;
+  const int64_t row = rb * 16 + j;
+  uint32_t w[2 * NG];
+  if (row < O) {
+    const int64_t col = ((int64_t)s * 4 + q) * (NG * 4);
+    const f32x4* gp = (const f32x4*)(G + row * ldg + col);
+    f32x4 g[NG];
+#pragma unroll
+    for (int c = 0; c < NG; c++) g[c] = gp[c];
+    if (F32) {
+      float4* wp = (float4*)(W + row * ldw_bytes + col * 4);
+      float4 v[NG];
+#pragma unroll
+      for (int c = 0; c < NG; c++) v[c] = wp[c];
+#pragma unroll
+      for (int c = 0; c < NG; c++) {
+        v[c].x = v[c].x - alpha * g[c][0];
+        v[c].y = v[c].y - alpha * g[c][1];
+        v[c].z = v[c].z - alpha * g[c][2];
+        v[c].w = v[c].w - alpha * g[c][3];
+        wp[c] = v[c];
+        w[2 * c] = bf16_rne_pack(v[c].x, v[c].y);
+        w[2 * c + 1] = bf16_rne_pack(v[c].z, v[c].w);
+      }
+    } else {
+      uint4* wp = (uint4*)(W + row * ldw_bytes + col * 2);
+      uint4 v[NG / 2];
+#pragma unroll
+      for (int c = 0; c < NG / 2; c++) v[c] = wp[c];
+#pragma unroll
+      for (int c = 0; c < NG / 2; c++) {
+        const uint32_t in[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+        const float gg[8] = {g[2 * c][0], g[2 * c][1], g[2 * c][2], g[2 * c][3],
+                             g[2 * c + 1][0], g[2 * c + 1][1], g[2 * c + 1][2], g[2 * c + 1][3]};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          float a = u2f(in[e] << 16) - alpha * gg[2 * e];
+          float b = u2f(in[e] & 0xFFFF0000u) - alpha * gg[2 * e + 1];
+          w[4 * c + e] = bf16_rne_pack(a, b);
+        }
+        wp[c] = make_uint4(w[4 * c], w[4 * c + 1], w[4 * c + 2], w[4 * c + 3]);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 2 * NG; c++) w[c] = 0;
+  }
+  project_store<FP8, false>(w, blk, beta, val_scale, vals, meta, lane);
+}
+
+template <bool FP8, bool F32>
+__global__ void __launch_bounds__(256)
+k_sgd_project_pack(uint8_t* W, const float* __restrict__ G, int64_t O, int32_t steps, int64_t n_blocks,
+                   int64_t ldw_bytes, int64_t ldg, float alpha, float beta, float val_scale,
+                   uint4* __restrict__ vals, void* __restrict__ meta) {
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= n_blocks) return;
+  sgd_block<FP8, F32>(W, G, O, steps, blk, ldw_bytes, ldg, alpha, beta, val_scale, vals, meta, lane);
+}
+
+// Many tensors in one grid, like k_project_pack_batch.  80 bytes per item, layout shared with api.hip.
+// The learning rate is a launch argument: it changes every iteration, the table does not.
+struct UpdateTableItem {
+  uint8_t* W;
+  const float* G;
+  uint4* vals;
+  void* meta;
+  int64_t O;
+  int64_t ldw_bytes;
+  int64_t ldg;
+  int64_t first_block;
+  int32_t steps;
+  float beta;
+  float val_scale;
+  int32_t pad;
+};
+static_assert(sizeof(UpdateTableItem) == 80, "table item size is part of the C ABI (SSTE_UPDATE_TABLE_ITEM_BYTES)");
+
+template <bool FP8, bool F32>
+__global__ void __launch_bounds__(256)
+k_sgd_project_pack_batch(const UpdateTableItem* __restrict__ table, int n_items, int64_t total_blocks, float alpha) {
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  if (blk >= total_blocks) return;
+  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (table[mid].first_block <= blk) lo = mid;
+    else hi = mid - 1;
+  }
+  const UpdateTableItem it = table[lo];
+  sgd_block<FP8, F32>(it.W, it.G, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.ldg, alpha, it.beta, it.val_scale,
+                      it.vals, it.meta, lane);
 }
 
 template <bool FP8, bool AMAX>
@@ -178,6 +297,42 @@ hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw,
     SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
   else
     SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd_project_pack(void* W, bool w_f32, int64_t O, int64_t I, int64_t ldw, const float* G, int64_t ldg,
+                                   float alpha, float beta, int val_dtype, float val_scale, void* vals, void* meta,
+                                   hipStream_t s) {
+  bool fp8 = val_dtype == SSTE_F8E4M3;
+  int64_t steps = I / (fp8 ? 128 : 64), n = ((O + 15) / 16) * steps;
+  if (n == 0) return hipSuccess;
+  dim3 grid((unsigned)((n + 3) / 4)), block(256);
+  uint8_t* w = (uint8_t*)W;
+  int64_t ldw_bytes = ldw * (w_f32 ? 4 : 2);
+#define SGD_CASE(F8, F32)                                                                                      \
+  SSTE_LAUNCH(SSTE_K_SGD_PROJECT_PACK, (k_sgd_project_pack<F8, F32>), grid, block, s, w, G, O, (int32_t)steps, n, \
+              ldw_bytes, ldg, alpha, beta, val_scale, (uint4*)vals, meta)
+  if (fp8 && w_f32) SGD_CASE(true, true);
+  else if (fp8) SGD_CASE(true, false);
+  else if (w_f32) SGD_CASE(false, true);
+  else SGD_CASE(false, false);
+#undef SGD_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t total_blocks, bool w_f32, int val_dtype,
+                                         float alpha, hipStream_t s) {
+  if (n_items == 0 || total_blocks == 0) return hipSuccess;
+  dim3 grid((unsigned)((total_blocks + 3) / 4)), block(256);
+  const UpdateTableItem* t = (const UpdateTableItem*)table;
+  bool fp8 = val_dtype == SSTE_F8E4M3;
+#define SGD_CASE(F8, F32) \
+  SSTE_LAUNCH(SSTE_K_SGD_PROJECT_PACK, (k_sgd_project_pack_batch<F8, F32>), grid, block, s, t, n_items, total_blocks, alpha)
+  if (fp8 && w_f32) SGD_CASE(true, true);
+  else if (fp8) SGD_CASE(true, false);
+  else if (w_f32) SGD_CASE(false, true);
+  else SGD_CASE(false, false);
+#undef SGD_CASE
   return hipGetLastError();
 }
 

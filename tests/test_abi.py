@@ -170,3 +170,57 @@ def test_linear_dgrad_validation(lib):
     assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 1
     assert f(fake, 4, 64, 64, 5, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 4
     assert f(fake, 0, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 0         # no tokens: nothing to do
+
+
+def test_sgd_project_pack_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_sgd_project_pack
+    f.argtypes = [P, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, P, ctypes.c_int64, ctypes.c_float,
+                  ctypes.c_float, ctypes.c_int, ctypes.c_float, P, P, P]
+    assert f(fake, 1, 16, 64, 64, fake, 64, 0.1, 1.0, 0, 1.0, fake, fake, None) == 4     # W is bf16 or float32 only
+    assert f(fake, 0, 16, 64, 68, fake, 64, 0.1, 1.0, 0, 1.0, fake, fake, None) == 3     # bf16 rows: ldw % 8
+    assert f(fake, 2, 16, 64, 66, fake, 64, 0.1, 1.0, 0, 1.0, fake, fake, None) == 3     # float32 rows: ldw % 4
+    assert f(fake, 0, 16, 64, 64, fake, 32, 0.1, 1.0, 0, 1.0, fake, fake, None) == 2     # ldg < I
+    assert f(fake, 0, 16, 64, 64, fake, 66, 0.1, 1.0, 0, 1.0, fake, fake, None) == 3
+    assert f(fake, 0, 16, 64, 64, None, 64, 0.1, 1.0, 0, 1.0, fake, fake, None) == 1
+    assert f(fake, 0, 16, 64, 64, P(0x1004), 64, 0.1, 1.0, 0, 1.0, fake, fake, None) == 3
+    assert f(fake, 0, 16, 64, 64, fake, 64, float("nan"), 1.0, 0, 1.0, fake, fake, None) == 5
+    assert f(fake, 0, 16, 64, 64, fake, 64, 0.1, -1.0, 0, 1.0, fake, fake, None) == 5
+    assert f(fake, 0, 16, 96, 96, fake, 96, 0.1, 1.0, 0, 1.0, fake, fake, None) == 7
+    assert f(None, 2, 0, 64, 64, None, 64, 0.1, 1.0, 0, 1.0, None, None, None) == 0       # empty: nothing to do
+
+
+def test_sgd_project_pack_batch_prepare(lib):
+    class Item(ctypes.Structure):
+        _fields_ = [("W", ctypes.c_void_p), ("G", ctypes.c_void_p), ("vals", ctypes.c_void_p), ("meta", ctypes.c_void_p),
+                    ("O", ctypes.c_int64), ("I", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldg", ctypes.c_int64),
+                    ("beta", ctypes.c_float), ("val_scale", ctypes.c_float)]
+
+    prep = lib.sste_sgd_project_pack_batch_prepare
+    prep.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)]
+    items = (Item * 3)(Item(0x1000, 0x2000, 0x3000, 0x4000, 33, 128, 128, 132, 1.5, 1.0),
+                       Item(None, None, None, None, 0, 64, 64, 64, 1.0, 1.0),
+                       Item(0x5000, 0x6000, 0x7000, 0x8000, 16, 64, 64, 64, 2.0, 1.0))
+    table = (ctypes.c_uint8 * (3 * 80))()
+    total = ctypes.c_int64(-1)
+    assert prep(items, 3, 2, 0, table, ctypes.byref(total)) == 0
+    assert total.value == 3 * 2 + 0 + 1
+    raw = bytes(table)
+    import struct
+    W, G, vals, meta, O, ldw_bytes, ldg, first, steps, beta, scale, _ = struct.unpack("<QQQQqqqqiffi", raw[:80])
+    assert (W, G, vals, meta, O, ldw_bytes, ldg, first, steps, beta) == (0x1000, 0x2000, 0x3000, 0x4000, 33, 512, 132, 0, 2, 1.5)
+    assert struct.unpack("<q", raw[160 + 56:160 + 64])[0] == 6          # first block of the third item
+    assert prep(items, 3, 0, 0, table, ctypes.byref(total)) == 0          # bf16 rows: 128 % 8 == 0
+    assert struct.unpack("<q", bytes(table)[40:48])[0] == 256
+    assert prep(items, 3, 1, 0, table, ctypes.byref(total)) == 4
+    items[2].ldg = 66
+    assert prep(items, 3, 2, 0, table, ctypes.byref(total)) == 3
+    assert b"item 2" in lib.sste_last_error()
+    launch = lib.sste_sgd_project_pack_batch
+    launch.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+    assert launch(None, 1, 4, 0, 0, 0.1, None) == 1
+    assert launch(0x1008, 1, 4, 0, 0, 0.1, None) == 3
+    assert launch(0x1000, 1, 4, 0, 0, float("inf"), None) == 5
+    assert launch(0x1000, 1, 4, 1, 0, 0.1, None) == 4
+    assert launch(None, 0, 0, 2, 1, 0.1, None) == 0

@@ -149,6 +149,107 @@ def test_project_pack_batch_bit_exact(sste, dtype):
             assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv), k
 
 
+@pytest.mark.parametrize("master", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+@pytest.mark.parametrize("case", ["cfg1", "ragged_strided", "alpha0"])
+def test_sgd_project_pack_bit_exact(sste, master, dtype, case):
+    """Eq. (7) step fused with project + pack: the updated dense weight, the packed values and the
+    metadata are the oracle's, bit for bit; padding outside strided views is untouched."""
+    wl = WL.WORKLOADS[1]
+    O, I = (256, 1024) if case != "ragged_strided" else (77, 1152)
+    wb = WL.weight_bits(wl, 0, O=O, I=I)
+    rng = np.random.default_rng(11)
+    # gradients large enough that a step moves many weights across rounding and flip boundaries
+    g = (rng.standard_normal((O, I)) * 2e-2).astype(np.float32)
+    alpha = 0.0 if case == "alpha0" else 0.3
+    beta = np.float32(1.31)
+    scale = np.float32(1.0) if dtype == "bf16" else np.float32(0.0007)
+    w0 = wb if master == "bf16" else (F.bf16_to_f32(wb) + (rng.standard_normal((O, I)) * 1e-5).astype(np.float32))
+    pad = 64 if case == "ragged_strided" else 0
+    if master == "bf16":
+        Wbig = torch.full((O, I + pad), 7.0, dtype=torch.bfloat16, device="cuda")
+        Wbig[:, :I] = bf16_dev(w0)
+    else:
+        Wbig = torch.full((O, I + pad), 7.0, dtype=torch.float32, device="cuda")
+        Wbig[:, :I] = dev(w0)
+    Gbig = torch.full((O, I + pad // 2), 3.0, dtype=torch.float32, device="cuda")
+    Gbig[:, :I] = dev(g)
+    Wd, Gd = Wbig[:, :I], Gbig[:, :I]
+    vals, meta = sste.sgd_project_pack(Wd, Gd, alpha, float(beta), dt(sste, dtype), float(scale))
+    w_next, rv, rm = OP.sgd_project_pack(w0, g, alpha, beta, master, dtype, scale)
+    if master == "bf16":
+        got_w = host(Wd).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got_w, w_next)
+    else:
+        assert np.array_equal(host(Wd).numpy().view(np.uint32), w_next.view(np.uint32))
+    if pad:
+        assert bool((Wbig[:, I:] == 7.0).all()) and bool((Gbig[:, I:] == 3.0).all())
+    assert np.array_equal(host(Gd).numpy(), g)
+    fv, fm = OP.to_fragment_major(rv, rm, dtype)
+    assert np.array_equal(host(meta).numpy().reshape(-1), fm)
+    assert np.array_equal(host(vals).numpy().view(fv.dtype).reshape(-1), fv)
+    if case == "alpha0" and master == "bf16":
+        v2, m2 = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, dtype), float(scale))
+        assert torch.equal(v2, vals) and torch.equal(m2, meta)
+
+
+@pytest.mark.parametrize("master", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+def test_sgd_project_pack_batch_bit_exact(sste, master, dtype):
+    """Many tensors, one launch, two iterations with different learning rates: weights and packed forms
+    follow the oracle's iteration bit for bit (ragged rows, a strided tensor and an empty one included)."""
+    wl = WL.WORKLOADS[1]
+    shapes = [(256, 1024), (77, 1152), (16, 128), (0, 128), (33, 256)]
+    rng = np.random.default_rng(21)
+    ws, gs = [], []
+    for k, (O, I) in enumerate(shapes):
+        wb = WL.weight_bits(wl, k % len(wl.layers), O=O, I=I) if O else np.zeros((0, I), dtype=np.uint16)
+        ws.append(wb if master == "bf16" else (F.bf16_to_f32(wb) + (rng.standard_normal((O, I)) * 1e-5).astype(np.float32)))
+        gs.append((rng.standard_normal((O, I)) * 2e-2).astype(np.float32))
+    betas = [np.float32(1.25 + 0.125 * k) for k in range(len(ws))]
+    scales = [np.float32(1.0)] * len(ws) if dtype == "bf16" else [np.float32(0.0006 * (k + 1)) for k in range(len(ws))]
+    tdt = torch.bfloat16 if master == "bf16" else torch.float32
+    Wd, Gd = [], []
+    for k, (w, g) in enumerate(zip(ws, gs)):
+        O, I = g.shape
+        pad = 64 if k == 4 else 0
+        Wbig = torch.zeros((O, I + pad), dtype=tdt, device="cuda")
+        Gbig = torch.zeros((O, I + pad), dtype=torch.float32, device="cuda")
+        if O:
+            Wbig[:, :I] = bf16_dev(w) if master == "bf16" else dev(w)
+            Gbig[:, :I] = dev(g)
+        Wd.append(Wbig[:, :I])
+        Gd.append(Gbig[:, :I])
+    batch = sste.UpdateBatch(Wd, Gd, [float(b) for b in betas], dt(sste, dtype), [float(x) for x in scales])
+    for alpha in (0.3, -0.11):
+        vals, metas = batch.launch(alpha)
+        for k in range(len(ws)):
+            if ws[k].shape[0] == 0:
+                continue
+            ws[k], rv, rm = OP.sgd_project_pack(ws[k], gs[k], alpha, betas[k], master, dtype, scales[k])
+            if master == "bf16":
+                assert np.array_equal(host(Wd[k]).view(torch.int16).numpy().view(np.uint16), ws[k]), k
+            else:
+                assert np.array_equal(host(Wd[k]).numpy().view(np.uint32), ws[k].view(np.uint32)), k
+            fv, fm = OP.to_fragment_major(rv, rm, dtype)
+            assert np.array_equal(host(metas[k]).numpy().reshape(-1), fm), k
+            assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv), k
+
+
+def test_sgd_project_pack_errors(sste):
+    W = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    G = torch.zeros((16, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.sgd_project_pack(W, G, float("inf"), 1.0)
+    assert ei.value.status == 5
+    with pytest.raises(sste.SsteError) as ei:
+        sste.sgd_project_pack(W, torch.zeros((16, 66), dtype=torch.float32, device="cuda")[:, :64], 0.1, 1.0)
+    assert ei.value.status == 3
+    e = torch.empty((0, 64), dtype=torch.float32, device="cuda")
+    vals, meta = sste.sgd_project_pack(e, e.clone(), 0.1, 1.0)
+    assert vals.shape == (0, 32)
+
+
 def test_project_pack_empty_and_errors(sste):
     e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     vals, meta = sste.project_pack(e, 1.0)
