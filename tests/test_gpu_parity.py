@@ -570,3 +570,44 @@ def test_linear_dgrad_strided_and_errors(sste):
     with pytest.raises(sste.SsteError) as ei:
         sste.linear_dgrad(dYbig[:, :O], vals, meta, 96)
     assert ei.value.status == 7
+
+
+# ------------------------------------------------------------------------------------------ whole iterations
+
+def test_training_iterations_chain(sste):
+    """Three iterations of one layer through the C ABI: project+pack -> forward -> weight gradient and
+    input gradient -> dense-weight step fused with the next projection (Sec. 2, the three steps of an
+    iteration).  Every stage is checked against the oracle evaluated on that stage's inputs as the GPU
+    holds them: packed weight, weights after the step and estimator draws are bit-exact; GEMM outputs meet
+    the bf16 bar.  The recorded positions must change somewhere over the iterations (flips, Sec. 3.3)."""
+    wl = WL.WORKLOADS[1]
+    T, O, I = 512, 256, 1024
+    wb = WL.weight_bits(wl, 0)
+    xc, xs = WL.activations(wl, 0)
+    dyc, dys = WL.output_gradient(wl, 0)
+    beta = np.float32(OP.beta_mse(F.bf16_to_f32(wb).astype(np.float64)))
+    W = bf16_dev(wb)
+    X, dY = bf16_dev(xc), bf16_dev(dyc)
+    vals, meta = sste.project_pack(W, float(beta))
+    w_host = wb.copy()
+    rv, rm, _ = OP.project_pack(w_host, beta)
+    first_meta = rm.copy()
+    alpha = 0.2                                              # steps of about a quarter of a typical weight: groups flip
+    for it in range(3):
+        fv, fm = OP.to_fragment_major(rv, rm)
+        assert np.array_equal(host(meta).numpy().reshape(-1), fm), it
+        assert np.array_equal(host(vals).numpy().view(np.uint16).reshape(-1), fv), it
+        Z = sste.linear_fwd(X, vals, meta, O)
+        assert rel_err(z_to_f64(Z), OL.linear_fwd(xc, rv, rm, "bf16", xs, np.float32(1.0))) <= TOL["bf16"]
+        dX = sste.linear_dgrad(dY, vals, meta, I, sste.BF16, float(dys), 1.0)
+        assert rel_err(z_to_f64(dX), OL.linear_dgrad(dyc, rv, rm, "bf16", dys, np.float32(1.0))) <= TOL["bf16"]
+        dW = sste.linear_wgrad(dY, X, 77, it, sste.BF16, float(dys), float(xs))
+        ref_dw = OL.linear_wgrad(dyc, xc, 77, it, "bf16", dys, xs)
+        assert rel_err(host(dW).numpy().astype(np.float64), ref_dw) <= 1e-4
+        g = host(dW).numpy()                                 # the step is checked on the gradient the GPU holds
+        vals, meta = sste.sgd_project_pack(W, dW, alpha, float(beta), vals=vals, meta=meta)
+        w_host, rv, rm = OP.sgd_project_pack(w_host, g, alpha, beta)
+        assert np.array_equal(host(W).view(torch.int16).numpy().view(np.uint16), w_host), it
+    fv, fm = OP.to_fragment_major(rv, rm)
+    assert np.array_equal(host(meta).numpy().reshape(-1), fm)
+    assert np.count_nonzero(OP.structural_mask(first_meta) ^ OP.structural_mask(rm)) > 0
