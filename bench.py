@@ -294,7 +294,7 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
-    if not fp8:
+    if True:
         # the layer's third GEMM, grad_X = grad_Z S(W): dense by the paper's choice, not part of `value`
         dXs = [torch.empty((T, I), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
         for i in range(5):
@@ -307,8 +307,6 @@ def main():
         dg_ms = (time.perf_counter() - g0) * 1e3 / args.steps
         out_dgrad = {"ms": dg_ms, "TFLOP_per_s": gemm_flops / (dg_ms * 1e-3) * 1e-12, "frac_dense_mfma_peak": gemm_flops / (dg_ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
         del dXs
-    else:
-        out_dgrad = None
     if args.dense_context and not fp8:
         # what the vendor's dense GEMM reaches on the same layer (forward Z = X W^T; weight gradient dY^T X)
         def dense_us(fn, iters=50):

@@ -349,17 +349,17 @@ int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
   if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_dgrad: unknown dtype %d", dtype);
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_dgrad: I=%lld is not a multiple of 8", (long long)I);
   if (!good_scale(dy_scale) || !good_scale(w_scale)) return fail(SSTE_ERR_VALUE, "linear_dgrad: scales must be finite and > 0");
-  if (dtype != SSTE_BF16) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: only bf16 operands are built");
-  if (I % 64 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: I=%lld must be a multiple of 64", (long long)I);
-  if (O % 8 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: O=%lld must be a multiple of 8", (long long)O);
+  const int ks = dtype == SSTE_F8E4M3 ? 128 : 64, e16 = elems_per_16B(dtype);
+  if (I % ks != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: I=%lld must be a multiple of %d", (long long)I, ks);
+  if (O % e16 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: O=%lld must be a multiple of %d", (long long)O, e16);
   if (lddy < O || lddx < I) return fail(SSTE_ERR_SHAPE, "linear_dgrad: leading dimension smaller than the row length");
-  if (lddy % 8 != 0 || lddx % 8 != 0) return fail(SSTE_ERR_ALIGN, "linear_dgrad: lddy / lddx break the 16-byte row rule");
+  if (lddy % e16 != 0 || lddx % 8 != 0) return fail(SSTE_ERR_ALIGN, "linear_dgrad: lddy / lddx break the 16-byte row rule");
   bool empty_out = (T == 0 || I == 0);
   if (!empty_out && !dX) return fail(SSTE_ERR_NULL, "linear_dgrad: NULL dX");
   if (!empty_out && O > 0 && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "linear_dgrad: NULL dY, vals or meta");
   if (!aligned16(dY) || !aligned16(vals) || !aligned16(dX)) return fail(SSTE_ERR_ALIGN, "linear_dgrad: dY, vals and dX must be 16-byte aligned");
   if (!linear_dgrad_supported(T, O, lddy, I, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: problem too large for 32-bit tile offsets");
-  return hip_status(launch_linear_dgrad(dY, T, O, lddy, dy_scale * w_scale, vals, meta, I, dX, lddx, (hipStream_t)hip_stream),
+  return hip_status(launch_linear_dgrad(dY, T, O, lddy, dtype, dy_scale * w_scale, vals, meta, I, dX, lddx, (hipStream_t)hip_stream),
                     "linear_dgrad launch");
 }
 

@@ -176,7 +176,7 @@ hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t
                                          float alpha, hipStream_t s);
 hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t total_blocks, int val_dtype, hipStream_t s);
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype);
-hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, float scale, const void* vals,
+hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
                                const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s);
 hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
                                hipStream_t s);

@@ -21,12 +21,20 @@
 // row block ahead, the grad_Z tile s + 2 is requested and, last, the packed blocks s + 3 are loaded.
 // Loads get one k-step (about 2000 clocks here) to complete; that keeps the LDS at exactly 160 KiB.
 // Epilogue as in the forward GEMM: transposed through LDS, 16-byte streaming stores of bf16 rows.
+//
+// e4m3 operands (per-tensor scales, Sec. 5.2): the same kernel with 128 channels per k-step, so that a
+// grad_Z row of the tile is again 128 bytes and both LDS rings keep their size.  One
+// v_mfma_f32_16x16x128_f8f6f4 per tile and k-step; the only layout requirement of that instruction
+// used here is that byte e of lane (., q) of both operands is the same channel.  The decoded tile has
+// 256-byte channel rows of 16-byte feature chunks (chunk c of row r at position c ^ (r % 16)), read
+// with ds_read_b64_tr_b8; a group expands with one byte permute.
 #include "common.h"
 
 namespace sste {
 
 namespace {
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
 
 // One group of a packed 2:4 operand -> its four dense bf16: w = value0 | value1 << 16 (ascending
 // positions), nib = pos0 | pos1 << 2 with pos0 < pos1.  lo holds positions 0, 1; hi positions 2, 3.
@@ -37,17 +45,31 @@ __device__ __forceinline__ void expand_group(uint32_t w, uint32_t nib, uint32_t&
   lo = (uint32_t)d;
   hi = (uint32_t)(d >> 32);
 }
+
+// The same for e4m3 values: w holds value0 at byte b0 and value1 at byte b0 + 1; the result is the four
+// dense bytes of the group.  A byte permute with a computed selector: selector bytes 0..3 pick from the
+// zero operand, 4..7 from w.
+__device__ __forceinline__ uint32_t expand_group8(uint32_t w, uint32_t b0, uint32_t nib) {
+  const uint32_t sel = ((4u + b0) << (((nib & 3u) << 3) & 31u)) | ((5u + b0) << (((nib & 12u) << 1) & 31u));
+  return __builtin_amdgcn_perm(w, 0u, sel);
+}
 }  // namespace
 
-template <int NI_>
+template <bool FP8, int NI_>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
                float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
   constexpr int WN = 4, NW = 8, MI_ = 8;
+  constexpr int EB = FP8 ? 1 : 2;
+  constexpr int KC = FP8 ? 128 : 64;                // channels per k-step (128 bytes of a grad_Z row)
+  constexpr int RBK = KC / 16;                      // packed row blocks per k-step
+  constexpr int CST = FP8 ? 2 : 4;                  // packed column steps per 256 features
+  constexpr int MBLK = FP8 ? 256 : 128;             // metadata bytes per packed block
   constexpr int BM = 256, BN = 64 * NI_;            // features x tokens per workgroup (256 x 256 or 256 x 128)
-  constexpr int ASLOT = 64 * 512;                   // decoded S(W): 64 channels x 256 features bf16
-  constexpr int BSLOT = BN * 128;                   // grad_Z: BN tokens x 64 channels bf16
+  constexpr int AROW = BM * EB;                     // bytes of one channel row of the decoded tile
+  constexpr int ASLOT = KC * AROW;                  // decoded S(W): KC channels x 256 features
+  constexpr int BSLOT = BN * 128;                   // grad_Z: BN tokens x KC channels
   constexpr int NRA = 3, NRB = 2;
   constexpr int LB = BSLOT / 1024 / NW;             // direct-to-LDS loads per wave and k-step: 4 / 2
   constexpr int EROW = 32 * MI_ + 16;
@@ -64,12 +86,12 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   const int wm = wave / WN, wn = wave % WN;
   const int j = lane & 15, q = lane >> 4;
   const int64_t i0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
-  const int nsteps = (int)((O + 63) / 64);
+  const int nsteps = (int)((O + KC - 1) / KC);
   const int64_t rbn = (O + 15) / 16;
 
   // grad_Z tile: exactly the valid rows and channels; what lies outside reads as zeros
   const int rows_b = (int)((T - t0) < BN ? (T - t0) : BN);
-  const i32x4 bb = rsrc_words(dY + t0 * lddy_bytes, (uint32_t)((rows_b - 1) * lddy_bytes + O * 2));
+  const i32x4 bb = rsrc_words(dY + t0 * lddy_bytes, (uint32_t)((rows_b - 1) * lddy_bytes + O * EB));
   uint32_t offb[LB];
 #pragma unroll
   for (int i = 0; i < LB; i++) {
@@ -80,44 +102,56 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   const uint32_t ldsB = (uint32_t)(uintptr_t)(lds_u8*)smemB;
   constexpr uint32_t DEAD = 0x40000000u;
 
-  // packed S(W): this wave's two blocks of a k-step are (row block 4 s + rbl, column step 4 tm + csl)
+  // packed S(W): this wave's two blocks of a k-step are (row block RBK s + rbl, column step CST tm + csl)
   const BufferRsrc rv = make_rsrc(vals, (uint32_t)(rbn * isteps * 1024));
-  const BufferRsrc rm = make_rsrc(meta, (uint32_t)(rbn * isteps * 128));
+  const BufferRsrc rm = make_rsrc(meta, (uint32_t)(rbn * isteps * MBLK));
   uint32_t pv_off[2], pm_off[2], dec_off[2];
 #pragma unroll
   for (int e = 0; e < 2; e++) {
-    const int blkid = 2 * wave + e, rbl = blkid >> 2, csl = blkid & 3;
-    const int cs = 4 * tm + csl;
+    const int blkid = 2 * wave + e, rbl = blkid / CST, csl = blkid % CST;
+    const int cs = CST * tm + csl;
     const bool live = cs < isteps;                  // column steps past the last feature: nothing to fetch
     pv_off[e] = live ? (uint32_t)((rbl * isteps + cs) * 1024 + lane * 16) : 0x80000000u;
-    pm_off[e] = live ? (uint32_t)((rbl * isteps + cs) * 128 + lane * 2) : 0x80000000u;
-    const int row = 16 * rbl + j, p = 4 * csl + q;
-    dec_off[e] = (uint32_t)(row * 512 + ((p ^ (row & 15)) * 32));
+    pm_off[e] = live ? (uint32_t)((rbl * isteps + cs) * MBLK + lane * (MBLK / 64)) : 0x80000000u;
+    // the lane's 32 dense bytes: bf16 one 32-byte feature pair, e4m3 two 16-byte chunks (second at ^ 16)
+    const int row = 16 * rbl + j, p = FP8 ? 8 * csl + 2 * q : 4 * csl + q;
+    dec_off[e] = (uint32_t)(row * AROW + ((p ^ (row & 15)) * (FP8 ? 16 : 32)));
   }
   uint4 pk[2], pk2[2];                // packed blocks in flight / being expanded (second set: 256 x 128 tile only)
   uint32_t pmeta[2], pmeta2[2];
   uint32_t dec[8];                    // one block row being expanded: 16 dense bf16
 #define DG_LOAD_PACKED(step, PK, PM)                                                                            \
   do {                                                                                                    \
-    const uint32_t sv_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 1024u;                                \
-    const uint32_t sm_ = (uint32_t)(step) * 4u * (uint32_t)isteps * 128u;                                 \
+    const uint32_t sv_ = (uint32_t)(step) * (uint32_t)RBK * (uint32_t)isteps * 1024u;                     \
+    const uint32_t sm_ = (uint32_t)(step) * (uint32_t)RBK * (uint32_t)isteps * (uint32_t)MBLK;            \
     _Pragma("unroll") for (int e = 0; e < 2; e++) {                                                       \
       /* row blocks past the last one (tail of the channel axis, k-steps past the end) fetch nothing */    \
-      const bool live_ = 4 * (int64_t)(step) + ((2 * wave + e) >> 2) < rbn;                               \
+      const bool live_ = RBK * (int64_t)(step) + ((2 * wave + e) / CST) < rbn;                            \
       PK[e] = buffer_load_b128(rv, live_ ? pv_off[e] : 0x80000000u, live_ ? sv_ : 0u);                    \
-      PM[e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
-                                                                         (int)(live_ ? sm_ : 0u), 0);    \
+      if (FP8)                                                                                            \
+        PM[e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
+                                                               (int)(live_ ? sm_ : 0u), 0);               \
+      else                                                                                                \
+        PM[e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rm, (int)(live_ ? pm_off[e] : 0x80000000u), \
+                                                                           (int)(live_ ? sm_ : 0u), 0);  \
     }                                                                                                     \
   } while (0)
-// expansion of group g of block e into the staging registers; after the fourth group the 32 bytes are written
+// expansion of quarter g of block e (one bf16 group / two e4m3 groups: eight dense bytes) into the
+// staging registers; after the fourth quarter the 32 bytes are written
 #define DG_DECODE_PIECE(slot_, e, g, PK, PM)                                                                    \
   do {                                                                                                    \
     const uint32_t w_ = (g) == 0 ? PK[e].x : (g) == 1 ? PK[e].y : (g) == 2 ? PK[e].z : PK[e].w;           \
-    expand_group(w_, (PM[e] >> (4 * (g))) & 15u, dec[2 * (g)], dec[2 * (g) + 1]);                         \
+    if (FP8) {                                                                                            \
+      dec[2 * (g)] = expand_group8(w_, 0u, (PM[e] >> (8 * (g))) & 15u);                                   \
+      dec[2 * (g) + 1] = expand_group8(w_, 2u, (PM[e] >> (8 * (g) + 4)) & 15u);                           \
+    } else {                                                                                              \
+      expand_group(w_, (PM[e] >> (4 * (g))) & 15u, dec[2 * (g)], dec[2 * (g) + 1]);                       \
+    }                                                                                                     \
     if ((g) == 3) {                                                                                       \
       uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
+      uint8_t* dst2_ = smemA + (slot_) * ASLOT + (FP8 ? (dec_off[e] ^ 16u) : (dec_off[e] + 16u));         \
       *(uint4*)dst_ = make_uint4(dec[0], dec[1], dec[2], dec[3]);                                         \
-      *(uint4*)(dst_ + 16) = make_uint4(dec[4], dec[5], dec[6], dec[7]);                                  \
+      *(uint4*)dst2_ = make_uint4(dec[4], dec[5], dec[6], dec[7]);                                        \
     }                                                                                                     \
   } while (0)
 #define DG_DECODE(slot_, PK, PM)                                                                             \
@@ -137,11 +171,17 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   // fragment addresses.  S(W): transposing reads, piece r covers channels 8q + 4 (r & 1) + 32 (r >> 1) .. + 3
   // of the 16 features of row block mi; the feature pair index 8 wm + mi enters through the XOR below
   // (mi only touches the low three bits of the pair position).
+  // e4m3: piece r covers channels 16q + 8 (r & 1) + 64 (r >> 1) .. + 7 of the 16 features of chunk 8 wm + mi.
   uint32_t fa_off[4];
 #pragma unroll
   for (int r = 0; r < 4; r++) {
-    int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
-    fa_off[r] = (uint32_t)(row * 512 + (((8 * wm) ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+    if (FP8) {
+      int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
+      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ (row & 15)) * 16) + 8 * (j & 1));
+    } else {
+      int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
+      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+    }
   }
   const int rb0 = 16 * NI_ * wn + j;
   const int cb0 = q ^ ((j >> 1) & 7);
@@ -151,8 +191,17 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
 #define DG_READ_A(dst, base, mi_)                                                                         \
   do {                                                                                                    \
     _Pragma("unroll") for (int r = 0; r < 4; r++) {                                                       \
-      bf16x4 t_ = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)((base) + (fa_off[r] ^ (uint32_t)((mi_) * 32)))); \
-      __builtin_memcpy(&dst[r], &t_, 8);                                                                  \
+      /* e4m3 256 x 256 tile: the offset is made opaque so that the 32 swizzled addresses of a k-step   */ \
+      /* are formed where they are used (one XOR each); kept in registers across the loop they spill    */ \
+      uint32_t o_ = fa_off[r];                                                                            \
+      if (FP8 && NI_ == 4) asm volatile("" : "+v"(o_));                                                   \
+      if (FP8) {                                                                                          \
+        i32x2 t_ = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2*)((base) + (o_ ^ (uint32_t)((mi_) * 16)))); \
+        dst[r] = make_uint2((uint32_t)t_[0], (uint32_t)t_[1]);                                            \
+      } else {                                                                                            \
+        bf16x4 t_ = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)((base) + (o_ ^ (uint32_t)((mi_) * 32)))); \
+        __builtin_memcpy(&dst[r], &t_, 8);                                                                \
+      }                                                                                                   \
     }                                                                                                     \
   } while (0)
 
@@ -208,13 +257,22 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
       _Pragma("unroll") for (int n = 0; n < LB; n++)                                                      \
         if (n == mi) DG_DMA_B(n, step + 2, 1 - b1);                                                       \
       _Pragma("unroll") for (int ni = 0; ni < NI_; ni++) {                                                \
-        bf16x8 av0, av1, bv0, bv1;                                                                        \
-        __builtin_memcpy(&av0, &fa[mi & (AB - 1)][0], 16);                                                       \
-        __builtin_memcpy(&av1, &fa[mi & (AB - 1)][2], 16);                                                       \
-        __builtin_memcpy(&bv0, &BC[ni][0], 16);                                                           \
-        __builtin_memcpy(&bv1, &BC[ni][1], 16);                                                           \
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av0, bv0, acc[mi][ni], 0, 0, 0);            \
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av1, bv1, acc[mi][ni], 0, 0, 0);            \
+        if (FP8) {                                                                                        \
+          /* one 128-channel instruction; byte e of both operands is the same channel (16q + e, then    */ \
+          /* 64 + 16q + e - 16), zero scale arguments select the unscaled form                          */ \
+          i32x8 av, bv;                                                                                   \
+          __builtin_memcpy(&av, &fa[mi & (AB - 1)][0], 32);                                               \
+          __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
+          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[mi][ni], 0, 0, 0, 0, 0, 0); \
+        } else {                                                                                          \
+          bf16x8 av0, av1, bv0, bv1;                                                                      \
+          __builtin_memcpy(&av0, &fa[mi & (AB - 1)][0], 16);                                              \
+          __builtin_memcpy(&av1, &fa[mi & (AB - 1)][2], 16);                                              \
+          __builtin_memcpy(&bv0, &BC[ni][0], 16);                                                         \
+          __builtin_memcpy(&bv1, &BC[ni][1], 16);                                                         \
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av0, bv0, acc[mi][ni], 0, 0, 0);          \
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av1, bv1, acc[mi][ni], 0, 0, 0);          \
+        }                                                                                                 \
       }                                                                                                   \
       __builtin_amdgcn_sched_barrier(0);                                                                  \
     }                                                                                                     \
@@ -277,28 +335,31 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
 }
 
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype) {
-  if (dtype != SSTE_BF16) return false;                                   // e4m3 operands: not built
-  if (256 * lddy * 2 >= (1ll << 30)) return false;                        // 32-bit offsets inside a grad_Z tile
+  const int eb = dtype == SSTE_F8E4M3 ? 1 : 2;
+  if (256 * lddy * eb >= (1ll << 30)) return false;                       // 32-bit offsets inside a grad_Z tile
   if (((O + 15) / 16 * 16) * I >= (1ll << 31)) return false;              // packed operand addressed with 32-bit offsets
   if (((I + 255) / 256) * ((T + 255) / 256) > 0x7FFFFFFFll) return false;
   return true;
 }
 
-hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, float scale, const void* vals,
+hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
                                const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s) {
   if (T == 0 || I == 0) return hipSuccess;
+  const bool fp8 = dtype == SSTE_F8E4M3;
   int m_tiles = (int)((I + 255) / 256);
   // 256 x 256 tiles unless they leave a quarter or more of the CUs without work in the only round
   int64_t big = (int64_t)m_tiles * ((T + 255) / 256);
   bool half = big < 192;
   int n_tiles = (int)((T + (half ? 127 : 255)) / (half ? 128 : 256));
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
-  if (half)
-    SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<2>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
-                (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
-  else
-    SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<4>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, (const uint8_t*)vals,
-                (const uint8_t*)meta, I, (int)(I / 64), scale, (uint16_t*)dX, lddx, m_tiles);
+#define DG_CASE(F8, NI)                                                                                                \
+  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI>), grid, block, s, (const uint8_t*)dY, T, O, lddy*(F8 ? 1 : 2),    \
+              (const uint8_t*)vals, (const uint8_t*)meta, I, (int)(I / (F8 ? 128 : 64)), scale, (uint16_t*)dX, lddx, m_tiles)
+  if (fp8 && half) DG_CASE(true, 2);
+  else if (fp8) DG_CASE(true, 4);
+  else if (half) DG_CASE(false, 2);
+  else DG_CASE(false, 4);
+#undef DG_CASE
   return hipGetLastError();
 }
 

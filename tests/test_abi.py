@@ -161,7 +161,8 @@ def test_linear_dgrad_validation(lib):
     f.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float, P, P, ctypes.c_int64,
                   ctypes.c_float, P, ctypes.c_int64, P]
     assert f(fake, -4, 64, 64, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 2
-    assert f(fake, 4, 64, 64, 1, 1.0, fake, fake, 128, 1.0, fake, 128, None) == 7      # e4m3 operands are not built
+    assert f(fake, 4, 64, 64, 1, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 7        # e4m3: I must be a multiple of 128
+    assert f(fake, 4, 72, 80, 1, 1.0, fake, fake, 128, 1.0, fake, 128, None) == 7      # e4m3: O must be a multiple of 16
     assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 96, 1.0, fake, 96, None) == 7        # I must be a multiple of 64
     assert f(fake, 4, 60, 64, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 7        # O must be a multiple of 8
     assert f(fake, 4, 64, 32, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 2        # lddy < O

@@ -518,35 +518,42 @@ def test_step_under_graph_capture_replays_bit_exact(sste):
 
 # ------------------------------------------------------------------------------------------ input gradient
 
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
 @pytest.mark.parametrize("T,O,I", [
     (512, 256, 1024),          # the tiny workload's shapes
-    (300, 264, 320),           # ragged token tile, channel count not a multiple of the 64-channel k-step, ragged feature tile
-    (1, 8, 64),                # single token, one partial k-step
-    (1000, 520, 384),          # several k-steps, two feature tiles
-    (8, 0, 64),                # no channels: zeros
+    (300, 272, 384),           # ragged token tile, channel count not a multiple of the k-step, ragged feature tile
+    (1, 16, 128),              # single token, one partial k-step
+    (1000, 528, 640),          # several k-steps, three feature tiles
+    (8, 0, 128),               # no channels: zeros
+    (16384, 144, 128),         # many token tiles: the 256 x 256 tile kernel
 ])
-def test_linear_dgrad_matches_oracle(sste, T, O, I):
-    wl = WL.WORKLOADS[1]
+def test_linear_dgrad_matches_oracle(sste, dtype, T, O, I):
+    wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
     beta = np.float32(1.4830322)
-    dyc, dys = WL.output_gradient(wl, 0, T=T, O=max(O, 8))
+    dyc, dys = WL.output_gradient(wl, 0, T=T, O=max(O, 16))
     dyc = dyc[:, :O]
+    ws = np.float32(1.0)
     if O:
         wb = WL.weight_bits(wl, 0, O=O, I=I)
-        rv, rm, _ = OP.project_pack(wb, beta)
-        vals, meta = sste.project_pack(bf16_dev(wb), float(beta))
-        ref = OL.linear_dgrad(dyc, rv, rm, "bf16", dys, np.float32(1.0))
-        dY = bf16_dev(np.ascontiguousarray(dyc))
+        if dtype == "e4m3":
+            _, _, amax = OP.project_pack(wb, beta)
+            ws = np.float32(amax / np.float32(448.0))
+        rv, rm, _ = OP.project_pack(wb, beta, dtype, ws)
+        vals, meta = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, dtype), float(ws))
+        ref = OL.linear_dgrad(dyc, rv, rm, dtype, dys, ws)
+        dY = act_dev(np.ascontiguousarray(dyc), dtype)
     else:
-        vals, meta = sste.packed_buffers(0, I, sste.BF16, "cuda")
+        vals, meta = sste.packed_buffers(0, I, dt(sste, dtype), "cuda")
         ref = np.zeros((T, I))
-        dY = torch.zeros((T, 8), dtype=torch.bfloat16, device="cuda")[:, :0]      # no channels, valid row pitch
+        dY = torch.zeros((T, 16), dtype=torch.bfloat16 if dtype == "bf16" else torch.uint8, device="cuda")[:, :0]
     dX = torch.full((T, I), 7.0, dtype=torch.bfloat16, device="cuda")
-    sste.linear_dgrad(dY, vals, meta, I, sste.BF16, float(dys), 1.0, dX=dX)
+    sste.linear_dgrad(dY, vals, meta, I, dt(sste, dtype), float(dys), float(ws), dX=dX)
     got = z_to_f64(dX)
     if O == 0:
         assert np.all(got == 0.0)
         return
-    assert rel_err(got, ref) <= TOL["bf16"]
+    assert rel_err(got, ref) <= TOL[dtype]
+    # operands are identical on both sides: only float32 accumulation order and the bf16 output rounding differ
     assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + np.max(np.abs(ref)) * 1e-4)
 
 
@@ -564,8 +571,8 @@ def test_linear_dgrad_strided_and_errors(sste):
     ref = OL.linear_dgrad(dyc, rv, rm, "bf16", dys, np.float32(1.0))
     assert rel_err(z_to_f64(dXbig[:, :I]), ref) <= TOL["bf16"]
     assert float((dXbig[:, I:].float() + 5.0).abs().max()) == 0.0
-    with pytest.raises(sste.SsteError) as ei:          # e4m3 operands are not built for this product
-        sste.linear_dgrad(torch.zeros((T, 80), dtype=torch.uint8, device="cuda"), vals, meta, I, sste.F8E4M3)
+    with pytest.raises(sste.SsteError) as ei:          # e4m3 rows are 16 channels to the 16 bytes
+        sste.linear_dgrad(torch.zeros((T, 72), dtype=torch.uint8, device="cuda"), vals, meta, I, sste.F8E4M3)
     assert ei.value.status == 7
     with pytest.raises(sste.SsteError) as ei:
         sste.linear_dgrad(dYbig[:, :O], vals, meta, 96)
