@@ -56,10 +56,16 @@ __device__ __forceinline__ uint32_t expand_group8(uint32_t w, uint32_t b0, uint3
 }  // namespace
 
 template <bool FP8, int NI_>
-__global__ void __launch_bounds__(512, 1)
-k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
-               const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
-               float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
+constexpr int dgrad_smem() {
+  return 3 * (FP8 ? 128 : 64) * 256 * (FP8 ? 1 : 2) + 2 * 64 * NI_ * 128;
+}
+
+// One tile: features [256 tm, 256 tm + 256) x tokens [t0, t0 + 64 NI_), by a 512-thread workgroup.
+template <bool FP8, int NI_>
+__device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restrict__ dY, int64_t T, int64_t O,
+                                           int64_t lddy_bytes, const uint8_t* __restrict__ vals,
+                                           const uint8_t* __restrict__ meta, int64_t I, int isteps, float scale,
+                                           uint16_t* __restrict__ dX, int64_t lddx, int tm, int64_t t0) {
   constexpr int WN = 4, NW = 8, MI_ = 8;
   constexpr int EB = FP8 ? 1 : 2;
   constexpr int KC = FP8 ? 128 : 64;                // channels per k-step (128 bytes of a grad_Z row)
@@ -74,18 +80,16 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   constexpr int LB = BSLOT / 1024 / NW;             // direct-to-LDS loads per wave and k-step: 4 / 2
   constexpr int EROW = 32 * MI_ + 16;
   constexpr int NPIECE = 2 * NI_;
+  static_assert(NRA * ASLOT + NRB * BSLOT == dgrad_smem<FP8, NI_>(), "LDS size");
   static_assert(NRA * ASLOT + NRB * BSLOT <= 160 * 1024 && NW * 16 * NI_ * EROW <= NRA * ASLOT + NRB * BSLOT, "LDS budget");
-  __shared__ __align__(1024) uint8_t smem[NRA * ASLOT + NRB * BSLOT];
   uint8_t* const smemA = smem;
   uint8_t* const smemB = smem + NRA * ASLOT;
 
-  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int tm = logical % m_tiles, tn = logical / m_tiles;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
   const int j = lane & 15, q = lane >> 4;
-  const int64_t i0 = (int64_t)tm * BM, t0 = (int64_t)tn * BN;
+  const int64_t i0 = (int64_t)tm * BM;
   const int nsteps = (int)((O + KC - 1) / KC);
   const int64_t rbn = (O + 15) / 16;
 
@@ -334,11 +338,44 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   }
 }
 
+template <bool FP8, int NI_>
+__global__ void __launch_bounds__(512, 1)
+k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
+               const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
+               float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
+  __shared__ __align__(1024) uint8_t smem[dgrad_smem<FP8, NI_>()];
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tm = logical % m_tiles, tn = logical / m_tiles;
+  dgrad_tile<FP8, NI_>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tm, (int64_t)tn * (64 * NI_));
+}
+
+// Whole rounds of 256 x 256 tiles (workgroups 0 .. n_big - 1), then the tiles of the last, partial round
+// as twice as many 256 x 128 tiles, so that the round takes half a tile time on twice the CUs.
+template <bool FP8>
+__global__ void __launch_bounds__(512, 1)
+k_linear_dgrad_dual(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
+                    const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
+                    float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles, int n_big) {
+  __shared__ __align__(1024) uint8_t smem[dgrad_smem<FP8, 4>()];
+  const int bid = blockIdx.x;
+  if (bid < n_big) {
+    const int logical = xcd_contiguous(bid, n_big);
+    dgrad_tile<FP8, 4>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, logical % m_tiles,
+                       (int64_t)(logical / m_tiles) * 256);
+  } else {
+    const int h = xcd_contiguous(bid - n_big, (int)gridDim.x - n_big);      // half-tile number
+    const int tile = n_big + (h >> 1);
+    const int64_t t0 = (int64_t)(tile / m_tiles) * 256 + 128 * (h & 1);
+    if (t0 >= T) return;                       // second half of a ragged last token tile: nothing to do
+    dgrad_tile<FP8, 2>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tile % m_tiles, t0);
+  }
+}
+
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype) {
   const int eb = dtype == SSTE_F8E4M3 ? 1 : 2;
   if (256 * lddy * eb >= (1ll << 30)) return false;                       // 32-bit offsets inside a grad_Z tile
   if (((O + 15) / 16 * 16) * I >= (1ll << 31)) return false;              // packed operand addressed with 32-bit offsets
-  if (((I + 255) / 256) * ((T + 255) / 256) > 0x7FFFFFFFll) return false;
+  if (((I + 255) / 256) * ((T + 127) / 128) > 0x7FFFFFFFll) return false;
   return true;
 }
 
@@ -349,12 +386,29 @@ hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
   int m_tiles = (int)((I + 255) / 256);
   // 256 x 256 tiles unless they leave a quarter or more of the CUs without work in the only round
   int64_t big = (int64_t)m_tiles * ((T + 255) / 256);
+  int64_t rem = big % 256;
+  const uint8_t* dy = (const uint8_t*)dY;
+  const uint8_t* pv = (const uint8_t*)vals;
+  const uint8_t* pm = (const uint8_t*)meta;
+  const int isteps = (int)(I / (fp8 ? 128 : 64));
+  const int64_t lddy_bytes = lddy * (fp8 ? 1 : 2);
+  if (big > 256 && rem > 0 && rem <= 128) {
+    int n_big = (int)(big - rem);
+    dim3 grid((unsigned)(n_big + 2 * rem)), block(512);
+    if (fp8)
+      SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<true>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,
+                  (uint16_t*)dX, lddx, m_tiles, n_big);
+    else
+      SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<false>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,
+                  (uint16_t*)dX, lddx, m_tiles, n_big);
+    return hipGetLastError();
+  }
   bool half = big < 192;
   int n_tiles = (int)((T + (half ? 127 : 255)) / (half ? 128 : 256));
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
 #define DG_CASE(F8, NI)                                                                                                \
-  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI>), grid, block, s, (const uint8_t*)dY, T, O, lddy*(F8 ? 1 : 2),    \
-              (const uint8_t*)vals, (const uint8_t*)meta, I, (int)(I / (F8 ? 128 : 64)), scale, (uint16_t*)dX, lddx, m_tiles)
+  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,  \
+              (uint16_t*)dX, lddx, m_tiles)
   if (fp8 && half) DG_CASE(true, 2);
   else if (fp8) DG_CASE(true, 4);
   else if (half) DG_CASE(false, 2);

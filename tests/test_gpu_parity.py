@@ -526,6 +526,7 @@ def test_step_under_graph_capture_replays_bit_exact(sste):
     (1000, 528, 640),          # several k-steps, three feature tiles
     (8, 0, 128),               # no channels: zeros
     (16384, 144, 128),         # many token tiles: the 256 x 256 tile kernel
+    (65892, 32, 128),          # 258 tiles: a whole round of 256 x 256 tiles + the rest as 256 x 128 halves, ragged tail
 ])
 def test_linear_dgrad_matches_oracle(sste, dtype, T, O, I):
     wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
