@@ -244,8 +244,8 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
  *   dX = (dy_scale * w_scale) * dY * decode(vals, meta),  float32 accumulation, dX stored as bf16 (RNE).
  *
  *   dY       in   device, T x O of `dtype`, leading dimension lddy
- *   T, O, I  in   T >= 0; O >= 0 and a multiple of 8; I a multiple of 64
- *   dtype    in   SSTE_BF16 (element type of dY and of vals).  SSTE_F8E4M3 -> ERR_UNSUPPORTED.
+ *   T, O, I  in   T >= 0; O >= 0 and a multiple of 8 (bf16) / 16 (e4m3); I a multiple of 64 / 128
+ *   dtype    in   SSTE_BF16 or SSTE_F8E4M3: element type of dY and of vals (per-tensor scales, Sec. 5.2)
  *   dy_scale, w_scale  in  finite, > 0
  *   vals, meta  in   packed S(W) (R = O rows, K = I columns) as written by sste_project_pack; rows past O
  *                    up to the next multiple of 16 must be the padding that call writes
