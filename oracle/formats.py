@@ -1,5 +1,6 @@
-"""Storage formats used by the bit-spec layer: bfloat16 and OCP FP8 e4m3fn (Sec. 5.2 of the
-paper uses per-tensor scaled FP8; the workload fixes e4m3 for weights, activations, gradients).
+"""Storage formats used by the bit-spec layer: bfloat16, OCP FP8 e4m3fn and OCP FP8 e5m2 (Sec. 5.2
+of the paper uses per-tensor scaled FP8, e5m2 in the backward pass; the workload fixes e4m3 for
+weights, activations, gradients -- e5m2 output gradients are the paper's own recipe).
 
 Test infrastructure only (see the package header).  Pinned: every function here is checked in
 ``tests/test_oracle_formats.py`` against the format definitions (exhaustive decode tables,
@@ -9,6 +10,7 @@ implementation of the same IEEE-style round-to-nearest-even conversions.
 import numpy as np
 
 E4M3_MAX = 448.0  # largest finite e4m3fn magnitude: 2^8 * 1.75
+E5M2_MAX = 57344.0  # largest finite e5m2 magnitude: 2^15 * 1.75
 
 
 def bf16_to_f32(bits):
@@ -59,5 +61,36 @@ def f32_to_e4m3_rne_sat(x):
     q = np.where(carry, 8, q).astype(np.int64)
     sub = q < 8                                      # below the smallest normal of binade -6
     code = np.where(sub, q, ((e + 7) << 3) | (q - 8))
+    code = code | (neg.astype(np.int64) << 7)
+    return code.astype(np.uint8)
+
+
+def e5m2_to_f32(codes):
+    """uint8 e5m2 codes -> float32.  1 sign, 5 exponent (bias 15), 2 mantissa bits: the top byte of an
+    IEEE half.  Exponent 0 is subnormal (m * 2^-16); exponent 31 is infinity (m = 0) or NaN."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    s = (c >> 7) & 1
+    e = (c >> 2) & 31
+    m = c & 3
+    mag = np.where(e == 0, m * 2.0 ** -16, (1.0 + m / 4.0) * np.exp2((e - 15).astype(np.float64)))
+    mag = np.where(e == 31, np.where(m == 0, np.inf, np.nan), mag)
+    return np.where(s == 1, -mag, mag).astype(np.float32)
+
+
+def f32_to_e5m2_rne_sat(x):
+    """float32 -> e5m2 codes (uint8): clamp to +-57344, then round to nearest, ties to even;
+    subnormals are kept; the sign of zero is kept.  Never produces infinity or NaN."""
+    x = np.asarray(x, dtype=np.float32)
+    neg = np.signbit(x)
+    a = np.minimum(np.abs(x).astype(np.float64), E5M2_MAX)
+    mant, ex = np.frexp(a)                           # a = mant * 2^ex, mant in [0.5, 1)
+    e = np.clip(np.where(a > 0, ex - 1, -14), -14, 15).astype(np.int64)
+    step = np.exp2((e - 2).astype(np.float64))      # spacing of representable values in that binade
+    q = np.rint(a / step)                            # half-to-even; q in [0, 8]
+    carry = q >= 8
+    e = np.where(carry, e + 1, e)
+    q = np.where(carry, 4, q).astype(np.int64)
+    sub = q < 4                                      # below the smallest normal 2^-14
+    code = np.where(sub, q, ((e + 15) << 2) | (q - 4))
     code = code | (neg.astype(np.int64) << 7)
     return code.astype(np.uint8)

@@ -21,7 +21,9 @@ def decode_activations(codes, dtype="bf16"):
         return formats.bf16_to_f32(codes).astype(np.float64)
     if dtype == "e4m3":
         return formats.e4m3_to_f32(codes).astype(np.float64)
-    raise ValueError("dtype must be 'bf16' or 'e4m3'")
+    if dtype == "e5m2":
+        return formats.e5m2_to_f32(codes).astype(np.float64)
+    raise ValueError("dtype must be 'bf16', 'e4m3' or 'e5m2'")
 
 
 def linear_fwd(x_codes, vals, meta, dtype="bf16", x_scale=1.0, w_scale=1.0):
@@ -52,13 +54,15 @@ def mvue_dense(dy_codes, seed, offset, dtype="bf16"):
     return projection.decode_packed(vals, meta, dtype).T            # (O, T) -> (T, O)
 
 
-def linear_wgrad(dy_codes, x_codes, seed, offset, dtype="bf16", dy_scale=1.0, x_scale=1.0):
-    """grad_W = scale * MVUE(dY^T) X in float64: (O, I).  scale = dy_scale * x_scale, times 2 for
-    e4m3 because the stored sparse operand holds theta / 2."""
+def linear_wgrad(dy_codes, x_codes, seed, offset, dtype="bf16", dy_scale=1.0, x_scale=1.0, x_dtype=None):
+    """grad_W = scale * MVUE(dY^T) X in float64: (O, I).  scale = dy_scale * x_scale, times 2 for the
+    8-bit formats because the stored sparse operand holds theta / 2.  `dtype` is the format of dY;
+    X has the same format unless x_dtype says otherwise (Sec. 5.2: e5m2 gradients against e4m3
+    activations)."""
     theta = mvue_dense(dy_codes, seed, offset, dtype)               # (T, O)
-    X = decode_activations(x_codes, dtype)
+    X = decode_activations(x_codes, x_dtype or dtype)
     scale = np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale))
-    if dtype == "e4m3":
+    if dtype in ("e4m3", "e5m2"):
         scale = scale * 2.0
     return (theta.T @ X) * scale
 
@@ -70,12 +74,12 @@ def linear_wgrad_dense(dy_codes, x_codes, dtype="bf16", dy_scale=1.0, x_scale=1.
     return (dY.T @ X) * (np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale)))
 
 
-def linear_dgrad(dy_codes, vals, meta, dtype="bf16", dy_scale=1.0, w_scale=1.0):
+def linear_dgrad(dy_codes, vals, meta, dtype="bf16", dy_scale=1.0, w_scale=1.0, w_dtype=None):
     """grad_X = (dy_scale * w_scale) * grad_Z . decode(vals, meta)   in float64 (Sec. 5.1: the input
-    gradient is the dense product with the projected weight; it is not sparsified).  dY: (T, O),
-    result (T, I)."""
+    gradient is the dense product with the projected weight; it is not sparsified).  dY: (T, O) in
+    `dtype`, the packed weight in w_dtype (default: the same), result (T, I)."""
     dY = decode_activations(dy_codes, dtype)
-    Wd = projection.decode_packed(vals, meta, dtype)                # (O, I)
+    Wd = projection.decode_packed(vals, meta, w_dtype or dtype)     # (O, I)
     return (dY @ Wd) * (np.float64(np.float32(dy_scale)) * np.float64(np.float32(w_scale)))
 
 

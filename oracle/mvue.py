@@ -41,6 +41,7 @@ steps 1-4, each rounded to float32; comparisons are exact.
   e4m3 storage: theta can reach twice the largest input, so the stored operand is theta/2
   (sign | RNE_e4m3(0.5*h), or sign | RNE_e4m3(0.5*m_p) where g_p itself is recorded) and the GEMM
   epilogue multiplies by 2.
+  e5m2 storage (the backward format of Sec. 5.2): the same with e5m2 codes and RNE_e5m2.
 
 Pinned (tests/test_oracle_mvue.py): worked groups, exactly-two-positions invariant, empirical
 inclusion frequencies against the closed-form pi, Monte-Carlo mean against g with the closed-
@@ -137,19 +138,20 @@ def mvue_sample(g, u):
 def mvue_groups_bits(g_codes, u, dtype="bf16"):
     """Bit-exact estimator on stored patterns.
 
-    g_codes : (n,4) uint16 bf16 patterns or uint8 e4m3 codes; u : (n,) float32 in [0,1).
+    g_codes : (n,4) uint16 bf16 patterns or uint8 e4m3 / e5m2 codes; u : (n,) float32 in [0,1).
     Returns (vals (n,2) patterns in ascending position order, nibble (n,) = pos0 | pos1 << 2).
-    For e4m3 the returned codes hold theta/2."""
+    For e4m3 and e5m2 the returned codes hold theta/2."""
     if dtype == "bf16":
         g_codes = np.asarray(g_codes, dtype=np.uint16).reshape(-1, 4)
         gf = formats.bf16_to_f32(g_codes)
         sign_mask = np.uint16(0x8000)
-    elif dtype == "e4m3":
+    elif dtype in ("e4m3", "e5m2"):
         g_codes = np.asarray(g_codes, dtype=np.uint8).reshape(-1, 4)
-        gf = formats.e4m3_to_f32(g_codes)
+        gf = formats.e4m3_to_f32(g_codes) if dtype == "e4m3" else formats.e5m2_to_f32(g_codes)
+        encode8 = formats.f32_to_e4m3_rne_sat if dtype == "e4m3" else formats.f32_to_e5m2_rne_sat
         sign_mask = np.uint8(0x80)
     else:
-        raise ValueError("dtype must be 'bf16' or 'e4m3'")
+        raise ValueError("dtype must be 'bf16', 'e4m3' or 'e5m2'")
     m = np.abs(gf).astype(np.float32)
     pos0, pos1, h = _select(m, np.asarray(u, dtype=np.float32), np.float32)
     n = m.shape[0]
@@ -157,7 +159,7 @@ def mvue_groups_bits(g_codes, u, dtype="bf16"):
     if dtype == "bf16":
         hq = formats.f32_to_bf16_rne(h)
     else:
-        hq = formats.f32_to_e4m3_rne_sat((np.float32(0.5) * h).astype(np.float32))
+        hq = encode8((np.float32(0.5) * h).astype(np.float32))
     out = []
     for pos in (pos0, pos1):
         code = g_codes[rows, pos]
@@ -166,7 +168,7 @@ def mvue_groups_bits(g_codes, u, dtype="bf16"):
         if dtype == "bf16":
             own = code
         else:
-            own = (code & sign_mask) | formats.f32_to_e4m3_rne_sat((np.float32(0.5) * mi).astype(np.float32))
+            own = (code & sign_mask) | encode8((np.float32(0.5) * mi).astype(np.float32))
         out.append(np.where((mi > h) | (mi == 0), own, common).astype(g_codes.dtype))
     vals = np.stack(out, axis=1)
     nib = (pos0 | (pos1 << 2)).astype(np.uint8)
@@ -181,7 +183,7 @@ def group_ids(T, O):
 def mvue_pack(dy_codes, seed, offset, dtype="bf16"):
     """MVUE(dY^T) in packed 2:4 form.
 
-    dy_codes : (T, O) stored patterns of the output gradient (bf16 uint16 / e4m3 uint8).
+    dy_codes : (T, O) stored patterns of the output gradient (bf16 uint16 / e4m3 or e5m2 uint8).
     Returns vals (O, T/2) and meta (O, T/8): row o holds, for token groups k = 0.. in order, the two
     recorded values and the nibble pos0 | pos1 << 2 (even k in the low nibble of byte k // 2)."""
     dy_codes = np.asarray(dy_codes)

@@ -228,7 +228,7 @@ def decode_packed(vals, meta, val_dtype="bf16"):
     """Packed (vals, meta) -> dense-with-zeros float64 (O, I) holding the exact stored values."""
     idx0, idx1 = kept_positions(meta)
     O, G = idx0.shape
-    v = formats.bf16_to_f32(vals) if val_dtype == "bf16" else formats.e4m3_to_f32(vals)
+    v = {"bf16": formats.bf16_to_f32, "e4m3": formats.e4m3_to_f32, "e5m2": formats.e5m2_to_f32}[val_dtype](vals)
     v = v.astype(np.float64).reshape(O, G, 2)
     dense = np.zeros((O, G, 4), dtype=np.float64)
     r, g = np.meshgrid(np.arange(O), np.arange(G), indexing="ij")
@@ -241,7 +241,7 @@ def decode_packed(vals, meta, val_dtype="bf16"):
 # --------------------------------------------------------------------------- device layout
 
 def k_step(val_dtype):
-    """Dense columns covered by one sparse matrix instruction step: 64 (bf16) / 128 (e4m3)."""
+    """Dense columns covered by one sparse matrix instruction step: 64 (bf16) / 128 (e4m3, e5m2)."""
     return 64 if val_dtype == "bf16" else 128
 
 

@@ -69,3 +69,43 @@ def test_e4m3_encode_matches_torch_cast_in_range():
     x = np.clip(x, -448, 448)
     ref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
     assert np.array_equal(ref, F.f32_to_e4m3_rne_sat(x))
+
+
+def test_e5m2_decode_table_by_definition():
+    assert F.e5m2_to_f32(np.array([0x3C], dtype=np.uint8))[0] == 1.0          # e=15,m=0
+    assert F.e5m2_to_f32(np.array([0x7B], dtype=np.uint8))[0] == 57344.0      # e=30,m=3
+    assert F.e5m2_to_f32(np.array([0x01], dtype=np.uint8))[0] == 2.0 ** -16   # smallest subnormal
+    assert F.e5m2_to_f32(np.array([0x04], dtype=np.uint8))[0] == 2.0 ** -14   # smallest normal
+    assert F.e5m2_to_f32(np.array([0xC2], dtype=np.uint8))[0] == -3.0
+    assert np.isinf(F.e5m2_to_f32(np.array([0x7C], dtype=np.uint8))[0])
+    assert np.isnan(F.e5m2_to_f32(np.array([0x7D], dtype=np.uint8))[0])
+    allc = np.arange(256, dtype=np.uint8)
+    # e5m2 is the top byte of an IEEE half: decode through numpy's float16 and through PyTorch's type
+    half = (allc.astype(np.uint16) << 8).view(np.float16).astype(np.float32)
+    ref = torch.from_numpy(allc.copy()).view(torch.float8_e5m2).float().numpy()
+    got = F.e5m2_to_f32(allc)
+    for r in (half, ref):
+        assert np.array_equal(np.isnan(r), np.isnan(got))
+        ok = ~np.isnan(r)
+        assert np.array_equal(r[ok], got[ok])
+
+
+def test_e5m2_encode_roundtrip_and_ties():
+    allc = np.array([c for c in range(256) if (c & 0x7C) != 0x7C], dtype=np.uint8)
+    assert np.array_equal(F.f32_to_e5m2_rne_sat(F.e5m2_to_f32(allc)), allc)
+    # 1.125 is halfway between 1.0 (m=0, even) and 1.25 (m=1): ties to even -> 1.0
+    assert F.f32_to_e5m2_rne_sat(np.array([1.125], dtype=np.float32))[0] == 0x3C
+    # 1.375 halfway between 1.25 (odd) and 1.5 (even) -> 1.5
+    assert F.f32_to_e5m2_rne_sat(np.array([1.375], dtype=np.float32))[0] == 0x3E
+    # saturation (never infinity), and subnormal rounding: 2^-17 is half the smallest subnormal -> 0
+    assert F.f32_to_e5m2_rne_sat(np.array([1e9, -1e9, 2.0 ** -17, 3 * 2.0 ** -17], dtype=np.float32)).tolist() == [0x7B, 0xFB, 0x00, 0x02]
+    # carry into the next binade: 1.9375 -> 2.0
+    assert F.f32_to_e5m2_rne_sat(np.array([1.9375], dtype=np.float32))[0] == 0x40
+
+
+def test_e5m2_encode_matches_torch_cast_in_range():
+    rng = np.random.default_rng(1)
+    x = (rng.standard_normal(300000) * np.exp(rng.uniform(-14, 9, 300000))).astype(np.float32)
+    x = np.clip(x, -57344, 57344)
+    ref = torch.from_numpy(x).to(torch.float8_e5m2).view(torch.uint8).numpy()
+    assert np.array_equal(ref, F.f32_to_e5m2_rne_sat(x))

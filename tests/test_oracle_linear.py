@@ -133,3 +133,26 @@ def test_dgrad_is_the_adjoint_of_the_forward_product():
         lhs = np.sum(Lin.decode_activations(dy, dtype) * Z)
         rhs = np.sum(dX * Lin.decode_activations(x, dtype))
         assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), abs(rhs))
+
+
+def test_e5m2_gradients_against_e4m3_operands():
+    """Sec. 5.2's backward formats: e5m2 output gradients with e4m3 activations / weights.  The weight
+    gradient is the loop product of the decoded half-theta operand, doubled; its mean over seeds
+    approaches the dense product; the input gradient equals the loop product on the decoded operands."""
+    rng = np.random.default_rng(31)
+    T, O, I = 16, 8, 16
+    dy = F.f32_to_e5m2_rne_sat((rng.standard_normal((T, O)) * 3000).astype(np.float32))
+    x = F.f32_to_e4m3_rne_sat((rng.standard_normal((T, I)) * 60).astype(np.float32))
+    dW = Lin.linear_wgrad(dy, x, 2, 3, "e5m2", dy_scale=0.5, x_scale=0.25, x_dtype="e4m3")
+    vals, meta = M.mvue_pack(dy, 2, 3, "e5m2")
+    half_theta = P.decode_packed(vals, meta, "e5m2")                       # (O, T)
+    want = Lin.linear_fwd_loops(F.e4m3_to_f32(x).astype(np.float64).T, half_theta).T * 2 * 0.5 * 0.25
+    assert np.allclose(dW, want, rtol=1e-12, atol=0)
+    mean = sum(Lin.linear_wgrad(dy, x, s, 0, "e5m2", x_dtype="e4m3") for s in range(3000)) / 3000
+    dense = F.e5m2_to_f32(dy).astype(np.float64).T @ F.e4m3_to_f32(x).astype(np.float64)
+    assert np.max(np.abs(mean - dense)) <= 0.08 * np.max(np.abs(dense))
+    wb = F.f32_to_bf16_rne((rng.standard_normal((O, I)) * 0.02).astype(np.float32)).reshape(O, I)
+    wv, wm, _ = P.project_pack(wb, 1.5, "e4m3", np.float32(0.0002))
+    dX = Lin.linear_dgrad(dy, wv, wm, "e5m2", dy_scale=0.5, w_scale=0.0002, w_dtype="e4m3")
+    want = Lin.linear_dgrad_loops(F.e5m2_to_f32(dy).astype(np.float64), P.decode_packed(wv, wm, "e4m3")) * (0.5 * np.float64(np.float32(0.0002)))
+    assert np.allclose(dX, want, rtol=1e-12, atol=0)

@@ -182,6 +182,40 @@ def test_e4m3_bitspec_stores_half_theta():
     assert np.all(np.abs(F.e4m3_to_f32(vals)) <= 448)
 
 
+def test_e5m2_bitspec_stores_half_theta_and_is_unbiased():
+    """The e5m2 storage (two mantissa bits) follows the float64 estimator to within its own rounding,
+    stays finite at the top of the range, and its mean over many draws converges to the stored gradient
+    (rounding of h to e5m2 is the only source of bias: below 2^-3 relative)."""
+    rng = np.random.default_rng(15)
+    x = (rng.standard_normal((4000, 4)) * 12000).astype(np.float32)
+    codes = F.f32_to_e5m2_rne_sat(np.clip(x, -57344, 57344))
+    codes[0] = [0x7B, 0xFB, 0x7B, 0x7B]                                # four elements at the largest magnitude
+    u = R.uniform24(2, 1, np.arange(4000))
+    vals, nib = M.mvue_groups_bits(codes, u, "e5m2")
+    g = F.e5m2_to_f32(codes).astype(np.float64)
+    theta, pos = M.mvue_sample(g, u.astype(np.float64))
+    same = ((nib & 3) == pos[:, 0]) & ((nib >> 2) == pos[:, 1])
+    assert same.mean() > 0.999
+    rows = np.arange(4000)[same]
+    for k in range(2):
+        got = 2.0 * F.e5m2_to_f32(vals[same, k]).astype(np.float64)
+        want = theta[rows, pos[same, k]]
+        assert np.all(np.abs(got - want) <= np.maximum(np.abs(want) * 2.0 ** -3, 2.0 ** -16))
+    assert np.all(np.isfinite(F.e5m2_to_f32(vals))) and np.all(np.abs(F.e5m2_to_f32(vals)) <= 57344)
+    # unbiasedness on one group whose h = (1.5 + 1 + 0.75 + 0.5) / 2 = 1.875 rounds to 2 in e5m2 after halving
+    # (0.9375 -> 1.0), and on one whose h is exactly representable
+    for grp, tol in (([1.5, -1.0, 0.75, 0.5], 0.08), ([2.0, -1.0, 0.5, 0.5], 0.02)):
+        c = F.f32_to_e5m2_rne_sat(np.array([grp], dtype=np.float32))
+        n = 40000
+        uu = R.uniform24(9, 9, np.arange(n))
+        v, nb = M.mvue_groups_bits(np.repeat(c, n, axis=0), uu, "e5m2")
+        dense = np.zeros((n, 4))
+        r = np.arange(n)
+        dense[r, nb & 3] = 2.0 * F.e5m2_to_f32(v[:, 0])
+        dense[r, nb >> 2] = 2.0 * F.e5m2_to_f32(v[:, 1])
+        assert np.all(np.abs(dense.mean(axis=0) - np.array(grp)) <= tol * np.abs(np.array(grp)) + 0.02)
+
+
 def test_pack_layout_and_group_ids():
     rng = np.random.default_rng(6)
     T, O = 32, 8
