@@ -62,7 +62,12 @@ typedef enum {
 typedef enum {
   SSTE_BF16 = 0,   /* bfloat16 */
   SSTE_F8E4M3 = 1, /* OCP FP8 e4m3fn: bias 7, max 448, no infinity */
-  SSTE_F32 = 2     /* float32: accepted only where an argument's description says so */
+  SSTE_F32 = 2,    /* float32: accepted only where an argument's description says so */
+  SSTE_F8E5M2 = 3  /* OCP FP8 e5m2 output gradients (the backward format of Sec. 5.2), accepted as `dtype` by
+                      sste_linear_wgrad, sste_linear_dgrad and sste_mvue_materialize only: dY (and the
+                      sparsified operand made from it) is e5m2, bias 15, max 57344, inputs finite; the
+                      other operand of the call (X, or the packed weight) is SSTE_F8E4M3.  Sizes and
+                      alignment follow SSTE_F8E4M3. */
 } sste_dtype;
 
 /*

@@ -9,6 +9,7 @@ cannot be loaded.
 from .binding import (  # noqa: F401
     BF16,
     F8E4M3,
+    F8E5M2,
     F32,
     PackBatch,
     SsteError,

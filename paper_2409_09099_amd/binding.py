@@ -8,6 +8,7 @@ import torch
 BF16 = 0
 F8E4M3 = 1
 F32 = 2
+F8E5M2 = 3         # e5m2 output gradients against e4m3 operands: backward calls only
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsste.so")
@@ -92,14 +93,14 @@ def _matrix(t: torch.Tensor, itemsize: int, name: str) -> Tuple[int, int, int]:
 
 
 def _esize(dtype: int) -> int:
-    return 1 if dtype == F8E4M3 else 2
+    return 1 if dtype in (F8E4M3, F8E5M2) else 2
 
 
 def packed_buffers(R: int, K: int, dtype: int, device):
     """Uninitialised device buffers for a packed 2:4 operand with R rows and K dense columns: the blocked
     layout pads the rows to a multiple of 16."""
     rows = (R + 15) // 16 * 16
-    vals = torch.empty((rows, K // 2), dtype=torch.uint8 if dtype == F8E4M3 else torch.int16, device=device)
+    vals = torch.empty((rows, K // 2), dtype=torch.uint8 if dtype in (F8E4M3, F8E5M2) else torch.int16, device=device)
     meta = torch.empty((rows, K // 8), dtype=torch.uint8, device=device)
     return vals, meta
 

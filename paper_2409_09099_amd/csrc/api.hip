@@ -57,7 +57,10 @@ RngKey derive_key(uint64_t seed, uint64_t offset) {
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static bool good_scale(float v) { return std::isfinite(v) && v > 0.0f; }
 static bool good_dtype(int d) { return d == SSTE_BF16 || d == SSTE_F8E4M3; }
-static int elems_per_16B(int d) { return d == SSTE_F8E4M3 ? 16 : 8; }
+// the backward calls also take e5m2 output gradients (against e4m3 activations / weights)
+static bool good_grad_dtype(int d) { return good_dtype(d) || d == SSTE_F8E5M2; }
+static bool is_8bit(int d) { return d == SSTE_F8E4M3 || d == SSTE_F8E5M2; }
+static int elems_per_16B(int d) { return is_8bit(d) ? 16 : 8; }
 
 static int hip_status(hipError_t e, const char* what) {
   if (e == hipSuccess) return SSTE_OK;
@@ -329,9 +332,9 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
 
 static int wgrad_shape_check(int64_t T, int64_t O, int64_t I, int dtype, const char* who) {
   if (T < 0 || O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "%s: negative size", who);
-  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "%s: unknown dtype %d", who, dtype);
+  if (!good_grad_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "%s: unknown dtype %d", who, dtype);
   if (T % 4 != 0) return fail(SSTE_ERR_SHAPE, "%s: T=%lld is not a multiple of 4 (groups of four tokens)", who, (long long)T);
-  int kmult = dtype == SSTE_F8E4M3 ? 128 : 64, nmult = elems_per_16B(dtype);
+  int kmult = is_8bit(dtype) ? 128 : 64, nmult = elems_per_16B(dtype);
   if (T % kmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "%s: T=%lld must be a multiple of %d for this element type", who, (long long)T, kmult);
   if (O % nmult != 0 || I % nmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "%s: O and I must be multiples of %d", who, nmult);
   return SSTE_OK;
@@ -346,10 +349,10 @@ int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
                       const void* meta, int64_t I, float w_scale, void* dX, int64_t lddx, void* hip_stream) {
   clear_error();
   if (T < 0 || I < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "linear_dgrad: negative size");
-  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_dgrad: unknown dtype %d", dtype);
+  if (!good_grad_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_dgrad: unknown dtype %d", dtype);
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_dgrad: I=%lld is not a multiple of 8", (long long)I);
   if (!good_scale(dy_scale) || !good_scale(w_scale)) return fail(SSTE_ERR_VALUE, "linear_dgrad: scales must be finite and > 0");
-  const int ks = dtype == SSTE_F8E4M3 ? 128 : 64, e16 = elems_per_16B(dtype);
+  const int ks = is_8bit(dtype) ? 128 : 64, e16 = elems_per_16B(dtype);
   if (I % ks != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: I=%lld must be a multiple of %d", (long long)I, ks);
   if (O % e16 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: O=%lld must be a multiple of %d", (long long)O, e16);
   if (lddy < O || lddx < I) return fail(SSTE_ERR_SHAPE, "linear_dgrad: leading dimension smaller than the row length");
@@ -385,7 +388,7 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
     if (!aligned16(workspace)) return fail(SSTE_ERR_ALIGN, "linear_wgrad: workspace must be 16-byte aligned");
   }
   float scale = dy_scale * x_scale;
-  if (dtype == SSTE_F8E4M3) scale *= 2.0f;      // the sparsified e4m3 operand is stored halved
+  if (is_8bit(dtype)) scale *= 2.0f;            // the sparsified 8-bit operand is stored halved
   return hip_status(launch_linear_wgrad(dY, T, O, lddy, dtype, X, I, ldx, scale, derive_key(seed, offset), dW, lddw, accumulate,
                                         workspace, (hipStream_t)hip_stream),
                     "linear_wgrad launch");
@@ -395,10 +398,10 @@ int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, in
                           void* vals, void* meta, void* hip_stream) {
   clear_error();
   if (T < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: negative size");
-  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "mvue_materialize: unknown dtype %d", dtype);
+  if (!good_grad_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "mvue_materialize: unknown dtype %d", dtype);
   if (T % 4 != 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: T=%lld is not a multiple of 4 (groups of four tokens)", (long long)T);
-  if (T % (dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
-    return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld must be a multiple of %d for this element type", (long long)T, dtype == SSTE_F8E4M3 ? 128 : 64);
+  if (T % (is_8bit(dtype) ? 128 : 64) != 0)
+    return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld must be a multiple of %d for this element type", (long long)T, is_8bit(dtype) ? 128 : 64);
   if (lddy < O) return fail(SSTE_ERR_SHAPE, "mvue_materialize: lddy < O");
   bool empty = (T == 0 || O == 0);
   if (!empty && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "mvue_materialize: NULL dY, vals or meta");

@@ -61,7 +61,7 @@ constexpr int dgrad_smem() {
 }
 
 // One tile: features [256 tm, 256 tm + 256) x tokens [t0, t0 + 64 NI_), by a 512-thread workgroup.
-template <bool FP8, int NI_>
+template <bool FP8, int NI_, bool BF8>
 __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restrict__ dY, int64_t T, int64_t O,
                                            int64_t lddy_bytes, const uint8_t* __restrict__ vals,
                                            const uint8_t* __restrict__ meta, int64_t I, int isteps, float scale,
@@ -267,7 +267,8 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
           i32x8 av, bv;                                                                                   \
           __builtin_memcpy(&av, &fa[mi & (AB - 1)][0], 32);                                               \
           __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
-          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[mi][ni], 0, 0, 0, 0, 0, 0); \
+          /* format arguments: A (expanded weight) e4m3; B (grad_Z) e4m3, or e5m2 when BF8              */ \
+          acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[mi][ni], 0, BF8 ? 1 : 0, 0, 0, 0, 0); \
         } else {                                                                                          \
           bf16x8 av0, av1, bv0, bv1;                                                                      \
           __builtin_memcpy(&av0, &fa[mi & (AB - 1)][0], 16);                                              \
@@ -338,7 +339,7 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
   }
 }
 
-template <bool FP8, int NI_>
+template <bool FP8, int NI_, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
@@ -346,12 +347,12 @@ k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t ldd
   __shared__ __align__(1024) uint8_t smem[dgrad_smem<FP8, NI_>()];
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tm = logical % m_tiles, tn = logical / m_tiles;
-  dgrad_tile<FP8, NI_>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tm, (int64_t)tn * (64 * NI_));
+  dgrad_tile<FP8, NI_, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tm, (int64_t)tn * (64 * NI_));
 }
 
 // Whole rounds of 256 x 256 tiles (workgroups 0 .. n_big - 1), then the tiles of the last, partial round
 // as twice as many 256 x 128 tiles, so that the round takes half a tile time on twice the CUs.
-template <bool FP8>
+template <bool FP8, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad_dual(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                     const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
@@ -360,19 +361,19 @@ k_linear_dgrad_dual(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_
   const int bid = blockIdx.x;
   if (bid < n_big) {
     const int logical = xcd_contiguous(bid, n_big);
-    dgrad_tile<FP8, 4>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, logical % m_tiles,
+    dgrad_tile<FP8, 4, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, logical % m_tiles,
                        (int64_t)(logical / m_tiles) * 256);
   } else {
     const int h = xcd_contiguous(bid - n_big, (int)gridDim.x - n_big);      // half-tile number
     const int tile = n_big + (h >> 1);
     const int64_t t0 = (int64_t)(tile / m_tiles) * 256 + 128 * (h & 1);
     if (t0 >= T) return;                       // second half of a ragged last token tile: nothing to do
-    dgrad_tile<FP8, 2>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tile % m_tiles, t0);
+    dgrad_tile<FP8, 2, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tile % m_tiles, t0);
   }
 }
 
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype) {
-  const int eb = dtype == SSTE_F8E4M3 ? 1 : 2;
+  const int eb = dtype != SSTE_BF16 ? 1 : 2;
   if (256 * lddy * eb >= (1ll << 30)) return false;                       // 32-bit offsets inside a grad_Z tile
   if (((O + 15) / 16 * 16) * I >= (1ll << 31)) return false;              // packed operand addressed with 32-bit offsets
   if (((I + 255) / 256) * ((T + 127) / 128) > 0x7FFFFFFFll) return false;
@@ -382,7 +383,7 @@ bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int d
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
                                const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s) {
   if (T == 0 || I == 0) return hipSuccess;
-  const bool fp8 = dtype == SSTE_F8E4M3;
+  const bool fp8 = dtype != SSTE_BF16, bf8 = dtype == SSTE_F8E5M2;
   int m_tiles = (int)((I + 255) / 256);
   // 256 x 256 tiles unless they leave a quarter or more of the CUs without work in the only round
   int64_t big = (int64_t)m_tiles * ((T + 255) / 256);
@@ -395,24 +396,27 @@ hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
   if (big > 256 && rem > 0 && rem <= 128) {
     int n_big = (int)(big - rem);
     dim3 grid((unsigned)(n_big + 2 * rem)), block(512);
-    if (fp8)
-      SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<true>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,
-                  (uint16_t*)dX, lddx, m_tiles, n_big);
-    else
-      SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<false>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,
-                  (uint16_t*)dX, lddx, m_tiles, n_big);
+#define DG_DUAL(F8, B8)                                                                                                \
+  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<F8, B8>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale, \
+              (uint16_t*)dX, lddx, m_tiles, n_big)
+    if (bf8) DG_DUAL(true, true);
+    else if (fp8) DG_DUAL(true, false);
+    else DG_DUAL(false, false);
+#undef DG_DUAL
     return hipGetLastError();
   }
   bool half = big < 192;
   int n_tiles = (int)((T + (half ? 127 : 255)) / (half ? 128 : 256));
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
-#define DG_CASE(F8, NI)                                                                                                \
-  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale,  \
+#define DG_CASE(F8, NI, B8)                                                                                            \
+  SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI, B8>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale, \
               (uint16_t*)dX, lddx, m_tiles)
-  if (fp8 && half) DG_CASE(true, 2);
-  else if (fp8) DG_CASE(true, 4);
-  else if (half) DG_CASE(false, 2);
-  else DG_CASE(false, 4);
+  if (bf8 && half) DG_CASE(true, 2, true);
+  else if (bf8) DG_CASE(true, 4, true);
+  else if (fp8 && half) DG_CASE(true, 2, false);
+  else if (fp8) DG_CASE(true, 4, false);
+  else if (half) DG_CASE(false, 2, false);
+  else DG_CASE(false, 4, false);
 #undef DG_CASE
   return hipGetLastError();
 }

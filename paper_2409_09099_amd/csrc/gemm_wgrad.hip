@@ -36,7 +36,7 @@ __device__ __forceinline__ uint32_t comp4(const uint4& v, int c) { return c == 0
 
 // ---------------------------------------------------------------------------------------------------------
 // 1. estimator -> packed operand.  One workgroup: one k-step (64 / 128 tokens) x 128 channels.
-template <bool FP8>
+template <bool FP8, bool BF8>
 __global__ void __launch_bounds__(256)
 k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes, RngKey key,
             uint8_t* __restrict__ vals, uint8_t* __restrict__ meta) {
@@ -89,7 +89,7 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
       const uint32_t bsel = (uint32_t)(e & 3) | ((uint32_t)(4 + (e & 3)) << 8) | 0x0c0c0000u;
       uint32_t t01 = __builtin_amdgcn_perm(w1, w0, bsel), t23 = __builtin_amdgcn_perm(w3, w2, bsel);
       uint32_t gw = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
-      v = mvue_group_e4m3(gw, x, nib);
+      v = mvue_group_f8<BF8>(gw, x, nib);
       *(uint16_t*)(slot + 2 * g) = (uint16_t)v;
     } else {
       uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
@@ -126,16 +126,22 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
 
 static void launch_mvue_pack(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key, void* vals,
                              void* meta, hipStream_t s, int timed_kind) {
-  bool fp8 = dtype == SSTE_F8E4M3;
+  bool fp8 = dtype != SSTE_BF16;
   int ks = fp8 ? 128 : 64;
   dim3 grid((unsigned)((O + 127) / 128), (unsigned)(T / ks)), block(256);
-  if (fp8) {
-    if (timed_kind >= 0) SSTE_LAUNCH(timed_kind, (k_mvue_pack<true>), grid, block, s, (const uint8_t*)dY, T, O, lddy, key, (uint8_t*)vals, (uint8_t*)meta);
-    else hipLaunchKernelGGL((k_mvue_pack<true>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy, key, (uint8_t*)vals, (uint8_t*)meta);
-  } else {
-    if (timed_kind >= 0) SSTE_LAUNCH(timed_kind, (k_mvue_pack<false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * 2, key, (uint8_t*)vals, (uint8_t*)meta);
-    else hipLaunchKernelGGL((k_mvue_pack<false>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy * 2, key, (uint8_t*)vals, (uint8_t*)meta);
-  }
+#define MP_CASE(F8, B8)                                                                                                  \
+  do {                                                                                                                   \
+    if (timed_kind >= 0)                                                                                                 \
+      SSTE_LAUNCH(timed_kind, (k_mvue_pack<F8, B8>), grid, block, s, (const uint8_t*)dY, T, O, lddy*(F8 ? 1 : 2), key,   \
+                  (uint8_t*)vals, (uint8_t*)meta);                                                                       \
+    else                                                                                                                 \
+      hipLaunchKernelGGL((k_mvue_pack<F8, B8>), grid, block, 0, s, (const uint8_t*)dY, T, O, lddy*(F8 ? 1 : 2), key,     \
+                         (uint8_t*)vals, (uint8_t*)meta);                                                                \
+  } while (0)
+  if (dtype == SSTE_F8E5M2) MP_CASE(true, true);
+  else if (fp8) MP_CASE(true, false);
+  else MP_CASE(false, false);
+#undef MP_CASE
 }
 
 hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,
@@ -156,7 +162,7 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 // (fp8) of token row r is stored at position p ^ (r % 16): the transposing reads below, which gather
 // 4 (8) token rows x 16 features per 16 lanes, then hit distinct banks.
 
-template <bool FP8, int MI_, int NI_>
+template <bool FP8, int MI_, int NI_, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t O, int64_t total_steps,
              const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, int steps_per_split, float scale,
@@ -322,7 +328,9 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
           i32x8 bv;                                                                                       \
           __builtin_memcpy(&av, &fa[mi & 1], 16);                                                         \
           __builtin_memcpy(&bv, &BC[ni][0], 32);                                                          \
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+          /* e5m2 sparsified gradient (packed operand) against e4m3 activations, or both e4m3 */          \
+          if (BF8) acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_bf8_fp8(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
+          else acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi & 1], 0, 0); \
         } else {                                                                                          \
           bf16x8 av;                                                                                      \
           bf16x16 bv;                                                                                     \
@@ -437,7 +445,7 @@ static double wgrad_model_us(int64_t O, int64_t I, int64_t steps, int mi, int ni
 
 static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   WgradPlan p{};
-  bool fp8 = dtype == SSTE_F8E4M3;
+  bool fp8 = dtype != SSTE_BF16;
   int ks = fp8 ? 128 : 64;
   int64_t steps = T / ks;
   // the pre-pass pays off once the GEMM tiles would re-derive each group several times and the problem
@@ -485,29 +493,32 @@ static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   return p;
 }
 
-template <bool FP8, int MI_, int NI_>
+template <bool FP8, int MI_, int NI_, bool BF8>
 static void launch_wgrad_gemm_cfg(const void* vals, const void* meta, int64_t O, int64_t steps, const void* X, int64_t I,
                                   int64_t ldx_bytes, int splits, int steps_per_split, float scale, int accumulate,
                                   float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
   int m_tiles = (int)((O + 32 * MI_ - 1) / (32 * MI_)), n_tiles = (int)((I + 64 * NI_ - 1) / (64 * NI_));
   dim3 grid((unsigned)(m_tiles * n_tiles * splits)), block(512);
-  SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<FP8, MI_, NI_>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
+  SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<FP8, MI_, NI_, BF8>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
               (const uint8_t*)X, I, ldx_bytes, steps_per_split, scale, accumulate, out, ld_out, split_stride, m_tiles, n_tiles);
 }
 
-static void launch_wgrad_gemm(bool fp8, int mi, int ni, const void* vals, const void* meta, int64_t O, int64_t steps,
+static void launch_wgrad_gemm(bool fp8, bool bf8, int mi, int ni, const void* vals, const void* meta, int64_t O, int64_t steps,
                               const void* X, int64_t I, int64_t ldx_bytes, int splits, int steps_per_split, float scale,
                               int accumulate, float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
-#define WG_CASE(F, M, N)                                                                                       \
-  if (fp8 == F && mi == M && ni == N)                                                                          \
-    return launch_wgrad_gemm_cfg<F, M, N>(vals, meta, O, steps, X, I, ldx_bytes, splits, steps_per_split, scale, \
-                                          accumulate, out, ld_out, split_stride, s)
-  WG_CASE(false, 8, 4);
-  WG_CASE(false, 6, 3);
-  WG_CASE(false, 8, 3);
-  WG_CASE(true, 8, 4);
-  WG_CASE(true, 6, 3);
-  WG_CASE(true, 8, 3);
+#define WG_CASE(F, M, N, B)                                                                                    \
+  if (fp8 == F && bf8 == B && mi == M && ni == N)                                                              \
+    return launch_wgrad_gemm_cfg<F, M, N, B>(vals, meta, O, steps, X, I, ldx_bytes, splits, steps_per_split, scale, \
+                                             accumulate, out, ld_out, split_stride, s)
+  WG_CASE(false, 8, 4, false);
+  WG_CASE(false, 6, 3, false);
+  WG_CASE(false, 8, 3, false);
+  WG_CASE(true, 8, 4, false);
+  WG_CASE(true, 6, 3, false);
+  WG_CASE(true, 8, 3, false);
+  WG_CASE(true, 8, 4, true);
+  WG_CASE(true, 6, 3, true);
+  WG_CASE(true, 8, 3, true);
 #undef WG_CASE
 }
 
@@ -517,7 +528,7 @@ size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
 }
 
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype) {
-  int64_t eb = dtype == SSTE_F8E4M3 ? 1 : 2;
+  int64_t eb = dtype != SSTE_BF16 ? 1 : 2;
   if (T * ldx * eb >= (1ll << 31)) return wgrad_plan(T, O, I, dtype).packed ? false : true;   // 32-bit offsets in the GEMM
   if (((O + 127) / 128) * ((I + 127) / 128) * 32 > 0x7FFFFFFFll) return false;
   return true;
@@ -527,7 +538,7 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
                                int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,
                                int accumulate, void* ws, hipStream_t s) {
   if (O == 0 || I == 0) return hipSuccess;
-  bool fp8 = dtype == SSTE_F8E4M3;
+  bool fp8 = dtype != SSTE_BF16;
   int ks = fp8 ? 128 : 64, eb = fp8 ? 1 : 2;
   int64_t steps = T / ks;
   if (steps == 0) {
@@ -550,7 +561,7 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
     uint8_t* vals = wsb;
     uint8_t* meta = wsb + p.vals_bytes;
     launch_mvue_pack(dY, T, O, lddy, dtype, key, vals, meta, s, SSTE_K_MVUE_PACK);
-    launch_wgrad_gemm(fp8, p.mi, p.ni, vals, meta, O, steps, X, I, ldx * eb, p.splits, p.steps_per_split, k_scale, k_acc, out,
+    launch_wgrad_gemm(fp8, dtype == SSTE_F8E5M2, p.mi, p.ni, vals, meta, O, steps, X, I, ldx * eb, p.splits, p.steps_per_split, k_scale, k_acc, out,
                       ld_out, split_stride, s);
   } else {
     hipError_t e = launch_wgrad_fused(dY, T, O, lddy, dtype, X, I, ldx, key, p.splits, p.steps_per_split, k_scale, k_acc,

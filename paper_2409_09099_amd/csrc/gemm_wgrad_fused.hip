@@ -30,7 +30,7 @@ typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
 }  // namespace
 
-template <bool FP8>
+template <bool FP8, bool BF8>
 __global__ void __launch_bounds__(256)
 k_linear_wgrad_fused(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, RngKey key,
@@ -110,7 +110,7 @@ k_linear_wgrad_fused(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64
         uint32_t w2 = comp(rdy[2], e >> 2), w3 = comp(rdy[3], e >> 2);                        \
         int sh = 8 * (e & 3);                                                                 \
         uint32_t g = ((w0 >> sh) & 0xFFu) | (((w1 >> sh) & 0xFFu) << 8) | (((w2 >> sh) & 0xFFu) << 16) | (((w3 >> sh) & 0xFFu) << 24); \
-        v = mvue_group_e4m3(g, x, nib);                                                       \
+        v = mvue_group_f8<BF8>(g, x, nib);                                                      \
         *(uint16_t*)(sA + row * A_STRIDE + 2 * kg) = (uint16_t)v;                             \
       } else {                                                                                \
         uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;                                   \
@@ -181,7 +181,8 @@ k_linear_wgrad_fused(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64
           i32x8 bv;
           __builtin_memcpy(&av, &fa[mi], 16);
           __builtin_memcpy(&bv, &piece[0], 32);
-          acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
+          if (BF8) acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_bf8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
+          else acc[mi][ni] = __builtin_amdgcn_smfmac_f32_16x16x128_fp8_fp8(av, bv, acc[mi][ni], fidx[mi], 0, 0);
         } else {
           bf16x8 av;
           bf16x16 bv;
@@ -222,14 +223,17 @@ k_linear_wgrad_fused(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64
 hipError_t launch_wgrad_fused(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X, int64_t I,
                               int64_t ldx, RngKey key, int splits, int steps_per_split, float scale, int accumulate,
                               float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
-  bool fp8 = dtype == SSTE_F8E4M3;
+  bool fp8 = dtype != SSTE_BF16, bf8 = dtype == SSTE_F8E5M2;
   int eb = fp8 ? 1 : 2;
   dim3 grid((unsigned)((O + BM - 1) / BM), (unsigned)((I + BN - 1) / BN), (unsigned)splits), block(256);
-  if (fp8)
-    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad_fused<true>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
+  if (bf8)
+    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad_fused<true, true>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
+                ldx * eb, key, steps_per_split, scale, accumulate, out, ld_out, split_stride);
+  else if (fp8)
+    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad_fused<true, false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
                 ldx * eb, key, steps_per_split, scale, accumulate, out, ld_out, split_stride);
   else
-    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad_fused<false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
+    SSTE_LAUNCH(SSTE_K_WGRAD, (k_linear_wgrad_fused<false, false>), grid, block, s, (const uint8_t*)dY, T, O, lddy * eb, (const uint8_t*)X, I,
                 ldx * eb, key, steps_per_split, scale, accumulate, out, ld_out, split_stride);
   return hipGetLastError();
 }

@@ -85,25 +85,39 @@ __device__ __forceinline__ uint32_t mvue_group_bf16(uint32_t lo, uint32_t hi, ui
   return out;
 }
 
-// e4m3 group: the four codes of one group in one dword (g0 in byte 0).  Returns the two recorded
-// codes of theta / 2 in the low 16 bits (pos0's in byte 0).
-__device__ __forceinline__ uint32_t mvue_group_e4m3(uint32_t g, uint32_t x, uint32_t& nib) {
+// 8-bit group (e4m3, or e5m2 when BF8): the four codes of one group in one dword (g0 in byte 0).
+// Returns the two recorded codes of theta / 2 in the low 16 bits (pos0's in byte 0).
+template <bool BF8>
+__device__ __forceinline__ float cvt8(uint32_t w) {
+  return BF8 ? __builtin_amdgcn_cvt_f32_bf8((int)w, 0) : __builtin_amdgcn_cvt_f32_fp8((int)w, 0);
+}
+template <bool BF8>
+__device__ __forceinline__ uint32_t mvue_group_f8(uint32_t g, uint32_t x, uint32_t& nib) {
   uint32_t ga = g & 0x7F7F7F7Fu;
-  float m0 = __builtin_amdgcn_cvt_f32_fp8(ga, 0), m1 = __builtin_amdgcn_cvt_f32_fp8(ga, 1);
-  float m2 = __builtin_amdgcn_cvt_f32_fp8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_fp8(ga, 3);
+  float m0, m1, m2, m3;
+  if (BF8) {
+    m0 = __builtin_amdgcn_cvt_f32_bf8(ga, 0), m1 = __builtin_amdgcn_cvt_f32_bf8(ga, 1);
+    m2 = __builtin_amdgcn_cvt_f32_bf8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_bf8(ga, 3);
+  } else {
+    m0 = __builtin_amdgcn_cvt_f32_fp8(ga, 0), m1 = __builtin_amdgcn_cvt_f32_fp8(ga, 1);
+    m2 = __builtin_amdgcn_cvt_f32_fp8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_fp8(ga, 3);
+  }
   Sel s = mvue_select(m0, m1, m2, m3, x);
   // recorded elements: shift their code down to byte 0 (the conversion reads byte 0 only)
   uint32_t sh0 = s.pos0 << 3, sh1 = s.pos1 << 3;
-  float mp0 = __builtin_amdgcn_cvt_f32_fp8(ga >> sh0, 0), mp1 = __builtin_amdgcn_cvt_f32_fp8(ga >> sh1, 0);
-  // stored magnitudes: 0.5 * m_p where g_p is kept as it is, else 0.5 * h; all <= 448
+  float mp0 = cvt8<BF8>(ga >> sh0), mp1 = cvt8<BF8>(ga >> sh1);
+  // stored magnitudes: 0.5 * m_p where g_p is kept as it is, else 0.5 * h; all within the format's range
   bool own0 = (f2u(mp0) - 1u) >= f2u(s.h);
   bool own1 = (f2u(mp1) - 1u) >= f2u(s.h);
   float v0 = 0.5f * (own0 ? mp0 : s.h);
   float v1 = 0.5f * (own1 ? mp1 : s.h);
-  uint32_t q = e4m3_rne_pack(v0, v1);
+  uint32_t q = BF8 ? ((uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(v0, v1, 0, false) & 0xFFFFu) : e4m3_rne_pack(v0, v1);
   uint32_t s0 = (g >> sh0) & 0x80u, s1 = (g >> sh1) & 0x80u;
   nib = s.pos0 | (s.pos1 << 2);
   return q | s0 | (s1 << 8);
+}
+__device__ __forceinline__ uint32_t mvue_group_e4m3(uint32_t g, uint32_t x, uint32_t& nib) {
+  return mvue_group_f8<false>(g, x, nib);
 }
 
 }  // namespace sste

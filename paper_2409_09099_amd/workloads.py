@@ -84,6 +84,19 @@ def quantize_e4m3(x_f32: np.ndarray):
     return t.view(torch.uint8).numpy().copy(), scale
 
 
+E5M2_MAX = 57344.0
+
+
+def quantize_e5m2(x_f32: np.ndarray):
+    """Per-tensor absmax scaling to OCP e5m2 (the backward format of Sec. 5.2): returns (codes uint8,
+    scale float32) with x ~= scale * decode(codes)."""
+    amax = float(np.max(np.abs(x_f32))) if x_f32.size else 0.0
+    scale = np.float32(amax / E5M2_MAX) if amax > 0 else np.float32(1.0)
+    t = torch.from_numpy(np.ascontiguousarray(x_f32)) / float(scale)
+    t = t.clamp_(-E5M2_MAX, E5M2_MAX).to(torch.float8_e5m2)
+    return t.view(torch.uint8).numpy().copy(), scale
+
+
 def weight_bits(wl: Workload, layer_index: int, O=None, I=None) -> np.ndarray:
     """bf16 master weight (O, I) as uint16 patterns."""
     L = wl.layers[layer_index]
@@ -107,10 +120,11 @@ def activations(wl: Workload, layer_index: int, T=None, I=None):
     return quantize_e4m3(x)
 
 
-def output_gradient(wl: Workload, layer_index: int, T=None, O=None):
-    """dY (T, O): returns (codes, scale) like ``activations``."""
+def output_gradient(wl: Workload, layer_index: int, T=None, O=None, e5m2=False):
+    """dY (T, O): returns (codes, scale) like ``activations``; e5m2=True quantises an 8-bit workload's
+    gradient to e5m2 instead of e4m3."""
     L = wl.layers[layer_index]
     g = gaussian_f32((T or wl.T, O or L.O), DY_STD, wl.base_seed, layer_index, KIND_DY)
     if wl.dtype == "bf16":
         return to_bf16_bits(g), np.float32(1.0)
-    return quantize_e4m3(g)
+    return quantize_e5m2(g) if e5m2 else quantize_e4m3(g)
