@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
     ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--grad-e5m2", action="store_true",
+                    help="8-bit workloads: output gradients in e5m2 (the paper's backward format) instead of e4m3")
     ap.add_argument("--dense-context", action="store_true",
                     help="also time the vendor dense bf16 GEMM (torch.matmul) on the same shapes: context, not the product")
     ap.add_argument("--no-prune-model", action="store_true",
@@ -51,7 +53,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32):
+def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32, grad_e5m2=False):
     """Times the oracle, as it stands, on one full step of the same workload (host cores)."""
     import numpy as np
     from oracle import linear as OL
@@ -73,7 +75,7 @@ def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32):
     t1 = time.perf_counter()
     OL.linear_fwd(xc, rv, rm, wl.dtype, xs, ws)
     t2 = time.perf_counter()
-    OL.linear_wgrad(dyc, xc, 0, 0, wl.dtype, dys, xs)
+    OL.linear_wgrad(dyc, xc, 0, 0, "e5m2" if grad_e5m2 else wl.dtype, dys, xs, x_dtype=wl.dtype)
     t3 = time.perf_counter()
     flops = 2 * 2.0 * wl.T * L.I * L.O
     return {
@@ -162,7 +164,9 @@ def main():
     # ---- seeded synthetic inputs, generated on the host and made resident in HBM before timing
     wb = WL.weight_bits(wl, args.layer)
     xc, xs = WL.activations(wl, args.layer)
-    dyc, dys = WL.output_gradient(wl, args.layer)
+    grad_e5m2 = bool(args.grad_e5m2 and fp8)
+    dyc, dys = WL.output_gradient(wl, args.layer, e5m2=grad_e5m2)
+    gdt = sste.F8E5M2 if grad_e5m2 else dt           # format of dY in the backward calls
 
     def up(a):
         t = torch.from_numpy(np.ascontiguousarray(a.view(np.int16) if a.dtype == np.uint16 else a)).cuda()
@@ -191,7 +195,7 @@ def main():
         s = i % nsets
         sste.project_pack(W, beta, dt, w_scale, vals=vals, meta=meta)
         sste.linear_fwd(Xs[s], vals, meta, O, dt, float(xs), w_scale, Z=Zs[s])
-        sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=dt, dy_scale=float(dys), x_scale=float(xs),
+        sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=gdt, dy_scale=float(dys), x_scale=float(xs),
                           dW=dWs[s], workspace=wss[s])
 
     if args.calibrate_copy:
@@ -289,7 +293,8 @@ def main():
         "dtype": wl.dtype if fp8 else "bf16",
         "data": "synthetic",
         "config": {"workload": "cfg%d %s layer %s (W %dx%d, %d tokens)" % (wl.cfg, wl.name, L.name, O, I, T),
-                   "buffer_sets": nsets, "wgrad_workspace_bytes": int(ws_bytes)},
+                   "buffer_sets": nsets, "wgrad_workspace_bytes": int(ws_bytes),
+                   "grad_format": "e5m2" if grad_e5m2 else wl.dtype},
         "frac_sparse_mfma_peak_whole_step": value / (2 * PEAK_DENSE_TFLOPS[wl.dtype]),
         "kernels": kernels,
         "roofline": roofline,
@@ -298,11 +303,11 @@ def main():
         # the layer's third GEMM, grad_X = grad_Z S(W): dense by the paper's choice, not part of `value`
         dXs = [torch.empty((T, I), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
         for i in range(5):
-            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, dt, float(dys), w_scale, dX=dXs[i % nsets])
+            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, gdt, float(dys), w_scale, dX=dXs[i % nsets])
         torch.cuda.synchronize()
         g0 = time.perf_counter()
         for i in range(args.steps):
-            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, dt, float(dys), w_scale, dX=dXs[i % nsets])
+            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, gdt, float(dys), w_scale, dX=dXs[i % nsets])
         torch.cuda.synchronize()
         dg_ms = (time.perf_counter() - g0) * 1e3 / args.steps
         out_dgrad = {"ms": dg_ms, "TFLOP_per_s": gemm_flops / (dg_ms * 1e-3) * 1e-12, "frac_dense_mfma_peak": gemm_flops / (dg_ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
@@ -338,7 +343,7 @@ def main():
     if not args.no_prune_model:
         out["prune_pack_model"] = prune_model(sste, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, args.layer, wb, xc, xs, dyc, dys, np.float32(beta))
+        out["cpu_baseline"] = cpu_baseline(wl, args.layer, wb, xc, xs, dyc, dys, np.float32(beta), grad_e5m2)
     print(json.dumps(out))
 
 

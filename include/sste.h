@@ -218,16 +218,17 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
  * Weight-gradient GEMM with the output gradient sparsified 2:4 on the fly by the minimum-variance
  * unbiased estimator (Sec. 5.1: grad_W = MVUE(grad_Z^T) X).
  *
- *   dW (+)= scale * MVUE(dY^T; seed, offset) * X,   scale = dy_scale * x_scale (times 2 for e4m3, whose
- *   sparsified operand is stored halved), float32 accumulation, dW float32.
+ *   dW (+)= scale * MVUE(dY^T; seed, offset) * X,   scale = dy_scale * x_scale (times 2 for the 8-bit
+ *   formats, whose sparsified operand is stored halved), float32 accumulation, dW float32.
  *
  * The estimator works on groups of four consecutive tokens t = 4k..4k+3 of one output channel o.
  * Its uniform number is a pure function of (seed, offset, group id = k * O + o), so the result does
  * not depend on tiling or on how the token axis is split.  See sste_mvue_materialize for the rule.
  *
+ *   dtype    in   SSTE_BF16, SSTE_F8E4M3, or SSTE_F8E5M2 (dY e5m2, X e4m3: the formats of Sec. 5.2)
  *   dY       in   device, T x O of `dtype`, leading dimension lddy
- *   X        in   device, T x I of `dtype`, leading dimension ldx
- *   T, O, I  in   T a multiple of 64 (bf16) / 128 (e4m3); O, I >= 0 and multiples of 8 (bf16) / 16 (e4m3)
+ *   X        in   device, T x I of `dtype` (e4m3 when dtype is SSTE_F8E5M2), leading dimension ldx
+ *   T, O, I  in   T a multiple of 64 (bf16) / 128 (8-bit); O, I >= 0 and multiples of 8 (bf16) / 16 (8-bit)
  *   seed, offset  in  random stream id (e.g. layer seed, training step)
  *   dW       out  device, O x I float32, leading dimension lddw (multiple of 4)
  *   accumulate in 0: dW is overwritten; 1: the product is added to dW
@@ -250,7 +251,8 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
  *
  *   dY       in   device, T x O of `dtype`, leading dimension lddy
  *   T, O, I  in   T >= 0; O >= 0 and a multiple of 8 (bf16) / 16 (e4m3); I a multiple of 64 / 128
- *   dtype    in   SSTE_BF16 or SSTE_F8E4M3: element type of dY and of vals (per-tensor scales, Sec. 5.2)
+ *   dtype    in   SSTE_BF16 or SSTE_F8E4M3: element type of dY and of vals (per-tensor scales, Sec. 5.2);
+ *                 SSTE_F8E5M2: dY is e5m2, vals e4m3
  *   dy_scale, w_scale  in  finite, > 0
  *   vals, meta  in   packed S(W) (R = O rows, K = I columns) as written by sste_project_pack; rows past O
  *                    up to the next multiple of 16 must be the padding that call writes
@@ -276,12 +278,13 @@ size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
  *   L = P2 + l3, h = L / 2; u = (x >> 8) * 2^-24 with x the 32-bit draw below; tau0 = u * h,
  *   tau1 = tau0 + h; i(tau) = #{k : P_k <= tau}; pos0 = min(i(tau0), 2), pos1 = min(3, max(i(tau1), pos0 + 1)).
  *   Recorded value at p: g_p itself if m_p > h or m_p == 0, else sign(g_p) * h (h rounded to the
- *   storage type).  e4m3 stores half of these values.
+ *   storage type).  e4m3 and e5m2 store half of these values.
  *   Draw: key = mix64(seed ^ mix64(offset + 0x9E3779B97F4A7C15)) (SplitMix64 finalizer), k0 = low,
  *   k1 = high word; x = (gid & 0xFFFFFFFF) ^ k0; x += (gid >> 32) * 0x9E3779B9; x ^= x >> 17;
  *   x *= 0xED5AD4BB; x += k1; x ^= x >> 11; x *= 0xAC4C1B51; x ^= x >> 15; x *= 0x31848BAB; x ^= x >> 14.
  *
- *   dY    in   device, T x O of `dtype`, leading dimension lddy;  T a multiple of 64 (bf16) / 128 (e4m3)
+ *   dY    in   device, T x O of `dtype` (SSTE_BF16, SSTE_F8E4M3 or SSTE_F8E5M2), leading dimension lddy;
+ *              T a multiple of 64 (bf16) / 128 (8-bit)
  *   vals, meta  out  device, packed format above with R = O rows and K = T columns (padding rows are
  *              left unwritten)
  */

@@ -170,6 +170,9 @@ def test_linear_dgrad_validation(lib):
     assert f(fake, 4, 64, 64, 0, 0.0, fake, fake, 64, 1.0, fake, 64, None) == 5
     assert f(fake, 4, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 1
     assert f(fake, 4, 64, 64, 5, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 4
+    assert f(fake, 4, 64, 64, 2, 1.0, fake, fake, 128, 1.0, fake, 128, None) == 4      # float32 is no gradient format
+    assert f(fake, 4, 72, 80, 3, 1.0, fake, fake, 128, 1.0, fake, 128, None) == 7      # e5m2 gradients: sizes as e4m3
+    assert f(fake, 0, 64, 64, 3, 1.0, fake, fake, 128, 1.0, None, 128, None) == 0
     assert f(fake, 0, 64, 64, 0, 1.0, fake, fake, 64, 1.0, None, 64, None) == 0         # no tokens: nothing to do
 
 

@@ -39,7 +39,7 @@ def up(a):
 
 
 def decode(codes, dtype):
-    return (F.bf16_to_f32(codes) if dtype == "bf16" else F.e4m3_to_f32(codes)).astype(np.float64)
+    return {"bf16": F.bf16_to_f32, "e4m3": F.e4m3_to_f32, "e5m2": F.e5m2_to_f32}[dtype](codes).astype(np.float64)
 
 
 def oracle_theta_column(dy_codes, o, seed, offset, dtype):
@@ -145,3 +145,58 @@ def test_full_size_layer(sste, cfg, layer):
     # run-to-run bitwise reproducible (fixed-order split reduction)
     dW2 = sste.linear_wgrad(dY, X, seed, offset, dt, float(dys), float(xs))
     assert torch.equal(dW, dW2)
+
+
+@pytest.mark.parametrize("layer", [2, 3])
+def test_full_size_e5m2_backward(sste, layer):
+    """Workload 5's fc1 / fc2 with the paper's backward format (Sec. 5.2): e5m2 output gradients against
+    e4m3 activations and an e4m3 packed weight.  Sparsified operand bit for bit on sampled channels,
+    weight gradient and input gradient on sampled outputs from the definition."""
+    wl = WL.WORKLOADS[5]
+    L = wl.layers[layer]
+    T, O, I = wl.T, L.O, L.I
+    rs = np.random.default_rng(500 + layer)
+    print(f"cfg 5 layer {L.name}: T={T} O={O} I={I} e5m2 gradients", flush=True)
+    wb = WL.weight_bits(wl, layer)
+    xc, xs = WL.activations(wl, layer)
+    dyc, dys = WL.output_gradient(wl, layer, e5m2=True)
+    X, dY = up(xc), up(dyc)
+    beta32 = np.float32(1.4830322)
+    _, _, amax = OP.project_pack(wb, beta32)
+    ws = np.float32(float(amax) / 448.0)
+    rv, rm, _ = OP.project_pack(wb, beta32, "e4m3", ws)
+    vals, meta = sste.project_pack(up(wb), float(beta32), sste.F8E4M3, float(ws))
+    Wd = OP.decode_packed(rv, rm, "e4m3")
+    Xf = decode(xc, "e4m3")
+
+    dX = sste.linear_dgrad(dY, vals, meta, I, sste.F8E5M2, float(dys), float(ws))
+    dYf = decode(dyc, "e5m2")
+    ts = np.concatenate([rs.integers(0, T, 60), [0, T - 1, 127, 128, 255, 256]])
+    is_ = np.concatenate([rs.integers(0, I, 60), [0, I - 1, 255, 256 % I, 63, 64]])
+    ref = np.einsum("no,on->n", dYf[ts], Wd[:, is_]) * float(np.float32(dys)) * float(np.float32(ws))
+    got = dX[torch.from_numpy(ts).cuda(), torch.from_numpy(is_).cuda()].float().cpu().numpy().astype(np.float64)
+    xmax = float(dX.float().abs().max())
+    assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-4 * xmax
+    assert torch.isfinite(dX.float()).all()
+
+    seed, offset = 55, 7
+    tv, tm = sste.mvue_materialize(dY, seed, offset, sste.F8E5M2)
+    gv, gm = OP.from_fragment_major(tv.cpu().numpy().reshape(-1), tm.cpu().numpy().reshape(-1), O, T, "e5m2")
+    chans = np.concatenate([rs.integers(0, O, 10), [0, O - 1]])
+    thetas = {}
+    for o in chans:
+        theta, ovals, onib = oracle_theta_column(dyc, int(o), seed, offset, "e5m2")
+        thetas[int(o)] = theta
+        assert np.array_equal(gv[o].reshape(-1, 2), ovals), o
+        assert np.array_equal(np.stack([gm[o] & 0xF, gm[o] >> 4], axis=1).reshape(-1), onib), o
+
+    dW = sste.linear_wgrad(dY, X, seed, offset, sste.F8E5M2, float(dys), float(xs))
+    scale = float(np.float32(dys)) * float(np.float32(xs)) * 2.0
+    dmax = float(dW.abs().max())
+    worst = 0.0
+    for o in chans:
+        cols = np.concatenate([rs.integers(0, I, 6), [0, I - 1]])
+        ref = (thetas[int(o)] @ Xf[:, cols]) * scale
+        worst = max(worst, float(np.max(np.abs(dW[int(o)].cpu().numpy().astype(np.float64)[cols] - ref))))
+    assert worst <= 1e-4 * dmax, (worst, dmax)
+    assert torch.isfinite(dW).all()
