@@ -204,21 +204,36 @@ struct UpdateTableItem {
 };
 static_assert(sizeof(UpdateTableItem) == 80, "table item size is part of the C ABI (SSTE_UPDATE_TABLE_ITEM_BYTES)");
 
+// A wave of the multi-tensor kernels takes kBatchRun consecutive global blocks: one table search, then
+// it walks on through the table (items are sorted by first_block; empty items own no block and are
+// stepped over).
+constexpr int kBatchRun = 2;
+
 template <bool FP8, bool F32>
 __global__ void __launch_bounds__(256)
 k_sgd_project_pack_batch(const UpdateTableItem* __restrict__ table, int n_items, int64_t total_blocks, float alpha) {
   const int lane = threadIdx.x & 63;
-  const int64_t blk = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  if (blk >= total_blocks) return;
-  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk
+  const int64_t blk0 = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * kBatchRun;
+  if (blk0 >= total_blocks) return;
+  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk0
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
-    if (table[mid].first_block <= blk) lo = mid;
+    if (table[mid].first_block <= blk0) lo = mid;
     else hi = mid - 1;
   }
-  const UpdateTableItem it = table[lo];
-  sgd_block<FP8, F32>(it.W, it.G, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.ldg, alpha, it.beta, it.val_scale,
-                      it.vals, it.meta, lane);
+  UpdateTableItem it = table[lo];
+  int64_t next_first = lo + 1 < n_items ? table[lo + 1].first_block : total_blocks;
+  for (int b = 0; b < kBatchRun; b++) {
+    const int64_t blk = blk0 + b;
+    if (blk >= total_blocks) break;
+    while (blk >= next_first) {
+      lo++;
+      it = table[lo];
+      next_first = lo + 1 < n_items ? table[lo + 1].first_block : total_blocks;
+    }
+    sgd_block<FP8, F32>(it.W, it.G, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.ldg, alpha, it.beta, it.val_scale,
+                        it.vals, it.meta, lane);
+  }
 }
 
 template <bool FP8, bool AMAX>
@@ -265,16 +280,26 @@ template <bool FP8>
 __global__ void __launch_bounds__(256)
 k_project_pack_batch(const PackTableItem* __restrict__ table, int n_items, int64_t total_blocks) {
   const int lane = threadIdx.x & 63;
-  const int64_t blk = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  if (blk >= total_blocks) return;
-  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk
+  const int64_t blk0 = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * kBatchRun;
+  if (blk0 >= total_blocks) return;
+  int lo = 0, hi = n_items - 1;                          // last item whose first_block <= blk0
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
-    if (table[mid].first_block <= blk) lo = mid;
+    if (table[mid].first_block <= blk0) lo = mid;
     else hi = mid - 1;
   }
-  const PackTableItem it = table[lo];
-  project_block<FP8, false>(it.W, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.beta, it.val_scale, it.vals, it.meta, lane);
+  PackTableItem it = table[lo];
+  int64_t next_first = lo + 1 < n_items ? table[lo + 1].first_block : total_blocks;
+  for (int b = 0; b < kBatchRun; b++) {
+    const int64_t blk = blk0 + b;
+    if (blk >= total_blocks) break;
+    while (blk >= next_first) {
+      lo++;
+      it = table[lo];
+      next_first = lo + 1 < n_items ? table[lo + 1].first_block : total_blocks;
+    }
+    project_block<FP8, false>(it.W, it.O, it.steps, blk - it.first_block, it.ldw_bytes, it.beta, it.val_scale, it.vals, it.meta, lane);
+  }
 }
 
 __global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
@@ -323,7 +348,7 @@ hipError_t launch_sgd_project_pack(void* W, bool w_f32, int64_t O, int64_t I, in
 hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t total_blocks, bool w_f32, int val_dtype,
                                          float alpha, hipStream_t s) {
   if (n_items == 0 || total_blocks == 0) return hipSuccess;
-  dim3 grid((unsigned)((total_blocks + 3) / 4)), block(256);
+  dim3 grid((unsigned)((total_blocks + 4 * kBatchRun - 1) / (4 * kBatchRun))), block(256);
   const UpdateTableItem* t = (const UpdateTableItem*)table;
   bool fp8 = val_dtype == SSTE_F8E4M3;
 #define SGD_CASE(F8, F32) \
@@ -338,7 +363,7 @@ hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t
 
 hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t total_blocks, int val_dtype, hipStream_t s) {
   if (n_items == 0 || total_blocks == 0) return hipSuccess;
-  dim3 grid((unsigned)((total_blocks + 3) / 4)), block(256);
+  dim3 grid((unsigned)((total_blocks + 4 * kBatchRun - 1) / (4 * kBatchRun))), block(256);
   if (val_dtype == SSTE_F8E4M3)
     SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack_batch<true>), grid, block, s, (const PackTableItem*)table, n_items, total_blocks);
   else
