@@ -228,3 +228,22 @@ def test_sgd_project_pack_batch_prepare(lib):
     assert launch(0x1000, 1, 4, 0, 0, float("inf"), None) == 5
     assert launch(0x1000, 1, 4, 1, 0, 0.1, None) == 4
     assert launch(None, 0, 0, 2, 1, 0.1, None) == 0
+
+
+def test_problems_beyond_the_32_bit_tile_offsets_are_refused(lib):
+    """The kernels address inside a tile with 32-bit offsets; sizes beyond that are refused on the host
+    (status 7) before anything is launched."""
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    i64, f32, ci = ctypes.c_int64, ctypes.c_float, ctypes.c_int
+    fwd = lib.sste_linear_fwd
+    fwd.argtypes = [P, i64, i64, i64, ci, f32, P, P, i64, f32, P, i64, P]
+    assert fwd(fake, 256, 64, 1 << 21, 0, 1.0, fake, fake, 16, 1.0, fake, 16, None) == 7      # a 256-row X tile spans 2^30 bytes
+    assert fwd(fake, 256, 1 << 21, 1 << 21, 0, 1.0, fake, fake, 16, 1.0, fake, 16, None) == 7
+    dg = lib.sste_linear_dgrad
+    dg.argtypes = [P, i64, i64, i64, ci, f32, P, P, i64, f32, P, i64, P]
+    assert dg(fake, 256, 64, 1 << 21, 0, 1.0, fake, fake, 64, 1.0, fake, 64, None) == 7
+    assert dg(fake, 256, 1 << 16, 1 << 16, 0, 1.0, fake, fake, 1 << 15, 1.0, fake, 1 << 15, None) == 7   # packed weight: 2^31 elements
+    wg = lib.sste_linear_wgrad
+    wg.argtypes = [P, i64, i64, i64, ci, f32, P, i64, i64, f32, ctypes.c_uint64, ctypes.c_uint64, P, i64, ci, P, ctypes.c_size_t, P]
+    assert wg(fake, 1 << 14, 256, 256, 0, 1.0, fake, 256, 1 << 17, 1.0, 0, 0, fake, 256, 0, fake, 1 << 40, None) == 7   # T * ldx * 2 = 2^32
