@@ -170,7 +170,8 @@ def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
     for idx in (idx0, idx1):
         ai = a[rows, idx]
         sd = (ai - np.copysign(t, ai)).astype(np.float32)             # a - t  or  a + t, one float32 op
-        p = (sd * beta32).astype(np.float32)
+        with np.errstate(over="ignore"):                              # weights near the bf16 maximum: p = inf, as in float32
+            p = (sd * beta32).astype(np.float32)
         if p.size:
             amax = max(amax, np.float32(np.max(np.abs(p))))
         if val_dtype == "bf16":
@@ -178,7 +179,8 @@ def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
                 raise ValueError("val_scale must be 1 for bf16 values")
             out_vals.append(formats.f32_to_bf16_rne(p))
         elif val_dtype == "e4m3":
-            q = (p / np.float32(val_scale)).astype(np.float32)
+            with np.errstate(over="ignore"):
+                q = (p / np.float32(val_scale)).astype(np.float32)
             out_vals.append(formats.f32_to_e4m3_rne_sat(q))
         else:
             raise ValueError("val_dtype must be 'bf16' or 'e4m3'")
