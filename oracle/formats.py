@@ -94,3 +94,16 @@ def f32_to_e5m2_rne_sat(x):
     code = np.where(sub, q, ((e + 15) << 2) | (q - 4))
     code = code | (neg.astype(np.int64) << 7)
     return code.astype(np.uint8)
+
+
+def cast_fp8(x_bits, scale, fmt="e4m3"):
+    """Per-tensor rescaling and cast of a bf16 tensor to an 8-bit format (Sec. 5.2: the operands are
+    rescaled per tensor before they are cast).  q = x / scale as ONE float32 division, clamped to the
+    format's largest finite value, rounded to nearest even.  Returns (codes uint8, amax float32) with
+    amax = max |x| over the tensor (exact: the inputs are bf16), from which a caller derives the next
+    scale (amax / format maximum)."""
+    x = bf16_to_f32(x_bits)
+    q = (x / np.float32(scale)).astype(np.float32)
+    codes = f32_to_e4m3_rne_sat(q) if fmt == "e4m3" else f32_to_e5m2_rne_sat(q)
+    amax = np.float32(np.max(np.abs(x))) if x.size else np.float32(0.0)
+    return codes.reshape(x.shape), amax

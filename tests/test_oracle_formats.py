@@ -109,3 +109,28 @@ def test_e5m2_encode_matches_torch_cast_in_range():
     x = np.clip(x, -57344, 57344)
     ref = torch.from_numpy(x).to(torch.float8_e5m2).view(torch.uint8).numpy()
     assert np.array_equal(ref, F.f32_to_e5m2_rne_sat(x))
+
+
+def test_cast_fp8_against_torch_and_by_hand():
+    """Scale-then-cast: hand values, saturation at the format maximum, and PyTorch's float32 division +
+    float8 casts as an independent implementation."""
+    rng = np.random.default_rng(3)
+    x = F.f32_to_bf16_rne(rng.standard_normal((64, 48)).astype(np.float32) * np.exp(rng.uniform(-6, 3, (64, 48))).astype(np.float32))
+    x = x.reshape(64, 48)
+    xf = torch.from_numpy(F.bf16_to_f32(x))
+    for fmt, tdt, mx in (("e4m3", torch.float8_e4m3fn, 448.0), ("e5m2", torch.float8_e5m2, 57344.0)):
+        amax_ref = float(xf.abs().max())
+        scale = np.float32(amax_ref / mx)
+        codes, amax = F.cast_fp8(x, scale, fmt)
+        assert float(amax) == amax_ref
+        ref = (xf / float(scale)).clamp(-mx, mx).to(tdt).view(torch.uint8).numpy()
+        assert np.array_equal(codes, ref)
+        # a scale that is too small saturates instead of overflowing
+        codes, _ = F.cast_fp8(x, np.float32(scale / 64), fmt)
+        dec = F.e4m3_to_f32(codes) if fmt == "e4m3" else F.e5m2_to_f32(codes)
+        assert np.all(np.isfinite(dec)) and np.max(np.abs(dec)) == mx
+    one = np.array([[0x3F80, 0xC000, 0x0000, 0x8000]], dtype=np.uint16)            # 1, -2, +0, -0
+    codes, amax = F.cast_fp8(one, 0.5, "e4m3")
+    assert codes.tolist() == [[0x40, 0xC8, 0x00, 0x80]] and amax == 2.0            # 2, -4, +0, -0
+    codes, _ = F.cast_fp8(one, 0.5, "e5m2")
+    assert codes.tolist() == [[0x40, 0xC4, 0x00, 0x80]]
