@@ -312,6 +312,24 @@ def main():
         dg_ms = (time.perf_counter() - g0) * 1e3 / args.steps
         out_dgrad = {"ms": dg_ms, "TFLOP_per_s": gemm_flops / (dg_ms * 1e-3) * 1e-12, "frac_dense_mfma_peak": gemm_flops / (dg_ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
         del dXs
+    if fp8:
+        # operand preparation of the 8-bit path: per-tensor rescale + cast of bf16 X and dY (3 B per element)
+        casts = {}
+        for name, rows, cols, fmt in (("X", T, I, sste.F8E4M3), ("dY", T, O, gdt if grad_e5m2 else sste.F8E4M3)):
+            src = torch.randn((rows, cols), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            q = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+            amax = torch.empty(1, dtype=torch.float32, device="cuda")
+            for _ in range(3):
+                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(20):
+                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - c0) * 1e3 / 20
+            casts[name] = {"ms": ms, "GB_per_s": rows * cols * 3 / ms * 1e-6, "frac_hbm_peak": rows * cols * 3 / ms * 1e-6 / PEAK_HBM_GBS}
+            del src, q
+        out["cast_fp8"] = casts
     if args.dense_context and not fp8:
         # what the vendor's dense GEMM reaches on the same layer (forward Z = X W^T; weight gradient dY^T X)
         def dense_us(fn, iters=50):

@@ -305,6 +305,28 @@ int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* b
 size_t sste_beta_workspace_bytes(int64_t O, int64_t I);
 
 /*
+ * Per-tensor rescaling and cast of a bf16 tensor to an 8-bit operand format (Sec. 5.2: the operands of
+ * the FP8 GEMMs are rescaled per tensor before they are cast; e4m3 for activations, e5m2 or e4m3 for
+ * the output gradient).
+ *
+ *   Q[r][c] = RNE_fmt(clamp(X[r][c] / scale, +-max_fmt)),   one float32 division per element;
+ *   *amax_out = max |X[r][c]| (exact; 0 for an empty tensor).
+ *
+ * The GEMM calls then take Q with x_scale / dy_scale = scale.  A caller that scales by the current
+ * tensor calls once with Q == NULL (largest magnitude only), sets scale = amax / max_fmt, and calls
+ * again; one that uses the previous iteration's amax (delayed scaling) calls once.
+ *
+ *   X         in   device, bf16, R x C, leading dimension ldx (>= C, multiple of 8); C a multiple of 8
+ *   out_dtype in   SSTE_F8E4M3 (max 448) or SSTE_F8E5M2 (max 57344)
+ *   scale     in   finite and > 0
+ *   Q         out  device, R x C bytes, leading dimension ldq (>= C, multiple of 8), 8-byte aligned; or NULL
+ *   amax_out  out  device float* or NULL (not both Q and amax_out NULL)
+ * Errors: as the other calls (ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_VALUE, ERR_NULL).
+ */
+int sste_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale,
+                  void* Q, int64_t ldq, float* amax_out, void* hip_stream);
+
+/*
  * Flip count of Sec. 3.3 (numerator of the flip rate r_k): number of positions whose recorded /
  * not-recorded state differs between two metadata arrays of the same O x I/8 shape.
  *   count_out  out  device uint64_t*; overwritten
@@ -328,7 +350,8 @@ typedef enum {
   SSTE_K_MVUE_PACK = 4,      /* estimator pre-pass of the weight-gradient path (large problems) */
   SSTE_K_DGRAD = 5,          /* input-gradient dense GEMM */
   SSTE_K_SGD_PROJECT_PACK = 6, /* dense-weight update fused with projection + pack */
-  SSTE_K_COUNT = 7
+  SSTE_K_CAST = 7,           /* per-tensor rescale + cast to an 8-bit format */
+  SSTE_K_COUNT = 8
 } sste_kernel_id;
 int sste_timing_begin(int max_launches);
 int sste_timing_end(double* total_ms, int* launches);

@@ -103,7 +103,8 @@ def cast_fp8(x_bits, scale, fmt="e4m3"):
     amax = max |x| over the tensor (exact: the inputs are bf16), from which a caller derives the next
     scale (amax / format maximum)."""
     x = bf16_to_f32(x_bits)
-    q = (x / np.float32(scale)).astype(np.float32)
+    with np.errstate(over="ignore"):                 # a scale far too small: infinity, then the clamp
+        q = (x / np.float32(scale)).astype(np.float32)
     codes = f32_to_e4m3_rne_sat(q) if fmt == "e4m3" else f32_to_e5m2_rne_sat(q)
     amax = np.float32(np.max(np.abs(x))) if x.size else np.float32(0.0)
     return codes.reshape(x.shape), amax

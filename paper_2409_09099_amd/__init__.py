@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     F32,
     PackBatch,
     SsteError,
+    cast_fp8,
     UpdateBatch,
     compute_beta,
     flip_count,

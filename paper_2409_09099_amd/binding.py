@@ -51,13 +51,14 @@ def library() -> ctypes.CDLL:
     lib.sste_compute_beta.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
     lib.sste_beta_workspace_bytes.argtypes = [i64, i64]
     lib.sste_beta_workspace_bytes.restype = sz
+    lib.sste_cast_fp8.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, vp, vp]
     lib.sste_flip_count.argtypes = [vp, vp, i64, i64, vp, vp]
     lib.sste_timing_begin.argtypes = [ci]
     lib.sste_timing_begin.restype = ci
     lib.sste_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.sste_timing_end.restype = ci
     for name in ("sste_project_pack", "sste_sgd_project_pack", "sste_sgd_project_pack_batch_prepare", "sste_sgd_project_pack_batch", "sste_project_pack_batch_prepare", "sste_project_pack_batch", "sste_linear_fwd", "sste_linear_dgrad",
-                 "sste_linear_wgrad", "sste_mvue_materialize", "sste_compute_beta", "sste_flip_count"):
+                 "sste_linear_wgrad", "sste_mvue_materialize", "sste_compute_beta", "sste_flip_count", "sste_cast_fp8"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -282,6 +283,23 @@ def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtyp
     return dW
 
 
+def cast_fp8(X: torch.Tensor, scale: float, out_dtype: int = F8E4M3, Q: Optional[torch.Tensor] = None,
+             amax_out: Optional[torch.Tensor] = None, store: bool = True):
+    """sste_cast_fp8: Q = RNE(clamp(X / scale)) as e4m3 / e5m2 codes, amax_out = max |X|.  store=False asks
+    for the largest magnitude only.  Returns (Q or None, amax_out)."""
+    R, C, ldx = _matrix(X, 2, "X")
+    if amax_out is None:
+        amax_out = torch.empty(1, dtype=torch.float32, device=X.device)
+    ldq = C
+    if store:
+        if Q is None:
+            Q = torch.empty((R, C), dtype=torch.uint8, device=X.device)
+        _, _, ldq = _matrix(Q, 1, "Q")
+    _check(library().sste_cast_fp8(_ptr(X), R, C, ldx, out_dtype, scale, _ptr(Q) if store else None, ldq, _ptr(amax_out),
+                                   _stream(X)))
+    return (Q if store else None), amax_out
+
+
 def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16):
     """sste_mvue_materialize: MVUE(dY^T) as a packed 2:4 operand.  Returns (vals (O, T/2), meta (O, T/8))."""
     T, O, lddy = _matrix(dY, _esize(dtype), "dY")
@@ -312,7 +330,7 @@ def flip_count(meta_a: torch.Tensor, meta_b: torch.Tensor, O: int) -> torch.Tens
     return out
 
 
-KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack", "dgrad", "sgd_project_pack")
+KERNEL_NAMES = ("project_pack", "fwd", "wgrad", "wgrad_reduce", "mvue_pack", "dgrad", "sgd_project_pack", "cast")
 
 
 def timing_begin(max_launches: int = 4096) -> None:

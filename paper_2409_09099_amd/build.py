@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsste.so")
 
-SOURCES = ["api.hip", "prune_pack.hip", "gemm_fwd.hip", "gemm_wgrad.hip", "gemm_wgrad_fused.hip", "gemm_dgrad.hip"]
+SOURCES = ["api.hip", "prune_pack.hip", "gemm_fwd.hip", "gemm_wgrad.hip", "gemm_wgrad_fused.hip", "gemm_dgrad.hip", "cast.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

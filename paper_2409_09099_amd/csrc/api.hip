@@ -432,6 +432,22 @@ int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* b
   return hip_status(launch_compute_beta(W, O, I, ldw, beta_out, workspace, (hipStream_t)hip_stream), "compute_beta launch");
 }
 
+int sste_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale, void* Q, int64_t ldq,
+                  float* amax_out, void* hip_stream) {
+  clear_error();
+  if (R < 0 || C < 0) return fail(SSTE_ERR_SHAPE, "cast_fp8: negative size");
+  if (C % 8 != 0) return fail(SSTE_ERR_SHAPE, "cast_fp8: C=%lld is not a multiple of 8", (long long)C);
+  if (out_dtype != SSTE_F8E4M3 && out_dtype != SSTE_F8E5M2) return fail(SSTE_ERR_DTYPE, "cast_fp8: out_dtype %d is no 8-bit format", out_dtype);
+  if (!good_scale(scale)) return fail(SSTE_ERR_VALUE, "cast_fp8: scale must be finite and > 0");
+  if (ldx < C || (Q && ldq < C)) return fail(SSTE_ERR_SHAPE, "cast_fp8: leading dimension smaller than the row length");
+  if (ldx % 8 != 0 || (Q && ldq % 8 != 0)) return fail(SSTE_ERR_ALIGN, "cast_fp8: ldx / ldq must be multiples of 8");
+  if (!Q && !amax_out) return fail(SSTE_ERR_NULL, "cast_fp8: both Q and amax_out are NULL");
+  if (R > 0 && C > 0 && !X) return fail(SSTE_ERR_NULL, "cast_fp8: NULL X");
+  if (!aligned16(X) || (reinterpret_cast<uintptr_t>(Q) & 7u) || (reinterpret_cast<uintptr_t>(amax_out) & 3u))
+    return fail(SSTE_ERR_ALIGN, "cast_fp8: X must be 16-byte, Q 8-byte, amax_out 4-byte aligned");
+  return hip_status(launch_cast_fp8(X, R, C, ldx, out_dtype, scale, Q, ldq, amax_out, (hipStream_t)hip_stream), "cast_fp8 launch");
+}
+
 int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I, unsigned long long* count_out, void* hip_stream) {
   clear_error();
   if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "flip_count: negative size");

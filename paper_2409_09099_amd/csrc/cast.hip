@@ -1,0 +1,103 @@
+// Per-tensor rescaling and cast of bf16 activations / gradients to the 8-bit operand formats (paper
+// Sec. 5.2: operands are rescaled per tensor before they are cast to FP8; e4m3 for the forward
+// operands, e5m2 for the output gradient).  One streaming pass: 2 B read and 1 B written per element,
+// plus the tensor's largest magnitude, from which the caller derives the scale of the next iteration.
+#include "common.h"
+
+namespace sste {
+
+__global__ void k_fill_u32_cast(uint32_t* p, uint32_t v) { *p = v; }
+
+// A lane converts 8 consecutive elements (16 bytes in, 8 bytes out) of kCastUnroll chunks per round, a
+// workgroup 256 x kCastUnroll consecutive chunks.  q = x / scale is a true float32 division; clamp to
+// the largest finite value; round to nearest even.
+// Largest magnitude: atomics on one address serialise in L2 (about 12 ns each), so a workgroup
+// publishes its maximum after its FIRST round -- those atomics then run under the streaming of the
+// remaining rounds -- and again at the end only if it can still raise the value, which is rare.
+constexpr int kCastUnroll = 4;
+
+__device__ __forceinline__ void publish_max(uint32_t m, uint32_t* __restrict__ amax_bits, uint32_t* wave_max) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
+  __syncthreads();                                   // wave_max may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    if (m > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, m);
+  }
+}
+
+// ROWS = false: X and Q are contiguous (leading dimension == row length), addressed as one long row; the
+// 64-bit division per chunk of the strided case costs as much as the conversions themselves.
+template <bool BF8, bool STORE, bool ROWS>
+__global__ void __launch_bounds__(256)
+k_cast_fp8(const uint8_t* __restrict__ X, int64_t R, int64_t chunks_per_row, int64_t ldx_bytes, float scale,
+           uint8_t* __restrict__ Q, int64_t ldq, uint32_t* __restrict__ amax_bits) {
+  __shared__ uint32_t wave_max[4];
+  const int64_t n = R * chunks_per_row;
+  const int64_t stride = (int64_t)gridDim.x * 256 * kCastUnroll;
+  uint32_t amax = 0;
+  bool first = true;
+  for (int64_t base = (int64_t)blockIdx.x * 256 * kCastUnroll; base < n; base += stride) {
+    i32x4 t[kCastUnroll];
+    int64_t row[kCastUnroll], col[kCastUnroll];
+#pragma unroll
+    for (int u = 0; u < kCastUnroll; u++) {
+      const int64_t c = base + u * 256 + threadIdx.x;
+      row[u] = ROWS ? c / chunks_per_row : 0;
+      col[u] = c - row[u] * chunks_per_row;
+      t[u] = (i32x4){0, 0, 0, 0};
+      if (c < n) t[u] = __builtin_nontemporal_load((const i32x4*)(X + row[u] * ldx_bytes + col[u] * 16));   // read once
+    }
+#pragma unroll
+    for (int u = 0; u < kCastUnroll; u++) {
+      uint32_t w[4] = {(uint32_t)t[u][0], (uint32_t)t[u][1], (uint32_t)t[u][2], (uint32_t)t[u][3]};
+      uint32_t out[2] = {0, 0};
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const uint32_t lo = w[e] << 16, hi = w[e] & 0xFFFF0000u;         // two bf16 as float32 bits
+        amax = max(amax, max(lo & 0x7FFFFFFFu, hi & 0x7FFFFFFFu));       // magnitudes order like their bit patterns
+        if (STORE) {
+          const float a = u2f(lo) / scale, b = u2f(hi) / scale;
+          uint32_t pair;
+          if (BF8)
+            pair = (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(__builtin_amdgcn_fmed3f(a, -57344.0f, 57344.0f),
+                                                             __builtin_amdgcn_fmed3f(b, -57344.0f, 57344.0f), 0, false) & 0xFFFFu;
+          else
+            pair = e4m3_rne_pack(clamp448(a), clamp448(b));
+          out[e >> 1] |= pair << (16 * (e & 1));
+        }
+      }
+      if (STORE && base + u * 256 + threadIdx.x < n) *(uint2*)(Q + row[u] * ldq + col[u] * 8) = make_uint2(out[0], out[1]);
+    }
+    if (amax_bits && first && base + stride < n) publish_max(amax, amax_bits, wave_max);   // uniform per workgroup
+    first = false;
+  }
+  if (amax_bits) publish_max(amax, amax_bits, wave_max);
+}
+
+hipError_t launch_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale, void* Q,
+                           int64_t ldq, float* amax_out, hipStream_t s) {
+  if (amax_out) hipLaunchKernelGGL(k_fill_u32_cast, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
+  const int64_t chunks = C / 8, n = R * chunks;
+  if (n == 0) return hipGetLastError();
+  int64_t blocks = (n + 256 * kCastUnroll - 1) / (256 * kCastUnroll);
+  if (blocks > 256 * 8) blocks = 256 * 8;                 // 8 workgroups (32 waves) per CU, grid-stride beyond
+  dim3 grid((unsigned)blocks), block(256);
+  const uint8_t* x = (const uint8_t*)X;
+  uint32_t* ab = (uint32_t*)amax_out;
+  const bool rows = !(ldx == C && (!Q || ldq == C));
+#define CAST_CASE(B8, ST)                                                                                              \
+  do {                                                                                                                 \
+    if (rows) SSTE_LAUNCH(SSTE_K_CAST, (k_cast_fp8<B8, ST, true>), grid, block, s, x, R, chunks, ldx * 2, scale, (uint8_t*)Q, ldq, ab); \
+    else SSTE_LAUNCH(SSTE_K_CAST, (k_cast_fp8<B8, ST, false>), grid, block, s, x, R, chunks, ldx * 2, scale, (uint8_t*)Q, ldq, ab);     \
+  } while (0)
+  if (!Q) CAST_CASE(false, false);
+  else if (out_dtype == SSTE_F8E5M2) CAST_CASE(true, true);
+  else CAST_CASE(false, true);
+#undef CAST_CASE
+  return hipGetLastError();
+}
+
+}  // namespace sste

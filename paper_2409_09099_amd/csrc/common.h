@@ -181,6 +181,8 @@ hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
 hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
                                hipStream_t s);
 size_t beta_workspace_bytes(int64_t O, int64_t I);
+hipError_t launch_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale, void* Q,
+                           int64_t ldq, float* amax_out, hipStream_t s);
 hipError_t launch_flip_count(const void* a, const void* b, int64_t nbytes, unsigned long long* out, hipStream_t s);
 hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,
                                    void* vals, void* meta, hipStream_t s);

@@ -247,3 +247,21 @@ def test_problems_beyond_the_32_bit_tile_offsets_are_refused(lib):
     wg = lib.sste_linear_wgrad
     wg.argtypes = [P, i64, i64, i64, ci, f32, P, i64, i64, f32, ctypes.c_uint64, ctypes.c_uint64, P, i64, ci, P, ctypes.c_size_t, P]
     assert wg(fake, 1 << 14, 256, 256, 0, 1.0, fake, 256, 1 << 17, 1.0, 0, 0, fake, 256, 0, fake, 1 << 40, None) == 7   # T * ldx * 2 = 2^32
+
+
+def test_cast_fp8_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_cast_fp8
+    f.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float, P, ctypes.c_int64, P, P]
+    assert f(fake, -1, 64, 64, 1, 1.0, fake, 64, None, None) == 2
+    assert f(fake, 4, 60, 64, 1, 1.0, fake, 64, None, None) == 2
+    assert f(fake, 4, 64, 32, 1, 1.0, fake, 64, None, None) == 2
+    assert f(fake, 4, 64, 68, 1, 1.0, fake, 64, None, None) == 3
+    assert f(fake, 4, 64, 64, 1, 1.0, fake, 68, None, None) == 3
+    assert f(fake, 4, 64, 64, 0, 1.0, fake, 64, None, None) == 4
+    assert f(fake, 4, 64, 64, 3, float("inf"), fake, 64, None, None) == 5
+    assert f(fake, 4, 64, 64, 3, 1.0, None, 64, None, None) == 1
+    assert f(None, 4, 64, 64, 3, 1.0, fake, 64, None, None) == 1
+    assert f(fake, 4, 64, 64, 3, 1.0, P(0x1004), 64, None, None) == 3
+    assert f(None, 0, 64, 64, 1, 1.0, None, 64, None, None) == 1               # nothing asked for

@@ -287,6 +287,59 @@ def test_compute_beta_and_flip_count(sste):
     assert int(host(sste.flip_count(m1, m1, wb.shape[0]))[0]) == 0
 
 
+# ------------------------------------------------------------------------------------------ 8-bit cast
+
+@pytest.mark.parametrize("fmt", ["e4m3", "e5m2"])
+@pytest.mark.parametrize("case", ["activations", "strided_ragged", "saturating"])
+def test_cast_fp8_bit_exact(sste, fmt, case):
+    """Per-tensor rescale + cast: codes and largest magnitude are the oracle's, bit for bit; the two-call
+    use (largest magnitude first, then the cast with the scale derived from it) reproduces the host-side
+    quantisation of the workloads."""
+    wl = WL.WORKLOADS[1]
+    mx = 448.0 if fmt == "e4m3" else 57344.0
+    R, C = (512, 1024) if case != "strided_ragged" else (77, 264)
+    xb = WL.activations(wl, 0, T=R, I=C)[0]                               # bf16 patterns ~ N(0, 1)
+    xb[0, :4] = [0x0000, 0x8000, 0x0001, 0x7F7F]                          # +0, -0, smallest subnormal, bf16 maximum
+    pad = 24 if case == "strided_ragged" else 0
+    Xbig = torch.full((R, C + pad), 9.0, dtype=torch.bfloat16, device="cuda")
+    Xbig[:, :C] = bf16_dev(xb)
+    Qbig = torch.full((R, C + pad), 0x55, dtype=torch.uint8, device="cuda")
+    X, Q = Xbig[:, :C], Qbig[:, :C]
+    _, amax = sste.cast_fp8(X, 1.0, dt(sste, fmt), store=False)
+    amax_ref = np.float32(np.max(np.abs(F.bf16_to_f32(xb))))
+    assert host(amax).numpy().view(np.uint32)[0] == amax_ref.view(np.uint32)
+    assert bool((Qbig == 0x55).all())
+    scale = np.float32(2.0 ** -20) if case == "saturating" else np.float32(float(amax_ref) / mx)
+    amax2 = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    sste.cast_fp8(X, float(scale), dt(sste, fmt), Q=Q, amax_out=amax2)
+    codes, _ = F.cast_fp8(xb, scale, fmt)
+    assert np.array_equal(host(Q).numpy(), codes)
+    assert host(amax2).numpy().view(np.uint32)[0] == amax_ref.view(np.uint32)
+    if pad:
+        assert bool((Qbig[:, C:] == 0x55).all())
+    if case == "activations" and fmt == "e4m3":
+        # the same tensor through the workload's host-side quantiser (PyTorch casts)
+        xf = F.bf16_to_f32(xb)
+        ref_codes, ref_scale = WL.quantize_e4m3(xf)
+        assert np.float32(ref_scale) == scale and np.array_equal(codes, ref_codes)
+
+
+def test_cast_fp8_empty_and_errors(sste):
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    q, amax = sste.cast_fp8(e, 1.0)
+    assert q.shape == (0, 64) and float(host(amax)[0]) == 0.0
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:
+        sste.cast_fp8(x, 0.0)
+    assert ei.value.status == 5
+    with pytest.raises(sste.SsteError) as ei:
+        sste.cast_fp8(x, 1.0, sste.BF16)
+    assert ei.value.status == 4
+    with pytest.raises(sste.SsteError) as ei:
+        sste.cast_fp8(torch.zeros((4, 60), dtype=torch.bfloat16, device="cuda"), 1.0)
+    assert ei.value.status == 2
+
+
 # ------------------------------------------------------------------------------------------ MVUE
 
 def _edge_gradients(dtype):
