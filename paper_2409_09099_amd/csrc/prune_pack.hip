@@ -255,7 +255,8 @@ k_project_pack(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t 
     __syncthreads();
     if (threadIdx.x == 0) {
       m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
-      atomicMax(amax_bits, m);
+      // atomics on one address serialise: only a workgroup that can raise the value issues one
+      if (m > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, m);
     }
   }
 }
