@@ -681,3 +681,47 @@ def test_training_iterations_chain(sste):
     fv, fm = OP.to_fragment_major(rv, rm)
     assert np.array_equal(host(meta).numpy().reshape(-1), fm)
     assert np.count_nonzero(OP.structural_mask(first_meta) ^ OP.structural_mask(rm)) > 0
+
+
+def test_fp8_iteration_with_gpu_side_casts(sste):
+    """The 8-bit recipe of Sec. 5.2 end to end through the C ABI: bf16 activations and output gradients
+    are rescaled per tensor and cast on the GPU (e4m3 / e5m2, scale from the tensor's own largest
+    magnitude), the weight is projected to e4m3 with its own scale, then forward, weight gradient and
+    input gradient run on the 8-bit operands.  Every stage against the oracle on that stage's inputs."""
+    wl = WL.WORKLOADS[1]
+    T, O, I = 512, 256, 1024
+    wb = WL.weight_bits(wl, 0)
+    xb = WL.activations(wl, 0)[0]                                   # bf16 patterns
+    dyb = WL.output_gradient(wl, 0)[0]
+    beta = np.float32(1.4830322)
+    W, X, dY = bf16_dev(wb), bf16_dev(xb), bf16_dev(dyb)
+
+    def cast(t, bits, fmt, mx):
+        _, amax = sste.cast_fp8(t, 1.0, dt(sste, fmt), store=False)
+        scale = np.float32(float(host(amax)[0]) / mx)
+        q, _ = sste.cast_fp8(t, float(scale), dt(sste, fmt))
+        codes, amax_ref = F.cast_fp8(bits, scale, fmt)
+        assert float(host(amax)[0]) == float(amax_ref)
+        assert np.array_equal(host(q).numpy(), codes)
+        return q, codes, scale
+
+    Xq, xc, xs = cast(X, xb, "e4m3", 448.0)
+    dYq, dyc, dys = cast(dY, dyb, "e5m2", 57344.0)
+    amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+    sste.project_pack(W, float(beta), amax_out=amax)
+    ws = np.float32(float(host(amax)[0]) / 448.0)
+    vals, meta = sste.project_pack(W, float(beta), sste.F8E4M3, float(ws))
+    rv, rm, ra = OP.project_pack(wb, beta, "e4m3", ws)
+    assert np.float32(float(ra) / 448.0) == ws
+    fv, fm = OP.to_fragment_major(rv, rm, "e4m3")
+    assert np.array_equal(host(vals).numpy().reshape(-1), fv) and np.array_equal(host(meta).numpy().reshape(-1), fm)
+    Z = sste.linear_fwd(Xq, vals, meta, O, sste.F8E4M3, float(xs), float(ws))
+    assert rel_err(z_to_f64(Z), OL.linear_fwd(xc, rv, rm, "e4m3", xs, ws)) <= TOL["e4m3"]
+    dW = sste.linear_wgrad(dYq, Xq, 3, 1, sste.F8E5M2, float(dys), float(xs))
+    assert rel_err(host(dW).numpy().astype(np.float64), OL.linear_wgrad(dyc, xc, 3, 1, "e5m2", dys, xs, x_dtype="e4m3")) <= 1e-4
+    dX = sste.linear_dgrad(dYq, vals, meta, I, sste.F8E5M2, float(dys), float(ws))
+    assert rel_err(z_to_f64(dX), OL.linear_dgrad(dyc, rv, rm, "e5m2", dys, ws, w_dtype="e4m3")) <= TOL["e4m3"]
+    # the 8-bit forward stays close to the bf16 one (quantisation noise only)
+    v16, m16 = sste.project_pack(W, float(beta))
+    Z16 = sste.linear_fwd(X, v16, m16, O)
+    assert rel_err(z_to_f64(Z), z_to_f64(Z16)) <= 0.1
