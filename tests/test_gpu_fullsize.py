@@ -200,3 +200,53 @@ def test_full_size_e5m2_backward(sste, layer):
         worst = max(worst, float(np.max(np.abs(dW[int(o)].cpu().numpy().astype(np.float64)[cols] - ref))))
     assert worst <= 1e-4 * dmax, (worst, dmax)
     assert torch.isfinite(dW).all()
+
+
+@pytest.mark.parametrize("cfg,layer,master", [(2, 0, "bf16"), (4, 2, "bf16"), (4, 3, "f32")])
+def test_full_size_update_and_reprojection(sste, cfg, layer, master):
+    """The dense-weight step fused with the re-projection on whole layers: updated weight, packed values and
+    metadata bit for bit (the gradient is the weight-gradient kernel's own output for this layer)."""
+    wl = WL.WORKLOADS[cfg]
+    L = wl.layers[layer]
+    T, O, I = wl.T, L.O, L.I
+    print(f"cfg {cfg} layer {L.name}: O={O} I={I} dense weight {master}", flush=True)
+    wb = WL.weight_bits(wl, layer)
+    xc, xs = WL.activations(wl, layer)
+    dyc, dys = WL.output_gradient(wl, layer)
+    dW = sste.linear_wgrad(up(dyc), up(xc), 9, 1, sste.BF16, float(dys), float(xs))
+    g = dW.cpu().numpy()
+    beta = np.float32(1.4830322)
+    alpha = 0.05
+    if master == "bf16":
+        w0 = wb
+        W = up(wb)
+    else:
+        w0 = F.bf16_to_f32(wb) + np.float32(3e-6)
+        W = torch.from_numpy(w0).cuda()
+    vals, meta = sste.sgd_project_pack(W, dW, alpha, float(beta))
+    w_next, rv, rm = OP.sgd_project_pack(w0, g, alpha, beta, master)
+    if master == "bf16":
+        assert np.array_equal(W.cpu().view(torch.int16).numpy().view(np.uint16), w_next)
+    else:
+        assert np.array_equal(W.cpu().numpy().view(np.uint32), w_next.view(np.uint32))
+    fv, fm = OP.to_fragment_major(rv, rm)
+    assert np.array_equal(vals.cpu().numpy().view(np.uint16).reshape(-1), fv)
+    assert np.array_equal(meta.cpu().numpy().reshape(-1), fm)
+    assert np.count_nonzero(OP.structural_mask(rm) ^ OP.structural_mask(OP.project_pack(wb, beta)[1])) > 0     # some groups flipped
+
+
+@pytest.mark.parametrize("fmt", ["e4m3", "e5m2"])
+def test_full_size_cast(sste, fmt):
+    """Per-tensor rescale + cast of a workload-5-sized activation tensor (32768 x 1280), bit for bit."""
+    wl = WL.WORKLOADS[4]                                         # bf16 patterns of the same shapes as workload 5
+    xb = np.concatenate([WL.activations(wl, 2)[0], WL.activations(wl, 0)[0]], axis=0)       # 32768 x 1280
+    mx = 448.0 if fmt == "e4m3" else 57344.0
+    X = up(xb)
+    code = sste.F8E4M3 if fmt == "e4m3" else sste.F8E5M2
+    _, amax = sste.cast_fp8(X, 1.0, code, store=False)
+    amax_ref = np.float32(np.max(np.abs(F.bf16_to_f32(xb))))
+    assert float(amax.cpu()[0]) == float(amax_ref)
+    scale = np.float32(float(amax_ref) / mx)
+    q, _ = sste.cast_fp8(X, float(scale), code)
+    codes, _ = F.cast_fp8(xb, scale, fmt)
+    assert np.array_equal(q.cpu().numpy(), codes)
