@@ -343,8 +343,10 @@ def main():
             return (time.perf_counter() - d0) / iters * 1e6
         f_us = dense_us(lambda i: torch.matmul(Xs[i % nsets], W.t(), out=Zs[i % nsets]))
         w_us = dense_us(lambda i: torch.matmul(dYs[i % nsets].t(), Xs[i % nsets]))
+        d_us = dense_us(lambda i: torch.matmul(dYs[i % nsets], W))
         out["dense_context"] = {"library": "torch.matmul (bf16 in, bf16 out)", "fwd_us": f_us, "fwd_TFLOP_per_s": gemm_flops / f_us * 1e-6,
-                                "wgrad_us": w_us, "wgrad_TFLOP_per_s": gemm_flops / w_us * 1e-6}
+                                "wgrad_us": w_us, "wgrad_TFLOP_per_s": gemm_flops / w_us * 1e-6,
+                                "dgrad_us": d_us, "dgrad_TFLOP_per_s": gemm_flops / d_us * 1e-6}
     if out_dgrad is not None:
         out["dgrad_dense"] = out_dgrad
     if wl.cfg == 4:
