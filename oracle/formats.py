@@ -29,7 +29,19 @@ def f32_to_bf16_rne(x):
 
 def e4m3_to_f32(codes):
     """uint8 e4m3fn codes -> float32.  1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent 0 is
-    subnormal (m * 2^-9); there is no infinity; S.1111.111 is NaN."""
+    subnormal (m * 2^-9); there is no infinity; S.1111.111 is NaN.  The definition is evaluated on the
+    256 codes once and then indexed (same values, far fewer transcendental calls on large tensors)."""
+    global _E4M3_TABLE
+    if _E4M3_TABLE is None:
+        _E4M3_TABLE = _e4m3_decode_definition(np.arange(256, dtype=np.uint8))
+    return _E4M3_TABLE[np.asarray(codes, dtype=np.uint8)]
+
+
+_E4M3_TABLE = None
+_E5M2_TABLE = None
+
+
+def _e4m3_decode_definition(codes):
     c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
     s = (c >> 7) & 1
     e = (c >> 3) & 15
@@ -45,15 +57,10 @@ def f32_to_e4m3_rne_sat(x):
     x = np.asarray(x, dtype=np.float32)
     neg = np.signbit(x)
     a = np.minimum(np.abs(x).astype(np.float64), E4M3_MAX)
-    # exponent of the binade that holds a (clamped below at the subnormal binade 2^-6)
-    with np.errstate(divide="ignore"):
-        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
-    e = np.clip(e, -6, 8)
-    # re-derive with frexp to be safe against log2 rounding at binade edges
+    # exponent of the binade that holds a (clamped below at the subnormal binade 2^-6), from frexp (exact)
     mant, ex = np.frexp(a)            # a = mant * 2^ex, mant in [0.5, 1)
-    e_exact = np.where(a > 0, ex - 1, -6)
-    e = np.clip(e_exact, -6, 8).astype(np.int64)
-    step = np.exp2((e - 3).astype(np.float64))      # spacing of representable values in that binade
+    e = np.clip(np.where(a > 0, ex - 1, -6), -6, 8).astype(np.int64)
+    step = np.ldexp(1.0, e - 3)                      # spacing of representable values in that binade
     q = np.rint(a / step)                            # half-to-even, exact scaling by a power of two
     # q is in [0, 16]; q == 16 carries into the next binade
     carry = q >= 16
@@ -67,7 +74,15 @@ def f32_to_e4m3_rne_sat(x):
 
 def e5m2_to_f32(codes):
     """uint8 e5m2 codes -> float32.  1 sign, 5 exponent (bias 15), 2 mantissa bits: the top byte of an
-    IEEE half.  Exponent 0 is subnormal (m * 2^-16); exponent 31 is infinity (m = 0) or NaN."""
+    IEEE half.  Exponent 0 is subnormal (m * 2^-16); exponent 31 is infinity (m = 0) or NaN.  Evaluated
+    on the 256 codes once, then indexed."""
+    global _E5M2_TABLE
+    if _E5M2_TABLE is None:
+        _E5M2_TABLE = _e5m2_decode_definition(np.arange(256, dtype=np.uint8))
+    return _E5M2_TABLE[np.asarray(codes, dtype=np.uint8)]
+
+
+def _e5m2_decode_definition(codes):
     c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
     s = (c >> 7) & 1
     e = (c >> 2) & 31
@@ -85,7 +100,7 @@ def f32_to_e5m2_rne_sat(x):
     a = np.minimum(np.abs(x).astype(np.float64), E5M2_MAX)
     mant, ex = np.frexp(a)                           # a = mant * 2^ex, mant in [0.5, 1)
     e = np.clip(np.where(a > 0, ex - 1, -14), -14, 15).astype(np.int64)
-    step = np.exp2((e - 2).astype(np.float64))      # spacing of representable values in that binade
+    step = np.ldexp(1.0, e - 2)                      # spacing of representable values in that binade
     q = np.rint(a / step)                            # half-to-even; q in [0, 8]
     carry = q >= 8
     e = np.where(carry, e + 1, e)

@@ -43,7 +43,14 @@ steps 1-4, each rounded to float32; comparisons are exact.
   epilogue multiplies by 2.
   e5m2 storage (the backward format of Sec. 5.2): the same with e5m2 codes and RNE_e5m2.
 
-Pinned (tests/test_oracle_mvue.py): worked groups, exactly-two-positions invariant, empirical
+``mvue_definition`` is the same estimator written straight from the definition above (two-case
+probabilities, cumulative probabilities on [0, 2), owners of u and u + 1, values g / pi), with no
+code in common with the branch-free sequence; ``mvue_sample`` and the bit-spec layer are checked
+against it draw by draw.
+
+Pinned (tests/test_oracle_mvue.py): worked groups, the per-draw agreement of the branch-free
+sequence with ``mvue_definition`` on random, tied, zero-laden and capped-boundary groups,
+exactly-two-positions invariant, empirical
 inclusion frequencies against the closed-form pi, Monte-Carlo mean against g with the closed-
 form variance, optimality of pi against random feasible alternatives, continuity of the law
 at mx == r, groups with one, two or no nonzeros, and a maximum that dwarfs the other elements.
@@ -116,6 +123,64 @@ def _select(m, u, ft):
     return pos0, pos1, h
 
 
+# --------------------------------------------------------------------------- plain definition
+
+def mvue_definition(g, u):
+    """The estimator written out from its definition, in float64, one group at a time.
+
+    It shares nothing with ``_select``: no clamped line, no common threshold h.  For each group:
+      * the optimal inclusion probabilities in their two-case closed form (capped iff the largest
+        magnitude exceeds the sum of the other three; the largest is the lowest index attaining it);
+      * the probabilities laid end to end on [0, 2) in index order: element i owns
+        [C_{i-1}, C_i) with C_i = pi_0 + ... + pi_i;
+      * systematic sampling: the recorded positions are the owners of the points u and u + 1;
+      * a recorded element holds g_i / pi_i.
+    Groups with fewer than two nonzeros leave the end of [0, 2) unowned (sum pi < 2).  The rule
+    there: a point that no interval contains belongs to the last element with pi > 0 (element 3 if
+    there is none); the first position is at most 2 and the second lies after the first (the next
+    index when both points have the same owner); an element with pi_i = 0 that is recorded this
+    way holds g_i = 0 itself.
+    Returns dense theta (n, 4) and positions (n, 2); a per-group Python loop, for tests."""
+    g = np.asarray(g, dtype=np.float64).reshape(-1, 4)
+    u = np.asarray(u, dtype=np.float64).reshape(-1)
+    theta = np.zeros_like(g)
+    positions = np.zeros((g.shape[0], 2), dtype=np.int64)
+    for n in range(g.shape[0]):
+        m = [abs(float(x)) for x in g[n]]
+        c = m.index(max(m))
+        r = sum(m[i] for i in range(4) if i != c)
+        if m[c] > r:                                   # capped: the largest element is always kept
+            pi = [1.0 if i == c else (m[i] / r if r > 0 else 0.0) for i in range(4)]
+        else:                                          # proportional to magnitude, sum = 2
+            s = r + m[c]
+            pi = [2.0 * m[i] / s if s > 0 else 0.0 for i in range(4)]
+        C = [pi[0], pi[0] + pi[1], pi[0] + pi[1] + pi[2], pi[0] + pi[1] + pi[2] + pi[3]]
+        owners = [i for i in range(4) if pi[i] > 0]
+
+        def owner(point):
+            for i in range(4):
+                if point < C[i]:
+                    return i
+            return owners[-1] if owners else 3
+
+        p0 = min(owner(float(u[n])), 2)
+        p1 = min(3, max(owner(float(u[n]) + 1.0), p0 + 1))
+        for p in (p0, p1):
+            theta[n, p] = g[n, p] / pi[p] if pi[p] > 0 else g[n, p]
+        positions[n] = (p0, p1)
+    return theta, positions
+
+
+def definition_edge_distance(g, u):
+    """min over the interval ends C_0..C_2 and the two sampling points u, u + 1 of |C_k - point|,
+    per group (float64).  Tests use it to tell groups whose draw sits on an interval end -- where
+    two correctly rounded evaluations of the same rule may legitimately differ -- from the rest."""
+    pi = inclusion_probabilities(g)
+    C = np.cumsum(pi, axis=1)[:, :3]
+    u = np.asarray(u, dtype=np.float64).reshape(-1, 1)
+    return np.minimum(np.abs(C - u), np.abs(C - (u + 1.0))).min(axis=1)
+
+
 # --------------------------------------------------------------------------- math layer
 
 def mvue_sample(g, u):
@@ -175,12 +240,17 @@ def mvue_groups_bits(g_codes, u, dtype="bf16"):
     return vals, nib
 
 
-def group_ids(T, O):
-    """gid[k, o] = k * O + o for token group k = t // 4 and output channel o."""
-    return (np.arange(T // 4, dtype=np.uint64)[:, None] * np.uint64(O) + np.arange(O, dtype=np.uint64)[None, :])
+def group_ids(T, O, first_token=0):
+    """gid[k, o] = (first_token // 4 + k) * O + o for token group k = t // 4 and output channel o.
+    first_token is the global index of the tensor's first token row (a multiple of 4): a shard of
+    the token axis draws the numbers the whole tensor would draw for the same tokens."""
+    if first_token % 4 != 0:
+        raise ValueError("first_token must be a multiple of 4 (whole groups)")
+    k = np.arange(T // 4, dtype=np.uint64) + np.uint64(first_token // 4)
+    return k[:, None] * np.uint64(O) + np.arange(O, dtype=np.uint64)[None, :]
 
 
-def mvue_pack(dy_codes, seed, offset, dtype="bf16"):
+def mvue_pack(dy_codes, seed, offset, dtype="bf16", first_token=0):
     """MVUE(dY^T) in packed 2:4 form.
 
     dy_codes : (T, O) stored patterns of the output gradient (bf16 uint16 / e4m3 or e5m2 uint8).
@@ -191,7 +261,7 @@ def mvue_pack(dy_codes, seed, offset, dtype="bf16"):
     if T % 8 != 0:
         raise ValueError("T must be a multiple of 8 (two groups per metadata byte)")
     g = dy_codes.reshape(T // 4, 4, O).transpose(0, 2, 1).reshape(-1, 4)       # [(k, o), 4]
-    u = _rng.uniform24(seed, offset, group_ids(T, O).reshape(-1))
+    u = _rng.uniform24(seed, offset, group_ids(T, O, first_token).reshape(-1))
     vals, nib = mvue_groups_bits(g, u, dtype)
     vals = vals.reshape(T // 4, O, 2).transpose(1, 0, 2).reshape(O, T // 2)
     nib = nib.reshape(T // 4, O).T.reshape(O, T // 8, 2)

@@ -35,8 +35,10 @@ Readings taken where the paper is silent (all restated in the design notes of th
 
 Pinned (tests/test_oracle_projection.py): worked groups, the appendix's sorted form, the 2:4
 invariant, idempotence (projection), homogeneity, the 2-delta continuity bound of the Theorem 1
-proof, agreement of supports with the hard threshold, optimality of beta, and
-decode(pack(w)) against the float64 definition.
+proof, agreement of supports with the hard threshold, optimality of beta,
+decode(pack(w)) against the float64 definition, and the blocked device layout
+(``to_fragment_major`` / ``from_fragment_major`` / ``k_step``) against an index-by-index
+construction from its description, with round trips on ragged row counts.
 """
 import numpy as np
 

@@ -14,14 +14,18 @@ number.  The function specified for this build is:
           x ^= x>>17; x *= 0xED5AD4BB; x += k1; x ^= x>>11; x *= 0xAC4C1B51; x ^= x>>15;
           x *= 0x31848BAB; x ^= x>>14
           (a three-round 32-bit multiply-xorshift integer hash with the second key word injected
-          after the first multiply; all arithmetic modulo 2^32.  A two-round hash of this family
+          after the first multiply; all arithmetic modulo 2^32.  The three shift / multiplier
+          pairs are those of the public-domain "triple32" hash published by C. Wellons' hash-
+          prospector search for low-bias 32-bit mixers; the keying around them is this build's.  A two-round hash of this family
           was tried first and rejected: on consecutive counters its top bits failed the
           chi-square test below by ten standard deviations);
   u     : (x >> 8) * 2^-24, an exact float32 in [0, 1).
 
-Pinned (tests/test_oracle_rng.py): fixed known-answer values computed by hand-expanded Python
-integer arithmetic, chi-square uniformity, lag-1 correlation across consecutive group ids,
-across consecutive seeds and across consecutive offsets, and bijectivity on a 2^16 window.
+Pinned (tests/test_oracle_rng.py): frozen key words, draws and uniforms in
+tests/golden/rng_known_answers.txt, the published SplitMix64 outputs for seed 1234567 (key
+mixer), step-by-step inversion of the draw with the modular inverses of its multipliers,
+chi-square uniformity, lag-1 correlation across consecutive group ids, across consecutive seeds
+and across consecutive offsets, and bijectivity on a 2^16 window.
 """
 import numpy as np
 

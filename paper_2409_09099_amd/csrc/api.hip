@@ -403,9 +403,14 @@ int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, in
   if (T % (is_8bit(dtype) ? 128 : 64) != 0)
     return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld must be a multiple of %d for this element type", (long long)T, is_8bit(dtype) ? 128 : 64);
   if (lddy < O) return fail(SSTE_ERR_SHAPE, "mvue_materialize: lddy < O");
+  // the kernel reads dY in 16-byte pieces of 8 (bf16) / 16 (8-bit) channels
+  const int e16 = elems_per_16B(dtype);
+  if (O % e16 != 0) return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: O=%lld must be a multiple of %d", (long long)O, e16);
+  if (lddy % e16 != 0) return fail(SSTE_ERR_ALIGN, "mvue_materialize: lddy=%lld is not a multiple of %d", (long long)lddy, e16);
   bool empty = (T == 0 || O == 0);
   if (!empty && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "mvue_materialize: NULL dY, vals or meta");
-  if (!aligned16(vals)) return fail(SSTE_ERR_ALIGN, "mvue_materialize: vals must be 16-byte aligned");
+  if (!aligned16(dY) || !aligned16(vals) || (reinterpret_cast<uintptr_t>(meta) & 3u))
+    return fail(SSTE_ERR_ALIGN, "mvue_materialize: dY and vals must be 16-byte aligned, meta 4-byte aligned");
   if (T / 8 > 65535) return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld exceeds 524280", (long long)T);
   return hip_status(launch_mvue_materialize(dY, T, O, lddy, dtype, derive_key(seed, offset), vals, meta, (hipStream_t)hip_stream),
                     "mvue_materialize launch");

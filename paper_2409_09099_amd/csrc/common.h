@@ -111,19 +111,24 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0F70 | ((N >> 4) << 14));
 }
 
-// 64 lanes x 16 B (or 4 B) from a buffer descriptor straight into LDS at lds_addr + lane * 16 (4)
+// 64 lanes x 16 B (or 4 B) from a buffer descriptor straight into LDS at lds_addr + lane * 16 (4).
+// The statements overwrite M0 and say so in their clobber list, so the compiler never keeps a value
+// of its own in M0 across them (it warns that M0 is a reserved register; that is the point).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
                : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory");
+               : "memory", "m0");
 }
 __device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                :
                : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory");
+               : "memory", "m0");
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
   uint64_t p = (uint64_t)base;
   i32x4 r;

@@ -1,8 +1,8 @@
 """Seeded synthetic inputs for the S-STE sparse-linear hot path.
 
-This module holds NO arithmetic of the method (no projection, no sparsifier, no GEMM): it only
-draws Gaussian tensors with the shapes and scales of GPT-2 layers and casts them to the storage
-formats, using PyTorch's CPU casts.  Both the HIP path and the CPU oracle are fed from here so
+This module holds NO arithmetic of the method (no projection, no sparsifier, no GEMM, no 8-bit
+rescaling): it only draws Gaussian tensors with the shapes and scales of GPT-2 layers and rounds them
+to bf16 with PyTorch's CPU cast.  Both the HIP path and the CPU oracle are fed from here so
 that they see identical bits.
 
 Shapes: W is (O, I) = (out, in) row-major, X is (T, I), dY is (T, O); T = batch x sequence tokens.
@@ -49,7 +49,6 @@ WORKLOADS = {
 }
 
 W_STD, X_STD, DY_STD, UPDATE_STD = 0.02, 1.0, 1e-3, 1e-4
-E4M3_MAX = 448.0
 
 
 def _generator(base_seed: int, layer_index: int, kind: int, step: int = 0) -> np.random.Generator:
@@ -74,29 +73,6 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return t.numpy().copy()
 
 
-def quantize_e4m3(x_f32: np.ndarray):
-    """Per-tensor absmax scaling to OCP e4m3fn: returns (codes uint8, scale float32) with
-    x ~= scale * decode(codes)."""
-    amax = float(np.max(np.abs(x_f32))) if x_f32.size else 0.0
-    scale = np.float32(amax / E4M3_MAX) if amax > 0 else np.float32(1.0)
-    t = torch.from_numpy(np.ascontiguousarray(x_f32)) / float(scale)
-    t = t.clamp_(-E4M3_MAX, E4M3_MAX).to(torch.float8_e4m3fn)
-    return t.view(torch.uint8).numpy().copy(), scale
-
-
-E5M2_MAX = 57344.0
-
-
-def quantize_e5m2(x_f32: np.ndarray):
-    """Per-tensor absmax scaling to OCP e5m2 (the backward format of Sec. 5.2): returns (codes uint8,
-    scale float32) with x ~= scale * decode(codes)."""
-    amax = float(np.max(np.abs(x_f32))) if x_f32.size else 0.0
-    scale = np.float32(amax / E5M2_MAX) if amax > 0 else np.float32(1.0)
-    t = torch.from_numpy(np.ascontiguousarray(x_f32)) / float(scale)
-    t = t.clamp_(-E5M2_MAX, E5M2_MAX).to(torch.float8_e5m2)
-    return t.view(torch.uint8).numpy().copy(), scale
-
-
 def weight_bits(wl: Workload, layer_index: int, O=None, I=None) -> np.ndarray:
     """bf16 master weight (O, I) as uint16 patterns."""
     L = wl.layers[layer_index]
@@ -112,19 +88,16 @@ def weight_update_bits(w_bits: np.ndarray, wl: Workload, layer_index: int, step:
 
 
 def activations(wl: Workload, layer_index: int, T=None, I=None):
-    """X (T, I): returns (codes, scale).  bf16: uint16 patterns, scale 1; e4m3: uint8 codes + scale."""
+    """X (T, I) as bf16 patterns (uint16), and the scale 1 that goes with unquantised storage.  The
+    8-bit workload derives its e4m3 operand from these with the per-tensor rescale + cast of Sec. 5.2,
+    which is part of the method: the library's sste_cast_fp8 on one side, the oracle's cast on the other."""
     L = wl.layers[layer_index]
     x = gaussian_f32((T or wl.T, I or L.I), X_STD, wl.base_seed, layer_index, KIND_X)
-    if wl.dtype == "bf16":
-        return to_bf16_bits(x), np.float32(1.0)
-    return quantize_e4m3(x)
+    return to_bf16_bits(x), np.float32(1.0)
 
 
-def output_gradient(wl: Workload, layer_index: int, T=None, O=None, e5m2=False):
-    """dY (T, O): returns (codes, scale) like ``activations``; e5m2=True quantises an 8-bit workload's
-    gradient to e5m2 instead of e4m3."""
+def output_gradient(wl: Workload, layer_index: int, T=None, O=None):
+    """dY (T, O) as bf16 patterns (uint16) and the scale 1, like ``activations``."""
     L = wl.layers[layer_index]
     g = gaussian_f32((T or wl.T, O or L.O), DY_STD, wl.base_seed, layer_index, KIND_DY)
-    if wl.dtype == "bf16":
-        return to_bf16_bits(g), np.float32(1.0)
-    return quantize_e5m2(g) if e5m2 else quantize_e4m3(g)
+    return to_bf16_bits(g), np.float32(1.0)

@@ -49,6 +49,28 @@ def act_dev(codes, dtype):
     return bf16_dev(codes) if dtype == "bf16" else dev(codes)
 
 
+FMT_MAX = {"e4m3": 448.0, "e5m2": 57344.0}
+
+
+def operand(lib, bits, dtype):
+    """bf16 patterns -> (the oracle's copy of the operand, its scale, the GPU's copy) in storage format
+    `dtype`.  For the 8-bit formats each side runs its OWN per-tensor rescale + cast of Sec. 5.2 (oracle:
+    formats.cast_fp8; GPU: sste_cast_fp8) with scale = largest magnitude / format maximum, and the two
+    must agree bit for bit before anything is built on them."""
+    bits = np.ascontiguousarray(bits)
+    if dtype == "bf16":
+        return bits, np.float32(1.0), bf16_dev(bits)
+    xd = bf16_dev(bits)
+    _, amax = lib.cast_fp8(xd, 1.0, dt(lib, dtype), store=False)
+    amax_ref = np.float32(np.max(np.abs(F.bf16_to_f32(bits)))) if bits.size else np.float32(0.0)
+    assert float(host(amax)[0]) == float(amax_ref)
+    scale = np.float32(float(amax_ref) / FMT_MAX[dtype]) if amax_ref > 0 else np.float32(1.0)
+    codes, _ = F.cast_fp8(bits, scale, dtype)
+    q, _ = lib.cast_fp8(xd, float(scale), dt(lib, dtype))
+    assert np.array_equal(host(q).numpy(), codes)
+    return codes, scale, q
+
+
 def rel_err(got, ref):
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))
 
@@ -318,10 +340,10 @@ def test_cast_fp8_bit_exact(sste, fmt, case):
     if pad:
         assert bool((Qbig[:, C:] == 0x55).all())
     if case == "activations" and fmt == "e4m3":
-        # the same tensor through the workload's host-side quantiser (PyTorch casts)
-        xf = F.bf16_to_f32(xb)
-        ref_codes, ref_scale = WL.quantize_e4m3(xf)
-        assert np.float32(ref_scale) == scale and np.array_equal(codes, ref_codes)
+        # the same tensor through PyTorch's CPU cast (an independent implementation of the same rounding)
+        t = torch.from_numpy(F.bf16_to_f32(xb).copy()) / float(scale)
+        ref_codes = t.clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(codes, ref_codes)
 
 
 def test_cast_fp8_empty_and_errors(sste):
@@ -361,13 +383,14 @@ def _edge_gradients(dtype):
 def test_mvue_materialize_bit_exact(sste, dtype, case):
     wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
     if case == "cfg1":
-        codes, _ = WL.output_gradient(wl, 0, T=512, O=256, e5m2=dtype == "e5m2")
-    elif case == "ragged":
-        codes, _ = WL.output_gradient(wl, 0, T=384, O=333, e5m2=dtype == "e5m2")
+        codes, _, dYd = operand(sste, WL.output_gradient(wl, 0, T=512, O=256)[0], dtype)
+    elif case == "ragged":             # 2.6 tiles of 128 channels, a half-filled last block of 16 rows (bf16: 8-channel pieces)
+        codes, _, dYd = operand(sste, WL.output_gradient(wl, 0, T=384, O=328 if dtype == "bf16" else 336)[0], dtype)
     else:
         codes = _edge_gradients(dtype)
+        dYd = act_dev(codes, dtype)
     for seed, offset in [(0, 0), (1, 0), (12345678901234567, 99)]:
-        vals, meta = sste.mvue_materialize(act_dev(codes, dtype), seed, offset, dt(sste, dtype))
+        vals, meta = sste.mvue_materialize(dYd, seed, offset, dt(sste, dtype))
         rv, rm = OM.mvue_pack(codes, seed, offset, dtype)
         T_, O_ = codes.shape
         gv, gm = OP.from_fragment_major(host(vals).numpy().view(rv.dtype).reshape(-1), host(meta).numpy().reshape(-1), O_, T_, dtype)
@@ -375,12 +398,29 @@ def test_mvue_materialize_bit_exact(sste, dtype, case):
         assert np.array_equal(gv, rv), (case, seed, np.argwhere(gv != rv)[:5])
 
 
+def test_mvue_materialize_refuses_partial_pieces(sste):
+    """The estimator kernel reads dY in 16-byte pieces: channel counts and leading dimensions that are not
+    whole pieces, and misaligned bases, are refused before anything is launched."""
+    for dtype, tdt, O in (("bf16", torch.bfloat16, 333), ("e4m3", torch.uint8, 328), ("e5m2", torch.uint8, 24)):
+        dY = torch.zeros((128, O), dtype=tdt, device="cuda")
+        with pytest.raises(sste.SsteError) as ei:
+            sste.mvue_materialize(dY, 0, 0, dt(sste, dtype))
+        assert ei.value.status == 7, dtype
+    wide = torch.zeros((128, 72), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sste.SsteError) as ei:          # rows of 72 elements, 68-element stride is impossible; 8-element view of a 12-stride buffer
+        sste.mvue_materialize(torch.zeros((128, 12), dtype=torch.bfloat16, device="cuda")[:, :8], 0, 0)
+    assert ei.value.status == 3
+    with pytest.raises(sste.SsteError) as ei:          # base pointer 8 bytes into a row
+        sste.mvue_materialize(wide[:, 4:68], 0, 0)
+    assert ei.value.status == 3
+
+
 # ------------------------------------------------------------------------------------------ forward GEMM
 
 def _fwd_case(sste, dtype, T, O, I, seed_layer=0):
     wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
     wb = WL.weight_bits(wl, seed_layer, O=O, I=I)
-    xc, xs = WL.activations(wl, seed_layer, T=T, I=I)
+    xc, xs, Xd = operand(sste, WL.activations(wl, seed_layer, T=T, I=I)[0], dtype)
     beta = np.float32(1.4830322)
     if dtype == "bf16":
         ws = np.float32(1.0)
@@ -391,7 +431,7 @@ def _fwd_case(sste, dtype, T, O, I, seed_layer=0):
         ws = np.float32(max(float(amax), 1e-30) / 448.0)
         rv, rm, _ = OP.project_pack(wb, beta, "e4m3", ws)
         vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(ws))
-    Z = sste.linear_fwd(act_dev(xc, dtype), vals, meta, O, dt(sste, dtype), float(xs), float(ws))
+    Z = sste.linear_fwd(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws))
     ref = OL.linear_fwd(xc, rv, rm, dtype, xs, ws)
     return z_to_f64(Z), ref
 
@@ -434,9 +474,9 @@ def test_linear_fwd_empty_and_errors(sste):
 
 def _wgrad_case(sste, dtype, T, O, I, seed=3, offset=5, **kw):
     wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
-    dyc, dys = WL.output_gradient(wl, 0, T=T, O=O, e5m2=dtype == "e5m2")
-    xc, xs = WL.activations(wl, 0, T=T, I=I)
-    dW = sste.linear_wgrad(act_dev(dyc, dtype), act_dev(xc, dtype), seed, offset, dt(sste, dtype), float(dys), float(xs), **kw)
+    dyc, dys, dYd = operand(sste, WL.output_gradient(wl, 0, T=T, O=O)[0], dtype)
+    xc, xs, Xd = operand(sste, WL.activations(wl, 0, T=T, I=I)[0], "e4m3" if dtype == "e5m2" else dtype)
+    dW = sste.linear_wgrad(dYd, Xd, seed, offset, dt(sste, dtype), float(dys), float(xs), **kw)
     ref = OL.linear_wgrad(dyc, xc, seed, offset, dtype, dys, xs, x_dtype="e4m3" if dtype == "e5m2" else None)
     return dW, ref
 
@@ -592,8 +632,9 @@ def test_step_under_graph_capture_replays_bit_exact(sste):
 def test_linear_dgrad_matches_oracle(sste, dtype, T, O, I):
     wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
     beta = np.float32(1.4830322)
-    dyc, dys = WL.output_gradient(wl, 0, T=T, O=max(O, 16), e5m2=dtype == "e5m2")
-    dyc = dyc[:, :O]
+    dys = np.float32(1.0)
+    if O:
+        dyc, dys, dY = operand(sste, WL.output_gradient(wl, 0, T=T, O=O)[0], dtype)
     ws = np.float32(1.0)
     wdt = "e4m3" if dtype == "e5m2" else dtype                 # e5m2 gradients meet an e4m3 weight (Sec. 5.2)
     if O:
@@ -604,7 +645,6 @@ def test_linear_dgrad_matches_oracle(sste, dtype, T, O, I):
         rv, rm, _ = OP.project_pack(wb, beta, wdt, ws)
         vals, meta = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, wdt), float(ws))
         ref = OL.linear_dgrad(dyc, rv, rm, dtype, dys, ws, w_dtype=wdt)
-        dY = act_dev(np.ascontiguousarray(dyc), dtype)
     else:
         vals, meta = sste.packed_buffers(0, I, dt(sste, wdt), "cuda")
         ref = np.zeros((T, I))

@@ -230,3 +230,100 @@ def test_pack_layout_and_group_ids():
     assert (int(meta[o, k // 2]) >> (4 * (k % 2))) & 0xF == int(n1[0])
     with pytest.raises(ValueError):
         M.mvue_pack(dy[:12], 0, 0)
+
+
+# ------------------------------------------------------------------ the plain definition, draw by draw
+
+def _definition_groups(rs, n):
+    """Random groups of every kind the estimator distinguishes: generic, capped, on the cap boundary,
+    with zeros, with ties, one huge element beside tiny ones."""
+    g = rs.standard_normal((n, 4)) * np.exp(rs.uniform(-3, 3, (n, 1)))
+    kind = rs.integers(0, 8, n)
+    big = kind == 1                                     # clearly capped
+    g[big, rs.integers(0, 4, big.sum())] *= 50.0
+    for k, zeros in ((2, 1), (3, 2), (4, 3)):           # one, two, three zeros
+        rows = np.flatnonzero(kind == k)
+        for z in range(zeros):
+            g[rows, (rs.integers(0, 4, rows.size) + z) % 4 if z == 0 else rs.integers(0, 4, rows.size)] = 0.0
+    ties = np.flatnonzero(kind == 5)                    # equal magnitudes, mixed signs
+    g[ties] = np.sign(g[ties]) * np.abs(g[ties, :1]) * rs.choice([1.0, 1.0, 2.0, 0.5], (ties.size, 4))
+    edge = np.flatnonzero(kind == 6)                    # largest == sum of the others, exactly (small integers)
+    small = rs.integers(0, 6, (edge.size, 3)).astype(np.float64)
+    col = rs.integers(0, 4, edge.size)
+    ge = np.zeros((edge.size, 4))
+    for n_, (row, c) in enumerate(zip(small, col)):
+        others = [i for i in range(4) if i != c]
+        ge[n_, others] = row * rs.choice([-1.0, 1.0], 3)
+        ge[n_, c] = row.sum()
+    g[edge] = ge
+    tiny = np.flatnonzero(kind == 7)                    # a huge element next to tiny ones
+    g[tiny] *= 1e-12
+    g[tiny, rs.integers(0, 4, tiny.size)] = rs.choice([-1.0, 1.0], tiny.size) * 1e6
+    return g
+
+
+def test_branch_free_sequence_equals_the_plain_definition_draw_by_draw():
+    """mvue_sample (the branch-free sequence in float64) records the same positions and values as the
+    estimator written out from its definition, on >= 1e5 groups of every kind, for draws that do not
+    sit on an interval end (there two roundings of the same rule may differ; such draws are rare and
+    counted)."""
+    rs = np.random.default_rng(20240911)
+    n = 120000
+    g = _definition_groups(rs, n)
+    u = rs.integers(0, 1 << 24, n).astype(np.float64) * 2.0 ** -24        # the 24-bit uniforms the draw produces
+    theta_d, pos_d = M.mvue_definition(g, u)
+    theta_s, pos_s = M.mvue_sample(g, u)
+    clear = M.definition_edge_distance(g, u) > 1e-9
+    assert clear.mean() > 0.97
+    assert np.array_equal(pos_d[clear], pos_s[clear])
+    scale = np.abs(g).sum(axis=1, keepdims=True) + 1e-300
+    assert np.max(np.abs(theta_d[clear] - theta_s[clear]) / scale[clear]) < 1e-12
+    # on an interval end the two may pick either neighbour, nothing else
+    off = ~clear & np.any(pos_d != pos_s, axis=1)
+    assert np.all(np.abs(pos_d[off] - pos_s[off]).max(axis=1) <= 1)
+
+
+def test_plain_definition_on_exact_inputs_including_interval_ends():
+    """Small-integer groups and dyadic u: every quantity is exact in both forms, so they must agree
+    everywhere, also when u sits exactly on an interval end; the worked groups of the golden file too."""
+    vals = np.array([0.0, 1.0, -1.0, 2.0, -2.0, 4.0])
+    grid = np.stack(np.meshgrid(vals, vals, vals, vals, indexing="ij"), axis=-1).reshape(-1, 4)
+    # keep groups whose probabilities are dyadic: sum of magnitudes (uncapped) or of the three others (capped) a power of two
+    m = np.abs(grid)
+    s = m.sum(axis=1)
+    r = s - m.max(axis=1)
+    capped = m.max(axis=1) > r
+    denom = np.where(capped, r, s)
+    dyadic = (denom > 0) & (np.log2(np.where(denom > 0, denom, 1.0)) % 1 == 0)
+    grid = grid[dyadic]
+    assert grid.shape[0] > 150
+    for u in (0.0, 0.125, 0.25, 0.5, 0.75, 0.875, 1.0 - 2.0 ** -24):
+        uu = np.full(grid.shape[0], u)
+        theta_d, pos_d = M.mvue_definition(grid, uu)
+        theta_s, pos_s = M.mvue_sample(grid, uu)
+        assert np.array_equal(pos_d, pos_s), u
+        assert np.array_equal(theta_d, theta_s), u
+    for g, u, th, pos in _golden():
+        theta, p = M.mvue_definition(g[None, :], np.array([u]))
+        assert np.array_equal(theta[0], th) and p[0].tolist() == pos.tolist(), (g, u)
+
+
+def test_bitspec_positions_equal_the_plain_definition_on_stored_patterns():
+    """The float32 rounding sequence on bf16 / e4m3 patterns records the positions of the definition
+    (evaluated in float64 on the decoded values) wherever the draw is clear of an interval end by more
+    than float32 rounding, and its values are the definition's rounded to the storage format."""
+    rs = np.random.default_rng(7)
+    n = 60000
+    g = _definition_groups(rs, n).astype(np.float32)
+    codes = F.f32_to_bf16_rne(g)
+    gq = F.bf16_to_f32(codes).astype(np.float64)
+    u32 = (rs.integers(0, 1 << 24, n).astype(np.float32) * np.float32(2.0 ** -24))
+    vals, nib = M.mvue_groups_bits(codes, u32, "bf16")
+    theta_d, pos_d = M.mvue_definition(gq, u32.astype(np.float64))
+    clear = M.definition_edge_distance(gq, u32.astype(np.float64)) > 1e-5
+    assert clear.mean() > 0.95
+    assert np.array_equal((nib & 3)[clear], pos_d[clear, 0]) and np.array_equal((nib >> 2)[clear], pos_d[clear, 1])
+    rows = np.flatnonzero(clear)
+    got = F.bf16_to_f32(vals[rows]).astype(np.float64)
+    want = np.stack([theta_d[rows, pos_d[rows, 0]], theta_d[rows, pos_d[rows, 1]]], axis=1)
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-45)          # one bf16 rounding of h

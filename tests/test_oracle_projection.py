@@ -243,3 +243,55 @@ def test_sgd_project_pack_is_step_then_projection_of_the_definition():
     got = dense.astype(np.float64)
     assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -8 + 1e-30)
     assert np.array_equal(got != 0, want != 0)
+
+
+# ------------------------------------------------------------------ the blocked device layout (pure data movement)
+
+def _fragment_major_by_hand(vals, meta, KS):
+    """The blocked layout written with explicit indices from its description: block (rb, s) of 16 rows x
+    one column step; in a block, slot 16 q + j holds row 16 rb + j, dense columns [KS s + KS/4 q, KS s +
+    KS/4 (q + 1)): KS/8 recorded values and KS/32 metadata bytes (two groups per byte); blocks follow each
+    other in (rb, s) order; rows past R are all-zero rows (values 0, nibbles 0 | 1 << 2)."""
+    R, half = vals.shape
+    K = 2 * half
+    S, RB = K // KS, (R + 15) // 16
+    per, mper = KS // 8, KS // 32
+    out_v = np.zeros(RB * S * 64 * per, dtype=vals.dtype)
+    out_m = np.zeros(RB * S * 64 * mper, dtype=np.uint8)
+    for rb in range(RB):
+        for s in range(S):
+            for q in range(4):
+                for j in range(16):
+                    slot = (rb * S + s) * 64 + 16 * q + j
+                    row = 16 * rb + j
+                    col0 = KS * s + KS // 4 * q                     # first dense column of the slot
+                    for e in range(per):
+                        out_v[slot * per + e] = vals[row, col0 // 2 + e] if row < R else 0
+                    for e in range(mper):
+                        out_m[slot * mper + e] = meta[row, col0 // 8 + e] if row < R else 0x44
+    return out_v, out_m
+
+
+@pytest.mark.parametrize("val_dtype,R,K", [("bf16", 37, 192), ("bf16", 16, 64), ("e4m3", 20, 256), ("e5m2", 3, 128)])
+def test_fragment_major_layout_by_hand_and_round_trip(val_dtype, R, K):
+    rs = np.random.default_rng(R * 1000 + K)
+    KS = P.k_step(val_dtype)
+    assert KS == (64 if val_dtype == "bf16" else 128)
+    if val_dtype == "bf16":
+        vals = rs.integers(0, 1 << 16, (R, K // 2)).astype(np.uint16)
+    else:
+        vals = rs.integers(0, 256, (R, K // 2)).astype(np.uint8)
+    meta = rs.integers(0, 256, (R, K // 8)).astype(np.uint8)
+    fv, fm = P.to_fragment_major(vals, meta, val_dtype)
+    hv, hm = _fragment_major_by_hand(vals, meta, KS)
+    assert fv.dtype == vals.dtype and np.array_equal(fv, hv)
+    assert np.array_equal(fm, hm)
+    rv, rm = P.from_fragment_major(fv, fm, R, K, val_dtype)
+    assert np.array_equal(rv, vals) and np.array_equal(rm, meta)
+    # one slot spelled out: block (rb = 0, s = last), q = 2, j = 5 holds row 5, dense columns KS (S - 1) + KS / 2 ...
+    if R > 5:
+        S = K // KS
+        per = KS // 8
+        slot = (0 * S + (S - 1)) * 64 + 16 * 2 + 5
+        first_col = KS * (S - 1) + KS // 2
+        assert np.array_equal(fv[slot * per:(slot + 1) * per], vals[5, first_col // 2:first_col // 2 + per])

@@ -83,3 +83,62 @@ def test_draw_is_a_bijection_of_the_low_word():
     k0, k1 = rng.derive_key(1, 2)
     x = rng.draw_u32(k0, k1, np.arange(1 << 16, dtype=np.uint64))
     assert len(np.unique(x)) == 1 << 16
+
+
+# ------------------------------------------------------------------ values the oracle itself cannot move
+
+def test_frozen_known_answers():
+    """tests/golden/rng_known_answers.txt freezes key words, draws and uniforms (written once by the
+    committed script beside it, which calls only oracle/): a later edit of the draw, consistent or not,
+    fails here."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "rng_known_answers.txt")
+    n = 0
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        ids, keys, draw, num = [p.split() for p in line.split("|")]
+        seed, offset, gid = (int(v) for v in ids)
+        assert rng.derive_key(seed, offset) == (int(keys[0], 16), int(keys[1], 16)), line
+        k0, k1 = rng.derive_key(seed, offset)
+        assert int(rng.draw_u32(k0, k1, np.array([gid], dtype=np.uint64))[0]) == int(draw[0], 16), line
+        u = rng.uniform24(seed, offset, np.array([gid], dtype=np.uint64))[0]
+        assert u == np.float32(int(num[0]) * 2.0 ** -24) and int(num[0]) == int(draw[0], 16) >> 8, line
+        n += 1
+    assert n >= 12
+
+
+def test_key_mixer_reproduces_the_published_generator_outputs():
+    """mix64 is the output function of the SplitMix64 generator (state advances by the golden-ratio
+    increment).  Its published reference outputs for seed 1234567 are reproduced here."""
+    want = [6457827717110365317, 3203168211198807973, 9817491932198370423, 4593380528125082431, 16408922859458223821]
+    state = 1234567
+    for w in want:
+        state = (state + rng.GOLDEN64) & ((1 << 64) - 1)
+        assert rng.mix64(state) == w
+
+
+def test_draw_inverts_step_by_step():
+    """With zero key words the draw is a chain of invertible steps (xor-shifts and odd multipliers);
+    undoing them with the modular inverses of the multipliers recovers the group id.  A wrong shift,
+    multiplier or step order breaks the inversion, whatever the forward code says."""
+    def unxorshift(x, s):
+        y = x
+        for _ in range(32 // s + 1):
+            y = x ^ (y >> s)
+        return y & 0xFFFFFFFF
+
+    m = 0xFFFFFFFF
+    inv = [pow(c, -1, 1 << 32) for c in (0x31848BAB, 0xAC4C1B51, 0xED5AD4BB)]
+    gids = np.array([0, 1, 2, 0xDEADBEEF, 0xFFFFFFFF, 123456789], dtype=np.uint64)
+    out = rng.draw_u32(0, 0, gids)
+    for gid, x in zip(gids.tolist(), out.tolist()):
+        x = unxorshift(x, 14)
+        x = x * inv[0] & m
+        x = unxorshift(x, 15)
+        x = x * inv[1] & m
+        x = unxorshift(x, 11)
+        x = x * inv[2] & m
+        x = unxorshift(x, 17)
+        assert x == gid
