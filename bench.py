@@ -1,15 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the S-STE 2:4 sparse linear-layer hot path on one MI355X.
 
-A step is one pass of the whole hot path over one batch of synthetic input:
+A step is one pass of the whole hot path over one batch of synthetic input, for EVERY linear layer of the
+workload, back to back on one stream:
   project + scale + pack of W  ->  forward sparse GEMM  ->  MVUE weight-gradient sparse GEMM.
-The default workload is the GPT-2-124M FFN fc1 layer (W 3072 x 768, 8192 tokens, bf16).
-Prints ONE JSON line.  `value` = dense-equivalent TFLOP/s of forward + weight gradient
-(2 * 2*T*I*O flops per step) over the whole step time, pruning included.
+The default (headline) workload is the largest one: the four linears of a GPT-2-774M block in the 8-bit
+format (e4m3 weights, activations and gradients, 32768 tokens).  The same measurement on the bf16 block
+(16384 tokens) and on the GPT-2-124M fc1 layer rides along in `secondary`.
+Prints ONE JSON line.  `value` = dense-equivalent TFLOP/s of forward + weight gradient of all layers
+(sum of 2 * 2*T*I*O flops) over the whole step time, pruning included.
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -20,42 +25,273 @@ if ROOT not in sys.path:
 # published MI355X peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_DENSE_TFLOPS = {"bf16": 2500.0, "e4m3": 5000.0}
-
-# HBM bytes per launch on the headline workload, from two rocprofv3 --pmc runs of this file (FETCH_SIZE
-# scaled by 2.000, WRITE_SIZE by 1.000: what a plain 256 MiB copy reads on the same counters); the
-# summary with the commands is committed under profiles/.  KiB read + KiB written.
-HBM_TRAFFIC_KIB = {
-    (2, "project_pack"): 4658 + 2592,
-    (2, "fwd"): 42304 + 49211,
-    (2, "mvue_pack"): 49246 + 27648,
-    (2, "wgrad"): 67784 + 36887,
-}
+FMT_MAX = {"e4m3": 448.0, "e5m2": 57344.0}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload number (1-5); 2 is the headline one")
-    ap.add_argument("--layer", type=int, default=0, help="layer index inside the workload")
-    ap.add_argument("--sets", type=int, default=4, help="activation buffer sets rotated over steps (1 = cache-warm)")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=5, help="workload number (1-5); 5 is the headline one")
+    ap.add_argument("--layer", type=int, default=-1, help="layer index inside the workload; -1 = every layer (the block)")
+    ap.add_argument("--sets", type=int, default=0,
+                    help="activation buffer sets rotated over steps; 0 = as many as it takes to exceed the 256 MB cache twice over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the bf16 block and the 124M layer")
     ap.add_argument("--grad-e5m2", action="store_true",
                     help="8-bit workloads: output gradients in e5m2 (the paper's backward format) instead of e4m3")
     ap.add_argument("--dense-context", action="store_true",
                     help="also time the vendor dense bf16 GEMM (torch.matmul) on the same shapes: context, not the product")
     ap.add_argument("--no-prune-model", action="store_true",
                     help="skip the whole-model re-projection measurement (144 weight tensors of GPT-2-774M, 2.2 GB)")
-    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with events (debug)")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="do not bracket kernels with events (for counter runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies before the warm-up (reference for HBM byte counters)")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32, grad_e5m2=False):
-    """Times the oracle, as it stands, on one full step of the same workload (host cores)."""
-    import numpy as np
+def hbm_traffic_table():
+    """(workload, kernel kind) -> HBM bytes per launch, read from the committed rocprofv3 counter summary
+    profiles/hbm_traffic.md (FETCH_SIZE and WRITE_SIZE runs of this file, scaled as that summary states).
+    Rows look like `| 5 | wgrad | 123456 | 65432 |` (KiB fetched, KiB written, averages per launch)."""
+    table = {}
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    if not os.path.exists(path):
+        return table
+    for line in open(path):
+        m = re.match(r"^\|\s*(\d+)\s*\|\s*([a-z_]+)\s*\|\s*([0-9.]+)\s*\|\s*([0-9.]+)\s*\|", line)
+        if m:
+            table[(int(m.group(1)), m.group(2))] = (float(m.group(3)) + float(m.group(4))) * 1024.0
+    return table
+
+
+class LayerState:
+    """Device-resident operands and outputs of one linear layer (several rotating sets of the big ones)."""
+    pass
+
+
+def make_layer(sste, torch, np, WL, wl, li, nsets, grad_e5m2):
+    L = wl.layers[li]
+    T, O, I = wl.T, L.O, L.I
+    fp8 = wl.dtype == "e4m3"
+    st = LayerState()
+    st.name, st.T, st.O, st.I, st.fp8 = L.name, T, O, I, fp8
+    st.dt = sste.F8E4M3 if fp8 else sste.BF16
+    st.gdt = sste.F8E5M2 if (fp8 and grad_e5m2) else st.dt
+    st.esize = 1 if fp8 else 2
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits.view(np.int16))).cuda().view(torch.bfloat16)
+
+    st.wb = WL.weight_bits(wl, li)
+    st.W = up(st.wb)
+    xb = WL.activations(wl, li)[0]
+    dyb = WL.output_gradient(wl, li)[0]
+    Xb, dYb = up(xb), up(dyb)
+    del xb, dyb
+    if fp8:
+        # operand preparation of Sec. 5.2 on the GPU, before the timed region: per-tensor largest magnitude,
+        # then rescale + cast
+        def quantise(t, fmt_code, fmt_max):
+            _, amax = sste.cast_fp8(t, 1.0, fmt_code, store=False)
+            scale = float(np.float32(float(amax.cpu()[0]) / fmt_max))
+            q, _ = sste.cast_fp8(t, scale, fmt_code)
+            return q, scale
+        X0, st.xs = quantise(Xb, sste.F8E4M3, FMT_MAX["e4m3"])
+        dY0, st.dys = quantise(dYb, st.gdt, FMT_MAX["e5m2" if st.gdt == sste.F8E5M2 else "e4m3"])
+        del Xb, dYb
+    else:
+        X0, dY0, st.xs, st.dys = Xb, dYb, 1.0, 1.0
+    st.Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
+    st.dYs = [dY0] + [dY0.clone() for _ in range(nsets - 1)]
+    st.Zs = [torch.empty((T, O), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+    st.dWs = [torch.empty((O, I), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    st.vals, st.meta = sste.packed_buffers(O, I, st.dt, "cuda")
+    st.ws_bytes = sste.wgrad_workspace_bytes(T, O, I, st.gdt)
+    st.wss = [torch.empty(max(st.ws_bytes, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    # beta: computed once from the initial weights, then frozen (Sec. 4.2)
+    st.beta = float(sste.compute_beta(st.W).cpu()[0])
+    if fp8:
+        amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+        sste.project_pack(st.W, st.beta, sste.BF16, 1.0, amax_out=amax)
+        st.w_scale = float(np.float32(float(amax.cpu()[0]) / 448.0))
+    else:
+        st.w_scale = 1.0
+    st.flops = 2.0 * T * I * O                        # dense-equivalent flops of one GEMM
+    st.nsets = nsets
+    return st
+
+
+def layer_step(sste, st, seed, i):
+    s = i % st.nsets
+    sste.project_pack(st.W, st.beta, st.dt, st.w_scale, vals=st.vals, meta=st.meta)
+    sste.linear_fwd(st.Xs[s], st.vals, st.meta, st.O, st.dt, st.xs, st.w_scale, Z=st.Zs[s])
+    sste.linear_wgrad(st.dYs[s], st.Xs[s], seed=seed, offset=i, dtype=st.gdt, dy_scale=st.dys, x_scale=st.xs,
+                      dW=st.dWs[s], workspace=st.wss[s])
+
+
+def kernel_table(sste, layers, kt, dtype):
+    """Per-kind averages over all launches of the events pass, with the algorithmic work the launches did."""
+    def avg_ms(name):
+        ms, n = kt[name]
+        return ms / n if n else float("nan")
+
+    n_layers = len(layers)
+    flops = sum(st.flops for st in layers) / n_layers                     # mean dense-equivalent flops per GEMM launch
+    pp_bytes = sum(st.O * st.I * (2 + st.esize / 2 + 0.125) for st in layers) / n_layers
+    mv_bytes = sum(st.T * st.O * st.esize * (1 + 0.5 + 0.0625) for st in layers if st.ws_bytes) / max(1, sum(1 for st in layers if st.ws_bytes))
+    kernels = {}
+    ms = avg_ms("project_pack")
+    kernels["project_pack"] = {"ms": ms, "launches": kt["project_pack"][1], "GB_per_s": pp_bytes / (ms * 1e-3) * 1e-9,
+                               "frac_hbm_peak": pp_bytes / (ms * 1e-3) * 1e-9 / PEAK_HBM_GBS}
+    for k in ("fwd", "wgrad"):
+        ms = avg_ms(k)
+        kernels[k] = {"ms": ms, "launches": kt[k][1], "dense_equiv_TFLOP_per_s": flops / (ms * 1e-3) * 1e-12}
+        kernels[k]["frac_sparse_mfma_peak"] = kernels[k]["dense_equiv_TFLOP_per_s"] / (2 * PEAK_DENSE_TFLOPS[dtype])
+    if kt["wgrad_reduce"][1]:
+        kernels["wgrad_reduce"] = {"ms": avg_ms("wgrad_reduce"), "launches": kt["wgrad_reduce"][1]}
+    if kt["mvue_pack"][1]:
+        ms = avg_ms("mvue_pack")
+        kernels["mvue_pack"] = {"ms": ms, "launches": kt["mvue_pack"][1], "GB_per_s": mv_bytes / (ms * 1e-3) * 1e-9,
+                                "frac_hbm_peak": mv_bytes / (ms * 1e-3) * 1e-9 / PEAK_HBM_GBS}
+    # the weight-gradient row as a whole: estimator pre-pass + GEMM + reduction, per layer
+    row_ms = sum(kt[k][0] for k in ("wgrad", "wgrad_reduce", "mvue_pack")) / max(1, kt["wgrad"][1])
+    kernels["wgrad_row"] = {"ms": row_ms, "dense_equiv_TFLOP_per_s": flops / (row_ms * 1e-3) * 1e-12,
+                            "frac_sparse_mfma_peak": flops / (row_ms * 1e-3) * 1e-12 / (2 * PEAK_DENSE_TFLOPS[dtype])}
+    return kernels, flops
+
+
+def roofline_of(kernels, flops, dtype, cfg, traffic):
+    """The `roofline` object for the kernel kind with the longest average launch, and `roofline_row` for the
+    weight-gradient row (pre-pass + GEMM + reduction together).  The sparse MFMA executes half of the
+    dense-equivalent multiply-adds: algorithmic flops per launch = T*I*O (I/2 or T/2 MACs per output element),
+    held against the published dense MFMA peak of the operand type."""
+    dom = max([k for k in ("project_pack", "fwd", "wgrad", "mvue_pack") if k in kernels], key=lambda k: kernels[k]["ms"])
+    if dom in ("project_pack", "mvue_pack"):
+        achieved = kernels[dom]["GB_per_s"]
+        roof = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
+    else:
+        peak = PEAK_DENSE_TFLOPS[dtype]
+        achieved = 0.5 * flops / (kernels[dom]["ms"] * 1e-3) * 1e-12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak}
+    roof["avg_launch_ms"] = kernels[dom]["ms"]
+    roof["traffic"] = traffic.get((cfg, dom))
+    peak = PEAK_DENSE_TFLOPS[dtype]
+    row = {"kernel": "mvue_pack + wgrad + wgrad_reduce", "bound": "mfma",
+           "achieved": 0.5 * flops / (kernels["wgrad_row"]["ms"] * 1e-3) * 1e-12, "peak": peak, "unit": "TFLOP/s",
+           "avg_row_ms": kernels["wgrad_row"]["ms"]}
+    row["frac"] = row["achieved"] / peak
+    parts = [traffic.get((cfg, k)) for k in ("mvue_pack", "wgrad", "wgrad_reduce") if k in kernels]
+    row["traffic"] = sum(parts) if parts and all(p is not None for p in parts) else None
+    return roof, row
+
+
+def measure(sste, torch, np, WL, cfg, layer_sel, steps, warmup, sets, grad_e5m2, with_events, traffic, chunks=10):
+    """Builds the workload's layers in HBM, runs `warmup` untimed and exactly `steps` timed steps between two
+    synchronisations, then (optionally) the same steps again with an event pair around every hot kernel."""
+    wl = WL.WORKLOADS[cfg]
+    sel = list(range(len(wl.layers))) if layer_sel < 0 else [layer_sel]
+    # bytes one set of a step's big operands and outputs occupies; rotate enough sets to exceed the cache twice
+    esize = 1 if wl.dtype == "e4m3" else 2
+    set_bytes = sum(wl.T * (wl.layers[i].I * esize + wl.layers[i].O * (esize + 2)) for i in sel)
+    nsets = sets if sets > 0 else max(1, min(8, -(-(512 << 20) // set_bytes)))
+    layers = [make_layer(sste, torch, np, WL, wl, i, nsets, grad_e5m2) for i in sel]
+
+    def step(i):
+        for st in layers:
+            layer_step(sste, st, cfg, i)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps between two synchronisations -> `value`
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    t_enq = time.perf_counter()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # ---- spread: the same steps in `chunks` separately synchronised pieces (median / min per step)
+    per = max(1, steps // chunks)
+    chunk_ms = []
+    for c in range(chunks):
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(per):
+            step(warmup + steps + c * per + i)
+        torch.cuda.synchronize()
+        chunk_ms.append((time.perf_counter() - c0) * 1e3 / per)
+
+    # ---- cache-warm regime: one buffer set reused (what fits stays in the 256 MB Infinity Cache)
+    for st in layers:
+        st.nsets_saved, st.nsets = st.nsets, 1
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(per * 2):
+        step(i)
+    torch.cuda.synchronize()
+    warm_ms = (time.perf_counter() - w0) * 1e3 / (per * 2)
+    for st in layers:
+        st.nsets = st.nsets_saved
+
+    flops_step = sum(2 * st.flops for st in layers)
+    out = {
+        "workload": "cfg%d %s: %s" % (wl.cfg, wl.name, ", ".join("%s %dx%d" % (st.name, st.O, st.I) for st in layers)),
+        "value": flops_step / (ms_per_step * 1e-3) * 1e-12,
+        "ms_per_step": ms_per_step,
+        "ms_per_step_median_of_chunks": statistics.median(chunk_ms),
+        "ms_per_step_min_of_chunks": min(chunk_ms),
+        "ms_per_step_cache_warm": warm_ms,
+        "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / steps,
+        "buffer_sets": nsets,
+        "dtype": wl.dtype,
+        "frac_sparse_mfma_peak_whole_step": flops_step / (ms_per_step * 1e-3) * 1e-12 / (2 * PEAK_DENSE_TFLOPS[wl.dtype]),
+    }
+    if with_events:
+        # the same steps again, every hot kernel bracketed by its own HIP event pair -> per-kernel durations.
+        # The event pairs serialise the queue (about 8 us per launch), so this pass is slower per step than the
+        # one above and is not what `value` is quoted on.
+        sste.timing_begin(8 * len(layers) * steps + 16)
+        torch.cuda.synchronize()
+        e0 = time.perf_counter()
+        for i in range(steps):
+            step(warmup + 2 * steps + i)
+        torch.cuda.synchronize()
+        out["ms_per_step_with_kernel_events"] = (time.perf_counter() - e0) * 1e3 / steps
+        kt = sste.timing_end()
+        kernels, flops = kernel_table(sste, layers, kt, wl.dtype)
+        out["kernels"] = kernels
+        out["roofline"], out["roofline_row"] = roofline_of(kernels, flops, wl.dtype, wl.cfg, traffic)
+        # per layer: one short events pass each, so that every GEMM shape has its own figures
+        per_layer = {}
+        for st in layers:
+            sste.timing_begin(8 * 20 + 16)
+            for i in range(20):
+                layer_step(sste, st, cfg, i)
+            torch.cuda.synchronize()
+            lk = sste.timing_end()
+            row = {k: (lk[k][0] / lk[k][1] if lk[k][1] else 0.0) for k in ("project_pack", "fwd", "mvue_pack", "wgrad", "wgrad_reduce")}
+            wrow = row["mvue_pack"] + row["wgrad"] + row["wgrad_reduce"]
+            peak2 = 2 * PEAK_DENSE_TFLOPS[wl.dtype]
+            per_layer[st.name] = {"us": {k: v * 1e3 for k, v in row.items()},
+                                  "fwd_frac_sparse_peak": st.flops / (row["fwd"] * 1e-3) * 1e-12 / peak2,
+                                  "wgrad_gemm_frac_sparse_peak": st.flops / (row["wgrad"] * 1e-3) * 1e-12 / peak2,
+                                  "wgrad_row_frac_sparse_peak": st.flops / (wrow * 1e-3) * 1e-12 / peak2}
+        out["layers"] = per_layer
+    return out, layers
+
+
+def cpu_baseline(np, WL, cfg):
+    """Times the oracle, as it stands (its numpy forms), on a bounded sample of the headline workload: one
+    step (8-bit casts of X and dY, project + pack, forward, estimator + weight gradient) of the block's
+    attention-projection layer on the first 2048 tokens.  Median of three runs."""
+    from oracle import formats as OF
     from oracle import linear as OL
     from oracle import projection as OP
     try:
@@ -63,27 +299,42 @@ def cpu_baseline(wl, layer, wb, xc, xs, dyc, dys, beta32, grad_e5m2=False):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    L = wl.layers[layer]
-    t0 = time.perf_counter()
-    if wl.dtype == "bf16":
-        rv, rm, _ = OP.project_pack(wb, beta32)
-        ws = np.float32(1.0)
-    else:
-        _, _, amax = OP.project_pack(wb, beta32)
-        ws = np.float32(float(amax) / 448.0)
-        rv, rm, _ = OP.project_pack(wb, beta32, "e4m3", ws)
-    t1 = time.perf_counter()
-    OL.linear_fwd(xc, rv, rm, wl.dtype, xs, ws)
-    t2 = time.perf_counter()
-    OL.linear_wgrad(dyc, xc, 0, 0, "e5m2" if grad_e5m2 else wl.dtype, dys, xs, x_dtype=wl.dtype)
-    t3 = time.perf_counter()
-    flops = 2 * 2.0 * wl.T * L.I * L.O
+    wl = WL.WORKLOADS[cfg]
+    li = 1 if len(wl.layers) > 1 else 0
+    L = wl.layers[li]
+    T = min(wl.T, 2048)
+    wb = WL.weight_bits(wl, li)
+    xb = WL.activations(wl, li, T=T)[0]
+    dyb = WL.output_gradient(wl, li, T=T)[0]
+    beta32 = np.float32(OP.beta_mse(OF.bf16_to_f32(wb).astype(np.float64)))
+    times = []
+    for _ in range(3):
+        t0 = time.perf_counter()
+        if wl.dtype == "e4m3":
+            def q(bits):
+                amax = np.float32(np.max(np.abs(OF.bf16_to_f32(bits))))
+                scale = np.float32(float(amax) / 448.0)
+                return OF.cast_fp8(bits, scale, "e4m3")[0], scale
+            xc, xs = q(xb)
+            dyc, dys = q(dyb)
+            _, _, amax = OP.project_pack(wb, beta32)
+            ws = np.float32(float(amax) / 448.0)
+            rv, rm, _ = OP.project_pack(wb, beta32, "e4m3", ws)
+        else:
+            xc, xs, dyc, dys, ws = xb, np.float32(1.0), dyb, np.float32(1.0), np.float32(1.0)
+            rv, rm, _ = OP.project_pack(wb, beta32)
+        OL.linear_fwd(xc, rv, rm, wl.dtype, xs, ws)
+        OL.linear_wgrad(dyc, xc, 0, 0, wl.dtype, dys, xs)
+        times.append(time.perf_counter() - t0)
+    flops = 2 * 2.0 * T * L.I * L.O
+    t = statistics.median(times)
     return {
-        "value": flops / (t3 - t0) * 1e-12,
+        "value": flops / t * 1e-12,
         "unit": "TFLOP/s",
         "cores": int(cores),
         "kind": "oracle",
-        "sample": "one full step of the same workload (project+pack %.2fs, fwd %.2fs, MVUE+wgrad %.2fs)" % (t1 - t0, t2 - t1, t3 - t2),
+        "sample": "one step of cfg%d layer %s (W %dx%d) on the first %d of %d tokens: casts, project+pack, forward, estimator + weight "
+                  "gradient; median of 3 runs (%.2f s each)" % (wl.cfg, L.name, L.O, L.I, T, wl.T, t),
     }
 
 
@@ -136,6 +387,81 @@ def prune_model(sste, torch, iters=20):
     return out
 
 
+def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context):
+    """Figures that are not part of `value`: the layer's third GEMM (input gradient, dense by the paper's
+    choice), the 8-bit operand casts, the flip rate of workload 4, the vendor's dense GEMM as context."""
+    out = {}
+    wl = WL.WORKLOADS[cfg]
+    dgrad = {}
+    for st in layers:
+        dX = torch.empty((st.T, st.I), dtype=torch.bfloat16, device="cuda")
+        for i in range(3):
+            sste.linear_dgrad(st.dYs[i % st.nsets], st.vals, st.meta, st.I, st.gdt, st.dys, st.w_scale, dX=dX)
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        n = max(10, steps // 4)
+        for i in range(n):
+            sste.linear_dgrad(st.dYs[i % st.nsets], st.vals, st.meta, st.I, st.gdt, st.dys, st.w_scale, dX=dX)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - g0) * 1e3 / n
+        dgrad[st.name] = {"ms": ms, "TFLOP_per_s": st.flops / (ms * 1e-3) * 1e-12,
+                          "frac_dense_mfma_peak": st.flops / (ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
+        del dX
+    out["dgrad_dense"] = dgrad
+    if wl.dtype == "e4m3":
+        casts = {}
+        T = wl.T
+        for name, cols, fmt in (("X 32768x1280", 1280, sste.F8E4M3), ("dY 32768x5120", 5120, sste.F8E5M2 if grad_e5m2 else sste.F8E4M3)):
+            src = torch.randn((T, cols), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            q = torch.empty((T, cols), dtype=torch.uint8, device="cuda")
+            amax = torch.empty(1, dtype=torch.float32, device="cuda")
+            for _ in range(3):
+                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(20):
+                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - c0) * 1e3 / 20
+            casts[name] = {"ms": ms, "GB_per_s": T * cols * 3 / ms * 1e-6, "frac_hbm_peak": T * cols * 3 / ms * 1e-6 / PEAK_HBM_GBS}
+            del src, q
+        out["cast_fp8"] = casts
+    if wl.cfg == 4:
+        # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta; the
+        # fraction of positions whose kept / pruned state changes (flip rate, Sec. 3.3) is a sanity number
+        st = layers[min(2, len(layers) - 1)]
+        li = [l.name for l in wl.layers].index(st.name)
+
+        def up(bits):
+            return torch.from_numpy(np.ascontiguousarray(bits.view(np.int16))).cuda().view(torch.bfloat16)
+        flips, w_bits = [], st.wb
+        _, m_prev = sste.project_pack(up(w_bits), st.beta, st.dt, st.w_scale)
+        for k in range(10):
+            w_bits = WL.weight_update_bits(w_bits, wl, li, k)
+            _, m_new = sste.project_pack(up(w_bits), st.beta, st.dt, st.w_scale)
+            flips.append(int(sste.flip_count(m_prev, m_new, st.O).cpu()[0]) / float(st.O * st.I))
+            m_prev = m_new
+        out["flip_rate_per_step"] = {"layer": st.name, "rates": flips}
+    if dense_context and wl.dtype == "bf16":
+        ctx = {}
+        for st in layers:
+            def dense_us(fn, iters=30):
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                d0 = time.perf_counter()
+                for i in range(iters):
+                    fn(i)
+                torch.cuda.synchronize()
+                return (time.perf_counter() - d0) / iters * 1e6
+            f_us = dense_us(lambda i: torch.matmul(st.Xs[i % st.nsets], st.W.t(), out=st.Zs[i % st.nsets]))
+            w_us = dense_us(lambda i: torch.matmul(st.dYs[i % st.nsets].t(), st.Xs[i % st.nsets]))
+            d_us = dense_us(lambda i: torch.matmul(st.dYs[i % st.nsets], st.W))
+            ctx[st.name] = {"fwd_us": f_us, "wgrad_us": w_us, "dgrad_us": d_us}
+        out["dense_context"] = {"library": "torch.matmul (bf16 in, bf16 out)", "layers": ctx}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -153,50 +479,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     sste.library()
-
-    wl = WL.WORKLOADS[args.config]
-    L = wl.layers[args.layer]
-    T, O, I = wl.T, L.O, L.I
-    fp8 = wl.dtype == "e4m3"
-    dt = sste.F8E4M3 if fp8 else sste.BF16
-    esize = 1 if fp8 else 2
-
-    # ---- seeded synthetic inputs, generated on the host and made resident in HBM before timing
-    wb = WL.weight_bits(wl, args.layer)
-    xc, xs = WL.activations(wl, args.layer)
-    grad_e5m2 = bool(args.grad_e5m2 and fp8)
-    dyc, dys = WL.output_gradient(wl, args.layer, e5m2=grad_e5m2)
-    gdt = sste.F8E5M2 if grad_e5m2 else dt           # format of dY in the backward calls
-
-    def up(a):
-        t = torch.from_numpy(np.ascontiguousarray(a.view(np.int16) if a.dtype == np.uint16 else a)).cuda()
-        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
-
-    W = up(wb)
-    nsets = max(1, args.sets)
-    Xs = [up(xc)] + [up(xc).clone() for _ in range(nsets - 1)]
-    dYs = [up(dyc)] + [up(dyc).clone() for _ in range(nsets - 1)]
-    Zs = [torch.empty((T, O), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
-    dWs = [torch.empty((O, I), dtype=torch.float32, device="cuda") for _ in range(nsets)]
-    vals, meta = sste.packed_buffers(O, I, dt, "cuda")
-    ws_bytes = sste.wgrad_workspace_bytes(T, O, I, dt)
-    wss = [torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
-
-    # beta: computed once from the initial weights, then frozen (paper Sec. 4.2)
-    beta = float(sste.compute_beta(W).cpu()[0])
-    if fp8:
-        amax = torch.zeros(1, dtype=torch.float32, device="cuda")
-        sste.project_pack(W, beta, sste.BF16, 1.0, amax_out=amax)
-        w_scale = float(amax.cpu()[0]) / 448.0
-    else:
-        w_scale = 1.0
-
-    def step(i):
-        s = i % nsets
-        sste.project_pack(W, beta, dt, w_scale, vals=vals, meta=meta)
-        sste.linear_fwd(Xs[s], vals, meta, O, dt, float(xs), w_scale, Z=Zs[s])
-        sste.linear_wgrad(dYs[s], Xs[s], seed=args.config, offset=i, dtype=gdt, dy_scale=float(dys), x_scale=float(xs),
-                          dW=dWs[s], workspace=wss[s])
+    traffic = hbm_traffic_table()
+    events = not args.no_kernel_timing
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -206,164 +490,45 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly K steps between two synchronisations -> `value`
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    t_enq = time.perf_counter()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-
-    # ---- the same K steps again, every hot kernel bracketed by its own HIP event pair -> per-kernel
-    # durations and the roofline.  The event pairs serialise the queue (about 8 us per launch on this
-    # box), so this pass is slower per step than the one above and is not what `value` is quoted on.
-    ms_per_step_events = float("nan")
-    if not args.no_kernel_timing:
-        sste.timing_begin(8 * args.steps + 16)
-        torch.cuda.synchronize()
-        e0 = time.perf_counter()
-        for i in range(args.steps):
-            step(args.warmup + args.steps + i)
-        torch.cuda.synchronize()
-        ms_per_step_events = (time.perf_counter() - e0) * 1e3 / args.steps
-        kt = sste.timing_end()
-    else:
-        kt = {k: (float("nan"), 1) for k in sste.binding.KERNEL_NAMES}
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    gemm_flops = 2.0 * T * I * O                 # dense-equivalent flops of one GEMM
-    value = 2 * gemm_flops / (ms_per_step * 1e-3) * 1e-12
-
-    def avg_ms(name):
-        ms, n = kt[name]
-        return ms / n if n else float("nan")
-
-    pp_bytes = O * I * (2 + esize / 2 + 0.125)   # algorithmic bytes: read W, write values + metadata
-    kernels = {
-        "project_pack": {"ms": avg_ms("project_pack"), "GB_per_s": pp_bytes / (avg_ms("project_pack") * 1e-3) * 1e-9,
-                         "frac_hbm_peak": pp_bytes / (avg_ms("project_pack") * 1e-3) * 1e-9 / PEAK_HBM_GBS},
-        "fwd": {"ms": avg_ms("fwd"), "dense_equiv_TFLOP_per_s": gemm_flops / (avg_ms("fwd") * 1e-3) * 1e-12},
-        "wgrad": {"ms": avg_ms("wgrad"), "dense_equiv_TFLOP_per_s": gemm_flops / (avg_ms("wgrad") * 1e-3) * 1e-12},
-        "wgrad_reduce": {"ms": avg_ms("wgrad_reduce")},
-    }
-    if kt["mvue_pack"][1]:
-        mv_bytes = T * O * esize * (1 + 0.5 + 0.0625)          # read dY, write packed values + position bits
-        kernels["mvue_pack"] = {"ms": avg_ms("mvue_pack"), "GB_per_s": mv_bytes / (avg_ms("mvue_pack") * 1e-3) * 1e-9,
-                                "frac_hbm_peak": mv_bytes / (avg_ms("mvue_pack") * 1e-3) * 1e-9 / PEAK_HBM_GBS}
-    wgrad_total_ms = sum(kernels[k]["ms"] for k in ("wgrad", "wgrad_reduce", "mvue_pack") if k in kernels and kernels[k]["ms"] == kernels[k]["ms"])
-    kernels["wgrad_all"] = {"ms": wgrad_total_ms, "dense_equiv_TFLOP_per_s": gemm_flops / (max(wgrad_total_ms, 1e-9) * 1e-3) * 1e-12}
-    for k in ("fwd", "wgrad"):
-        kernels[k]["frac_sparse_mfma_peak"] = kernels[k]["dense_equiv_TFLOP_per_s"] / (2 * PEAK_DENSE_TFLOPS[wl.dtype])
-
-    # roofline of the dominant kernel.  The sparse MFMA executes half of the dense-equivalent
-    # multiply-adds: algorithmic flops per launch = T*I*O (I/2 MACs per output element), held against
-    # the published dense MFMA peak of the operand type.
-    dom = max([k for k in ("project_pack", "fwd", "wgrad", "mvue_pack") if k in kernels], key=lambda k: kernels[k]["ms"])
-    if dom in ("project_pack", "mvue_pack"):
-        achieved = kernels[dom]["GB_per_s"]
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
-    else:
-        achieved = 0.5 * gemm_flops / (kernels[dom]["ms"] * 1e-3) * 1e-12
-        peak = PEAK_DENSE_TFLOPS[wl.dtype]
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                    "frac": achieved / peak, "traffic": None}
-    roofline["avg_launch_ms"] = kernels[dom]["ms"]
-    kib = HBM_TRAFFIC_KIB.get((wl.cfg, dom)) if args.layer == 0 else None
-    roofline["traffic"] = kib * 1024 if kib is not None else None
-
+    head, layers = measure(sste, torch, np, WL, args.config, args.layer, args.steps, args.warmup, args.sets,
+                           args.grad_e5m2, events, traffic)
+    wl = WL.WORKLOADS[args.config]
     out = {
         "metric": "S-STE 2:4 linear fwd+wgrad TFLOP/s (dense-equivalent, project+pack inside the step)",
-        "value": value,
+        "value": head["value"],
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / args.steps,
-        "ms_per_step_with_kernel_events": ms_per_step_events,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": wl.dtype if fp8 else "bf16",
+        "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": "cfg%d %s layer %s (W %dx%d, %d tokens)" % (wl.cfg, wl.name, L.name, O, I, T),
-                   "buffer_sets": nsets, "wgrad_workspace_bytes": int(ws_bytes),
-                   "grad_format": "e5m2" if grad_e5m2 else wl.dtype},
-        "frac_sparse_mfma_peak_whole_step": value / (2 * PEAK_DENSE_TFLOPS[wl.dtype]),
-        "kernels": kernels,
-        "roofline": roofline,
+        "config": {"workload": head["workload"], "tokens": wl.T, "buffer_sets": head["buffer_sets"],
+                   "grad_format": "e5m2" if (args.grad_e5m2 and wl.dtype == "e4m3") else wl.dtype},
     }
-    if True:
-        # the layer's third GEMM, grad_X = grad_Z S(W): dense by the paper's choice, not part of `value`
-        dXs = [torch.empty((T, I), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
-        for i in range(5):
-            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, gdt, float(dys), w_scale, dX=dXs[i % nsets])
-        torch.cuda.synchronize()
-        g0 = time.perf_counter()
-        for i in range(args.steps):
-            sste.linear_dgrad(dYs[i % nsets], vals, meta, I, gdt, float(dys), w_scale, dX=dXs[i % nsets])
-        torch.cuda.synchronize()
-        dg_ms = (time.perf_counter() - g0) * 1e3 / args.steps
-        out_dgrad = {"ms": dg_ms, "TFLOP_per_s": gemm_flops / (dg_ms * 1e-3) * 1e-12, "frac_dense_mfma_peak": gemm_flops / (dg_ms * 1e-3) * 1e-12 / PEAK_DENSE_TFLOPS[wl.dtype]}
-        del dXs
-    if fp8:
-        # operand preparation of the 8-bit path: per-tensor rescale + cast of bf16 X and dY (3 B per element)
-        casts = {}
-        for name, rows, cols, fmt in (("X", T, I, sste.F8E4M3), ("dY", T, O, gdt if grad_e5m2 else sste.F8E4M3)):
-            src = torch.randn((rows, cols), device="cuda", dtype=torch.float32).to(torch.bfloat16)
-            q = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
-            amax = torch.empty(1, dtype=torch.float32, device="cuda")
-            for _ in range(3):
-                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
-            torch.cuda.synchronize()
-            c0 = time.perf_counter()
-            for _ in range(20):
-                sste.cast_fp8(src, 0.01, fmt, Q=q, amax_out=amax)
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - c0) * 1e3 / 20
-            casts[name] = {"ms": ms, "GB_per_s": rows * cols * 3 / ms * 1e-6, "frac_hbm_peak": rows * cols * 3 / ms * 1e-6 / PEAK_HBM_GBS}
-            del src, q
-        out["cast_fp8"] = casts
-    if args.dense_context and not fp8:
-        # what the vendor's dense GEMM reaches on the same layer (forward Z = X W^T; weight gradient dY^T X)
-        def dense_us(fn, iters=50):
-            for i in range(5):
-                fn(i)
-            torch.cuda.synchronize()
-            d0 = time.perf_counter()
-            for i in range(iters):
-                fn(i)
-            torch.cuda.synchronize()
-            return (time.perf_counter() - d0) / iters * 1e6
-        f_us = dense_us(lambda i: torch.matmul(Xs[i % nsets], W.t(), out=Zs[i % nsets]))
-        w_us = dense_us(lambda i: torch.matmul(dYs[i % nsets].t(), Xs[i % nsets]))
-        d_us = dense_us(lambda i: torch.matmul(dYs[i % nsets], W))
-        out["dense_context"] = {"library": "torch.matmul (bf16 in, bf16 out)", "fwd_us": f_us, "fwd_TFLOP_per_s": gemm_flops / f_us * 1e-6,
-                                "wgrad_us": w_us, "wgrad_TFLOP_per_s": gemm_flops / w_us * 1e-6,
-                                "dgrad_us": d_us, "dgrad_TFLOP_per_s": gemm_flops / d_us * 1e-6}
-    if out_dgrad is not None:
-        out["dgrad_dense"] = out_dgrad
-    if wl.cfg == 4:
-        # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta;
-        # the fraction of positions whose kept / pruned state changes (flip rate, paper Sec. 3.3) is a sanity number
-        flips, w_bits = [], wb
-        v_prev, m_prev = sste.project_pack(up(w_bits), beta, dt, w_scale)
-        for k in range(10):
-            w_bits = WL.weight_update_bits(w_bits, wl, args.layer, k)
-            v_new, m_new = sste.project_pack(up(w_bits), beta, dt, w_scale)
-            flips.append(int(sste.flip_count(m_prev, m_new, O).cpu()[0]) / float(O * I))
-            m_prev = m_new
-        out["flip_rate_per_step"] = flips
+    for k in ("ms_per_step_median_of_chunks", "ms_per_step_min_of_chunks", "ms_per_step_cache_warm", "host_enqueue_ms_per_step",
+              "ms_per_step_with_kernel_events", "frac_sparse_mfma_peak_whole_step", "kernels", "layers", "roofline", "roofline_row"):
+        if k in head:
+            out[k] = head[k]
+    out.update(extras(sste, torch, np, WL, args.config, layers, args.steps, args.grad_e5m2, args.dense_context))
+    del layers
+    torch.cuda.empty_cache()
+
+    if not args.no_secondary and args.layer < 0 and args.config == 5:
+        secondary = {}
+        for cfg in (4, 2):
+            sec, sl = measure(sste, torch, np, WL, cfg, -1, max(20, args.steps // 2), args.warmup, 0, False, events, traffic)
+            del sl
+            torch.cuda.empty_cache()
+            secondary["cfg%d" % cfg] = sec
+        out["secondary"] = secondary
     if not args.no_prune_model:
         out["prune_pack_model"] = prune_model(sste, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, args.layer, wb, xc, xs, dyc, dys, np.float32(beta), grad_e5m2)
+        out["cpu_baseline"] = cpu_baseline(np, WL, args.config)
     print(json.dumps(out))
 
 

@@ -72,14 +72,15 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
 #pragma unroll
     for (int r = 0; r < 4; r++) rdy[r] = make_uint4(0, 0, 0, 0);
   }
+  // Group ids of this lane: gid_base + e.  O and och are multiples of CH, so gid_base is one too and the
+  // CH consecutive ids share their high word (no carry out of the low word inside the piece).
   const uint64_t gid_base = (uint64_t)(s * GROUPS + kg) * (uint64_t)O + (uint64_t)och;
-  const uint32_t gid_lo0 = (uint32_t)gid_base, gid_hi0 = (uint32_t)(gid_base >> 32);
-  const uint32_t hi_term0 = gid_hi0 * 0x9E3779B9u, hi_term1 = (gid_hi0 + 1u) * 0x9E3779B9u;
+  const uint32_t gid_lo0 = (uint32_t)gid_base;
+  const uint32_t hi_term = (uint32_t)(gid_base >> 32) * 0x9E3779B9u;
   const int q = kg / GPQ, g = kg % GPQ;
 #pragma unroll
   for (int e = 0; e < CH; e++) {
-    uint32_t gid_lo = gid_lo0 + (uint32_t)e;                 // group id gid_base + e: low word, carry into the high word
-    uint32_t x = draw_u32_pre(key.k0, key.k1, gid_lo, gid_lo < gid_lo0 ? hi_term1 : hi_term0);
+    uint32_t x = draw_u32_pre(key.k0, key.k1, gid_lo0 + (uint32_t)e, hi_term);
     uint32_t nib, v;
     int c = oc * CH + e;                           // channel inside the tile
     uint8_t* slot = sV + (c >> 4) * VPITCH + (16 * q + (c & 15)) * 16;

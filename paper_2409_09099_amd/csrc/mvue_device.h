@@ -54,12 +54,14 @@ __device__ __forceinline__ Sel mvue_select(float m0f, float m1f, float m2f, floa
   float tau0 = u * h;
   float tau1 = tau0 + h;
   uint32_t p0 = f2u(P0), p1 = f2u(P1), p2 = f2u(P2), t0 = f2u(tau0), t1 = f2u(tau1);
-  uint32_t i0 = (uint32_t)(p0 <= t0) + (uint32_t)(p1 <= t0) + (uint32_t)(p2 <= t0);
-  uint32_t i1 = (uint32_t)(p0 <= t1) + (uint32_t)(p1 <= t1) + (uint32_t)(p2 <= t1);
+  // pos0 = min(#{k : P_k <= tau0}, 2): the prefix sums never decrease, so P2 <= tau0 implies the other
+  // two and the count capped at 2 is the count over P0 and P1 alone.  pos1 = min(3, max(i1, pos0 + 1))
+  // with i1 <= 3 and pos0 <= 2: the outer min never acts.
   Sel s;
   s.h = h;
-  s.pos0 = min(i0, 2u);
-  s.pos1 = min(3u, max(i1, s.pos0 + 1u));
+  s.pos0 = (uint32_t)(p0 <= t0) + (uint32_t)(p1 <= t0);
+  uint32_t i1 = (uint32_t)(p0 <= t1) + (uint32_t)(p1 <= t1) + (uint32_t)(p2 <= t1);
+  s.pos1 = max(i1, s.pos0 + 1u);
   return s;
 }
 
@@ -69,20 +71,28 @@ __device__ __forceinline__ uint32_t mvue_group_bf16(uint32_t lo, uint32_t hi, ui
   float m0 = u2f((lo << 16) & 0x7FFFFFFFu), m1 = u2f(lo & 0x7FFF0000u);
   float m2 = u2f((hi << 16) & 0x7FFFFFFFu), m3 = u2f(hi & 0x7FFF0000u);
   Sel s = mvue_select(m0, m1, m2, m3, x);
-  uint32_t hq = bf16_rne(s.h);
-  uint32_t out = 0;
-#pragma unroll
-  for (int k = 0; k < 2; k++) {
-    uint32_t p = k ? s.pos1 : s.pos0;
-    uint32_t gb = pick16_as_f32bits(lo, hi, p);          // g_p as float32 bits
-    uint32_t mb = gb & 0x7FFFFFFFu;
-    // keep g_p itself when m_p > h or m_p == 0: (mb - 1) as unsigned >= bits(h) covers both
-    bool own = (mb - 1u) >= f2u(s.h);
-    uint32_t v = own ? (gb >> 16) : (((gb >> 16) & 0x8000u) | hq);
-    out |= v << (16 * k);
-  }
+  // Both recorded elements at once, as a pair of 16-bit patterns (pos0's in the low half): one byte
+  // permute of {hi:lo} with selector bytes (2 pos0, 2 pos0 + 1, 2 pos1, 2 pos1 + 1).
+  typedef __attribute__((__vector_size__(2 * sizeof(uint16_t)))) uint16_t u16x2;
+  const uint32_t pp = s.pos0 | (s.pos1 << 16);
+  const uint32_t sel = ((pp << 1) | (pp << 9)) + 0x01000100u;
+  const uint32_t g = __builtin_amdgcn_perm(hi, lo, sel);
+  // An element keeps its own pattern when m_p > h or m_p == 0.  On the 15-bit magnitude fields (the low
+  // 16 bits of a bf16's float32 pattern are zero): field > bits(h) >> 16, or field == 0; both at once as
+  // (field - 1) mod 2^16 >= bits(h) >> 16, evaluated for the pair with packed 16-bit arithmetic:
+  // the saturating difference hh - (field - 1) is zero exactly for the elements that keep their pattern.
+  const uint32_t hh = f2u(s.h) >> 16;
+  u16x2 field, one = {1, 1}, hh2 = {(uint16_t)hh, (uint16_t)hh};
+  const uint32_t gm = g & 0x7FFF7FFFu;
+  __builtin_memcpy(&field, &gm, 4);
+  u16x2 d = __builtin_elementwise_sub_sat(hh2, (u16x2)(field - one));
+  u16x2 common_mask = (u16x2){0, 0} - __builtin_elementwise_min(d, one);        // 0xFFFF where sign | RNE(h) is stored
+  uint32_t cm;
+  __builtin_memcpy(&cm, &common_mask, 4);
+  const uint32_t hq = bf16_rne(s.h);
+  const uint32_t common = (g & 0x80008000u) | (hq | (hq << 16));
   nib = s.pos0 | (s.pos1 << 2);
-  return out;
+  return (common & cm) | (g & ~cm);
 }
 
 // 8-bit group (e4m3, or e5m2 when BF8): the four codes of one group in one dword (g0 in byte 0).
