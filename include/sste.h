@@ -245,6 +245,27 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * sste_linear_wgrad for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results; the scratch that sste_linear_wgrad takes as
+ * `workspace` is an array of SSTE_NOALLOC_SCRATCH_BYTES bytes inside the library's own device image
+ * (each GPU the library runs on holds its copy until the process ends).  The call allocates nothing and
+ * frees nothing; on its first use on a device it asks the runtime once for the array's address there.
+ * Problems whose sste_wgrad_workspace_bytes() exceeds SSTE_NOALLOC_SCRATCH_BYTES are refused with
+ * SSTE_ERR_WORKSPACE before anything is launched (64 MiB covers the 3072 x 768 layer at 8192 tokens;
+ * larger layers need sste_linear_wgrad with a caller-owned workspace).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or different threads) race; calls on one stream are ordered and safe.  Nothing in the array
+ * has to start at zero (every byte a call reads it has written before), so the previous call's contents,
+ * of any size, do no harm.
+ */
+#define SSTE_NOALLOC_SCRATCH_BYTES (64u << 20)
+int sste_linear_wgrad_noalloc(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                              const void* X, int64_t I, int64_t ldx, float x_scale,
+                              uint64_t seed, uint64_t offset,
+                              float* dW, int64_t lddw, int accumulate, void* hip_stream);
+
+/*
  * Input gradient (Sec. 5.1: grad_X_l = grad_Z_l S(W_l); the paper keeps this product dense).
  *
  *   dX = (dy_scale * w_scale) * dY * decode(vals, meta),  float32 accumulation, dX stored as bf16 (RNE).

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     linear_dgrad,
     linear_fwd,
     linear_wgrad,
+    linear_wgrad_noalloc,
     mvue_materialize,
     packed_buffers,
     project_pack,

@@ -45,6 +45,8 @@ def library() -> ctypes.CDLL:
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_dgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
+    lib.sste_linear_wgrad_noalloc.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp]
+    lib.sste_linear_wgrad_noalloc.restype = ci
     lib.sste_wgrad_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.sste_wgrad_workspace_bytes.restype = sz
     lib.sste_mvue_materialize.argtypes = [vp, i64, i64, i64, ci, u64, u64, vp, vp, vp]
@@ -280,6 +282,23 @@ def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtyp
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(library().sste_linear_wgrad(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(X), I, ldx, x_scale, seed, offset, _ptr(dW),
                                        lddw, int(bool(accumulate)), _ptr(workspace), ws_bytes, _stream(X)))
+    return dW
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def linear_wgrad_noalloc(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dW: torch.Tensor, dtype: int = BF16,
+                         dy_scale: float = 1.0, x_scale: float = 1.0, accumulate: bool = False) -> torch.Tensor:
+    """sste_linear_wgrad_noalloc: the weight gradient into a caller-owned dW with the library's built-in
+    scratch; nothing is allocated on the way (not by this wrapper either)."""
+    T, O, lddy = _matrix(dY, _esize(dtype), "dY")
+    T2, I, ldx = _matrix(X, _esize(dtype), "X")
+    if T2 != T:
+        raise ValueError("dY and X must have the same number of rows (tokens)")
+    _, _, lddw = _matrix(dW, 4, "dW")
+    _check(library().sste_linear_wgrad_noalloc(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(X), I, ldx, x_scale, seed, offset,
+                                               _ptr(dW), lddw, int(bool(accumulate)), _stream(X)))
     return dW
 
 

@@ -366,21 +366,52 @@ int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
                     "linear_dgrad launch");
 }
 
+// Argument checks shared by sste_linear_wgrad and its variant that brings its own scratch.
+static int check_wgrad_args(const char* who, const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                            const void* X, int64_t I, int64_t ldx, float x_scale, const float* dW, int64_t lddw, int accumulate) {
+  int st = wgrad_shape_check(T, O, I, dtype, who);
+  if (st != SSTE_OK) return st;
+  if (!good_scale(dy_scale) || !good_scale(x_scale)) return fail(SSTE_ERR_VALUE, "%s: scales must be finite and > 0", who);
+  if (accumulate != 0 && accumulate != 1) return fail(SSTE_ERR_VALUE, "%s: accumulate must be 0 or 1", who);
+  if (lddy < O || ldx < I || lddw < I) return fail(SSTE_ERR_SHAPE, "%s: leading dimension smaller than the row length", who);
+  int e16 = elems_per_16B(dtype);
+  if (lddy % e16 != 0 || ldx % e16 != 0 || lddw % 4 != 0) return fail(SSTE_ERR_ALIGN, "%s: leading dimensions break the 16-byte row rule", who);
+  bool empty = (O == 0 || I == 0);
+  if (!empty && (!dW || (T > 0 && (!dY || !X)))) return fail(SSTE_ERR_NULL, "%s: NULL dY, X or dW", who);
+  if (!aligned16(dY) || !aligned16(X) || !aligned16(dW)) return fail(SSTE_ERR_ALIGN, "%s: dY, X and dW must be 16-byte aligned", who);
+  if (!linear_wgrad_supported(T, O, I, ldx, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "%s: this problem does not fit 32-bit tile offsets", who);
+  return SSTE_OK;
+}
+
+int sste_linear_wgrad_noalloc(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
+                              int64_t I, int64_t ldx, float x_scale, uint64_t seed, uint64_t offset, float* dW, int64_t lddw,
+                              int accumulate, void* hip_stream) {
+  clear_error();
+  int st = check_wgrad_args("linear_wgrad_noalloc", dY, T, O, lddy, dtype, dy_scale, X, I, ldx, x_scale, dW, lddw, accumulate);
+  if (st != SSTE_OK) return st;
+  size_t need = sste_wgrad_workspace_bytes(T, O, I, dtype);
+  if (need > (size_t)SSTE_NOALLOC_SCRATCH_BYTES)
+    return fail(SSTE_ERR_WORKSPACE, "linear_wgrad_noalloc: this problem needs %zu bytes of scratch, the built-in scratch holds %zu; use sste_linear_wgrad with a workspace",
+                need, (size_t)SSTE_NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if (need > 0) {
+    hipError_t e = hipSuccess;
+    ws = noalloc_scratch(&e);
+    if (!ws) return hip_status(e == hipSuccess ? hipErrorUnknown : e, "linear_wgrad_noalloc: address of the built-in scratch");
+  }
+  float scale = dy_scale * x_scale;
+  if (is_8bit(dtype)) scale *= 2.0f;            // the sparsified 8-bit operand is stored halved
+  return hip_status(launch_linear_wgrad(dY, T, O, lddy, dtype, X, I, ldx, scale, derive_key(seed, offset), dW, lddw, accumulate, ws,
+                                        (hipStream_t)hip_stream),
+                    "linear_wgrad_noalloc launch");
+}
+
 int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
                       int64_t I, int64_t ldx, float x_scale, uint64_t seed, uint64_t offset, float* dW, int64_t lddw,
                       int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
   clear_error();
-  int st = wgrad_shape_check(T, O, I, dtype, "linear_wgrad");
+  int st = check_wgrad_args("linear_wgrad", dY, T, O, lddy, dtype, dy_scale, X, I, ldx, x_scale, dW, lddw, accumulate);
   if (st != SSTE_OK) return st;
-  if (!good_scale(dy_scale) || !good_scale(x_scale)) return fail(SSTE_ERR_VALUE, "linear_wgrad: scales must be finite and > 0");
-  if (accumulate != 0 && accumulate != 1) return fail(SSTE_ERR_VALUE, "linear_wgrad: accumulate must be 0 or 1");
-  if (lddy < O || ldx < I || lddw < I) return fail(SSTE_ERR_SHAPE, "linear_wgrad: leading dimension smaller than the row length");
-  int e16 = elems_per_16B(dtype);
-  if (lddy % e16 != 0 || ldx % e16 != 0 || lddw % 4 != 0) return fail(SSTE_ERR_ALIGN, "linear_wgrad: leading dimensions break the 16-byte row rule");
-  bool empty = (O == 0 || I == 0);
-  if (!empty && (!dW || (T > 0 && (!dY || !X)))) return fail(SSTE_ERR_NULL, "linear_wgrad: NULL dY, X or dW");
-  if (!aligned16(dY) || !aligned16(X) || !aligned16(dW)) return fail(SSTE_ERR_ALIGN, "linear_wgrad: dY, X and dW must be 16-byte aligned");
-  if (!linear_wgrad_supported(T, O, I, ldx, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_wgrad: this problem does not fit 32-bit tile offsets");
   size_t need = sste_wgrad_workspace_bytes(T, O, I, dtype);
   if (need > 0) {
     if (!workspace) return fail(SSTE_ERR_WORKSPACE, "linear_wgrad: workspace is NULL, %zu bytes needed", need);

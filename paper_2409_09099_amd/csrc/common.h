@@ -196,6 +196,7 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
 size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype);
+void* noalloc_scratch(hipError_t* err);   // this GPU's copy of the library's static scratch array
 hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
                                int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,
                                int accumulate, void* ws, hipStream_t s);

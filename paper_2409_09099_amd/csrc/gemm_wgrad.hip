@@ -20,6 +20,8 @@
 #include "common.h"
 #include "mvue_device.h"
 
+#include <mutex>
+
 namespace sste {
 
 hipError_t launch_wgrad_fused(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X, int64_t I,
@@ -576,6 +578,38 @@ hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
                 scale, accumulate, dW, lddw);
   }
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Scratch for callers that cannot allocate: the workspace of launch_linear_wgrad inside the library's own
+// device image.  Every GPU the library runs on holds its own copy of the array until the process ends.  In
+// host code the array's name is only a handle for the runtime; the device address is asked for once per
+// device (with that device current) and used from then on.
+static __device__ __align__(256) unsigned char scratch[SSTE_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+// Device address of this GPU's scratch array (nullptr + *err on failure).  No allocation takes place.
+void* noalloc_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
 }
 
 }  // namespace sste
