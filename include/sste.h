@@ -215,8 +215,15 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
                     void* Z, int64_t ldz, void* hip_stream);
 
 /*
- * Weight-gradient GEMM with the output gradient sparsified 2:4 on the fly by the minimum-variance
- * unbiased estimator (Sec. 5.1: grad_W = MVUE(grad_Z^T) X).
+ * Weight-gradient GEMM with the output gradient sparsified 2:4 by the minimum-variance unbiased
+ * estimator (Sec. 5.1: grad_W = MVUE(grad_Z^T) X).
+ *
+ * Which kernels run: problems with T >= 2048, O >= 256 and I >= 256 (every layer of the GPT-2 workloads)
+ * sparsify dY ONCE into the workspace (a packed 2:4 operand in the format above, rows = channels,
+ * columns = tokens), run a sparse GEMM on it that is split over the token axis, and sum the splits in a
+ * fixed order.  Smaller problems sparsify inside the GEMM's operand load (one kernel, the workspace only
+ * holds split partial sums, if any).  The result is the same function of (dY, X, seed, offset) on
+ * either path.
  *
  *   dW (+)= scale * MVUE(dY^T; seed, offset) * X,   scale = dy_scale * x_scale (times 2 for the 8-bit
  *   formats, whose sparsified operand is stored halved), float32 accumulation, dW float32.
@@ -243,6 +250,20 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
                       uint64_t seed, uint64_t offset,
                       float* dW, int64_t lddw, int accumulate,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * sste_linear_wgrad for a SHARD of the token axis (data parallelism over tokens: every GPU holds a
+ * slice of the batch).  `first_token` is the global index of row 0 of dY and X, a multiple of 4; the
+ * estimator's group id becomes ((first_token + t) / 4) * O + o, so the shards of a batch draw exactly
+ * the numbers the whole batch would draw and the sum of their results does not depend on how the
+ * batch was cut.  first_token = 0 is sste_linear_wgrad.  first_token < 0 or not a multiple of 4 ->
+ * ERR_SHAPE; group ids beyond 64 bits -> ERR_UNSUPPORTED.
+ */
+int sste_linear_wgrad_at(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                         const void* X, int64_t I, int64_t ldx, float x_scale,
+                         uint64_t seed, uint64_t offset, int64_t first_token,
+                         float* dW, int64_t lddw, int accumulate,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * sste_linear_wgrad for callers that cannot allocate device memory and have no workspace to pass: code
@@ -290,6 +311,16 @@ int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
 size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 
 /*
+ * For tests and tuning: fixes the workgroup tile and the number of token-axis splits of the large-problem
+ * weight-gradient GEMM instead of letting the library choose them per problem.  (mi, ni) is one of
+ * (8, 4) = 256 channels x 256 features, (6, 3) = 192 x 192, (8, 3) = 256 x 192, or (0, 0) = automatic;
+ * splits is 1..32 (capped by the problem), or 0 = automatic.  Process-wide, takes effect for the calls
+ * that follow (sste_wgrad_workspace_bytes included, which must be asked again); results stay exact to
+ * the same tolerance for every choice.  Other values -> SSTE_ERR_VALUE, nothing changes.
+ */
+int sste_wgrad_plan_override(int mi, int ni, int splits);
+
+/*
  * The estimator of sste_linear_wgrad written out as a packed 2:4 operand (same device function).
  * Used to check the sparsifier bit for bit; also usable as a stand-alone pre-pass.
  *
@@ -306,11 +337,19 @@ size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
  *
  *   dY    in   device, T x O of `dtype` (SSTE_BF16, SSTE_F8E4M3 or SSTE_F8E5M2), leading dimension lddy;
  *              T a multiple of 64 (bf16) / 128 (8-bit)
- *   vals, meta  out  device, packed format above with R = O rows and K = T columns (padding rows are
- *              left unwritten)
+ *   O     a multiple of 8 (bf16) / 16 (8-bit); lddy likewise; dY 16-byte aligned (the kernel reads whole
+ *              16-byte pieces of a token row)
+ *   vals, meta  out  device, packed format above with R = O rows and K = T columns.  Rows O .. 16 RB - 1
+ *              of the last row block are written as all-zero rows (values 0; their position bits are
+ *              those the estimator gives an all-zero group, 2 | 3 << 2)
  */
 int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype,
                           uint64_t seed, uint64_t offset, void* vals, void* meta, void* hip_stream);
+
+/* sste_mvue_materialize for a shard of the token axis: `first_token` as in sste_linear_wgrad_at. */
+int sste_mvue_materialize_at(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype,
+                             uint64_t seed, uint64_t offset, int64_t first_token,
+                             void* vals, void* meta, void* hip_stream);
 
 /*
  * MSE-optimal scale of Sec. 4.2: beta = <W, S_soft(W)> / ||S_soft(W)||^2, computed once from the

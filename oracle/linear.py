@@ -47,19 +47,19 @@ def linear_fwd_loops(X, Wd):
     return np.array(Z, dtype=np.float64)
 
 
-def mvue_dense(dy_codes, seed, offset, dtype="bf16"):
+def mvue_dense(dy_codes, seed, offset, dtype="bf16", first_token=0):
     """theta = MVUE(dY^T)^T as a dense-with-zeros (T, O) float64 matrix of the STORED operand values
     (for e4m3 these are theta/2; the factor 2 belongs to the epilogue scale)."""
-    vals, meta = mvue.mvue_pack(dy_codes, seed, offset, dtype)
+    vals, meta = mvue.mvue_pack(dy_codes, seed, offset, dtype, first_token)
     return projection.decode_packed(vals, meta, dtype).T            # (O, T) -> (T, O)
 
 
-def linear_wgrad(dy_codes, x_codes, seed, offset, dtype="bf16", dy_scale=1.0, x_scale=1.0, x_dtype=None):
+def linear_wgrad(dy_codes, x_codes, seed, offset, dtype="bf16", dy_scale=1.0, x_scale=1.0, x_dtype=None, first_token=0):
     """grad_W = scale * MVUE(dY^T) X in float64: (O, I).  scale = dy_scale * x_scale, times 2 for the
     8-bit formats because the stored sparse operand holds theta / 2.  `dtype` is the format of dY;
     X has the same format unless x_dtype says otherwise (Sec. 5.2: e5m2 gradients against e4m3
     activations)."""
-    theta = mvue_dense(dy_codes, seed, offset, dtype)               # (T, O)
+    theta = mvue_dense(dy_codes, seed, offset, dtype, first_token)  # (T, O); first_token: dY is a shard of the token axis
     X = decode_activations(x_codes, x_dtype or dtype)
     scale = np.float64(np.float32(dy_scale)) * np.float64(np.float32(x_scale))
     if dtype in ("e4m3", "e5m2"):

@@ -28,5 +28,6 @@ from .binding import (  # noqa: F401
     sgd_project_pack,
     timing_begin,
     timing_end,
+    wgrad_plan_override,
     wgrad_workspace_bytes,
 )

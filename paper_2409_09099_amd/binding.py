@@ -47,9 +47,15 @@ def library() -> ctypes.CDLL:
     lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
     lib.sste_linear_wgrad_noalloc.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp]
     lib.sste_linear_wgrad_noalloc.restype = ci
+    lib.sste_wgrad_plan_override.argtypes = [ci, ci, ci]
+    lib.sste_wgrad_plan_override.restype = ci
     lib.sste_wgrad_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.sste_wgrad_workspace_bytes.restype = sz
     lib.sste_mvue_materialize.argtypes = [vp, i64, i64, i64, ci, u64, u64, vp, vp, vp]
+    lib.sste_mvue_materialize_at.argtypes = [vp, i64, i64, i64, ci, u64, u64, i64, vp, vp, vp]
+    lib.sste_mvue_materialize_at.restype = ci
+    lib.sste_linear_wgrad_at.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, i64, vp, i64, ci, vp, sz, vp]
+    lib.sste_linear_wgrad_at.restype = ci
     lib.sste_compute_beta.argtypes = [vp, i64, i64, i64, vp, vp, sz, vp]
     lib.sste_beta_workspace_bytes.argtypes = [i64, i64]
     lib.sste_beta_workspace_bytes.restype = sz
@@ -259,14 +265,20 @@ def linear_dgrad(dY: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, I: in
     return dX
 
 
+def wgrad_plan_override(mi: int = 0, ni: int = 0, splits: int = 0) -> None:
+    """sste_wgrad_plan_override: fix the tile / split choice of the large-problem weight gradient (0 = automatic)."""
+    _check(library().sste_wgrad_plan_override(mi, ni, splits))
+
+
 def wgrad_workspace_bytes(T: int, O: int, I: int, dtype: int = BF16) -> int:
     return int(library().sste_wgrad_workspace_bytes(T, O, I, dtype))
 
 
 def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtype: int = BF16, dy_scale: float = 1.0,
                  x_scale: float = 1.0, dW: Optional[torch.Tensor] = None, accumulate: bool = False,
-                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """sste_linear_wgrad: dW (+)= scale * MVUE(dY^T; seed, offset) X, float32 output."""
+                 workspace: Optional[torch.Tensor] = None, first_token: int = 0) -> torch.Tensor:
+    """sste_linear_wgrad(_at): dW (+)= scale * MVUE(dY^T; seed, offset) X, float32 output.  first_token: global
+    index of the first token row when dY and X are a shard of the token axis."""
     T, O, lddy = _matrix(dY, _esize(dtype), "dY")
     T2, I, ldx = _matrix(X, _esize(dtype), "X")
     if T2 != T:
@@ -280,8 +292,8 @@ def linear_wgrad(dY: torch.Tensor, X: torch.Tensor, seed: int, offset: int, dtyp
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(library().sste_linear_wgrad(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(X), I, ldx, x_scale, seed, offset, _ptr(dW),
-                                       lddw, int(bool(accumulate)), _ptr(workspace), ws_bytes, _stream(X)))
+    _check(library().sste_linear_wgrad_at(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(X), I, ldx, x_scale, seed, offset,
+                                          first_token, _ptr(dW), lddw, int(bool(accumulate)), _ptr(workspace), ws_bytes, _stream(X)))
     return dW
 
 
@@ -319,13 +331,14 @@ def cast_fp8(X: torch.Tensor, scale: float, out_dtype: int = F8E4M3, Q: Optional
     return (Q if store else None), amax_out
 
 
-def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16):
-    """sste_mvue_materialize: MVUE(dY^T) as a packed 2:4 operand.  Returns (vals (O, T/2), meta (O, T/8))."""
+def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16, first_token: int = 0):
+    """sste_mvue_materialize(_at): MVUE(dY^T) as a packed 2:4 operand.  Returns (vals (O, T/2), meta (O, T/8))."""
     T, O, lddy = _matrix(dY, _esize(dtype), "dY")
     vals, meta = packed_buffers(O, T, dtype, dY.device)
     vals.zero_()
     meta.zero_()
-    _check(library().sste_mvue_materialize(_ptr(dY), T, O, lddy, dtype, seed, offset, _ptr(vals), _ptr(meta), _stream(dY)))
+    _check(library().sste_mvue_materialize_at(_ptr(dY), T, O, lddy, dtype, seed, offset, first_token, _ptr(vals), _ptr(meta),
+                                              _stream(dY)))
     return vals, meta
 
 

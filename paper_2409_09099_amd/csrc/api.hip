@@ -51,6 +51,7 @@ RngKey derive_key(uint64_t seed, uint64_t offset) {
   RngKey r;
   r.k0 = (uint32_t)k;
   r.k1 = (uint32_t)(k >> 32);
+  r.first_group = 0;
   return r;
 }
 
@@ -340,6 +341,13 @@ static int wgrad_shape_check(int64_t T, int64_t O, int64_t I, int dtype, const c
   return SSTE_OK;
 }
 
+int sste_wgrad_plan_override(int mi, int ni, int splits) {
+  clear_error();
+  if (!wgrad_plan_override(mi, ni, splits))
+    return fail(SSTE_ERR_VALUE, "wgrad_plan_override: tile (%d, %d) is none of (8,4), (6,3), (8,3), (0,0), or splits=%d is outside 0..32", mi, ni, splits);
+  return SSTE_OK;
+}
+
 size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
   if (wgrad_shape_check(T, O, I, dtype, "wgrad_workspace_bytes") != SSTE_OK) return 0;
   return wgrad_workspace_bytes(T, O, I, dtype);
@@ -406,11 +414,28 @@ int sste_linear_wgrad_noalloc(const void* dY, int64_t T, int64_t O, int64_t lddy
                     "linear_wgrad_noalloc launch");
 }
 
+// first_token: global index of the tensor's first token row; whole groups, and (first_token / 4 + T / 4) * O < 2^64
+static int check_first_token(const char* who, int64_t first_token, int64_t T, int64_t O) {
+  if (first_token < 0 || first_token % 4 != 0) return fail(SSTE_ERR_SHAPE, "%s: first_token=%lld must be >= 0 and a multiple of 4", who, (long long)first_token);
+  const unsigned __int128 last = ((unsigned __int128)(first_token / 4) + (unsigned __int128)(T / 4) + 1) * (unsigned __int128)(O > 0 ? O : 1);
+  if (last >> 64) return fail(SSTE_ERR_UNSUPPORTED, "%s: group ids of this shard exceed 64 bits", who);
+  return SSTE_OK;
+}
+
 int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
                       int64_t I, int64_t ldx, float x_scale, uint64_t seed, uint64_t offset, float* dW, int64_t lddw,
                       int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return sste_linear_wgrad_at(dY, T, O, lddy, dtype, dy_scale, X, I, ldx, x_scale, seed, offset, 0, dW, lddw, accumulate, workspace,
+                              workspace_bytes, hip_stream);
+}
+
+int sste_linear_wgrad_at(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* X,
+                         int64_t I, int64_t ldx, float x_scale, uint64_t seed, uint64_t offset, int64_t first_token,
+                         float* dW, int64_t lddw, int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
   clear_error();
   int st = check_wgrad_args("linear_wgrad", dY, T, O, lddy, dtype, dy_scale, X, I, ldx, x_scale, dW, lddw, accumulate);
+  if (st != SSTE_OK) return st;
+  st = check_first_token("linear_wgrad", first_token, T, O);
   if (st != SSTE_OK) return st;
   size_t need = sste_wgrad_workspace_bytes(T, O, I, dtype);
   if (need > 0) {
@@ -420,13 +445,20 @@ int sste_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
   }
   float scale = dy_scale * x_scale;
   if (is_8bit(dtype)) scale *= 2.0f;            // the sparsified 8-bit operand is stored halved
-  return hip_status(launch_linear_wgrad(dY, T, O, lddy, dtype, X, I, ldx, scale, derive_key(seed, offset), dW, lddw, accumulate,
+  RngKey key = derive_key(seed, offset);
+  key.first_group = (uint64_t)(first_token / 4);
+  return hip_status(launch_linear_wgrad(dY, T, O, lddy, dtype, X, I, ldx, scale, key, dW, lddw, accumulate,
                                         workspace, (hipStream_t)hip_stream),
                     "linear_wgrad launch");
 }
 
 int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, uint64_t seed, uint64_t offset,
                           void* vals, void* meta, void* hip_stream) {
+  return sste_mvue_materialize_at(dY, T, O, lddy, dtype, seed, offset, 0, vals, meta, hip_stream);
+}
+
+int sste_mvue_materialize_at(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, uint64_t seed, uint64_t offset,
+                             int64_t first_token, void* vals, void* meta, void* hip_stream) {
   clear_error();
   if (T < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "mvue_materialize: negative size");
   if (!good_grad_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "mvue_materialize: unknown dtype %d", dtype);
@@ -443,7 +475,11 @@ int sste_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, in
   if (!aligned16(dY) || !aligned16(vals) || (reinterpret_cast<uintptr_t>(meta) & 3u))
     return fail(SSTE_ERR_ALIGN, "mvue_materialize: dY and vals must be 16-byte aligned, meta 4-byte aligned");
   if (T / 8 > 65535) return fail(SSTE_ERR_UNSUPPORTED, "mvue_materialize: T=%lld exceeds 524280", (long long)T);
-  return hip_status(launch_mvue_materialize(dY, T, O, lddy, dtype, derive_key(seed, offset), vals, meta, (hipStream_t)hip_stream),
+  int st = check_first_token("mvue_materialize", first_token, T, O);
+  if (st != SSTE_OK) return st;
+  RngKey key = derive_key(seed, offset);
+  key.first_group = (uint64_t)(first_token / 4);
+  return hip_status(launch_mvue_materialize(dY, T, O, lddy, dtype, key, vals, meta, (hipStream_t)hip_stream),
                     "mvue_materialize launch");
 }
 

@@ -169,7 +169,9 @@ __device__ __forceinline__ void store_stream_b128(void* p, float4 v) {
 }
 
 // ---- host-side launch entry points implemented in the .hip files --------------------------------
-struct RngKey { uint32_t k0, k1; };
+// Key words of the draw, plus the global index of the tensor's first token group (the group id of
+// token group k and channel o is (first_group + k) * O + o).
+struct RngKey { uint32_t k0, k1; uint64_t first_group; };
 RngKey derive_key(uint64_t seed, uint64_t offset);
 
 hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
@@ -196,6 +198,7 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
 size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype);
+bool wgrad_plan_override(int mi, int ni, int splits);
 void* noalloc_scratch(hipError_t* err);   // this GPU's copy of the library's static scratch array
 hipError_t launch_linear_wgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, const void* X,
                                int64_t I, int64_t ldx, float scale, RngKey key, float* dW, int64_t lddw,

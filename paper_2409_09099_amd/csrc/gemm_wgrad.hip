@@ -20,6 +20,7 @@
 #include "common.h"
 #include "mvue_device.h"
 
+#include <atomic>
 #include <mutex>
 
 namespace sste {
@@ -76,7 +77,7 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
   }
   // Group ids of this lane: gid_base + e.  O and och are multiples of CH, so gid_base is one too and the
   // CH consecutive ids share their high word (no carry out of the low word inside the piece).
-  const uint64_t gid_base = (uint64_t)(s * GROUPS + kg) * (uint64_t)O + (uint64_t)och;
+  const uint64_t gid_base = (key.first_group + (uint64_t)(s * GROUPS + kg)) * (uint64_t)O + (uint64_t)och;
   const uint32_t gid_lo0 = (uint32_t)gid_base;
   const uint32_t hi_term = (uint32_t)(gid_base >> 32) * 0x9E3779B9u;
   const int q = kg / GPQ, g = kg % GPQ;
@@ -446,6 +447,18 @@ static double wgrad_model_us(int64_t O, int64_t I, int64_t steps, int mi, int ni
   return t;
 }
 
+// Tile shape / split count forced by sste_wgrad_plan_override (0 = automatic choice).
+static std::atomic<int> g_force_mi{0}, g_force_ni{0}, g_force_splits{0};
+
+bool wgrad_plan_override(int mi, int ni, int splits) {
+  const bool shape_ok = (mi == 0 && ni == 0) || (mi == 8 && ni == 4) || (mi == 6 && ni == 3) || (mi == 8 && ni == 3);
+  if (!shape_ok || splits < 0 || splits > 32) return false;
+  g_force_mi = mi;
+  g_force_ni = ni;
+  g_force_splits = splits;
+  return true;
+}
+
 static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   WgradPlan p{};
   bool fp8 = dtype != SSTE_BF16;
@@ -463,11 +476,14 @@ static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   }
   if (p.packed) {
     static const int shapes[3][2] = {{8, 4}, {6, 3}, {8, 3}};
+    const int fmi = g_force_mi, fni = g_force_ni, fs = g_force_splits;
     double best = 1e30;
     for (int k = 0; k < 3; k++) {
+      if (fmi && (shapes[k][0] != fmi || shapes[k][1] != fni)) continue;
       int64_t smax = steps / 8 < 32 ? steps / 8 : 32;
       if (smax < 1) smax = 1;
       for (int64_t s = 1; s <= smax; s++) {
+        if (fs && s != (fs < smax ? fs : smax)) continue;
         int64_t sps;
         double t = wgrad_model_us(O, I, steps, shapes[k][0], shapes[k][1], s, &sps);
         if (t < best) {

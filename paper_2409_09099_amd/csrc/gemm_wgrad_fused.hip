@@ -99,7 +99,7 @@ k_linear_wgrad_fused(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64
   // the layout the sparse MFMA reads, then the X tile.
 #define WG_SPARSIFY_AND_STORE(step)                                                           \
   do {                                                                                        \
-    uint64_t gid_base = (uint64_t)((int64_t)(step) * GROUPS + kg) * (uint64_t)O + (uint64_t)(o0 + (int64_t)oc * CH); \
+    uint64_t gid_base = (key.first_group + (uint64_t)((int64_t)(step) * GROUPS + kg)) * (uint64_t)O + (uint64_t)(o0 + (int64_t)oc * CH); \
     _Pragma("unroll") for (int e = 0; e < CH; e++) {                                          \
       uint64_t gid = gid_base + e;                                                            \
       uint32_t x = draw_u32(key.k0, key.k1, (uint32_t)gid, (uint32_t)(gid >> 32));            \

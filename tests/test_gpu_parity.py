@@ -398,6 +398,48 @@ def test_mvue_materialize_bit_exact(sste, dtype, case):
         assert np.array_equal(gv, rv), (case, seed, np.argwhere(gv != rv)[:5])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+def test_mvue_group_ids_beyond_32_bits_and_token_shards(sste, dtype):
+    """The draw takes the 64-bit group id ((first_token + t) / 4) * O + o.  Shards of the token axis placed
+    where the ids cross 2^32 inside the tensor, and far beyond it, against the oracle bit for bit; and a
+    tensor cut into two shards gives the very operand of the whole."""
+    wl = WL.WORKLOADS[1]
+    T, O = 512, 256
+    codes, _, dYd = operand(sste, WL.output_gradient(wl, 0, T=T, O=O)[0], dtype)
+    for first_token in (4 * ((1 << 24) - 3), 1 << 40, 4 * ((1 << 54) + 5)):       # (2^24 - 3) * 256 = 2^32 - 768: ids cross 2^32 at group row 3
+        vals, meta = sste.mvue_materialize(dYd, 9, 3, dt(sste, dtype), first_token=first_token)
+        rv, rm = OM.mvue_pack(codes, 9, 3, dtype, first_token=first_token)
+        gv, gm = OP.from_fragment_major(host(vals).numpy().view(rv.dtype).reshape(-1), host(meta).numpy().reshape(-1), O, T, dtype)
+        assert np.array_equal(gm, rm) and np.array_equal(gv, rv), first_token
+    whole_v, whole_m = OM.mvue_pack(codes, 9, 3, dtype)
+    half = T // 2
+    v2, m2 = sste.mvue_materialize(dYd[half:], 9, 3, dt(sste, dtype), first_token=half)
+    gv, gm = OP.from_fragment_major(host(v2).numpy().view(whole_v.dtype).reshape(-1), host(m2).numpy().reshape(-1), O, half, dtype)
+    assert np.array_equal(gv, whole_v[:, half // 2:]) and np.array_equal(gm, whole_m[:, half // 8:])
+    with pytest.raises(sste.SsteError) as ei:
+        sste.mvue_materialize(dYd, 9, 3, dt(sste, dtype), first_token=6)
+    assert ei.value.status == 2
+
+
+@pytest.mark.parametrize("T,O,I", [(512, 256, 128), (4096, 512, 256)])       # in-GEMM estimator; pre-pass + packed GEMM
+def test_linear_wgrad_token_shards_add_up_to_the_whole(sste, T, O, I):
+    wl = WL.WORKLOADS[1]
+    dyb, xb = WL.output_gradient(wl, 0, T=T, O=O)[0], WL.activations(wl, 0, T=T, I=I)[0]
+    dY, X = bf16_dev(dyb), bf16_dev(xb)
+    whole = sste.linear_wgrad(dY, X, 5, 8)
+    half = T // 2
+    parts = sste.linear_wgrad(dY[:half], X[:half], 5, 8)
+    sste.linear_wgrad(dY[half:], X[half:], 5, 8, dW=parts, accumulate=True, first_token=half)
+    ref = OL.linear_wgrad(dyb, xb, 5, 8)
+    assert rel_err(host(parts).numpy().astype(np.float64), ref) <= 1e-4
+    assert rel_err(host(whole).numpy().astype(np.float64), ref) <= 1e-4
+    ref2 = OL.linear_wgrad(dyb[half:], xb[half:], 5, 8, first_token=half)
+    got2 = sste.linear_wgrad(dY[half:], X[half:], 5, 8, first_token=half)
+    assert rel_err(host(got2).numpy().astype(np.float64), ref2) <= 1e-4
+    wrong = sste.linear_wgrad(dY[half:], X[half:], 5, 8)                      # without its place in the batch: other draws
+    assert not torch.equal(wrong, got2)
+
+
 def test_mvue_materialize_refuses_partial_pieces(sste):
     """The estimator kernel reads dY in 16-byte pieces: channel counts and leading dimensions that are not
     whole pieces, and misaligned bases, are refused before anything is launched."""
@@ -505,6 +547,26 @@ def test_linear_wgrad_matches_oracle(sste, dtype, T, O, I):
     assert err <= TOL.get(dtype, 6e-2), err
     # the sparse operand is bit-identical on both sides, so only float32 accumulation order differs
     assert err <= 1e-4, err
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3", "e5m2"])
+@pytest.mark.parametrize("mi,ni,splits", [(8, 4, 1), (8, 4, 3), (8, 3, 2), (8, 3, 5), (6, 3, 4)])
+def test_linear_wgrad_every_tile_shape_with_ragged_tails(sste, dtype, mi, ni, splits):
+    """The large-problem path with each workgroup tile (256 x 256, 256 x 192, 192 x 192) and several split
+    counts forced, on shapes whose channel and feature counts end inside a tile and inside a 16-row block:
+    every element against the oracle, and the split count must not change the estimator's draws."""
+    T, O, I = (2560, 520, 456) if dtype == "bf16" else (2560, 528, 464)
+    try:
+        sste.wgrad_plan_override(mi, ni, splits)
+        dW, ref = _wgrad_case(sste, dtype, T, O, I, seed=17, offset=2)
+        got = host(dW).numpy().astype(np.float64)
+    finally:
+        sste.wgrad_plan_override(0, 0, 0)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= 1e-4
+    with pytest.raises(sste.SsteError) as ei:
+        sste.wgrad_plan_override(4, 4, 0)
+    assert ei.value.status == 5
 
 
 def test_linear_wgrad_accumulate_and_reproducible(sste):

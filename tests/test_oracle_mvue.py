@@ -327,3 +327,18 @@ def test_bitspec_positions_equal_the_plain_definition_on_stored_patterns():
     got = F.bf16_to_f32(vals[rows]).astype(np.float64)
     want = np.stack([theta_d[rows, pos_d[rows, 0]], theta_d[rows, pos_d[rows, 1]]], axis=1)
     assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-45)          # one bf16 rounding of h
+
+
+def test_token_shards_draw_what_the_whole_tensor_draws():
+    """first_token places a shard of the token axis in the whole batch: its packed operand is the
+    corresponding column range of the whole tensor's, and group ids follow (first_token / 4 + k) * O + o."""
+    rs = np.random.default_rng(11)
+    codes = F.f32_to_bf16_rne(rs.standard_normal((64, 24)).astype(np.float32)).reshape(64, 24)
+    wv, wm = M.mvue_pack(codes, 3, 9)
+    for cut in (8, 32, 56):
+        sv, sm = M.mvue_pack(codes[cut:], 3, 9, first_token=cut)
+        assert np.array_equal(sv, wv[:, cut // 2:]) and np.array_equal(sm, wm[:, cut // 8:])
+    ids = M.group_ids(16, 24, first_token=4 * 1000)
+    assert ids.shape == (4, 24) and int(ids[0, 0]) == 1000 * 24 and int(ids[3, 23]) == 1003 * 24 + 23
+    with pytest.raises(ValueError):
+        M.group_ids(16, 24, first_token=6)
