@@ -215,6 +215,43 @@ int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype,
                     void* Z, int64_t ldz, void* hip_stream);
 
 /*
+ * sste_linear_fwd with a choice of output format and the output's largest magnitude (Sec. 5.2: the
+ * operands of the FP8 GEMMs are rescaled per tensor before the cast; the output of one layer is an
+ * operand of the next, so casting it where it is produced saves a pass over it).
+ *
+ *   z_dtype SSTE_BF16  : Z = RNE_bf16((x_scale * w_scale) * acc); z_scale must be 1; amax_out optional.
+ *   z_dtype SSTE_F8E4M3: Z = RNE_e4m3(clamp(acc * q, +-448)) with q = (x_scale * w_scale) / z_scale formed
+ *                        in float32 on the host (one product, one division); the consumer reads Z with
+ *                        scale z_scale.  O and ldz multiples of 16.  amax_out is required.
+ *   amax_out           : device float* or NULL; receives max |acc| * (x_scale * w_scale), the largest
+ *                        magnitude of the unrounded output in real units (0 for an empty output), from
+ *                        which the caller derives z_scale of a later iteration (delayed scaling: the
+ *                        scale used now comes from earlier iterations, see sste_amax_history_push).
+ * acc is the float32 accumulator of the product.  Everything else as sste_linear_fwd.
+ */
+int sste_linear_fwd_ex(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale,
+                       const void* vals, const void* meta, int64_t O, float w_scale,
+                       void* Z, int64_t ldz, int z_dtype, float z_scale, float* amax_out, void* hip_stream);
+
+/*
+ * Delayed scaling (the per-tensor scaling recipe Sec. 5.2 refers to): the scale of an 8-bit tensor in
+ * iteration k is derived from the largest magnitudes seen in the last `length` iterations, so no pass
+ * over the tensor is needed before it is cast.  Host-only helper; the caller owns the struct.
+ *   sste_amax_history_init  empties the window (length clamped to 1 .. SSTE_AMAX_HISTORY_MAX).
+ *   sste_amax_history_push  records `amax` (a finite value >= 0 read back from an amax_out; anything else
+ *                           is ignored) and returns the scale to use next: max(window) / format_max, or 1
+ *                           while the window holds only zeros.  format_max: 448 (e4m3) / 57344 (e5m2).
+ */
+#define SSTE_AMAX_HISTORY_MAX 64
+typedef struct sste_amax_history {
+  float window[SSTE_AMAX_HISTORY_MAX];
+  int length;
+  int next;
+} sste_amax_history;
+void sste_amax_history_init(sste_amax_history* h, int length);
+float sste_amax_history_push(sste_amax_history* h, float amax, float format_max);
+
+/*
  * Weight-gradient GEMM with the output gradient sparsified 2:4 by the minimum-variance unbiased
  * estimator (Sec. 5.1: grad_W = MVUE(grad_Z^T) X).
  *

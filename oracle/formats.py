@@ -123,3 +123,12 @@ def cast_fp8(x_bits, scale, fmt="e4m3"):
     codes = f32_to_e4m3_rne_sat(q) if fmt == "e4m3" else f32_to_e5m2_rne_sat(q)
     amax = np.float32(np.max(np.abs(x))) if x.size else np.float32(0.0)
     return codes.reshape(x.shape), amax
+
+
+def delayed_scale(amax_window, fmt="e4m3"):
+    """Delayed scaling (the per-tensor recipe Sec. 5.2 refers to): the scale of an 8-bit tensor from the
+    largest magnitudes of earlier iterations -- max(window) / format maximum in float32, 1 while the
+    window holds only zeros."""
+    fmax = np.float32(E4M3_MAX if fmt == "e4m3" else E5M2_MAX)
+    m = np.float32(max([np.float32(a) for a in amax_window], default=np.float32(0.0)))
+    return np.float32(m / fmax) if m > 0 else np.float32(1.0)

@@ -33,6 +33,26 @@ def linear_fwd(x_codes, vals, meta, dtype="bf16", x_scale=1.0, w_scale=1.0):
     return (X @ Wd.T) * (np.float64(np.float32(x_scale)) * np.float64(np.float32(w_scale)))
 
 
+def linear_fwd_e4m3_out(x_codes, vals, meta, dtype="bf16", x_scale=1.0, w_scale=1.0, z_scale=1.0):
+    """The forward product with an 8-bit output (Sec. 5.2: every operand of an FP8 GEMM is rescaled per
+    tensor and cast; the output of one layer is an operand of the next).
+
+    acc = X . decode(vals, meta)^T in float64 (the exact product of the stored operands);
+    real = x_scale * w_scale (one float32 product);  q = real / z_scale (one float32 division);
+    code = RNE_e4m3(clamp(float32(acc * q), +-448));  amax = max |acc| * real  (float32).
+    Returns (codes uint8 (T, O), amax float32).  The consumer reads the codes with scale z_scale."""
+    X = decode_activations(x_codes, dtype)
+    Wd = projection.decode_packed(vals, meta, dtype)
+    acc = X @ Wd.T
+    real = np.float32(np.float32(x_scale) * np.float32(w_scale))
+    q = np.float32(real / np.float32(z_scale))
+    with np.errstate(over="ignore"):
+        stored = (acc * np.float64(q)).astype(np.float32)
+    codes = formats.f32_to_e4m3_rne_sat(stored).reshape(acc.shape)
+    amax = np.float32(np.float32(np.max(np.abs(acc))) * real) if acc.size else np.float32(0.0)
+    return codes, amax
+
+
 def linear_fwd_loops(X, Wd):
     """Triple loop Z[t][o] = sum_i X[t][i] Wd[o][i] for tiny shapes (pure Python floats)."""
     T, I = X.shape

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     library,
     linear_dgrad,
     linear_fwd,
+    linear_fwd_ex,
+    AmaxHistory,
     linear_wgrad,
     linear_wgrad_noalloc,
     mvue_materialize,

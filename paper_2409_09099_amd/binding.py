@@ -43,6 +43,12 @@ def library() -> ctypes.CDLL:
     lib.sste_project_pack_batch_prepare.argtypes = [vp, ci, ci, vp, ctypes.POINTER(i64)]
     lib.sste_project_pack_batch.argtypes = [vp, ci, i64, ci, vp]
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
+    lib.sste_linear_fwd_ex.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, ci, f32, vp, vp]
+    lib.sste_linear_fwd_ex.restype = ci
+    lib.sste_amax_history_init.argtypes = [vp, ci]
+    lib.sste_amax_history_init.restype = None
+    lib.sste_amax_history_push.argtypes = [vp, f32, f32]
+    lib.sste_amax_history_push.restype = f32
     lib.sste_linear_dgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_wgrad.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp, sz, vp]
     lib.sste_linear_wgrad_noalloc.argtypes = [vp, i64, i64, i64, ci, f32, vp, i64, i64, f32, u64, u64, vp, i64, ci, vp]
@@ -250,6 +256,37 @@ def linear_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, 
     _check(library().sste_linear_fwd(_ptr(X), T, I, ldx, dtype, x_scale, _ptr(vals), _ptr(meta), O, w_scale, _ptr(Z), ldz,
                                      _stream(X)))
     return Z
+
+
+def linear_fwd_ex(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, dtype: int = BF16, x_scale: float = 1.0,
+                  w_scale: float = 1.0, z_dtype: int = BF16, z_scale: float = 1.0, Z: Optional[torch.Tensor] = None,
+                  amax_out: Optional[torch.Tensor] = None):
+    """sste_linear_fwd_ex: the forward product with a bf16 or e4m3 output and the output's largest magnitude.
+    Returns (Z, amax_out)."""
+    T, I, ldx = _matrix(X, _esize(dtype), "X")
+    if Z is None:
+        Z = torch.empty((T, O), dtype=torch.uint8 if z_dtype == F8E4M3 else torch.bfloat16, device=X.device)
+    if amax_out is None and z_dtype == F8E4M3:
+        amax_out = torch.empty(1, dtype=torch.float32, device=X.device)
+    _, _, ldz = _matrix(Z, _esize(z_dtype), "Z")
+    _check(library().sste_linear_fwd_ex(_ptr(X), T, I, ldx, dtype, x_scale, _ptr(vals), _ptr(meta), O, w_scale, _ptr(Z), ldz,
+                                        z_dtype, z_scale, _ptr(amax_out), _stream(X)))
+    return Z, amax_out
+
+
+class AmaxHistory:
+    """sste_amax_history: window of the last `length` largest magnitudes of one tensor (host side)."""
+
+    class _Struct(ctypes.Structure):
+        _fields_ = [("window", ctypes.c_float * 64), ("length", ctypes.c_int), ("next", ctypes.c_int)]
+
+    def __init__(self, length: int):
+        self._h = AmaxHistory._Struct()
+        library().sste_amax_history_init(ctypes.byref(self._h), length)
+
+    def push(self, amax: float, format_max: float) -> float:
+        """Records amax and returns the scale to use next."""
+        return float(library().sste_amax_history_push(ctypes.byref(self._h), amax, format_max))
 
 
 def linear_dgrad(dY: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, I: int, dtype: int = BF16, dy_scale: float = 1.0,

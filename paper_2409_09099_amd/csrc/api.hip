@@ -312,23 +312,59 @@ int sste_project_pack_batch(const void* table_device, int n_items, int64_t total
 
 int sste_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale, const void* vals,
                     const void* meta, int64_t O, float w_scale, void* Z, int64_t ldz, void* hip_stream) {
+  return sste_linear_fwd_ex(X, T, I, ldx, dtype, x_scale, vals, meta, O, w_scale, Z, ldz, SSTE_BF16, 1.0f, nullptr, hip_stream);
+}
+
+int sste_linear_fwd_ex(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale, const void* vals,
+                       const void* meta, int64_t O, float w_scale, void* Z, int64_t ldz, int z_dtype, float z_scale,
+                       float* amax_out, void* hip_stream) {
   clear_error();
   if (T < 0 || I < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "linear_fwd: negative size");
   if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_fwd: unknown dtype %d", dtype);
+  if (!good_dtype(z_dtype)) return fail(SSTE_ERR_DTYPE, "linear_fwd: z_dtype %d is neither bf16 nor e4m3", z_dtype);
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_fwd: I=%lld is not a multiple of 8", (long long)I);
-  if (!good_scale(x_scale) || !good_scale(w_scale)) return fail(SSTE_ERR_VALUE, "linear_fwd: scales must be finite and > 0");
+  if (!good_scale(x_scale) || !good_scale(w_scale) || !good_scale(z_scale)) return fail(SSTE_ERR_VALUE, "linear_fwd: scales must be finite and > 0");
+  const bool z8 = z_dtype == SSTE_F8E4M3;
+  if (!z8 && z_scale != 1.0f) return fail(SSTE_ERR_VALUE, "linear_fwd: z_scale must be 1 for a bf16 output");
+  if (z8 && !amax_out) return fail(SSTE_ERR_NULL, "linear_fwd: an e4m3 output needs amax_out (the next scale is derived from it)");
+  if (reinterpret_cast<uintptr_t>(amax_out) & 3u) return fail(SSTE_ERR_ALIGN, "linear_fwd: amax_out must be 4-byte aligned");
   int kmult = dtype == SSTE_F8E4M3 ? 128 : 64;
   if (I % kmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: I=%lld must be a multiple of %d for this element type", (long long)I, kmult);
-  if (O % 8 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: O=%lld must be a multiple of 8", (long long)O);
+  const int zmult = z8 ? 16 : 8;
+  if (O % zmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: O=%lld must be a multiple of %d", (long long)O, zmult);
   if (ldx < I || ldz < O) return fail(SSTE_ERR_SHAPE, "linear_fwd: leading dimension smaller than the row length");
-  if (ldx % elems_per_16B(dtype) != 0 || ldz % 8 != 0) return fail(SSTE_ERR_ALIGN, "linear_fwd: ldx / ldz break the 16-byte row rule");
+  if (ldx % elems_per_16B(dtype) != 0 || ldz % zmult != 0) return fail(SSTE_ERR_ALIGN, "linear_fwd: ldx / ldz break the 16-byte row rule");
   bool empty = (T == 0 || O == 0);
   if (!empty && (!Z || (I > 0 && (!X || !vals || !meta)))) return fail(SSTE_ERR_NULL, "linear_fwd: NULL X, vals, meta or Z");
   if (!aligned16(X) || !aligned16(vals) || !aligned16(meta) || !aligned16(Z))
     return fail(SSTE_ERR_ALIGN, "linear_fwd: X, vals, meta and Z must be 16-byte aligned");
   if (!linear_fwd_supported(T, I, ldx, O, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd: a tile of this problem does not fit 32-bit offsets");
-  float scale = x_scale * w_scale;
-  return hip_status(launch_linear_fwd(X, T, I, ldx, dtype, scale, vals, meta, O, Z, ldz, (hipStream_t)hip_stream), "linear_fwd launch");
+  const float real_scale = x_scale * w_scale;                 // accumulator -> the tensor's real units
+  const float store_scale = z8 ? real_scale / z_scale : real_scale;
+  return hip_status(launch_linear_fwd(X, T, I, ldx, dtype, store_scale, vals, meta, O, Z, ldz, z_dtype, real_scale, amax_out,
+                                      (hipStream_t)hip_stream),
+                    "linear_fwd launch");
+}
+
+// ---- delayed scaling (host only) ----------------------------------------------------------------------
+void sste_amax_history_init(sste_amax_history* h, int length) {
+  if (!h) return;
+  if (length < 1) length = 1;
+  if (length > SSTE_AMAX_HISTORY_MAX) length = SSTE_AMAX_HISTORY_MAX;
+  for (int i = 0; i < SSTE_AMAX_HISTORY_MAX; i++) h->window[i] = 0.0f;
+  h->length = length;
+  h->next = 0;
+}
+
+float sste_amax_history_push(sste_amax_history* h, float amax, float format_max) {
+  if (!h || h->length < 1 || h->length > SSTE_AMAX_HISTORY_MAX || !(format_max > 0.0f)) return 1.0f;
+  if (std::isfinite(amax) && amax >= 0.0f) {                   // anything else leaves the window as it is
+    h->window[h->next] = amax;
+    h->next = (h->next + 1) % h->length;
+  }
+  float m = 0.0f;
+  for (int i = 0; i < h->length; i++) m = h->window[i] > m ? h->window[i] : m;
+  return m > 0.0f ? m / format_max : 1.0f;
 }
 
 static int wgrad_shape_check(int64_t T, int64_t O, int64_t I, int dtype, const char* who) {

@@ -194,7 +194,8 @@ hipError_t launch_flip_count(const void* a, const void* b, int64_t nbytes, unsig
 hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, RngKey key,
                                    void* vals, void* meta, hipStream_t s);
 hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
-                             const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s);
+                             const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, int z_dtype,
+                             float amax_scale, float* amax_out, hipStream_t s);
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
 size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype);

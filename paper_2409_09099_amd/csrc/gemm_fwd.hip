@@ -49,11 +49,47 @@ constexpr int NUM_CU = 256;
 
 }  // namespace
 
-template <bool FP8, int WM, int WN, int NS>
+// Output side of the forward GEMMs.  z8 == nullptr: Z is bf16, value = acc * scale.  Otherwise Z is e4m3
+// with its own per-tensor scale folded into `scale` by the host (Sec. 5.2: the output of an FP8 layer is
+// rescaled per tensor and cast; the consumer multiplies by z_scale again).  amax_bits, if given,
+// receives max |acc| * amax_scale over the whole tensor (float32 bits; non-negative floats order like
+// their patterns): one atomic per workgroup, skipped when it cannot raise the value.
+struct FwdOut {
+  uint16_t* z16;          // bf16 output (ZF8 = false)
+  uint8_t* z8;            // e4m3 output (ZF8 = true)
+  int64_t ldz;            // leading dimension in elements
+  float scale;            // acc -> stored value (before rounding)
+  float amax_scale;       // acc -> the tensor's real units
+  uint32_t* amax_bits;    // nullable
+};
+
+// max |acc| of the calling workgroup (NW waves) -> *amax_bits.  `red` is NW dwords of LDS nobody else uses
+// between the two barriers.
+template <int NW>
+__device__ __forceinline__ void publish_tile_amax(uint32_t m, float amax_scale, uint32_t* __restrict__ amax_bits, uint32_t* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < NW; w++) m = max(m, red[w]);
+    const uint32_t v = f2u(u2f(m) * amax_scale);
+    if (v > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, v);
+  }
+  __syncthreads();
+}
+
+__global__ void k_fill_u32_fwd(uint32_t* p, uint32_t v) { *p = v; }
+
+template <bool FP8, int WM, int WN, int NS, bool ZF8, bool AMAX>
 __global__ void __launch_bounds__(64 * WM * WN, (WM * WN <= 4 && NS <= 2) ? 2 : 1)
 k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
              const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
-             int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
+             int64_t O, FwdOut out, int m_tiles) {
+  const float scale = out.scale;
+  uint16_t* __restrict__ Z = out.z16;
+  const int64_t ldz = out.ldz;
   constexpr int NW = WM * WN;
   constexpr int BM = 128 * WM, BN = 64 * WN;
   constexpr int MB = FP8 ? 16 : 8;                // position bytes per row and k-step
@@ -185,7 +221,36 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
   // epilogue: accumulators -> LDS (row = token, the wave's 128 channels contiguous) -> 16-byte stores
   wait_vmcnt<0>();
   __syncthreads();
+  if (AMAX) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) m = max(m, f2u(acc[mi][ni][r]) & 0x7FFFFFFFu);
+    publish_tile_amax<NW>(m, out.amax_scale, out.amax_bits, (uint32_t*)smem);
+  }
   uint8_t* eb = smem + wave * (64 * EPI_ROW);
+  if (ZF8) {
+    // e4m3 output: a lane's four values of a tile are four consecutive channels = one dword
+#pragma unroll
+    for (int mi = 0; mi < MI; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI; ni++) {
+        int w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(acc[mi][ni][0] * scale), clamp448(acc[mi][ni][1] * scale), 0, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(acc[mi][ni][2] * scale), clamp448(acc[mi][ni][3] * scale), w, true);
+        *(int*)(eb + (16 * ni + j) * EPI_ROW + 16 * mi + 4 * q) = w;
+      }
+#pragma unroll
+    for (int it = 0; it < 8; it++) {
+      int row = 8 * it + (lane >> 3), chunk = lane & 7;
+      uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
+      int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 16 * chunk;
+      if (t < T && o < O) store_stream_b128(out.z8 + t * ldz + o, v);
+    }
+    return;
+  }
 #pragma unroll
   for (int mi = 0; mi < MI; mi++)
 #pragma unroll
@@ -233,11 +298,14 @@ constexpr int fwd_pipe_smem() {
 }
 
 // One output tile: channels [o0, o0 + 32 MI_) x tokens [t0, t0 + 64 NI_).  `smem` is the workgroup's LDS.
-template <bool FP8, int MI_, int NI_>
+template <bool FP8, int MI_, int NI_, bool ZF8, bool AMAX>
 __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes,
                                               int64_t ldx_bytes, const uint8_t* __restrict__ vals,
-                                              const uint8_t* __restrict__ meta, int64_t O, float scale,
-                                              uint16_t* __restrict__ Z, int64_t ldz, int64_t o0, int64_t t0) {
+                                              const uint8_t* __restrict__ meta, int64_t O, const FwdOut& out,
+                                              int64_t o0, int64_t t0) {
+  const float scale = out.scale;
+  uint16_t* __restrict__ Z = out.z16;
+  const int64_t ldz = out.ldz;
   constexpr int WN = 4, NW = 8, BM = 32 * MI_, BN = 64 * NI_, NR = 3;
   constexpr int MB = FP8 ? 16 : 8, MBLK = 16 * MB;
   constexpr int LA = (BM / 16 + NW - 1) / NW;                    // weight blocks (1 KiB) per wave and k-step
@@ -392,7 +460,42 @@ __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __re
   // epilogue: accumulators -> LDS (row = token, the wave's 16 MI_ channels contiguous) -> 16-byte stores
   wait_vmcnt<0>();
   __syncthreads();
+  if (AMAX) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int mi = 0; mi < MI_; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI_; ni++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) m = max(m, f2u(acc[mi][ni][r]) & 0x7FFFFFFFu);
+    publish_tile_amax<NW>(m, out.amax_scale, out.amax_bits, (uint32_t*)smem);
+  }
   uint8_t* eb = smem + wave * (16 * NI_ * EROW);
+  if (ZF8) {
+    // e4m3 output: a lane's four values of a tile are four consecutive channels = one dword; a token row of
+    // the wave is 16 MI_ bytes
+#pragma unroll
+    for (int mi = 0; mi < MI_; mi++)
+#pragma unroll
+      for (int ni = 0; ni < NI_; ni++) {
+        int w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(acc[mi][ni][0] * scale), clamp448(acc[mi][ni][1] * scale), 0, false);
+        w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(acc[mi][ni][2] * scale), clamp448(acc[mi][ni][3] * scale), w, true);
+        *(int*)(eb + (16 * ni + j) * EROW + 16 * mi + 4 * q) = w;
+      }
+    constexpr int CHUNKS8 = MI_;                                 // 16-byte chunks (16 channels) per token row
+    constexpr int NCH8 = 16 * NI_ * CHUNKS8;
+#pragma unroll
+    for (int it = 0; it < (NCH8 + 63) / 64; it++) {
+      int c = 64 * it + lane;
+      if (c < NCH8) {
+        int row = c / CHUNKS8, chunk = c % CHUNKS8;
+        uint4 v = *(const uint4*)(eb + row * EROW + chunk * 16);
+        int64_t t = t0 + 16 * NI_ * wn + row, o = o0 + 16 * MI_ * wm + 16 * chunk;
+        if (t < T && o < O) store_stream_b128(out.z8 + t * ldz + o, v);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mi = 0; mi < MI_; mi++)
 #pragma unroll
@@ -419,75 +522,75 @@ __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __re
 
 // One tile shape for the whole grid.  Workgroups are numbered so that each XCD works on a contiguous
 // range of tiles, o-tiles fastest.
-template <bool FP8, int MI_, int NI_>
+template <bool FP8, int MI_, int NI_, bool ZF8, bool AMAX>
 __global__ void __launch_bounds__(512, 1)
 k_linear_fwd_pipe(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
                   const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
-                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles) {
+                  int64_t O, FwdOut out, int m_tiles) {
   __shared__ __align__(1024) uint8_t smem[fwd_pipe_smem<FP8, MI_, NI_>()];
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tm = logical % m_tiles, tn = logical / m_tiles;
-  fwd_pipe_tile<FP8, MI_, NI_>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * (32 * MI_),
-                               (int64_t)tn * (64 * NI_));
+  fwd_pipe_tile<FP8, MI_, NI_, ZF8, AMAX>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, out, (int64_t)tm * (32 * MI_),
+                                          (int64_t)tn * (64 * NI_));
 }
 
 // Two tile shapes in one grid, for layers whose 256 x 256 tiles fill the CUs a whole number of times plus
 // a remainder of at most half a round: the first n_big workgroups take 256 x 256 tiles, the rest take
 // the remaining tiles as 256 x 128 halves.  The last round then has twice as many, half as long
 // workgroups instead of leaving more than half of the CUs idle for a full tile time.
-template <bool FP8>
+template <bool FP8, bool ZF8, bool AMAX>
 __global__ void __launch_bounds__(512, 1)
 k_linear_fwd_dual(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t ldx_bytes,
                   const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
-                  int64_t O, float scale, uint16_t* __restrict__ Z, int64_t ldz, int m_tiles, int n_big) {
+                  int64_t O, FwdOut out, int m_tiles, int n_big) {
   __shared__ __align__(1024) uint8_t smem[fwd_pipe_smem<FP8, 8, 4>()];
   static_assert(fwd_pipe_smem<FP8, 8, 2>() <= fwd_pipe_smem<FP8, 8, 4>(), "the half tile fits in the full tile's LDS");
   const int bid = blockIdx.x;
   if (bid < n_big) {
     const int logical = xcd_contiguous(bid, n_big);
     const int tm = logical % m_tiles, tn = logical / m_tiles;
-    fwd_pipe_tile<FP8, 8, 4>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * 256, (int64_t)tn * 256);
+    fwd_pipe_tile<FP8, 8, 4, ZF8, AMAX>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, out, (int64_t)tm * 256, (int64_t)tn * 256);
   } else {
     const int h = xcd_contiguous(bid - n_big, (int)gridDim.x - n_big);      // half-tile number
     const int tile = n_big + (h >> 1);
     const int tm = tile % m_tiles, tn = tile / m_tiles;
     const int64_t t0 = (int64_t)tn * 256 + 128 * (h & 1);
     if (t0 >= T) return;                       // second half of a ragged last token tile: nothing to do
-    fwd_pipe_tile<FP8, 8, 2>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, scale, Z, ldz, (int64_t)tm * 256, t0);
+    fwd_pipe_tile<FP8, 8, 2, ZF8, AMAX>(smem, X, T, k_bytes, ldx_bytes, vals, meta, O, out, (int64_t)tm * 256, t0);
   }
 }
 
-template <bool FP8, int MI_, int NI_>
-static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
-                            const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
+template <bool FP8, int MI_, int NI_, bool ZF8, bool AMAX>
+static void launch_fwd_pipe(const void* X, int64_t T, int64_t I, int64_t ldx, const FwdOut& out, const void* vals,
+                            const void* meta, int64_t O, hipStream_t s) {
   constexpr int BM = 32 * MI_, BN = 64 * NI_;
   int m_tiles = (int)((O + BM - 1) / BM), n_tiles = (int)((T + BN - 1) / BN);
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
   int64_t eb = FP8 ? 1 : 2;
-  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8, MI_, NI_>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
-              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_pipe<FP8, MI_, NI_, ZF8, AMAX>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+              (const uint8_t*)vals, (const uint8_t*)meta, O, out, m_tiles);
 }
 
-template <bool FP8>
-static void launch_fwd_dual(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
-                            const void* meta, int64_t O, void* Z, int64_t ldz, int n_big, hipStream_t s) {
+template <bool FP8, bool ZF8, bool AMAX>
+static void launch_fwd_dual(const void* X, int64_t T, int64_t I, int64_t ldx, const FwdOut& out, const void* vals,
+                            const void* meta, int64_t O, int n_big, hipStream_t s) {
   int m_tiles = (int)((O + 255) / 256), n_tiles = (int)((T + 255) / 256);
   int n_small = 2 * (m_tiles * n_tiles - n_big);
   dim3 grid((unsigned)(n_big + n_small)), block(512);
   int64_t eb = FP8 ? 1 : 2;
-  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_dual<FP8>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
-              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles, n_big);
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd_dual<FP8, ZF8, AMAX>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+              (const uint8_t*)vals, (const uint8_t*)meta, O, out, m_tiles, n_big);
 }
 
-template <bool FP8, int WM, int WN, int NS>
-static void launch_fwd_cfg(const void* X, int64_t T, int64_t I, int64_t ldx, float scale, const void* vals,
-                           const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
+template <bool FP8, int WM, int WN, int NS, bool ZF8, bool AMAX>
+static void launch_fwd_cfg(const void* X, int64_t T, int64_t I, int64_t ldx, const FwdOut& out, const void* vals,
+                           const void* meta, int64_t O, hipStream_t s) {
   constexpr int BM = 128 * WM, BN = 64 * WN;
   int m_tiles = (int)((O + BM - 1) / BM), n_tiles = (int)((T + BN - 1) / BN);
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(64 * WM * WN);
   int64_t eb = FP8 ? 1 : 2;
-  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<FP8, WM, WN, NS>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
-              (const uint8_t*)vals, (const uint8_t*)meta, O, scale, (uint16_t*)Z, ldz, m_tiles);
+  SSTE_LAUNCH(SSTE_K_FWD, (k_linear_fwd<FP8, WM, WN, NS, ZF8, AMAX>), grid, block, s, (const uint8_t*)X, T, I * eb, ldx * eb,
+              (const uint8_t*)vals, (const uint8_t*)meta, O, out, m_tiles);
 }
 
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype) {
@@ -498,30 +601,50 @@ bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtyp
   return true;
 }
 
-hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
-                             const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, hipStream_t s) {
-  if (T == 0 || O == 0) return hipSuccess;
-  bool fp8 = dtype == SSTE_F8E4M3;
+// Kernel choice for one combination of operand type, output type and amax.
+template <bool FP8, bool ZF8, bool AMAX>
+static void launch_fwd_variant(const void* X, int64_t T, int64_t I, int64_t ldx, const FwdOut& out, const void* vals,
+                               const void* meta, int64_t O, hipStream_t s) {
   // 256 x 256 tiles (8 waves, 3-stage ring) unless the problem has too few of them to occupy the chip;
   // measured faster than 256 x 128 even at 1.5 rounds of tiles (3072 x 8192 outputs: 33.6 vs 36.4 us)
   int64_t big_tiles = ((O + 255) / 256) * ((T + 255) / 256);
   int64_t rem = big_tiles % NUM_CU;
   if (big_tiles > NUM_CU && rem > 0 && rem <= NUM_CU / 2) {
     // whole rounds of 256 x 256 tiles, then the remainder as twice as many 256 x 128 tiles
-    int n_big = (int)(big_tiles - rem);
-    if (fp8) launch_fwd_dual<true>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, n_big, s);
-    else launch_fwd_dual<false>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, n_big, s);
+    launch_fwd_dual<FP8, ZF8, AMAX>(X, T, I, ldx, out, vals, meta, O, (int)(big_tiles - rem), s);
   } else if (big_tiles >= 128) {
-    if (fp8) launch_fwd_pipe<true, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_pipe<false, 8, 4>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    launch_fwd_pipe<FP8, 8, 4, ZF8, AMAX>(X, T, I, ldx, out, vals, meta, O, s);
   } else if (((O + 255) / 256) * ((T + 127) / 128) < 32) {
     // tiny problems: 128 x 64 tiles by one wave each, eight times as many workgroups (512 x 256 outputs: 14.1 vs 17.3 us)
-    if (fp8) launch_fwd_cfg<true, 1, 1, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_cfg<false, 1, 1, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    launch_fwd_cfg<FP8, 1, 1, 2, ZF8, AMAX>(X, T, I, ldx, out, vals, meta, O, s);
   } else {
-    if (fp8) launch_fwd_cfg<true, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
-    else launch_fwd_cfg<false, 2, 2, 2>(X, T, I, ldx, scale, vals, meta, O, Z, ldz, s);
+    launch_fwd_cfg<FP8, 2, 2, 2, ZF8, AMAX>(X, T, I, ldx, out, vals, meta, O, s);
   }
+}
+
+hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
+                             const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, int z_dtype,
+                             float amax_scale, float* amax_out, hipStream_t s) {
+  if (amax_out) hipLaunchKernelGGL(k_fill_u32_fwd, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
+  if (T == 0 || O == 0) return hipGetLastError();
+  const bool fp8 = dtype == SSTE_F8E4M3, zf8 = z_dtype == SSTE_F8E4M3;
+  FwdOut out;
+  out.z16 = zf8 ? nullptr : (uint16_t*)Z;
+  out.z8 = zf8 ? (uint8_t*)Z : nullptr;
+  out.ldz = ldz;
+  out.scale = scale;
+  out.amax_scale = amax_scale;
+  out.amax_bits = (uint32_t*)amax_out;
+  const bool amax = amax_out != nullptr;
+#define FWD_CASE(F, Z8, A)                                                                \
+  if (fp8 == F && zf8 == Z8 && amax == A) launch_fwd_variant<F, Z8, A>(X, T, I, ldx, out, vals, meta, O, s)
+  FWD_CASE(false, false, false);
+  FWD_CASE(false, false, true);
+  FWD_CASE(false, true, true);          // an e4m3 output always comes with its largest magnitude (the API insists)
+  FWD_CASE(true, false, false);
+  FWD_CASE(true, false, true);
+  FWD_CASE(true, true, true);
+#undef FWD_CASE
   return hipGetLastError();
 }
 

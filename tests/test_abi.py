@@ -265,3 +265,47 @@ def test_cast_fp8_validation(lib):
     assert f(None, 4, 64, 64, 3, 1.0, fake, 64, None, None) == 1
     assert f(fake, 4, 64, 64, 3, 1.0, P(0x1004), 64, None, None) == 3
     assert f(None, 0, 64, 64, 1, 1.0, None, 64, None, None) == 1               # nothing asked for
+
+
+def test_linear_fwd_ex_validation(lib):
+    P = ctypes.c_void_p
+    fake = P(0x1000)
+    f = lib.sste_linear_fwd_ex
+    f.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float, P, P, ctypes.c_int64,
+                  ctypes.c_float, P, ctypes.c_int64, ctypes.c_int, ctypes.c_float, P, P]
+    ok_args = lambda **kw: [kw.get("X", fake), 4, 128, 128, kw.get("dtype", 1), 1.0, fake, fake, kw.get("O", 16), 1.0, fake, kw.get("ldz", 16),
+                            kw.get("z_dtype", 1), kw.get("z_scale", 0.5), kw.get("amax", fake), None]
+    assert f(*ok_args(z_dtype=2)) == 4 and "z_dtype" in _err(lib)            # float32 is not an output format
+    assert f(*ok_args(z_dtype=3)) == 4                                        # nor is e5m2
+    assert f(*ok_args(z_scale=0.0)) == 5
+    assert f(*ok_args(z_dtype=0, z_scale=0.5)) == 5 and "z_scale must be 1" in _err(lib)
+    assert f(*ok_args(amax=None)) == 1 and "amax_out" in _err(lib)            # an 8-bit output needs its largest magnitude
+    assert f(*ok_args(O=8, ldz=8)) == 7                                       # e4m3 rows come in 16-channel pieces
+    assert f(*ok_args(ldz=24)) == 3
+    assert f(*ok_args(amax=P(0x1002))) == 3
+    assert f(*ok_args(X=None)) == 1
+
+
+def test_amax_history_is_a_sliding_window_maximum(lib):
+    from oracle import formats as F
+
+    class H(ctypes.Structure):
+        _fields_ = [("window", ctypes.c_float * 64), ("length", ctypes.c_int), ("next", ctypes.c_int)]
+
+    lib.sste_amax_history_init.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.sste_amax_history_init.restype = None
+    lib.sste_amax_history_push.argtypes = [ctypes.c_void_p, ctypes.c_float, ctypes.c_float]
+    lib.sste_amax_history_push.restype = ctypes.c_float
+    h = H()
+    lib.sste_amax_history_init(ctypes.byref(h), 3)
+    seen = []
+    for amax in [0.0, 2.0, 7.5, 1.0, 0.5, 0.25, 0.125, 900.0]:
+        seen.append(amax)
+        got = lib.sste_amax_history_push(ctypes.byref(h), amax, 448.0)
+        assert got == float(F.delayed_scale(seen[-3:], "e4m3")), (amax, got)
+    assert lib.sste_amax_history_push(ctypes.byref(h), float("nan"), 448.0) == float(F.delayed_scale(seen[-3:], "e4m3"))   # ignored
+    assert lib.sste_amax_history_push(ctypes.byref(h), -1.0, 448.0) == float(F.delayed_scale(seen[-3:], "e4m3"))
+    lib.sste_amax_history_init(ctypes.byref(h), 1000)                         # clamped to the struct's capacity
+    assert h.length == 64
+    assert lib.sste_amax_history_push(ctypes.byref(h), 57344.0 * 2, 57344.0) == 2.0
+    assert lib.sste_amax_history_push(None, 1.0, 448.0) == 1.0

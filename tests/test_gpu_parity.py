@@ -501,6 +501,108 @@ def test_linear_fwd_matches_oracle(sste, dtype, T, O, I):
     assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + np.max(np.abs(ref)) * 1e-4)
 
 
+@pytest.mark.parametrize("dtype,T,O,I", [
+    ("bf16", 512, 256, 1024),        # one-wave tiles
+    ("e4m3", 300, 272, 256),         # ragged token and channel tails
+    ("e4m3", 2100, 1040, 256),       # 256 x 128 four-wave tiles
+    ("bf16", 16424, 528, 128),       # pipelined 256 x 256 tiles, ragged tails
+    ("e4m3", 33344, 272, 128),       # two tile shapes in one grid
+])
+def test_linear_fwd_e4m3_output_and_amax(sste, dtype, T, O, I):
+    """The forward product cast to e4m3 where it is produced (Sec. 5.2) and its largest magnitude.  Both sides
+    round the same product, the GPU from a float32 accumulator and the oracle from float64, so codes may differ
+    where the product sits on a rounding boundary: they must agree almost everywhere, differ by one step where
+    they do not, and decode to the float64 product within half a step of the grid plus the accumulation noise.  The bf16 output with amax_out is the
+    plain forward result, bit for bit."""
+    wl = WL.WORKLOADS[1] if dtype == "bf16" else WL.WORKLOADS[5]
+    wb = WL.weight_bits(wl, 0, O=O, I=I)
+    xc, xs, Xd = operand(sste, WL.activations(wl, 0, T=T, I=I)[0], dtype)
+    beta = np.float32(1.4830322)
+    if dtype == "bf16":
+        ws = np.float32(1.0)
+        rv, rm, _ = OP.project_pack(wb, beta)
+    else:
+        _, _, amax_w = OP.project_pack(wb, beta)
+        ws = np.float32(float(amax_w) / 448.0)
+        rv, rm, _ = OP.project_pack(wb, beta, "e4m3", ws)
+    vals, meta = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, dtype), float(ws))
+    ref = OL.linear_fwd(xc, rv, rm, dtype, xs, ws)
+    amax_ref = float(np.max(np.abs(ref)))
+
+    # bf16 output + amax: the same Z as sste_linear_fwd, and the largest magnitude of the unrounded product
+    Z16, amax16 = sste.linear_fwd_ex(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws),
+                                     amax_out=torch.full((1,), -1.0, dtype=torch.float32, device="cuda"))
+    assert torch.equal(Z16, sste.linear_fwd(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws)))
+    assert abs(float(host(amax16)[0]) - amax_ref) <= 2e-5 * amax_ref
+
+    # e4m3 output with a scale from "earlier iterations": a little headroom over the true maximum
+    z_scale = np.float32(1.25 * amax_ref / 448.0)
+    Z8, amax8 = sste.linear_fwd_ex(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws), sste.F8E4M3, float(z_scale))
+    assert float(host(amax8)[0]) == float(host(amax16)[0])
+    want, amax_o = OL.linear_fwd_e4m3_out(xc, rv, rm, dtype, xs, ws, z_scale)
+    assert abs(float(amax_o) - float(host(amax8)[0])) <= 2e-5 * amax_ref
+    got = host(Z8).numpy()
+    assert got.shape == want.shape
+    diff = got != want
+    assert diff.mean() <= 2e-3, diff.mean()
+    # Where the codes differ, the two roundings saw products that differ by the float32 accumulation noise of
+    # the matrix pipe (the same allowance as for the bf16 output: 1e-4 of the largest output); for most outputs
+    # that is less than a step of the grid (neighbouring codes), for outputs near zero it can span a few steps.
+    back = F.e4m3_to_f32(got).astype(np.float64) * float(z_scale)
+    q = np.abs(ref) / float(z_scale)
+    step = np.where(q < 2.0 ** -6, 2.0 ** -9, 2.0 ** (np.floor(np.log2(np.maximum(q, 1e-300))) - 3)) * float(z_scale)
+    excess = np.abs(back - ref) - 0.5 * step * (1 + 1e-3)
+    print(f"e4m3 output: {diff.mean():.2e} of the codes differ, worst excess over half a step {excess.max() / amax_ref:.2e} of max|Z|", flush=True)
+    assert np.all(excess <= 1e-4 * amax_ref)
+    gm, wm = got[diff].astype(np.int32), want[diff].astype(np.int32)
+    near = (np.abs((gm & 0x7F) - (wm & 0x7F)) == 1) & ((gm >> 7) == (wm >> 7)) | ((gm & 0x7F) + (wm & 0x7F) <= 1)
+    assert near.mean() >= 0.9 if near.size else True
+    # saturation instead of overflow when the scale is far too small
+    Zs, _ = sste.linear_fwd_ex(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws), sste.F8E4M3, float(z_scale) / 64.0)
+    sat = host(Zs).numpy()
+    assert np.all((sat & 0x7F) <= 0x7E) and np.any((sat & 0x7F) == 0x7E)
+    # strided e4m3 output: the padding columns stay untouched
+    big = torch.full((T, O + 32), 0x55, dtype=torch.uint8, device="cuda")
+    sste.linear_fwd_ex(Xd, vals, meta, O, dt(sste, dtype), float(xs), float(ws), sste.F8E4M3, float(z_scale), Z=big[:, :O],
+                       amax_out=amax8)
+    assert torch.equal(big[:, :O], Z8) and bool((big[:, O:] == 0x55).all())
+
+
+def test_fp8_output_feeds_the_next_layer_with_delayed_scaling(sste):
+    """Two chained 8-bit layers over three iterations: layer 1 writes its output as e4m3 with a scale taken from
+    the amax history of earlier iterations, layer 2 consumes those codes directly.  Each stage against the oracle
+    on the inputs the GPU holds."""
+    wl = WL.WORKLOADS[5]
+    T, I, H, O = 256, 256, 384, 128
+    w1, w2 = WL.weight_bits(wl, 2, O=H, I=I), WL.weight_bits(wl, 3, O=O, I=H)
+    beta = np.float32(1.4830322)
+    packs = []
+    for wb in (w1, w2):
+        _, _, amax_w = OP.project_pack(wb, beta)
+        ws = np.float32(float(amax_w) / 448.0)
+        rv, rm, _ = OP.project_pack(wb, beta, "e4m3", ws)
+        v, m = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(ws))
+        packs.append((rv, rm, ws, v, m))
+    hist = sste.AmaxHistory(2)
+    z_scale = 1.0                                                   # first iteration: nothing known yet
+    for it in range(3):
+        xb = F.f32_to_bf16_rne((F.bf16_to_f32(WL.activations(wl, 0, T=T, I=I)[0]) * np.float32(1.0 + it)).astype(np.float32)).reshape(T, I)
+        xc, xs, Xd = operand(sste, xb, "e4m3")
+        rv, rm, ws, v, m = packs[0]
+        Z8, amax = sste.linear_fwd_ex(Xd, v, m, H, sste.F8E4M3, float(xs), float(ws), sste.F8E4M3, z_scale)
+        zc = host(Z8).numpy()
+        want, amax_o = OL.linear_fwd_e4m3_out(xc, rv, rm, "e4m3", xs, ws, np.float32(z_scale))
+        assert (zc != want).mean() <= 5e-3
+        assert abs(float(host(amax)[0]) - float(amax_o)) <= 2e-5 * float(amax_o)
+        # layer 2 reads the codes the GPU wrote, with the scale they were written with
+        rv2, rm2, ws2, v2, m2 = packs[1]
+        Y = sste.linear_fwd(Z8, v2, m2, O, sste.F8E4M3, z_scale, float(ws2))
+        assert rel_err(z_to_f64(Y), OL.linear_fwd(zc, rv2, rm2, "e4m3", np.float32(z_scale), ws2)) <= TOL["e4m3"]
+        z_scale = hist.push(float(host(amax)[0]), 448.0)           # scale of the next iteration
+        assert z_scale == float(F.delayed_scale([float(host(amax)[0])] if it == 0 else prev + [float(host(amax)[0])], "e4m3"))
+        prev = [float(host(amax)[0])]
+
+
 def test_linear_fwd_empty_and_errors(sste):
     X = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
     vals = torch.zeros((16, 32), dtype=torch.int16, device="cuda")

@@ -156,3 +156,61 @@ def test_e5m2_gradients_against_e4m3_operands():
     dX = Lin.linear_dgrad(dy, wv, wm, "e5m2", dy_scale=0.5, w_scale=0.0002, w_dtype="e4m3")
     want = Lin.linear_dgrad_loops(F.e5m2_to_f32(dy).astype(np.float64), P.decode_packed(wv, wm, "e4m3")) * (0.5 * np.float64(np.float32(0.0002)))
     assert np.allclose(dX, want, rtol=1e-12, atol=0)
+
+
+# ------------------------------------------------------------------ 8-bit output of the forward product
+
+def _tiny_layer(rs, T=6, O=8, I=16):
+    w = F.f32_to_bf16_rne((rs.standard_normal((O, I)) * 0.5).astype(np.float32)).reshape(O, I)
+    vals, meta, _ = P.project_pack(w, np.float32(1.25))
+    x = F.f32_to_bf16_rne(rs.standard_normal((T, I)).astype(np.float32)).reshape(T, I)
+    return x, vals, meta
+
+
+def test_e4m3_output_is_the_rounded_rescaled_product():
+    """decode(codes) * z_scale is the float64 product to within half a step of the e4m3 grid; amax is the
+    product's largest magnitude; a scale that is too small saturates at +-448 instead of wrapping."""
+    rs = np.random.default_rng(5)
+    x, vals, meta = _tiny_layer(rs)
+    Z = Lin.linear_fwd(x, vals, meta)
+    amax_true = np.max(np.abs(Z))
+    z_scale = np.float32(amax_true / 448.0)
+    codes, amax = Lin.linear_fwd_e4m3_out(x, vals, meta, z_scale=z_scale)
+    assert codes.shape == Z.shape and codes.dtype == np.uint8
+    assert abs(float(amax) - amax_true) <= 1e-6 * amax_true
+    back = F.e4m3_to_f32(codes).astype(np.float64) * float(z_scale)
+    q = np.abs(Z) / float(z_scale)
+    step = np.where(q < 2.0 ** -6, 2.0 ** -9, 2.0 ** (np.floor(np.log2(np.maximum(q, 1e-300))) - 3))     # grid spacing at |q|
+    assert np.all(np.abs(back - Z) <= (0.5 * step * float(z_scale)) * (1 + 1e-6) + 1e-12)
+    assert np.max(F.e4m3_to_f32(codes)) <= 448.0 and np.any(np.abs(F.e4m3_to_f32(codes)) >= 416.0)     # the range is used
+    # scale 16 times too small: everything beyond the range clamps, signs are kept
+    sat, _ = Lin.linear_fwd_e4m3_out(x, vals, meta, z_scale=np.float32(z_scale / 16.0))
+    big = np.abs(Z) >= 448.0 * float(z_scale) / 16.0 * 1.04
+    assert np.all((sat[big] & 0x7F) == 0x7E) and np.array_equal(sat[big] >> 7, (Z[big] < 0).astype(np.uint8))
+
+
+def test_e4m3_output_hand_values_and_ties():
+    """A 1 x 1 layer makes the accumulator a single known product: exact codes, ties to even, operand scales."""
+    one = F.f32_to_bf16_rne(np.array([[1.0, 0, 0, 0, 0, 0, 0, 0]], dtype=np.float32)).reshape(1, 8)
+    vals, meta, _ = P.project_pack(one, np.float32(1.0))              # S_soft keeps the 1 (t = 0): weight row (1, 0, ...)
+    assert P.decode_packed(vals, meta)[0, 0] == 1.0
+
+    def code_for(xval, **kw):
+        x = F.f32_to_bf16_rne(np.array([[xval, 0, 0, 0, 0, 0, 0, 0]], dtype=np.float32)).reshape(1, 8)
+        c, amax = Lin.linear_fwd_e4m3_out(x, vals, meta, **kw)
+        return int(c[0, 0]), float(amax)
+
+    assert code_for(1.0) == (0x38, 1.0)                               # 1.0 = exponent field 7, mantissa 0
+    assert code_for(-1.5)[0] == 0xBC                                  # sign | 1.5
+    assert code_for(1.0625)[0] == 0x38 and code_for(1.1875)[0] == 0x3A   # halfway 1.0|1.125 -> even (1.0); halfway 1.125|1.25 -> even (1.25)
+    assert code_for(3.0, z_scale=np.float32(2.0))[0] == 0x3C          # stored 1.5, read back as 1.5 * 2
+    assert code_for(3.0, x_scale=np.float32(0.5), w_scale=np.float32(4.0)) == (0x4C, 6.0)    # real value 6 = 1.5 * 2^2
+    assert code_for(1000.0)[0] == 0x7E                                # saturates at 448
+
+
+def test_delayed_scale_window():
+    assert F.delayed_scale([], "e4m3") == np.float32(1.0)
+    assert F.delayed_scale([0.0, 0.0], "e5m2") == np.float32(1.0)
+    assert F.delayed_scale([1.0, 448.0, 3.0], "e4m3") == np.float32(1.0)
+    assert F.delayed_scale([2.0, 1.0], "e4m3") == np.float32(np.float32(2.0) / np.float32(448.0))
+    assert F.delayed_scale([57344.0 * 3], "e5m2") == np.float32(3.0)
