@@ -234,6 +234,37 @@ int sste_linear_fwd_ex(const void* X, int64_t T, int64_t I, int64_t ldx, int dty
                        void* Z, int64_t ldz, int z_dtype, float z_scale, float* amax_out, void* hip_stream);
 
 /*
+ * The feed-forward block (Sec. 6: S-STE sparsifies the two linear layers of every FFN block; Appendix
+ * "Acceleration" times that block): fc1 -> activation -> fc2.  Two calls fuse the activation into the
+ * GEMM that touches its tensor anyway, so neither the activation nor its backward costs a pass over
+ * the T x 4d tensor:
+ *
+ *   sste_linear_fwd_act   H = RNE_bf16((x_scale * w_scale) * acc)   the pre-activation (stored if H != NULL:
+ *                                                                    training needs it for the backward pass)
+ *                         A = act(H)                                 evaluated in float32 on the bf16 H,
+ *                         stored as RNE_bf16(A) (a_dtype SSTE_BF16, a_scale 1, amax_out NULL) or as
+ *                         RNE_e4m3(clamp(A * (1 / a_scale), +-448)) with 1 / a_scale one float32 division
+ *                         on the host (a_dtype SSTE_F8E4M3; amax_out required, receives max |A|).
+ *   sste_linear_dgrad_act dX = RNE_bf16(g * act'(H)),  g = RNE_bf16((dy_scale * w_scale) * acc): the input
+ *                         gradient of the layer AFTER the activation, multiplied by the activation's
+ *                         derivative at the stored pre-activation H (T x I, bf16, leading dimension ldh).
+ *                         act = SSTE_ACT_NONE is sste_linear_dgrad.
+ *
+ * act: SSTE_ACT_GELU_TANH, 0.5 h (1 + tanh(sqrt(2 / pi) (h + 0.044715 h^3))) -- the paper does not name the
+ * activation; this is the one of the GPT-2 models whose layer shapes its experiments use.  Its derivative
+ * is the analytic one.  float32 arithmetic with the hardware's exp2 / reciprocal (about 1e-6 absolute).
+ * Everything not listed is as in sste_linear_fwd / sste_linear_dgrad (A takes the role of Z: T x O, lda).
+ */
+enum { SSTE_ACT_NONE = 0, SSTE_ACT_GELU_TANH = 1 };
+int sste_linear_fwd_act(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale,
+                        const void* vals, const void* meta, int64_t O, float w_scale,
+                        int act, void* H, int64_t ldh, void* A, int64_t lda, int a_dtype, float a_scale,
+                        float* amax_out, void* hip_stream);
+int sste_linear_dgrad_act(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale,
+                          const void* vals, const void* meta, int64_t I, float w_scale,
+                          int act, const void* H, int64_t ldh, void* dX, int64_t lddx, void* hip_stream);
+
+/*
  * Delayed scaling (the per-tensor scaling recipe Sec. 5.2 refers to): the scale of an 8-bit tensor in
  * iteration k is derived from the largest magnitudes seen in the last `length` iterations, so no pass
  * over the tensor is needed before it is cast.  Host-only helper; the caller owns the struct.

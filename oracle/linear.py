@@ -10,6 +10,7 @@ product grad_Z^T X; the input gradient is pinned by its own loop and by the adjo
 """
 import numpy as np
 
+from . import activation
 from . import formats
 from . import projection
 from . import mvue
@@ -115,3 +116,18 @@ def linear_dgrad_loops(dY, Wd):
                 acc += float(dY[t][o]) * float(Wd[o][i])
             dX[t][i] = acc
     return np.array(dX, dtype=np.float64)
+
+
+def ffn_reference(X, Wd1, Wd2, dY):
+    """The feed-forward block fc1 -> activation -> fc2 and its backward pass, all in float64 with no rounding
+    in between (Sec. 5.1 gives each linear layer's three products; the block chains two of them through the
+    activation of ``oracle.activation``).  X (T, d), Wd1 (h, d) and Wd2 (d2, h) dense-with-zeros projected
+    weights, dY (T, d2) the gradient of the block's output.  The weight gradients returned are the DENSE
+    products grad_Z^T X that the estimator of Sec. 5.1 approximates without bias."""
+    X = np.asarray(X, dtype=np.float64)
+    H = X @ Wd1.T
+    A = activation.gelu_tanh(H)
+    Y = A @ Wd2.T
+    dA = np.asarray(dY, dtype=np.float64) @ Wd2
+    dH = dA * activation.gelu_tanh_grad(H)
+    return {"H": H, "A": A, "Y": Y, "dA": dA, "dH": dH, "dX": dH @ Wd1, "dW2": np.asarray(dY, dtype=np.float64).T @ A, "dW1": dH.T @ X}

@@ -21,6 +21,10 @@ from .binding import (  # noqa: F401
     linear_dgrad,
     linear_fwd,
     linear_fwd_ex,
+    linear_fwd_act,
+    linear_dgrad_act,
+    ACT_GELU_TANH,
+    ACT_NONE,
     AmaxHistory,
     linear_wgrad,
     linear_wgrad_noalloc,

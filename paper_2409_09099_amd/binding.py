@@ -45,6 +45,10 @@ def library() -> ctypes.CDLL:
     lib.sste_linear_fwd.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, vp]
     lib.sste_linear_fwd_ex.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, vp, i64, ci, f32, vp, vp]
     lib.sste_linear_fwd_ex.restype = ci
+    lib.sste_linear_fwd_act.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, ci, vp, i64, vp, i64, ci, f32, vp, vp]
+    lib.sste_linear_fwd_act.restype = ci
+    lib.sste_linear_dgrad_act.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, i64, f32, ci, vp, i64, vp, i64, vp]
+    lib.sste_linear_dgrad_act.restype = ci
     lib.sste_amax_history_init.argtypes = [vp, ci]
     lib.sste_amax_history_init.restype = None
     lib.sste_amax_history_push.argtypes = [vp, f32, f32]
@@ -272,6 +276,41 @@ def linear_fwd_ex(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: in
     _check(library().sste_linear_fwd_ex(_ptr(X), T, I, ldx, dtype, x_scale, _ptr(vals), _ptr(meta), O, w_scale, _ptr(Z), ldz,
                                         z_dtype, z_scale, _ptr(amax_out), _stream(X)))
     return Z, amax_out
+
+
+ACT_NONE, ACT_GELU_TANH = 0, 1
+
+
+def linear_fwd_act(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, O: int, dtype: int = BF16, x_scale: float = 1.0,
+                   w_scale: float = 1.0, act: int = ACT_GELU_TANH, a_dtype: int = BF16, a_scale: float = 1.0,
+                   H: Optional[torch.Tensor] = None, A: Optional[torch.Tensor] = None, amax_out: Optional[torch.Tensor] = None,
+                   store_pre: bool = True):
+    """sste_linear_fwd_act: the forward product with the activation in its epilogue.  Returns (H or None, A, amax_out)."""
+    T, I, ldx = _matrix(X, _esize(dtype), "X")
+    if H is None and store_pre:
+        H = torch.empty((T, O), dtype=torch.bfloat16, device=X.device)
+    if A is None:
+        A = torch.empty((T, O), dtype=torch.uint8 if a_dtype == F8E4M3 else torch.bfloat16, device=X.device)
+    if amax_out is None and a_dtype == F8E4M3:
+        amax_out = torch.empty(1, dtype=torch.float32, device=X.device)
+    ldh = _matrix(H, 2, "H")[2] if H is not None else 0
+    _, _, lda = _matrix(A, _esize(a_dtype), "A")
+    _check(library().sste_linear_fwd_act(_ptr(X), T, I, ldx, dtype, x_scale, _ptr(vals), _ptr(meta), O, w_scale, act, _ptr(H), ldh,
+                                         _ptr(A), lda, a_dtype, a_scale, _ptr(amax_out), _stream(X)))
+    return H, A, amax_out
+
+
+def linear_dgrad_act(dY: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, I: int, H: torch.Tensor, dtype: int = BF16,
+                     dy_scale: float = 1.0, w_scale: float = 1.0, act: int = ACT_GELU_TANH, dX: Optional[torch.Tensor] = None):
+    """sste_linear_dgrad_act: dX = (dY decode(vals, meta)) * act'(H), bf16 output."""
+    T, O, lddy = _matrix(dY, _esize(dtype), "dY")
+    if dX is None:
+        dX = torch.empty((T, I), dtype=torch.bfloat16, device=dY.device)
+    _, _, lddx = _matrix(dX, 2, "dX")
+    _, _, ldh = _matrix(H, 2, "H")
+    _check(library().sste_linear_dgrad_act(_ptr(dY), T, O, lddy, dtype, dy_scale, _ptr(vals), _ptr(meta), I, w_scale, act, _ptr(H),
+                                           ldh, _ptr(dX), lddx, _stream(dY)))
+    return dX
 
 
 class AmaxHistory:

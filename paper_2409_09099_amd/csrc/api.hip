@@ -346,6 +346,37 @@ int sste_linear_fwd_ex(const void* X, int64_t T, int64_t I, int64_t ldx, int dty
                     "linear_fwd launch");
 }
 
+int sste_linear_fwd_act(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float x_scale, const void* vals,
+                        const void* meta, int64_t O, float w_scale, int act, void* H, int64_t ldh, void* A, int64_t lda,
+                        int a_dtype, float a_scale, float* amax_out, void* hip_stream) {
+  clear_error();
+  if (T < 0 || I < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "linear_fwd_act: negative size");
+  if (!good_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_fwd_act: unknown dtype %d", dtype);
+  if (!good_dtype(a_dtype)) return fail(SSTE_ERR_DTYPE, "linear_fwd_act: a_dtype %d is neither bf16 nor e4m3", a_dtype);
+  if (act != SSTE_ACT_GELU_TANH) return fail(SSTE_ERR_VALUE, "linear_fwd_act: unknown activation %d", act);
+  if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_fwd_act: I=%lld is not a multiple of 8", (long long)I);
+  if (!good_scale(x_scale) || !good_scale(w_scale) || !good_scale(a_scale)) return fail(SSTE_ERR_VALUE, "linear_fwd_act: scales must be finite and > 0");
+  const bool a8 = a_dtype == SSTE_F8E4M3;
+  if (!a8 && a_scale != 1.0f) return fail(SSTE_ERR_VALUE, "linear_fwd_act: a_scale must be 1 for a bf16 output");
+  if (a8 && !amax_out) return fail(SSTE_ERR_NULL, "linear_fwd_act: an e4m3 output needs amax_out (the next scale is derived from it)");
+  if (!a8 && amax_out) return fail(SSTE_ERR_VALUE, "linear_fwd_act: amax_out goes with an e4m3 output only");
+  if (reinterpret_cast<uintptr_t>(amax_out) & 3u) return fail(SSTE_ERR_ALIGN, "linear_fwd_act: amax_out must be 4-byte aligned");
+  int kmult = dtype == SSTE_F8E4M3 ? 128 : 64;
+  if (I % kmult != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd_act: I=%lld must be a multiple of %d for this element type", (long long)I, kmult);
+  if (O % 8 != 0) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd_act: O=%lld must be a multiple of 8", (long long)O);
+  if (ldx < I || lda < O || (H && ldh < O)) return fail(SSTE_ERR_SHAPE, "linear_fwd_act: leading dimension smaller than the row length");
+  if (ldx % elems_per_16B(dtype) != 0 || lda % 8 != 0 || (H && ldh % 8 != 0)) return fail(SSTE_ERR_ALIGN, "linear_fwd_act: leading dimensions break the row rule");
+  bool empty = (T == 0 || O == 0);
+  if (!empty && (!A || (I > 0 && (!X || !vals || !meta)))) return fail(SSTE_ERR_NULL, "linear_fwd_act: NULL X, vals, meta or A");
+  if (!aligned16(X) || !aligned16(vals) || !aligned16(meta) || !aligned16(H) || (reinterpret_cast<uintptr_t>(A) & (a8 ? 7u : 15u)))
+    return fail(SSTE_ERR_ALIGN, "linear_fwd_act: X, vals, meta, H must be 16-byte aligned, A 16-byte (bf16) / 8-byte (e4m3)");
+  if (!linear_fwd_supported(T, I, ldx, O, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_fwd_act: a tile of this problem does not fit 32-bit offsets");
+  const float inv = 1.0f / a_scale;
+  return hip_status(launch_linear_fwd_act(X, T, I, ldx, dtype, x_scale * w_scale, vals, meta, O, H, ldh, A, lda, a_dtype, inv, amax_out,
+                                          (hipStream_t)hip_stream),
+                    "linear_fwd_act launch");
+}
+
 // ---- delayed scaling (host only) ----------------------------------------------------------------------
 void sste_amax_history_init(sste_amax_history* h, int length) {
   if (!h) return;
@@ -391,7 +422,22 @@ size_t sste_wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
 
 int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* vals,
                       const void* meta, int64_t I, float w_scale, void* dX, int64_t lddx, void* hip_stream) {
+  return sste_linear_dgrad_act(dY, T, O, lddy, dtype, dy_scale, vals, meta, I, w_scale, SSTE_ACT_NONE, nullptr, 0, dX, lddx, hip_stream);
+}
+
+int sste_linear_dgrad_act(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float dy_scale, const void* vals,
+                          const void* meta, int64_t I, float w_scale, int act, const void* H, int64_t ldh, void* dX,
+                          int64_t lddx, void* hip_stream) {
   clear_error();
+  if (act != SSTE_ACT_NONE && act != SSTE_ACT_GELU_TANH) return fail(SSTE_ERR_VALUE, "linear_dgrad: unknown activation %d", act);
+  if (act == SSTE_ACT_NONE) {
+    H = nullptr;
+    ldh = 0;
+  } else {
+    if (T > 0 && I > 0 && !H) return fail(SSTE_ERR_NULL, "linear_dgrad: the activation's backward needs the stored pre-activation H");
+    if (ldh < I) return fail(SSTE_ERR_SHAPE, "linear_dgrad: ldh < I");
+    if (ldh % 8 != 0 || !aligned16(H)) return fail(SSTE_ERR_ALIGN, "linear_dgrad: H must be 16-byte aligned with ldh a multiple of 8");
+  }
   if (T < 0 || I < 0 || O < 0) return fail(SSTE_ERR_SHAPE, "linear_dgrad: negative size");
   if (!good_grad_dtype(dtype)) return fail(SSTE_ERR_DTYPE, "linear_dgrad: unknown dtype %d", dtype);
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "linear_dgrad: I=%lld is not a multiple of 8", (long long)I);
@@ -406,7 +452,7 @@ int sste_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dt
   if (!empty_out && O > 0 && (!dY || !vals || !meta)) return fail(SSTE_ERR_NULL, "linear_dgrad: NULL dY, vals or meta");
   if (!aligned16(dY) || !aligned16(vals) || !aligned16(dX)) return fail(SSTE_ERR_ALIGN, "linear_dgrad: dY, vals and dX must be 16-byte aligned");
   if (!linear_dgrad_supported(T, O, lddy, I, dtype)) return fail(SSTE_ERR_UNSUPPORTED, "linear_dgrad: problem too large for 32-bit tile offsets");
-  return hip_status(launch_linear_dgrad(dY, T, O, lddy, dtype, dy_scale * w_scale, vals, meta, I, dX, lddx, (hipStream_t)hip_stream),
+  return hip_status(launch_linear_dgrad(dY, T, O, lddy, dtype, dy_scale * w_scale, vals, meta, I, dX, lddx, H, ldh, (hipStream_t)hip_stream),
                     "linear_dgrad launch");
 }
 

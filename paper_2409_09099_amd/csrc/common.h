@@ -84,6 +84,28 @@ __device__ __forceinline__ uint32_t e4m3_rne_pack(float lo, float hi) {
 }
 __device__ __forceinline__ float clamp448(float x) { return __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f); }
 
+// ---- activation between the two FFN linears -----------------------------------------------------------
+// GELU in its tanh form, 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) -- the form of the GPT-2 models
+// whose layer shapes the workloads use (the paper does not name the activation).  float32 throughout;
+// tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 / reciprocal (about 1e-6 absolute).
+__device__ __forceinline__ float tanh_fast(float u) {
+  const float e = __builtin_amdgcn_exp2f(u * 2.8853900817779268f);       // exp(2u); inf / 0 at the ends give +-1 below
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+}
+__device__ __forceinline__ float gelu_tanh(float x) {
+  const float u = 0.7978845608028654f * (x + 0.044715f * (x * x * x));
+  return 0.5f * x * (1.0f + tanh_fast(u));
+}
+// d/dx of the above
+__device__ __forceinline__ float gelu_tanh_grad(float x) {
+  const float x2 = x * x;
+  const float t = tanh_fast(0.7978845608028654f * (x + 0.044715f * (x2 * x)));
+  const float du = 0.7978845608028654f * (1.0f + 0.134145f * x2);       // 3 * 0.044715
+  return 0.5f * (1.0f + t) + 0.5f * x * ((1.0f - t * t) * du);
+}
+__device__ __forceinline__ float bf16lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
 // ---- buffer-descriptor loads ---------------------------------------------------------------------
 // A raw buffer descriptor over [base, base + bytes): loads whose offset falls outside return zeros,
 // which replaces per-lane bounds branches at tile edges.  Offsets are 32-bit.
@@ -184,7 +206,7 @@ hipError_t launch_sgd_project_pack_batch(const void* table, int n_items, int64_t
 hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t total_blocks, int val_dtype, hipStream_t s);
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype);
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
-                               const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s);
+                               const void* meta, int64_t I, void* dX, int64_t lddx, const void* H, int64_t ldh, hipStream_t s);
 hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
                                hipStream_t s);
 size_t beta_workspace_bytes(int64_t O, int64_t I);
@@ -196,6 +218,9 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
                              const void* vals, const void* meta, int64_t O, void* Z, int64_t ldz, int z_dtype,
                              float amax_scale, float* amax_out, hipStream_t s);
+hipError_t launch_linear_fwd_act(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
+                                 const void* vals, const void* meta, int64_t O, void* H, int64_t ldh, void* A, int64_t lda,
+                                 int a_dtype, float a_inv_scale, float* amax_out, hipStream_t s);
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype);
 size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype);
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype);

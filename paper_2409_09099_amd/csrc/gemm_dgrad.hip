@@ -65,7 +65,8 @@ template <bool FP8, int NI_, bool BF8>
 __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restrict__ dY, int64_t T, int64_t O,
                                            int64_t lddy_bytes, const uint8_t* __restrict__ vals,
                                            const uint8_t* __restrict__ meta, int64_t I, int isteps, float scale,
-                                           uint16_t* __restrict__ dX, int64_t lddx, int tm, int64_t t0) {
+                                           uint16_t* __restrict__ dX, int64_t lddx, int tm, int64_t t0,
+                                           const uint16_t* __restrict__ H, int64_t ldh) {
   constexpr int WN = 4, NW = 8, MI_ = 8;
   constexpr int EB = FP8 ? 1 : 2;
   constexpr int KC = FP8 ? 128 : 64;                // channels per k-step (128 bytes of a grad_Z row)
@@ -334,7 +335,22 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
       int row = c / CHUNKS, chunk = c % CHUNKS;
       uint4 v = *(const uint4*)(eb + row * EROW + chunk * 16);
       int64_t t = t0 + 16 * NI_ * wn + row, i = i0 + 16 * MI_ * wm + 8 * chunk;
-      if (t < T && i < I) store_stream_b128(dX + t * lddx + i, v);
+      if (t < T && i < I) {
+        if (H) {
+          // backward of the activation that produced this layer's input: grad_H = grad_A * GELU'(H), on the
+          // bf16 gradient just formed and the stored pre-activation (read once: streaming load)
+          const i32x4 hv = __builtin_nontemporal_load((const i32x4*)(H + t * ldh + i));
+          const uint32_t g[4] = {v.x, v.y, v.z, v.w};
+          uint32_t r[4];
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const uint32_t hw = (uint32_t)hv[e];
+            r[e] = bf16_rne_pack(bf16lo_f32(g[e]) * gelu_tanh_grad(bf16lo_f32(hw)), bf16hi_f32(g[e]) * gelu_tanh_grad(bf16hi_f32(hw)));
+          }
+          v = make_uint4(r[0], r[1], r[2], r[3]);
+        }
+        store_stream_b128(dX + t * lddx + i, v);
+      }
     }
   }
 }
@@ -343,11 +359,11 @@ template <bool FP8, int NI_, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
-               float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles) {
+               float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles, const uint16_t* __restrict__ H, int64_t ldh) {
   __shared__ __align__(1024) uint8_t smem[dgrad_smem<FP8, NI_>()];
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tm = logical % m_tiles, tn = logical / m_tiles;
-  dgrad_tile<FP8, NI_, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tm, (int64_t)tn * (64 * NI_));
+  dgrad_tile<FP8, NI_, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tm, (int64_t)tn * (64 * NI_), H, ldh);
 }
 
 // Whole rounds of 256 x 256 tiles (workgroups 0 .. n_big - 1), then the tiles of the last, partial round
@@ -356,19 +372,20 @@ template <bool FP8, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_linear_dgrad_dual(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_bytes,
                     const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t I, int isteps,
-                    float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles, int n_big) {
+                    float scale, uint16_t* __restrict__ dX, int64_t lddx, int m_tiles, int n_big, const uint16_t* __restrict__ H,
+                    int64_t ldh) {
   __shared__ __align__(1024) uint8_t smem[dgrad_smem<FP8, 4>()];
   const int bid = blockIdx.x;
   if (bid < n_big) {
     const int logical = xcd_contiguous(bid, n_big);
     dgrad_tile<FP8, 4, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, logical % m_tiles,
-                       (int64_t)(logical / m_tiles) * 256);
+                       (int64_t)(logical / m_tiles) * 256, H, ldh);
   } else {
     const int h = xcd_contiguous(bid - n_big, (int)gridDim.x - n_big);      // half-tile number
     const int tile = n_big + (h >> 1);
     const int64_t t0 = (int64_t)(tile / m_tiles) * 256 + 128 * (h & 1);
     if (t0 >= T) return;                       // second half of a ragged last token tile: nothing to do
-    dgrad_tile<FP8, 2, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tile % m_tiles, t0);
+    dgrad_tile<FP8, 2, BF8>(smem, dY, T, O, lddy_bytes, vals, meta, I, isteps, scale, dX, lddx, tile % m_tiles, t0, H, ldh);
   }
 }
 
@@ -381,8 +398,9 @@ bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int d
 }
 
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
-                               const void* meta, int64_t I, void* dX, int64_t lddx, hipStream_t s) {
+                               const void* meta, int64_t I, void* dX, int64_t lddx, const void* H, int64_t ldh, hipStream_t s) {
   if (T == 0 || I == 0) return hipSuccess;
+  const uint16_t* hp = (const uint16_t*)H;
   const bool fp8 = dtype != SSTE_BF16, bf8 = dtype == SSTE_F8E5M2;
   int m_tiles = (int)((I + 255) / 256);
   // 256 x 256 tiles unless they leave a quarter or more of the CUs without work in the only round
@@ -398,7 +416,7 @@ hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
     dim3 grid((unsigned)(n_big + 2 * rem)), block(512);
 #define DG_DUAL(F8, B8)                                                                                                \
   SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad_dual<F8, B8>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale, \
-              (uint16_t*)dX, lddx, m_tiles, n_big)
+              (uint16_t*)dX, lddx, m_tiles, n_big, hp, ldh)
     if (bf8) DG_DUAL(true, true);
     else if (fp8) DG_DUAL(true, false);
     else DG_DUAL(false, false);
@@ -410,7 +428,7 @@ hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t ldd
   dim3 grid((unsigned)(m_tiles * n_tiles)), block(512);
 #define DG_CASE(F8, NI, B8)                                                                                            \
   SSTE_LAUNCH(SSTE_K_DGRAD, (k_linear_dgrad<F8, NI, B8>), grid, block, s, dy, T, O, lddy_bytes, pv, pm, I, isteps, scale, \
-              (uint16_t*)dX, lddx, m_tiles)
+              (uint16_t*)dX, lddx, m_tiles, hp, ldh)
   if (bf8 && half) DG_CASE(true, 2, true);
   else if (bf8) DG_CASE(true, 4, true);
   else if (fp8 && half) DG_CASE(true, 2, false);

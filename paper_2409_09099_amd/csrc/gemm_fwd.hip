@@ -55,13 +55,48 @@ constexpr int NUM_CU = 256;
 // receives max |acc| * amax_scale over the whole tensor (float32 bits; non-negative floats order like
 // their patterns): one atomic per workgroup, skipped when it cannot raise the value.
 struct FwdOut {
-  uint16_t* z16;          // bf16 output (ZF8 = false)
+  uint16_t* z16;          // bf16 output (ZF8 = false); with `act`: the pre-activation H, may then be null
   uint8_t* z8;            // e4m3 output (ZF8 = true)
   int64_t ldz;            // leading dimension in elements
   float scale;            // acc -> stored value (before rounding)
   float amax_scale;       // acc -> the tensor's real units
   uint32_t* amax_bits;    // nullable
+  // activation fused into the bf16 epilogue (kernels instantiated with ZF8 = false, AMAX = false):
+  // H = RNE_bf16(acc * scale) goes to z16 (if given), A = GELU(H) to a16 (bf16) or a8 (e4m3 of A * a_inv_scale);
+  // with a8 the largest |A| goes to amax_bits.
+  int act;                // 0: none
+  uint16_t* a16;
+  uint8_t* a8;
+  int64_t lda;
+  float a_inv_scale;
 };
+
+// Activation stage of the epilogue on one 16-byte piece (8 consecutive channels of one token): stores A in
+// the requested format and returns max |A| of the piece (float32 bits).
+__device__ __forceinline__ uint32_t fwd_act_piece(const uint4& h, const FwdOut& out, int64_t t, int64_t o) {
+  const uint32_t w[4] = {h.x, h.y, h.z, h.w};
+  float a[8];
+  uint32_t m = 0;
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    a[2 * e] = gelu_tanh(bf16lo_f32(w[e]));
+    a[2 * e + 1] = gelu_tanh(bf16hi_f32(w[e]));
+    m = max(m, max(f2u(a[2 * e]) & 0x7FFFFFFFu, f2u(a[2 * e + 1]) & 0x7FFFFFFFu));
+  }
+  if (out.a8) {
+    const float r = out.a_inv_scale;
+    int lo = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a[0] * r), clamp448(a[1] * r), 0, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a[2] * r), clamp448(a[3] * r), lo, true);
+    int hi = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a[4] * r), clamp448(a[5] * r), 0, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a[6] * r), clamp448(a[7] * r), hi, true);
+    i32x2 v = {lo, hi};
+    __builtin_nontemporal_store(v, (i32x2*)(out.a8 + t * out.lda + o));
+  } else {
+    uint4 v = make_uint4(bf16_rne_pack(a[0], a[1]), bf16_rne_pack(a[2], a[3]), bf16_rne_pack(a[4], a[5]), bf16_rne_pack(a[6], a[7]));
+    store_stream_b128(out.a16 + t * out.lda + o, v);
+  }
+  return m;
+}
 
 // max |acc| of the calling workgroup (NW waves) -> *amax_bits.  `red` is NW dwords of LDS nobody else uses
 // between the two barriers.
@@ -261,12 +296,20 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
       *(uint2*)(eb + (16 * ni + j) * EPI_ROW + (16 * mi + 4 * q) * 2) = v;
     }
   // same-wave LDS accesses are ordered; no barrier needed for a wave-private region
+  uint32_t act_max = 0;
 #pragma unroll
   for (int it = 0; it < 16; it++) {
     int row = 4 * it + (lane >> 4), chunk = lane & 15;
     uint4 v = *(const uint4*)(eb + row * EPI_ROW + chunk * 16);
     int64_t t = t0 + 64 * wn + row, o = o0 + 128 * wm + 8 * chunk;
-    if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
+    if (t < T && o < O) {
+      if (Z) store_stream_b128(Z + t * ldz + o, v);
+      if (out.act) act_max = max(act_max, fwd_act_piece(v, out, t, o));
+    }
+  }
+  if (out.act && out.amax_bits) {           // uniform over the workgroup
+    __syncthreads();                        // every wave is done with its part of the LDS
+    publish_tile_amax<NW>(act_max, 1.0f, out.amax_bits, (uint32_t*)smem);
   }
 }
 
@@ -508,6 +551,7 @@ __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __re
   // same-wave LDS accesses are ordered; no barrier needed for a wave-private region
   constexpr int CHUNKS = 2 * MI_;                                // 16-byte chunks per token row
   constexpr int NCH = 16 * NI_ * CHUNKS;
+  uint32_t act_max = 0;
 #pragma unroll
   for (int it = 0; it < (NCH + 63) / 64; it++) {
     int c = 64 * it + lane;
@@ -515,8 +559,15 @@ __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __re
       int row = c / CHUNKS, chunk = c % CHUNKS;
       uint4 v = *(const uint4*)(eb + row * EROW + chunk * 16);
       int64_t t = t0 + 16 * NI_ * wn + row, o = o0 + 16 * MI_ * wm + 8 * chunk;
-      if (t < T && o < O) store_stream_b128(Z + t * ldz + o, v);
+      if (t < T && o < O) {
+        if (Z) store_stream_b128(Z + t * ldz + o, v);
+        if (out.act) act_max = max(act_max, fwd_act_piece(v, out, t, o));
+      }
     }
+  }
+  if (out.act && out.amax_bits) {           // uniform over the workgroup
+    __syncthreads();                        // every wave is done with its part of the LDS
+    publish_tile_amax<NW>(act_max, 1.0f, out.amax_bits, (uint32_t*)smem);
   }
 }
 
@@ -635,6 +686,11 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   out.scale = scale;
   out.amax_scale = amax_scale;
   out.amax_bits = (uint32_t*)amax_out;
+  out.act = 0;
+  out.a16 = nullptr;
+  out.a8 = nullptr;
+  out.lda = 0;
+  out.a_inv_scale = 1.0f;
   const bool amax = amax_out != nullptr;
 #define FWD_CASE(F, Z8, A)                                                                \
   if (fp8 == F && zf8 == Z8 && amax == A) launch_fwd_variant<F, Z8, A>(X, T, I, ldx, out, vals, meta, O, s)
@@ -645,6 +701,30 @@ hipError_t launch_linear_fwd(const void* X, int64_t T, int64_t I, int64_t ldx, i
   FWD_CASE(true, false, true);
   FWD_CASE(true, true, true);
 #undef FWD_CASE
+  return hipGetLastError();
+}
+
+// Forward product with the activation in the epilogue: H = RNE_bf16(acc * scale) (stored if H != null),
+// A = GELU(H) stored as bf16 or as e4m3 of A * a_inv_scale (then with the largest |A| in amax_out).
+hipError_t launch_linear_fwd_act(const void* X, int64_t T, int64_t I, int64_t ldx, int dtype, float scale,
+                                 const void* vals, const void* meta, int64_t O, void* H, int64_t ldh, void* A, int64_t lda,
+                                 int a_dtype, float a_inv_scale, float* amax_out, hipStream_t s) {
+  if (amax_out) hipLaunchKernelGGL(k_fill_u32_fwd, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
+  if (T == 0 || O == 0) return hipGetLastError();
+  FwdOut out;
+  out.z16 = (uint16_t*)H;
+  out.z8 = nullptr;
+  out.ldz = ldh;
+  out.scale = scale;
+  out.amax_scale = 1.0f;
+  out.amax_bits = (uint32_t*)amax_out;
+  out.act = 1;
+  out.a16 = a_dtype == SSTE_F8E4M3 ? nullptr : (uint16_t*)A;
+  out.a8 = a_dtype == SSTE_F8E4M3 ? (uint8_t*)A : nullptr;
+  out.lda = lda;
+  out.a_inv_scale = a_inv_scale;
+  if (dtype == SSTE_F8E4M3) launch_fwd_variant<true, false, false>(X, T, I, ldx, out, vals, meta, O, s);
+  else launch_fwd_variant<false, false, false>(X, T, I, ldx, out, vals, meta, O, s);
   return hipGetLastError();
 }
 

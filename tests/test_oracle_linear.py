@@ -214,3 +214,32 @@ def test_delayed_scale_window():
     assert F.delayed_scale([1.0, 448.0, 3.0], "e4m3") == np.float32(1.0)
     assert F.delayed_scale([2.0, 1.0], "e4m3") == np.float32(np.float32(2.0) / np.float32(448.0))
     assert F.delayed_scale([57344.0 * 3], "e5m2") == np.float32(3.0)
+
+
+# ------------------------------------------------------------------ feed-forward block
+
+def test_ffn_backward_is_the_gradient_of_the_forward_pass():
+    """Numerical differentiation of L = <dY, Y(X, W1, W2)>: central differences in X, W1 and W2 reproduce dX,
+    dW1 and dW2 of the chained backward pass (a wrong transpose, a missing activation derivative or a swapped
+    operand fails this)."""
+    rs = np.random.default_rng(8)
+    T, d, h, d2 = 5, 6, 7, 4
+    X, W1, W2, dY = rs.standard_normal((T, d)), rs.standard_normal((h, d)), rs.standard_normal((d2, h)), rs.standard_normal((T, d2))
+    ref = Lin.ffn_reference(X, W1, W2, dY)
+
+    def loss(X_, W1_, W2_):
+        return float(np.sum(dY * Lin.ffn_reference(X_, W1_, W2_, dY)["Y"]))
+
+    eps = 1e-6
+    for name, base, grad in (("X", X, ref["dX"]), ("W1", W1, ref["dW1"]), ("W2", W2, ref["dW2"])):
+        num = np.zeros_like(base)
+        for idx in np.ndindex(base.shape):
+            p, m = base.copy(), base.copy()
+            p[idx] += eps
+            m[idx] -= eps
+            args_p = {"X": (p, W1, W2), "W1": (X, p, W2), "W2": (X, W1, p)}[name]
+            args_m = {"X": (m, W1, W2), "W1": (X, m, W2), "W2": (X, W1, m)}[name]
+            num[idx] = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+        assert np.allclose(num, grad, rtol=1e-6, atol=1e-7), name
+    # the stages are the single-layer products of this module
+    assert np.allclose(ref["H"], X @ W1.T) and np.allclose(ref["dA"], dY @ W2)
