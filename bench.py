@@ -290,7 +290,7 @@ def measure(sste, torch, np, WL, cfg, layer_sel, steps, warmup, sets, grad_e5m2,
 def cpu_baseline(np, WL, cfg):
     """Times the oracle, as it stands (its numpy forms), on a bounded sample of the headline workload: one
     step (8-bit casts of X and dY, project + pack, forward, estimator + weight gradient) of the block's
-    attention-projection layer on the first 2048 tokens.  Median of three runs."""
+    attention-projection layer (the smallest of the four; the whole block would take minutes).  Median of three runs."""
     from oracle import formats as OF
     from oracle import linear as OL
     from oracle import projection as OP
@@ -302,7 +302,7 @@ def cpu_baseline(np, WL, cfg):
     wl = WL.WORKLOADS[cfg]
     li = 1 if len(wl.layers) > 1 else 0
     L = wl.layers[li]
-    T = min(wl.T, 2048)
+    T = wl.T
     wb = WL.weight_bits(wl, li)
     xb = WL.activations(wl, li, T=T)[0]
     dyb = WL.output_gradient(wl, li, T=T)[0]
@@ -333,8 +333,8 @@ def cpu_baseline(np, WL, cfg):
         "unit": "TFLOP/s",
         "cores": int(cores),
         "kind": "oracle",
-        "sample": "one step of cfg%d layer %s (W %dx%d) on the first %d of %d tokens: casts, project+pack, forward, estimator + weight "
-                  "gradient; median of 3 runs (%.2f s each)" % (wl.cfg, L.name, L.O, L.I, T, wl.T, t),
+        "sample": "one step of cfg%d layer %s (W %dx%d, all %d tokens; the smallest of the block's four layers): casts, project+pack, "
+                  "forward, estimator + weight gradient; median of 3 runs (%.2f s each)" % (wl.cfg, L.name, L.O, L.I, T, t),
     }
 
 
@@ -462,6 +462,85 @@ def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context):
     return out
 
 
+def ffn_block(sste, torch, np, WL, cfg=4, iters=30):
+    """One training step of a feed-forward block (fc1 -> GELU -> fc2; the block the paper's appendix times) through
+    the library, bf16: re-projection of both weights, fc1 forward with the activation in its epilogue, fc2 forward,
+    fc2 input gradient with the activation's derivative in its epilogue, both weight gradients, fc1 input gradient.
+    Beside it, as context, the same block as dense torch.matmul + autograd on the same box."""
+    wl = WL.WORKLOADS[cfg]
+    names = [l.name for l in wl.layers]
+    l1, l2 = wl.layers[names.index("fc1")], wl.layers[names.index("fc2")]
+    T, d, h = wl.T, l1.I, l1.O
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits.view(np.int16))).cuda().view(torch.bfloat16)
+    W1, W2 = up(WL.weight_bits(wl, names.index("fc1"))), up(WL.weight_bits(wl, names.index("fc2")))
+    X = up(WL.activations(wl, names.index("fc1"))[0])
+    dY = up(WL.output_gradient(wl, names.index("fc2"))[0])
+    v1, m1 = sste.packed_buffers(h, d, sste.BF16, "cuda")
+    v2, m2 = sste.packed_buffers(d, h, sste.BF16, "cuda")
+    H = torch.empty((T, h), dtype=torch.bfloat16, device="cuda")
+    A = torch.empty_like(H)
+    Y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    dH = torch.empty_like(H)
+    dX = torch.empty_like(X)
+    dW1 = torch.empty((h, d), dtype=torch.float32, device="cuda")
+    dW2 = torch.empty((d, h), dtype=torch.float32, device="cuda")
+    ws1 = torch.empty(max(16, sste.wgrad_workspace_bytes(T, h, d, sste.BF16)), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(16, sste.wgrad_workspace_bytes(T, d, h, sste.BF16)), dtype=torch.uint8, device="cuda")
+    beta = 1.4830322
+
+    def step(i):
+        sste.project_pack(W1, beta, vals=v1, meta=m1)
+        sste.project_pack(W2, beta, vals=v2, meta=m2)
+        sste.linear_fwd_act(X, v1, m1, h, H=H, A=A)
+        sste.linear_fwd(A, v2, m2, d, Z=Y)
+        sste.linear_dgrad_act(dY, v2, m2, h, H, dX=dH)
+        sste.linear_wgrad(dY, A, seed=cfg, offset=2 * i, dW=dW2, workspace=ws2)
+        sste.linear_wgrad(dH, X, seed=cfg, offset=2 * i + 1, dW=dW1, workspace=ws1)
+        sste.linear_dgrad(dH, v1, m1, d, dX=dX)
+
+    def timed(fn, n):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    ms = timed(step, iters)
+    # the same products with the activation as separate passes (plain calls + torch elementwise ops): what the fusion saves
+    def unfused(i):
+        sste.project_pack(W1, beta, vals=v1, meta=m1)
+        sste.project_pack(W2, beta, vals=v2, meta=m2)
+        sste.linear_fwd(X, v1, m1, h, Z=H)
+        torch.nn.functional.gelu(H, approximate="tanh")
+        sste.linear_fwd(A, v2, m2, d, Z=Y)
+        sste.linear_dgrad(dY, v2, m2, h, dX=dH)
+        torch.ops.aten.gelu_backward(dH, H, approximate="tanh")
+        sste.linear_wgrad(dY, A, seed=cfg, offset=2 * i, dW=dW2, workspace=ws2)
+        sste.linear_wgrad(dH, X, seed=cfg, offset=2 * i + 1, dW=dW1, workspace=ws1)
+        sste.linear_dgrad(dH, v1, m1, d, dX=dX)
+    ms_unfused = timed(unfused, iters)
+
+    Xr = X.clone().requires_grad_(True)
+    W1r, W2r = W1.clone().requires_grad_(True), W2.clone().requires_grad_(True)
+
+    def dense(i):
+        Xr.grad = W1r.grad = W2r.grad = None
+        out = torch.nn.functional.gelu(Xr @ W1r.t(), approximate="tanh") @ W2r.t()
+        out.backward(dY)
+    ms_dense = timed(dense, iters)
+    flops = 6 * 2.0 * T * d * h                                  # six GEMMs of 2 T d h dense-equivalent flops
+    return {"workload": "cfg%d FFN block: fc1 %dx%d, GELU, fc2 %dx%d, %d tokens, bf16" % (cfg, h, d, d, h, T),
+            "ms_per_step": ms, "dense_equiv_TFLOP_per_s": flops / (ms * 1e-3) * 1e-12,
+            "ms_per_step_activation_as_separate_passes": ms_unfused,
+            "dense_context": {"library": "torch.matmul + torch gelu(tanh) + autograd, bf16", "ms_per_step": ms_dense,
+                              "speedup_over_dense": ms_dense / ms}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -525,6 +604,9 @@ def main():
             torch.cuda.empty_cache()
             secondary["cfg%d" % cfg] = sec
         out["secondary"] = secondary
+    if not args.no_secondary:
+        out["ffn_block"] = ffn_block(sste, torch, np, WL)
+        torch.cuda.empty_cache()
     if not args.no_prune_model:
         out["prune_pack_model"] = prune_model(sste, torch)
     if not args.no_cpu_baseline:
