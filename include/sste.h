@@ -99,6 +99,18 @@ int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float be
                       void* vals, void* meta, float* amax_out, void* hip_stream);
 
 /*
+ * sste_project_pack with the threshold of Sec. 4.1 "Choosing optimal threshold": any t between the
+ * third-largest magnitude m3 and the second-largest m2 of a group is feasible; t = m3 + gamma * (m2 - m3)
+ * (three float32 operations; the paper's interpolation with gamma = 0 giving its t = |t_2|, larger gamma
+ * moving t towards the second-largest magnitude and shrinking S_soft).  gamma = 0 is the method and is
+ * sste_project_pack bit for bit; gamma in (0, 1] reproduces the paper's ablation (its Table 3).  The
+ * recorded positions do not depend on gamma.  gamma outside [0, 1] (or NaN) -> ERR_VALUE.
+ */
+int sste_project_pack_gamma(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, float gamma,
+                            int val_dtype, float val_scale,
+                            void* vals, void* meta, float* amax_out, void* hip_stream);
+
+/*
  * Projection + scale + pack of MANY weight tensors in one launch (the per-iteration re-projection of
  * every sparse layer of a model, Sec. 4: S(W) is recomputed from the dense weights in every iteration).
  * Single layers are small enough that a launch per tensor is dominated by launch latency; one grid
@@ -431,6 +443,17 @@ int sste_mvue_materialize_at(const void* dY, int64_t T, int64_t O, int64_t lddy,
 int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t sste_beta_workspace_bytes(int64_t O, int64_t I);
+
+/*
+ * The scales Sec. 4.2 compares (its Table 4), for a threshold parameter gamma as in sste_project_pack_gamma:
+ *   SSTE_BETA_MSE  beta = <W, S_soft(W)> / ||S_soft(W)||^2      (the method; with gamma = 0 this is sste_compute_beta)
+ *   SSTE_BETA_L1   beta = ||W||_1 / ||S_soft(W)||_1             (keeps the total magnitude; the variant the paper rejects)
+ * Same arguments, workspace and reproducibility as sste_compute_beta; unknown kind or gamma outside [0, 1]
+ * -> ERR_VALUE.
+ */
+enum { SSTE_BETA_MSE = 0, SSTE_BETA_L1 = 1 };
+int sste_compute_beta_ex(const void* W, int64_t O, int64_t I, int64_t ldw, int kind, float gamma, float* beta_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Per-tensor rescaling and cast of a bf16 tensor to an 8-bit operand format (Sec. 5.2: the operands of

@@ -54,11 +54,18 @@ def _groups(a):
     return a.reshape(-1, 4)
 
 
-def soft_threshold(a):
-    """S_soft of Sec. 4.1 applied block-wise along the last axis (float64)."""
+def soft_threshold(a, gamma=0.0):
+    """S_soft of Sec. 4.1 applied block-wise along the last axis (float64).
+
+    gamma: the threshold ablation of Sec. 4.1 "Choosing optimal threshold".  Any t in [|t2|, |t3|] is
+    feasible; the paper writes the interpolation as gamma |t2| + (1 - gamma) |t3| but describes it the
+    other way round (larger gamma -> t closer to |t3|, gamma = 0 -> t = |t2|, which is the method).
+    Reading taken: t = (1 - gamma) |t2| + gamma |t3|, the one consistent with the text, the definition
+    above it and the table's best row gamma = 0."""
     a = np.asarray(a, dtype=np.float64)
     g = _groups(a)
-    t = np.sort(np.abs(g), axis=1)[:, 1:2]           # ascending magnitudes |t1|<=|t2|<=..: t = |t2|
+    mags = np.sort(np.abs(g), axis=1)                # ascending magnitudes |t1|<=|t2|<=..: t = |t2| for gamma = 0
+    t = (1.0 - gamma) * mags[:, 1:2] + gamma * mags[:, 2:3]
     out = np.where(g >= t, g - t, np.where(g <= -t, g + t, 0.0))
     # the middle case (-t, t) -> 0 takes precedence only where the intervals do not overlap; for
     # t == 0 the first and third intervals both contain 0 and both give 0, so no ambiguity.
@@ -97,20 +104,20 @@ def hard_threshold_mask(a):
     return (np.abs(g) >= t).reshape(a.shape)
 
 
-def beta_mse(w):
+def beta_mse(w, gamma=0.0):
     """Sec. 4.2: argmin_beta ||w - beta S_soft(w)||^2 = <w, S_soft(w)> / ||S_soft(w)||^2 (float64)."""
     w = np.asarray(w, dtype=np.float64)
-    s = soft_threshold(w)
+    s = soft_threshold(w, gamma)
     den = float(np.sum(s * s))
     if den == 0.0:
         raise ValueError("S_soft(w) is identically zero: beta is undefined")
     return float(np.sum(w * s)) / den
 
 
-def beta_l1(w):
+def beta_l1(w, gamma=0.0):
     """Sec. 4.2: the L1-norm preserving scale ||w||_1 / ||S_soft(w)||_1 (comparison variant)."""
     w = np.asarray(w, dtype=np.float64)
-    s = soft_threshold(w)
+    s = soft_threshold(w, gamma)
     return float(np.sum(np.abs(w))) / float(np.sum(np.abs(s)))
 
 
@@ -147,8 +154,18 @@ def rank_positions(w_bits):
     return idx0, idx1, third.astype(np.uint16)
 
 
-def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
+def second_magnitude_bits(w_bits):
+    """Magnitude field of the second-ranked element of each group (same order as ``rank_positions``)."""
+    bits = np.asarray(w_bits, dtype=np.uint16)
+    mag = (bits & np.uint16(0x7FFF)).reshape(-1, 4)
+    return np.sort(mag, axis=1)[:, 2].astype(np.uint16)
+
+
+def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0, gamma=0.0):
     """beta * S_soft(W) on a bf16 matrix, packed 2:4.
+
+    gamma (threshold ablation, see ``soft_threshold``): t = m3 + gamma * (m2 - m3) as three float32
+    operations on the third- and second-largest magnitudes; gamma = 0 leaves t = m3 untouched.
 
     w_bits : uint16 (O, I) bf16 patterns, groups of 4 along I.
     Returns (vals, meta, amax):
@@ -166,6 +183,11 @@ def project_pack(w_bits, beta, val_dtype="bf16", val_scale=1.0):
     idx0, idx1, third = rank_positions(w_bits)
     a = formats.bf16_to_f32(w_bits).reshape(-1, 4)
     t = formats.bf16_to_f32(third)                                    # >= 0
+    if float(gamma) != 0.0:
+        m2 = formats.bf16_to_f32(second_magnitude_bits(w_bits))
+        span = (m2 - t).astype(np.float32)
+        part = (np.float32(gamma) * span).astype(np.float32)
+        t = (t + part).astype(np.float32)
     rows = np.arange(a.shape[0])
     out_vals = []
     amax = np.float32(0.0)

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     cast_fp8,
     UpdateBatch,
     compute_beta,
+    BETA_MSE,
+    BETA_L1,
     flip_count,
     library,
     linear_dgrad,

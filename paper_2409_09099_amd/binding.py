@@ -37,6 +37,10 @@ def library() -> ctypes.CDLL:
     lib.sste_version.restype = ci
     lib.sste_last_error.restype = ctypes.c_char_p
     lib.sste_project_pack.argtypes = [vp, i64, i64, i64, f32, ci, f32, vp, vp, vp, vp]
+    lib.sste_project_pack_gamma.argtypes = [vp, i64, i64, i64, f32, f32, ci, f32, vp, vp, vp, vp]
+    lib.sste_project_pack_gamma.restype = ci
+    lib.sste_compute_beta_ex.argtypes = [vp, i64, i64, i64, ci, f32, vp, vp, sz, vp]
+    lib.sste_compute_beta_ex.restype = ci
     lib.sste_sgd_project_pack.argtypes = [vp, ci, i64, i64, i64, vp, i64, f32, f32, ci, f32, vp, vp, vp]
     lib.sste_sgd_project_pack_batch_prepare.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(i64)]
     lib.sste_sgd_project_pack_batch.argtypes = [vp, ci, i64, ci, ci, f32, vp]
@@ -126,15 +130,19 @@ def packed_buffers(R: int, K: int, dtype: int, device):
 
 def project_pack(W: torch.Tensor, beta: float, val_dtype: int = BF16, val_scale: float = 1.0,
                  vals: Optional[torch.Tensor] = None, meta: Optional[torch.Tensor] = None,
-                 amax_out: Optional[torch.Tensor] = None):
-    """sste_project_pack: beta * S_soft(W) packed 2:4.  Returns (vals, meta)."""
+                 amax_out: Optional[torch.Tensor] = None, gamma: float = 0.0):
+    """sste_project_pack(_gamma): beta * S_soft(W) packed 2:4.  Returns (vals, meta)."""
     O, I, ldw = _matrix(W, 2, "W")
     if vals is None or meta is None:
         v, m = packed_buffers(O, I, val_dtype, W.device)
         vals = v if vals is None else vals
         meta = m if meta is None else meta
-    _check(library().sste_project_pack(_ptr(W), O, I, ldw, beta, val_dtype, val_scale, _ptr(vals), _ptr(meta),
-                                       _ptr(amax_out), _stream(W)))
+    if gamma == 0.0:
+        _check(library().sste_project_pack(_ptr(W), O, I, ldw, beta, val_dtype, val_scale, _ptr(vals), _ptr(meta),
+                                           _ptr(amax_out), _stream(W)))
+    else:
+        _check(library().sste_project_pack_gamma(_ptr(W), O, I, ldw, beta, gamma, val_dtype, val_scale, _ptr(vals), _ptr(meta),
+                                                 _ptr(amax_out), _stream(W)))
     return vals, meta
 
 
@@ -418,13 +426,19 @@ def mvue_materialize(dY: torch.Tensor, seed: int, offset: int, dtype: int = BF16
     return vals, meta
 
 
-def compute_beta(W: torch.Tensor) -> torch.Tensor:
-    """sste_compute_beta: the MSE-optimal scale as a 1-element float32 device tensor."""
+BETA_MSE, BETA_L1 = 0, 1
+
+
+def compute_beta(W: torch.Tensor, kind: int = BETA_MSE, gamma: float = 0.0) -> torch.Tensor:
+    """sste_compute_beta(_ex): the MSE-optimal (or L1-preserving) scale as a 1-element float32 device tensor."""
     O, I, ldw = _matrix(W, 2, "W")
     need = int(library().sste_beta_workspace_bytes(O, I))
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=W.device)
     out = torch.empty(1, dtype=torch.float32, device=W.device)
-    _check(library().sste_compute_beta(_ptr(W), O, I, ldw, _ptr(out), _ptr(ws), ws.numel(), _stream(W)))
+    if kind == BETA_MSE and gamma == 0.0:
+        _check(library().sste_compute_beta(_ptr(W), O, I, ldw, _ptr(out), _ptr(ws), ws.numel(), _stream(W)))
+    else:
+        _check(library().sste_compute_beta_ex(_ptr(W), O, I, ldw, kind, gamma, _ptr(out), _ptr(ws), ws.numel(), _stream(W)))
     return out
 
 

@@ -165,11 +165,17 @@ static_assert(sizeof(PackTableItemHost) == SSTE_PACK_TABLE_ITEM_BYTES, "table it
 
 int sste_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype, float val_scale,
                       void* vals, void* meta, float* amax_out, void* hip_stream) {
+  return sste_project_pack_gamma(W, O, I, ldw, beta, 0.0f, val_dtype, val_scale, vals, meta, amax_out, hip_stream);
+}
+
+int sste_project_pack_gamma(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, float gamma, int val_dtype,
+                            float val_scale, void* vals, void* meta, float* amax_out, void* hip_stream) {
   clear_error();
   int st = check_pack_args("project_pack", W, O, I, ldw, beta, val_dtype, val_scale, vals, meta);
   if (st != SSTE_OK) return st;
+  if (!(gamma >= 0.0f && gamma <= 1.0f)) return fail(SSTE_ERR_VALUE, "project_pack: gamma must lie in [0, 1]");
   if (amax_out && (reinterpret_cast<uintptr_t>(amax_out) & 3u)) return fail(SSTE_ERR_ALIGN, "project_pack: amax_out must be 4-byte aligned");
-  return hip_status(launch_project_pack(W, O, I, ldw, beta, val_dtype, val_scale, vals, meta, amax_out, (hipStream_t)hip_stream),
+  return hip_status(launch_project_pack(W, O, I, ldw, beta, gamma, val_dtype, val_scale, vals, meta, amax_out, (hipStream_t)hip_stream),
                     "project_pack launch");
 }
 
@@ -572,7 +578,14 @@ size_t sste_beta_workspace_bytes(int64_t O, int64_t I) {
 
 int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
+  return sste_compute_beta_ex(W, O, I, ldw, SSTE_BETA_MSE, 0.0f, beta_out, workspace, workspace_bytes, hip_stream);
+}
+
+int sste_compute_beta_ex(const void* W, int64_t O, int64_t I, int64_t ldw, int kind, float gamma, float* beta_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
   clear_error();
+  if (kind != SSTE_BETA_MSE && kind != SSTE_BETA_L1) return fail(SSTE_ERR_VALUE, "compute_beta: unknown kind %d", kind);
+  if (!(gamma >= 0.0f && gamma <= 1.0f)) return fail(SSTE_ERR_VALUE, "compute_beta: gamma must lie in [0, 1]");
   if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "compute_beta: negative size");
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "compute_beta: I=%lld is not a multiple of 8", (long long)I);
   if (ldw < I) return fail(SSTE_ERR_SHAPE, "compute_beta: ldw < I");
@@ -583,7 +596,8 @@ int sste_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* b
   size_t need = beta_workspace_bytes(O, I);
   if (!workspace || workspace_bytes < need) return fail(SSTE_ERR_WORKSPACE, "compute_beta: workspace needs %zu bytes", need);
   if (!aligned16(workspace)) return fail(SSTE_ERR_ALIGN, "compute_beta: workspace must be 16-byte aligned");
-  return hip_status(launch_compute_beta(W, O, I, ldw, beta_out, workspace, (hipStream_t)hip_stream), "compute_beta launch");
+  return hip_status(launch_compute_beta(W, O, I, ldw, kind == SSTE_BETA_L1, gamma, beta_out, workspace, (hipStream_t)hip_stream),
+                    "compute_beta launch");
 }
 
 int sste_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale, void* Q, int64_t ldq,

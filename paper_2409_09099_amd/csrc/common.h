@@ -196,7 +196,7 @@ __device__ __forceinline__ void store_stream_b128(void* p, float4 v) {
 struct RngKey { uint32_t k0, k1; uint64_t first_group; };
 RngKey derive_key(uint64_t seed, uint64_t offset);
 
-hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
+hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, float gamma, int val_dtype,
                                float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s);
 hipError_t launch_sgd_project_pack(void* W, bool w_f32, int64_t O, int64_t I, int64_t ldw, const float* G, int64_t ldg,
                                    float alpha, float beta, int val_dtype, float val_scale, void* vals, void* meta,
@@ -207,7 +207,7 @@ hipError_t launch_project_pack_batch(const void* table, int n_items, int64_t tot
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype);
 hipError_t launch_linear_dgrad(const void* dY, int64_t T, int64_t O, int64_t lddy, int dtype, float scale, const void* vals,
                                const void* meta, int64_t I, void* dX, int64_t lddx, const void* H, int64_t ldh, hipStream_t s);
-hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
+hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, int l1, float gamma, float* beta_out, void* ws,
                                hipStream_t s);
 size_t beta_workspace_bytes(int64_t O, int64_t I);
 hipError_t launch_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtype, float scale, void* Q,

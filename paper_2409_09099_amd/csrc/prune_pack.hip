@@ -15,7 +15,11 @@ struct Proj {
 };
 
 // One group {hi:lo} of four bf16.  Order: magnitude field descending, then index ascending.
-__device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float beta) {
+// GAMMA: the threshold interpolated between the third-largest magnitude m3 (gamma = 0, the method) and the
+// second-largest m2 (gamma = 1), the ablation of Sec. 4.1 "Choosing optimal threshold":
+// t = m3 + gamma * (m2 - m3), three float32 operations.
+template <bool GAMMA = false>
+__device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float beta, float gamma = 0.0f) {
   // key = magnitude << 2 | (3 - index): a larger key ranks first, keys are distinct
   uint32_t k0 = ((lo & 0x7FFFu) << 2) | 3u;
   uint32_t k1 = ((lo >> 14) & 0x1FFFCu) | 2u;
@@ -32,6 +36,12 @@ __device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float be
   uint32_t pa = 3u - (first & 3u), pb = 3u - (second & 3u);
   uint32_t pos0 = min(pa, pb), pos1 = max(pa, pb);
   uint32_t tbits = (third >> 2) << 16;              // float32 pattern of t (>= 0)
+  if (GAMMA) {
+    const float m3 = u2f(tbits), m2 = u2f((second >> 2) << 16);
+    const float span = m2 - m3;
+    const float part = gamma * span;
+    tbits = f2u(m3 + part) & 0x7FFFFFFFu;
+  }
   Proj r;
   uint32_t g0 = pick16_as_f32bits(lo, hi, pos0), g1 = pick16_as_f32bits(lo, hi, pos1);
   float sd0 = u2f(g0) - u2f(tbits | (g0 & 0x80000000u));    // a - t  or  a + t
@@ -52,17 +62,17 @@ __device__ __forceinline__ Proj project_group(uint32_t lo, uint32_t hi, float be
 // Block `blk` (row block rb = blk / steps, column step s = blk % steps) of one tensor, by one wave.
 // Returns the largest |p| this lane recorded (only computed when AMAX).
 // The lane's weights (bf16 pairs, w[2g] and w[2g+1] = group g) -> its slot of block `blk`.
-template <bool FP8, bool AMAX>
+template <bool FP8, bool AMAX, bool GAMMA = false>
 __device__ __forceinline__ float project_store(const uint32_t (&w)[FP8 ? 16 : 8], int64_t blk, float beta,
                                                float val_scale, uint4* __restrict__ vals, void* __restrict__ meta,
-                                               int lane) {
+                                               int lane, float gamma = 0.0f) {
   constexpr int NG = FP8 ? 8 : 4;                       // groups per lane
   float amax = 0.0f;
   float p[2 * NG];
   uint32_t nibs = 0;
 #pragma unroll
   for (int g = 0; g < NG; g++) {
-    Proj r = project_group(w[2 * g], w[2 * g + 1], beta);
+    Proj r = project_group<GAMMA>(w[2 * g], w[2 * g + 1], beta, gamma);
     p[2 * g] = r.p0;
     p[2 * g + 1] = r.p1;
     nibs |= r.nib << (4 * g);
@@ -88,10 +98,11 @@ __device__ __forceinline__ float project_store(const uint32_t (&w)[FP8 ? 16 : 8]
   return amax;
 }
 
-template <bool FP8, bool AMAX>
+template <bool FP8, bool AMAX, bool GAMMA = false>
 __device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t blk,
                                                int64_t ldw_bytes, float beta, float val_scale,
-                                               uint4* __restrict__ vals, void* __restrict__ meta, int lane) {
+                                               uint4* __restrict__ vals, void* __restrict__ meta, int lane,
+                                               float gamma = 0.0f) {
   constexpr int NG = FP8 ? 8 : 4;
   const int64_t rb = blk / steps;
   const int32_t s = (int32_t)(blk - rb * steps);
@@ -109,7 +120,7 @@ __device__ __forceinline__ float project_block(const uint8_t* __restrict__ W, in
 #pragma unroll
     for (int c = 0; c < 2 * NG; c++) w[c] = 0;
   }
-  return project_store<FP8, AMAX>(w, blk, beta, val_scale, vals, meta, lane);
+  return project_store<FP8, AMAX, GAMMA>(w, blk, beta, val_scale, vals, meta, lane, gamma);
 }
 
 // Dense-weight step of Eq. (7) fused with the projection of the new weight (Sec. 2: update the dense
@@ -236,15 +247,15 @@ k_sgd_project_pack_batch(const UpdateTableItem* __restrict__ table, int n_items,
   }
 }
 
-template <bool FP8, bool AMAX>
+template <bool FP8, bool AMAX, bool GAMMA>
 __global__ void __launch_bounds__(256)
 k_project_pack(const uint8_t* __restrict__ W, int64_t O, int32_t steps, int64_t n_blocks, int64_t ldw_bytes,
                float beta, float val_scale, uint4* __restrict__ vals, void* __restrict__ meta,
-               uint32_t* __restrict__ amax_bits) {
+               uint32_t* __restrict__ amax_bits, float gamma) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   float amax = 0.0f;
-  if (blk < n_blocks) amax = project_block<FP8, AMAX>(W, O, steps, blk, ldw_bytes, beta, val_scale, vals, meta, lane);
+  if (blk < n_blocks) amax = project_block<FP8, AMAX, GAMMA>(W, O, steps, blk, ldw_bytes, beta, val_scale, vals, meta, lane, gamma);
   if (AMAX) {
     // non-negative floats order like their bit patterns: reduce as unsigned integers
     uint32_t m = f2u(amax);
@@ -306,7 +317,7 @@ k_project_pack_batch(const PackTableItem* __restrict__ table, int n_items, int64
 __global__ void k_fill_u32(uint32_t* p, uint32_t v) { *p = v; }
 __global__ void k_fill_u64(unsigned long long* p, unsigned long long v) { *p = v; }
 
-hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, int val_dtype,
+hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw, float beta, float gamma, int val_dtype,
                                float val_scale, void* vals, void* meta, float* amax_out, hipStream_t s) {
   if (amax_out) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(1), 0, s, (uint32_t*)amax_out, 0u);
   bool fp8 = val_dtype == SSTE_F8E4M3;
@@ -315,14 +326,20 @@ hipError_t launch_project_pack(const void* W, int64_t O, int64_t I, int64_t ldw,
   dim3 grid((unsigned)((n + 3) / 4)), block(256);
   const uint8_t* w = (const uint8_t*)W;
   uint32_t* ab = (uint32_t*)amax_out;
-  if (fp8 && amax_out)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
-  else if (fp8)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<true, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
-  else if (amax_out)
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, true>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
-  else
-    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<false, false>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, (uint4*)vals, meta, ab);
+  const bool am = amax_out != nullptr, gm = gamma != 0.0f;
+#define PP_CASE(F, A, G)                                                                                                   \
+  if (fp8 == F && am == A && gm == G)                                                                                      \
+    SSTE_LAUNCH(SSTE_K_PROJECT_PACK, (k_project_pack<F, A, G>), grid, block, s, w, O, (int32_t)steps, n, ldw * 2, beta, val_scale, \
+                (uint4*)vals, meta, ab, gamma)
+  PP_CASE(false, false, false);
+  PP_CASE(false, true, false);
+  PP_CASE(true, false, false);
+  PP_CASE(true, true, false);
+  PP_CASE(false, false, true);
+  PP_CASE(false, true, true);
+  PP_CASE(true, false, true);
+  PP_CASE(true, true, true);
+#undef PP_CASE
   return hipGetLastError();
 }
 
@@ -378,7 +395,7 @@ constexpr int kBetaBlocks = 1024;
 
 __global__ void __launch_bounds__(256)
 k_beta_partial(const uint4* __restrict__ W, int64_t n_chunks, int32_t chunks_per_row, int64_t ldw_chunks,
-               double* __restrict__ partial) {
+               double* __restrict__ partial, int l1, float gamma) {
   double num = 0.0, den = 0.0;
   for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (int64_t)gridDim.x * 256) {
     int64_t row = c / chunks_per_row;
@@ -387,12 +404,19 @@ k_beta_partial(const uint4* __restrict__ W, int64_t n_chunks, int32_t chunks_per
 #pragma unroll
     for (int g = 0; g < 2; g++) {
       uint32_t lo = g ? w.z : w.x, hi = g ? w.w : w.y;
-      Proj p = project_group(lo, hi, 1.0f);         // p = a -/+ t, exact float32 differences
+      Proj p = project_group<true>(lo, hi, 1.0f, gamma);   // p = a -/+ t as float32 (gamma = 0: t is the third magnitude)
       uint32_t pos0 = p.nib & 3u, pos1 = p.nib >> 2;
-      double a0 = (double)u2f(pick16_as_f32bits(lo, hi, pos0)), a1 = (double)u2f(pick16_as_f32bits(lo, hi, pos1));
       double s0 = (double)p.p0, s1 = (double)p.p1;
-      num += a0 * s0 + a1 * s1;
-      den += s0 * s0 + s1 * s1;
+      if (l1) {
+        // L1-preserving scale: ||w||_1 over all four elements of the group, ||S_soft(w)||_1 over the recorded two
+        num += (double)u2f((lo << 16) & 0x7FFFFFFFu) + (double)u2f(lo & 0x7FFF0000u) + (double)u2f((hi << 16) & 0x7FFFFFFFu) +
+               (double)u2f(hi & 0x7FFF0000u);
+        den += fabs(s0) + fabs(s1);
+      } else {
+        double a0 = (double)u2f(pick16_as_f32bits(lo, hi, pos0)), a1 = (double)u2f(pick16_as_f32bits(lo, hi, pos1));
+        num += a0 * s0 + a1 * s1;
+        den += s0 * s0 + s1 * s1;
+      }
     }
   }
   __shared__ double sn[256], sd[256];
@@ -441,11 +465,11 @@ static int beta_blocks(int64_t n_chunks) {
 
 size_t beta_workspace_bytes(int64_t O, int64_t I) { return (size_t)beta_blocks(O * (I / 8)) * 2 * sizeof(double); }
 
-hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, float* beta_out, void* ws,
+hipError_t launch_compute_beta(const void* W, int64_t O, int64_t I, int64_t ldw, int l1, float gamma, float* beta_out, void* ws,
                                hipStream_t s) {
   int64_t cpr = I / 8, n = O * cpr;
   int nb = beta_blocks(n);
-  hipLaunchKernelGGL(k_beta_partial, dim3(nb), dim3(256), 0, s, (const uint4*)W, n, (int32_t)(cpr ? cpr : 1), ldw / 8, (double*)ws);
+  hipLaunchKernelGGL(k_beta_partial, dim3(nb), dim3(256), 0, s, (const uint4*)W, n, (int32_t)(cpr ? cpr : 1), ldw / 8, (double*)ws, l1, gamma);
   hipLaunchKernelGGL(k_beta_final, dim3(1), dim3(256), 0, s, (const double*)ws, nb, beta_out);
   return hipGetLastError();
 }

@@ -137,6 +137,52 @@ def test_project_pack_e4m3_bit_exact(sste, case):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+@pytest.mark.parametrize("gamma", [0.33, 0.67, 1.0])
+def test_project_pack_threshold_interpolation_bit_exact(sste, dtype, gamma):
+    """The threshold ablation of Sec. 4.1 (t between the third- and the second-largest magnitude): packed values,
+    positions and largest magnitude are the oracle's, bit for bit; gamma = 0 is the plain call."""
+    wl = WL.WORKLOADS[1]
+    for wb in (WL.weight_bits(wl, 0, O=77, I=1152), _edge_weights()):
+        beta = np.float32(1.37)
+        scale = np.float32(1.0) if dtype == "bf16" else np.float32(0.0009 if wb.shape[0] == 77 else 0.37)
+        amax = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+        vals, meta = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, dtype), float(scale), amax_out=amax, gamma=gamma)
+        rv, rm, ra = OP.project_pack(wb, beta, dtype, scale, gamma=gamma)
+        fv, fm = OP.to_fragment_major(rv, rm, dtype)
+        assert np.array_equal(host(meta).numpy().reshape(-1), fm)
+        assert np.array_equal(host(vals).numpy().view(fv.dtype).reshape(-1), fv)
+        assert host(amax).numpy().view(np.uint32)[0] == np.float32(ra).view(np.uint32)
+    W = bf16_dev(WL.weight_bits(wl, 0))
+    v0, m0 = sste.project_pack(W, 1.37)
+    lib = sste.library()
+    v1, m1 = sste.packed_buffers(256, 1024, sste.BF16, "cuda")
+    assert lib.sste_project_pack_gamma(W.data_ptr(), 256, 1024, 1024, 1.37, 0.0, sste.BF16, 1.0, v1.data_ptr(), m1.data_ptr(), None,
+                                       torch.cuda.current_stream().cuda_stream) == 0
+    assert torch.equal(v0, v1) and torch.equal(m0, m1)
+    with pytest.raises(sste.SsteError) as ei:
+        sste.project_pack(W, 1.37, gamma=1.5)
+    assert ei.value.status == 5
+
+
+def test_compute_beta_variants(sste):
+    """The two scales Sec. 4.2 compares, for several thresholds: GPU reduction against the float64 definitions."""
+    wl = WL.WORKLOADS[1]
+    wb = WL.weight_bits(wl, 0, O=200, I=1024)
+    W = bf16_dev(wb)
+    w64 = F.bf16_to_f32(wb).astype(np.float64)
+    for gamma in (0.0, 0.33, 1.0):
+        # the kernel forms t in float32 from gamma as a float32: evaluate the definition at that gamma
+        g32 = float(np.float32(gamma))
+        for kind, ref in ((sste.BETA_MSE, OP.beta_mse(w64, g32)), (sste.BETA_L1, OP.beta_l1(w64, g32))):
+            got = float(host(sste.compute_beta(W, kind, gamma))[0])
+            assert abs(got - ref) <= 2e-5 * ref, (gamma, kind, got, ref)
+    assert 1.45 < float(host(sste.compute_beta(W))[0]) < 1.52 and 2.3 < float(host(sste.compute_beta(W, sste.BETA_L1))[0]) < 2.7
+    with pytest.raises(sste.SsteError) as ei:
+        sste.compute_beta(W, 5)
+    assert ei.value.status == 5
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
 def test_project_pack_batch_bit_exact(sste, dtype):
     """Many tensors in one launch: every tensor's packed form is the oracle's, bit for bit (shapes with a
     ragged row tail, a strided tensor, an empty tensor and the edge-case groups among them)."""

@@ -295,3 +295,47 @@ def test_fragment_major_layout_by_hand_and_round_trip(val_dtype, R, K):
         slot = (0 * S + (S - 1)) * 64 + 16 * 2 + 5
         first_col = KS * (S - 1) + KS // 2
         assert np.array_equal(fv[slot * per:(slot + 1) * per], vals[5, first_col // 2:first_col // 2 + per])
+
+
+# ------------------------------------------------------------------ threshold interpolation and the L1 scale (ablations)
+
+def test_threshold_interpolation_hand_values_and_monotone_norm():
+    """Sec. 4.1 'Choosing optimal threshold': gamma = 0 is the method (t = third-largest magnitude), gamma = 1
+    puts t on the second-largest magnitude (one survivor per group), and the norm of S_soft shrinks as gamma
+    grows -- the statement that fixes which way the paper's interpolation runs."""
+    g = np.array([1.0, -3.0, 0.5, 2.0])
+    assert P.soft_threshold(g, 0.0).tolist() == [0.0, -2.0, 0.0, 1.0]
+    assert P.soft_threshold(g, 0.5).tolist() == [0.0, -1.5, 0.0, 0.5]
+    assert P.soft_threshold(g, 1.0).tolist() == [0.0, -1.0, 0.0, 0.0]
+    w = np.random.default_rng(4).standard_normal((64, 32))
+    norms = [np.linalg.norm(P.soft_threshold(w, gm)) for gm in (0.0, 0.33, 0.67, 1.0)]
+    assert all(a > b for a, b in zip(norms, norms[1:]))
+    for gm in (0.33, 1.0):                              # still 2:4, still continuous (Theorem 1's bound holds for any feasible t)
+        s = P.soft_threshold(w, gm)
+        assert np.count_nonzero(s.reshape(-1, 4), axis=1).max() <= 2
+        e = np.random.default_rng(5).uniform(-1e-3, 1e-3, w.shape)
+        assert np.abs(P.soft_threshold(w + e, gm) - s).max() <= 2 * np.abs(e).max() * (1 + 1e-9)
+
+
+@pytest.mark.parametrize("gamma", [0.33, 0.67, 1.0])
+def test_pack_with_threshold_interpolation_equals_rounded_definition(gamma):
+    rs = np.random.default_rng(6)
+    w = F.f32_to_bf16_rne((rs.standard_normal((32, 64)) * 0.02).astype(np.float32)).reshape(32, 64)
+    beta = np.float32(1.3)
+    vals, meta, _ = P.project_pack(w, beta, gamma=gamma)
+    v0, m0, _ = P.project_pack(w, beta)
+    assert np.array_equal(meta, m0)                     # the recorded positions do not depend on gamma
+    dense = P.decode_packed(vals, meta)
+    want = float(beta) * P.soft_threshold(F.bf16_to_f32(w).astype(np.float64), float(np.float32(gamma)))
+    assert np.all(np.abs(dense - want) <= np.abs(want) * 2.0 ** -8 + 1e-9)          # float32 steps, then one bf16 rounding
+    assert np.array_equal(P.project_pack(w, beta, gamma=0.0)[0], v0)
+
+
+def test_l1_scale_hand_value_and_definition():
+    g = np.array([[1.0, -3.0, 0.5, 2.0]])
+    assert abs(P.beta_l1(g) - 6.5 / 3.0) < 1e-15        # ||w||_1 = 6.5, ||S_soft(w)||_1 = 3
+    assert abs(P.beta_l1(g, 1.0) - 6.5 / 1.0) < 1e-15
+    w = np.random.default_rng(7).standard_normal((128, 64))
+    b = P.beta_l1(w)
+    assert abs(np.abs(b * P.soft_threshold(w)).sum() - np.abs(w).sum()) < 1e-9 * np.abs(w).sum()
+    assert 2.3 < b < 2.7 and b > P.beta_mse(w)          # i.i.d. Gaussian weights: about 2.5 against 1.48
