@@ -141,6 +141,7 @@ static int check_pack_args(const char* who, const void* W, int64_t O, int64_t I,
   if (I % (val_dtype == SSTE_F8E4M3 ? 128 : 64) != 0)
     return fail(SSTE_ERR_UNSUPPORTED, "%s: I=%lld must be a multiple of %d for this value type", who, (long long)I, val_dtype == SSTE_F8E4M3 ? 128 : 64);
   if (ldw < I) return fail(SSTE_ERR_SHAPE, "%s: ldw=%lld < I=%lld", who, (long long)ldw, (long long)I);
+  if (product_reaches(O, ldw, 1ll << 40)) return fail(SSTE_ERR_UNSUPPORTED, "%s: more than 2^40 weights", who);
   if (ldw % ldw_multiple != 0) return fail(SSTE_ERR_ALIGN, "%s: ldw=%lld is not a multiple of %d", who, (long long)ldw, ldw_multiple);
   bool empty = (O == 0 || I == 0);
   if (!empty && (!W || !vals || !meta)) return fail(SSTE_ERR_NULL, "%s: NULL W, vals or meta", who);
@@ -572,7 +573,7 @@ int sste_mvue_materialize_at(const void* dY, int64_t T, int64_t O, int64_t lddy,
 }
 
 size_t sste_beta_workspace_bytes(int64_t O, int64_t I) {
-  if (O < 0 || I < 0 || I % 8 != 0) return 0;
+  if (O < 0 || I < 0 || I % 8 != 0 || product_reaches(O, I, 1ll << 40)) return 0;
   return beta_workspace_bytes(O, I);
 }
 
@@ -591,7 +592,8 @@ int sste_compute_beta_ex(const void* W, int64_t O, int64_t I, int64_t ldw, int k
   if (ldw < I) return fail(SSTE_ERR_SHAPE, "compute_beta: ldw < I");
   if (ldw % 8 != 0) return fail(SSTE_ERR_ALIGN, "compute_beta: ldw is not a multiple of 8");
   if (!beta_out) return fail(SSTE_ERR_NULL, "compute_beta: beta_out is NULL");
-  if (O * I > 0 && !W) return fail(SSTE_ERR_NULL, "compute_beta: W is NULL");
+  if (O > 0 && I > 0 && !W) return fail(SSTE_ERR_NULL, "compute_beta: W is NULL");
+  if (product_reaches(O, ldw, 1ll << 40)) return fail(SSTE_ERR_UNSUPPORTED, "compute_beta: more than 2^40 weights");
   if (!aligned16(W)) return fail(SSTE_ERR_ALIGN, "compute_beta: W must be 16-byte aligned");
   size_t need = beta_workspace_bytes(O, I);
   if (!workspace || workspace_bytes < need) return fail(SSTE_ERR_WORKSPACE, "compute_beta: workspace needs %zu bytes", need);
@@ -611,6 +613,7 @@ int sste_cast_fp8(const void* X, int64_t R, int64_t C, int64_t ldx, int out_dtyp
   if (ldx % 8 != 0 || (Q && ldq % 8 != 0)) return fail(SSTE_ERR_ALIGN, "cast_fp8: ldx / ldq must be multiples of 8");
   if (!Q && !amax_out) return fail(SSTE_ERR_NULL, "cast_fp8: both Q and amax_out are NULL");
   if (R > 0 && C > 0 && !X) return fail(SSTE_ERR_NULL, "cast_fp8: NULL X");
+  if (product_reaches(R, ldx, 1ll << 40) || product_reaches(R, Q ? ldq : 1, 1ll << 40)) return fail(SSTE_ERR_UNSUPPORTED, "cast_fp8: more than 2^40 elements");
   if (!aligned16(X) || (reinterpret_cast<uintptr_t>(Q) & 7u) || (reinterpret_cast<uintptr_t>(amax_out) & 3u))
     return fail(SSTE_ERR_ALIGN, "cast_fp8: X must be 16-byte, Q 8-byte, amax_out 4-byte aligned");
   return hip_status(launch_cast_fp8(X, R, C, ldx, out_dtype, scale, Q, ldq, amax_out, (hipStream_t)hip_stream), "cast_fp8 launch");
@@ -621,6 +624,7 @@ int sste_flip_count(const void* meta_a, const void* meta_b, int64_t O, int64_t I
   if (O < 0 || I < 0) return fail(SSTE_ERR_SHAPE, "flip_count: negative size");
   if (I % 8 != 0) return fail(SSTE_ERR_SHAPE, "flip_count: I=%lld is not a multiple of 8", (long long)I);
   if (!count_out) return fail(SSTE_ERR_NULL, "flip_count: count_out is NULL");
+  if (product_reaches(O / 16 * 16 + 16, I, 1ll << 43)) return fail(SSTE_ERR_UNSUPPORTED, "flip_count: more than 2^40 bytes of metadata");
   int64_t nbytes = ((O + 15) / 16 * 16) * (I / 8);
   if (nbytes > 0 && (!meta_a || !meta_b)) return fail(SSTE_ERR_NULL, "flip_count: NULL metadata");
   if ((reinterpret_cast<uintptr_t>(meta_a) & 3u) || (reinterpret_cast<uintptr_t>(meta_b) & 3u) || (reinterpret_cast<uintptr_t>(count_out) & 7u))

@@ -13,6 +13,13 @@ namespace sste {
 int fail(int status, const char* fmt, ...);   // records the message, returns `status`
 void clear_error();
 
+// ---- host: size arithmetic that cannot overflow ------------------------------------------------------
+// a * b >= limit for non-negative 64-bit a, b (limit > 0), without forming a product that may overflow
+inline bool product_reaches(int64_t a, int64_t b, int64_t limit) {
+  if (a <= 0 || b <= 0) return false;
+  return a >= (limit + b - 1) / b;
+}
+
 // ---- optional per-kernel timing (sste_timing_begin / sste_timing_end) ---------------------------
 // While timing is on, each launch of a hot-path kernel is bracketed by its own pair of HIP events on
 // the launch stream, so the time reported is that kernel's alone.

@@ -391,9 +391,9 @@ k_linear_dgrad_dual(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_
 
 bool linear_dgrad_supported(int64_t T, int64_t O, int64_t lddy, int64_t I, int dtype) {
   const int eb = dtype != SSTE_BF16 ? 1 : 2;
-  if (256 * lddy * eb >= (1ll << 30)) return false;                       // 32-bit offsets inside a grad_Z tile
-  if (((O + 15) / 16 * 16) * I >= (1ll << 31)) return false;              // packed operand addressed with 32-bit offsets
-  if (((I + 255) / 256) * ((T + 127) / 128) > 0x7FFFFFFFll) return false;
+  if (product_reaches(lddy, 256 * eb, 1ll << 30)) return false;           // 32-bit offsets inside a grad_Z tile
+  if (product_reaches(O / 16 * 16 + 16, I, 1ll << 31)) return false;      // packed operand addressed with 32-bit offsets
+  if (product_reaches(I / 256 + 1, T / 128 + 1, 0x80000000ll)) return false;
   return true;
 }
 

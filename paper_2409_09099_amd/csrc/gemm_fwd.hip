@@ -647,8 +647,8 @@ static void launch_fwd_cfg(const void* X, int64_t T, int64_t I, int64_t ldx, con
 bool linear_fwd_supported(int64_t T, int64_t I, int64_t ldx, int64_t O, int dtype) {
   int64_t eb = dtype == SSTE_F8E4M3 ? 1 : 2;
   // 32-bit offsets inside a tile, 32-bit tile count
-  if (256 * ldx * eb >= (1ll << 30) || 256 * I * eb >= (1ll << 30)) return false;
-  if (((O + 255) / 256) * ((T + 127) / 128) > 0x7FFFFFFFll) return false;
+  if (product_reaches(ldx, 256 * eb, 1ll << 30) || product_reaches(I, 256 * eb, 1ll << 30)) return false;
+  if (product_reaches(O / 256 + 1, T / 128 + 1, 0x80000000ll)) return false;
   return true;
 }
 

@@ -466,7 +466,7 @@ static WgradPlan wgrad_plan(int64_t T, int64_t O, int64_t I, int dtype) {
   int64_t steps = T / ks;
   // the pre-pass pays off once the GEMM tiles would re-derive each group several times and the problem
   // is large enough to fill the chip; everything else runs the fused kernel
-  p.packed = (T >= 2048) && (O >= 256) && (I >= 256) && ((T * ((O + 15) / 16 * 16)) < (1ll << 40));
+  p.packed = (T >= 2048) && (O >= 256) && (I >= 256) && !product_reaches(T, O / 16 * 16 + 16, 1ll << 40);
   p.mi = 8;
   p.ni = 4;
   if (steps <= 0) {
@@ -548,8 +548,9 @@ size_t wgrad_workspace_bytes(int64_t T, int64_t O, int64_t I, int dtype) {
 
 bool linear_wgrad_supported(int64_t T, int64_t O, int64_t I, int64_t ldx, int dtype) {
   int64_t eb = dtype != SSTE_BF16 ? 1 : 2;
-  if (T * ldx * eb >= (1ll << 31)) return wgrad_plan(T, O, I, dtype).packed ? false : true;   // 32-bit offsets in the GEMM
-  if (((O + 127) / 128) * ((I + 127) / 128) * 32 > 0x7FFFFFFFll) return false;
+  if (product_reaches(O / 128 + 1, I / 128 + 1, 0x80000000ll / 32)) return false;
+  if (product_reaches(T, O / 16 * 16 + 16, 1ll << 40)) return false;                            // the packed operand's size
+  if (product_reaches(T, ldx, (1ll << 31) / eb)) return wgrad_plan(T, O, I, dtype).packed ? false : true;   // 32-bit offsets in the GEMM
   return true;
 }
 
