@@ -123,9 +123,10 @@ def make_layer(sste, torch, np, WL, wl, li, nsets, grad_e5m2):
     return st
 
 
-def layer_step(sste, st, seed, i):
+def layer_step(sste, st, seed, i, project=True):
     s = i % st.nsets
-    sste.project_pack(st.W, st.beta, st.dt, st.w_scale, vals=st.vals, meta=st.meta)
+    if project:
+        sste.project_pack(st.W, st.beta, st.dt, st.w_scale, vals=st.vals, meta=st.meta)
     sste.linear_fwd(st.Xs[s], st.vals, st.meta, st.O, st.dt, st.xs, st.w_scale, Z=st.Zs[s])
     sste.linear_wgrad(st.dYs[s], st.Xs[s], seed=seed, offset=i, dtype=st.gdt, dy_scale=st.dys, x_scale=st.xs,
                       dW=st.dWs[s], workspace=st.wss[s])
@@ -139,7 +140,9 @@ def kernel_table(sste, layers, kt, dtype):
 
     n_layers = len(layers)
     flops = sum(st.flops for st in layers) / n_layers                     # mean dense-equivalent flops per GEMM launch
-    pp_bytes = sum(st.O * st.I * (2 + st.esize / 2 + 0.125) for st in layers) / n_layers
+    # project + pack: one launch per layer, or one multi-tensor launch per step for a block of layers
+    pp_per_step = sum(st.O * st.I * (2 + st.esize / 2 + 0.125) for st in layers)
+    pp_bytes = pp_per_step * (kt["fwd"][1] / n_layers) / max(1, kt["project_pack"][1])
     mv_bytes = sum(st.T * st.O * st.esize * (1 + 0.5 + 0.0625) for st in layers if st.ws_bytes) / max(1, sum(1 for st in layers if st.ws_bytes))
     kernels = {}
     ms = avg_ms("project_pack")
@@ -198,9 +201,16 @@ def measure(sste, torch, np, WL, cfg, layer_sel, steps, warmup, sets, grad_e5m2,
     nsets = sets if sets > 0 else max(1, min(8, -(-(512 << 20) // set_bytes)))
     layers = [make_layer(sste, torch, np, WL, wl, i, nsets, grad_e5m2) for i in sel]
 
+    # The re-projection of every layer's weight is one multi-tensor launch at the head of the step (what the
+    # batch entry point is for: single layers are launch-bound); forward and weight gradient follow per layer.
+    batch = sste.PackBatch([st.W for st in layers], [st.beta for st in layers], layers[0].dt, [st.w_scale for st in layers],
+                           vals=[st.vals for st in layers], metas=[st.meta for st in layers]) if len(layers) > 1 else None
+
     def step(i):
+        if batch is not None:
+            batch.launch()
         for st in layers:
-            layer_step(sste, st, cfg, i)
+            layer_step(sste, st, cfg, i, project=batch is None)
 
     for i in range(warmup):
         step(i)

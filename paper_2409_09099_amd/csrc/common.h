@@ -92,23 +92,22 @@ __device__ __forceinline__ uint32_t e4m3_rne_pack(float lo, float hi) {
 __device__ __forceinline__ float clamp448(float x) { return __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f); }
 
 // ---- activation between the two FFN linears -----------------------------------------------------------
-// GELU in its tanh form, 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) -- the form of the GPT-2 models
-// whose layer shapes the workloads use (the paper does not name the activation).  float32 throughout;
-// tanh(u) = 1 - 2 / (exp(2u) + 1) on the hardware exp2 / reciprocal (about 1e-6 absolute).
-__device__ __forceinline__ float tanh_fast(float u) {
-  const float e = __builtin_amdgcn_exp2f(u * 2.8853900817779268f);       // exp(2u); inf / 0 at the ends give +-1 below
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+// GELU in its tanh form, 0.5 x (1 + tanh(u)), u = sqrt(2/pi) (x + 0.044715 x^3) -- the form of the GPT-2 models
+// whose layer shapes the workloads use (the paper does not name the activation).  Evaluated as x * s with
+// s = 0.5 (1 + tanh(u)) = 1 / (1 + exp(-2u)) on the hardware exp2 / reciprocal: float32, about 1e-6 absolute.
+// The ends behave: exp2 -> inf gives s = 0, exp2 -> 0 gives s = 1.
+__device__ __forceinline__ float gelu_sigmoid(float x, float x2) {
+  const float p = __builtin_fmaf(x2, 0.044715f, 1.0f);                    // 1 + 0.044715 x^2
+  const float e = __builtin_amdgcn_exp2f((x * p) * -2.3022081981f);       // exp(-2u): -2 sqrt(2/pi) log2(e) = -2.3022082
+  return __builtin_amdgcn_rcpf(1.0f + e);
 }
-__device__ __forceinline__ float gelu_tanh(float x) {
-  const float u = 0.7978845608028654f * (x + 0.044715f * (x * x * x));
-  return 0.5f * x * (1.0f + tanh_fast(u));
-}
-// d/dx of the above
+__device__ __forceinline__ float gelu_tanh(float x) { return x * gelu_sigmoid(x, x * x); }
+// d/dx: s + x s (1 - s) * 2 du/dx, du/dx = sqrt(2/pi) (1 + 3 * 0.044715 x^2)
 __device__ __forceinline__ float gelu_tanh_grad(float x) {
   const float x2 = x * x;
-  const float t = tanh_fast(0.7978845608028654f * (x + 0.044715f * (x2 * x)));
-  const float du = 0.7978845608028654f * (1.0f + 0.134145f * x2);       // 3 * 0.044715
-  return 0.5f * (1.0f + t) + 0.5f * x * ((1.0f - t * t) * du);
+  const float s = gelu_sigmoid(x, x2);
+  const float q = __builtin_fmaf(x2, 0.2140644488f, 1.5957691216f);       // 2 sqrt(2/pi) (1 + 0.134145 x^2)
+  return __builtin_fmaf(x * q, s - s * s, s);
 }
 __device__ __forceinline__ float bf16lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
