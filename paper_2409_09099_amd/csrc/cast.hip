@@ -11,10 +11,14 @@ __global__ void k_fill_u32_cast(uint32_t* p, uint32_t v) { *p = v; }
 // A lane converts 8 consecutive elements (16 bytes in, 8 bytes out) of kCastUnroll chunks per round, a
 // workgroup 256 x kCastUnroll consecutive chunks.  q = x / scale is a true float32 division; clamp to
 // the largest finite value; round to nearest even.
-// Largest magnitude: atomics on one address serialise in L2 (about 12 ns each), so a workgroup
-// publishes its maximum after its FIRST round -- those atomics then run under the streaming of the
-// remaining rounds -- and again at the end only if it can still raise the value, which is rare.
+// Largest magnitude: atomics on one address serialise in L2 (about 12 ns each; one per workgroup would be
+// 25 us for the 2048 workgroups of a large launch, as long as the streaming itself).  One workgroup in
+// kEarlyPublishStride therefore publishes its maximum after its FIRST round -- few atomics, which run under
+// the streaming of the remaining rounds and leave a value close to the tensor's maximum -- and every
+// workgroup publishes at its end only if it can still raise the value it reads, which is then rare
+// (a workgroup beats the maximum of a sample s times as large as its own share with probability 1/(s+1)).
 constexpr int kCastUnroll = 4;
+constexpr int kEarlyPublishStride = 16;
 
 __device__ __forceinline__ void publish_max(uint32_t m, uint32_t* __restrict__ amax_bits, uint32_t* wave_max) {
 #pragma unroll
@@ -71,7 +75,8 @@ k_cast_fp8(const uint8_t* __restrict__ X, int64_t R, int64_t chunks_per_row, int
       }
       if (STORE && base + u * 256 + threadIdx.x < n) *(uint2*)(Q + row[u] * ldq + col[u] * 8) = make_uint2(out[0], out[1]);
     }
-    if (amax_bits && first && base + stride < n) publish_max(amax, amax_bits, wave_max);   // uniform per workgroup
+    if (amax_bits && first && blockIdx.x % kEarlyPublishStride == 0 && base + stride < n)
+      publish_max(amax, amax_bits, wave_max);                                              // uniform per workgroup
     first = false;
   }
   if (amax_bits) publish_max(amax, amax_bits, wave_max);
