@@ -217,6 +217,69 @@ def test_project_pack_batch_bit_exact(sste, dtype):
             assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv), k
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
+def test_project_pack_batch_whole_model_sized_launch(sste, dtype):
+    """A launch of more than 2^18 blocks (the size from which the multi-tensor kernels write their packed
+    values with the streaming hint): one tensor is compared with the oracle, every tensor with the
+    single-tensor launch of the same weight and scale (itself held to the oracle above), bit for bit."""
+    wl = WL.WORKLOADS[3]
+    O, I = 4096, 1024
+    n = 66 if dtype == "bf16" else 130                        # 4096 / 2048 blocks per tensor
+    wbs = [WL.weight_bits(wl, 0, O=O, I=I), WL.weight_bits(wl, 1, O=O, I=I)]
+    Wsrc = [bf16_dev(w) for w in wbs]
+    Ws = [Wsrc[k % 2] for k in range(n)]                      # inputs are only read: tensors may share them
+    betas = [float(np.float32(1.0 + k / 256.0)) for k in range(n)]
+    scales = [1.0] * n if dtype == "bf16" else [float(np.float32(0.0005 * (1 + k % 7))) for k in range(n)]
+    batch = sste.PackBatch(Ws, betas, dt(sste, dtype), scales)
+    assert batch.total_blocks > (1 << 18)
+    for v, m in zip(batch.vals, batch.metas):
+        v.fill_(0x55)
+        m.fill_(0xAA)
+    vals, metas = batch.launch()
+    for k in range(n):
+        v1, m1 = sste.project_pack(Ws[k], betas[k], dt(sste, dtype), scales[k])
+        assert torch.equal(v1.view(torch.uint8), vals[k].view(torch.uint8)) and torch.equal(m1, metas[k]), k
+    k = n - 1
+    rv, rm, _ = (OP.project_pack(wbs[k % 2], np.float32(betas[k])) if dtype == "bf16"
+                 else OP.project_pack(wbs[k % 2], np.float32(betas[k]), "e4m3", np.float32(scales[k])))
+    fv, fm = OP.to_fragment_major(rv, rm, dtype)
+    assert np.array_equal(host(metas[k]).numpy().reshape(-1), fm)
+    assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv)
+
+
+@pytest.mark.parametrize("master", ["bf16", "f32"])
+def test_sgd_project_pack_batch_whole_model_sized_launch(sste, master):
+    """The fused update + re-projection in a launch of more than 2^18 blocks: every tensor equals the
+    single-tensor call on a copy of the same weight and gradient, bit for bit; one is held to the oracle."""
+    wl = WL.WORKLOADS[3]
+    O, I, n = 4096, 1024, 66
+    rng = np.random.default_rng(31)
+    wb = WL.weight_bits(wl, 0, O=O, I=I)
+    g = (rng.standard_normal((O, I)) * 2e-2).astype(np.float32)
+    w0 = wb if master == "bf16" else (F.bf16_to_f32(wb) + (rng.standard_normal((O, I)) * 1e-5).astype(np.float32))
+    W0 = bf16_dev(w0) if master == "bf16" else dev(w0)
+    G = dev(g)
+    Wd = [W0.clone() for _ in range(n)]
+    betas = [float(np.float32(1.0 + k / 256.0)) for k in range(n)]
+    alpha = 0.3
+    batch = sste.UpdateBatch(Wd, [G] * n, betas, sste.BF16, [1.0] * n)
+    assert batch.total_blocks > (1 << 18)
+    vals, metas = batch.launch(alpha)
+    for k in range(n):
+        Wk = W0.clone()
+        v1, m1 = sste.sgd_project_pack(Wk, G, alpha, betas[k], sste.BF16, 1.0)
+        assert torch.equal(Wk, Wd[k]) and torch.equal(v1, vals[k]) and torch.equal(m1, metas[k]), k
+    k = n - 1
+    w_next, rv, rm = OP.sgd_project_pack(w0, g, alpha, np.float32(betas[k]), master, "bf16", np.float32(1.0))
+    if master == "bf16":
+        assert np.array_equal(host(Wd[k]).view(torch.int16).numpy().view(np.uint16), w_next)
+    else:
+        assert np.array_equal(host(Wd[k]).numpy().view(np.uint32), w_next.view(np.uint32))
+    fv, fm = OP.to_fragment_major(rv, rm, "bf16")
+    assert np.array_equal(host(metas[k]).numpy().reshape(-1), fm)
+    assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv)
+
+
 @pytest.mark.parametrize("master", ["bf16", "f32"])
 @pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
 @pytest.mark.parametrize("case", ["cfg1", "ragged_strided", "alpha0"])
