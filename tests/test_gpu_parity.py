@@ -129,11 +129,16 @@ def test_project_pack_e4m3_bit_exact(sste, case):
     _, _, amax = OP.project_pack(wb, beta)
     scale = np.float32(amax / np.float32(448.0)) if case == "cfg1" else np.float32(0.37)
     vals, meta = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(scale))
-    rv, rm, _ = OP.project_pack(wb, beta, "e4m3", scale)
+    rv, rm, ra = OP.project_pack(wb, beta, "e4m3", scale)
     fv, fm = OP.to_fragment_major(rv, rm, "e4m3")
     assert np.array_equal(host(meta).numpy().reshape(-1), fm)
     got = host(vals).numpy().reshape(-1)
     assert np.array_equal(got, fv), np.argwhere(got != fv)[:5]
+    # the same call reporting the largest projected magnitude (another instantiation of the kernel)
+    amax_d = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    v2, m2 = sste.project_pack(bf16_dev(wb), float(beta), sste.F8E4M3, float(scale), amax_out=amax_d)
+    assert torch.equal(v2, vals) and torch.equal(m2, meta)
+    assert host(amax_d).numpy().view(np.uint32)[0] == np.float32(ra).view(np.uint32)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
@@ -152,6 +157,9 @@ def test_project_pack_threshold_interpolation_bit_exact(sste, dtype, gamma):
         assert np.array_equal(host(meta).numpy().reshape(-1), fm)
         assert np.array_equal(host(vals).numpy().view(fv.dtype).reshape(-1), fv)
         assert host(amax).numpy().view(np.uint32)[0] == np.float32(ra).view(np.uint32)
+        # without the largest magnitude (another instantiation of the kernel): the same packed form
+        v2, m2 = sste.project_pack(bf16_dev(wb), float(beta), dt(sste, dtype), float(scale), gamma=gamma)
+        assert torch.equal(v2, vals) and torch.equal(m2, meta)
     W = bf16_dev(WL.weight_bits(wl, 0))
     v0, m0 = sste.project_pack(W, 1.37)
     lib = sste.library()
@@ -247,12 +255,14 @@ def test_project_pack_batch_whole_model_sized_launch(sste, dtype):
     assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "e4m3"])
 @pytest.mark.parametrize("master", ["bf16", "f32"])
-def test_sgd_project_pack_batch_whole_model_sized_launch(sste, master):
+def test_sgd_project_pack_batch_whole_model_sized_launch(sste, master, dtype):
     """The fused update + re-projection in a launch of more than 2^18 blocks: every tensor equals the
     single-tensor call on a copy of the same weight and gradient, bit for bit; one is held to the oracle."""
     wl = WL.WORKLOADS[3]
-    O, I, n = 4096, 1024, 66
+    O, I, n = 4096, 1024, (66 if dtype == "bf16" else 130)
+    vscale = 1.0 if dtype == "bf16" else float(np.float32(0.0007))
     rng = np.random.default_rng(31)
     wb = WL.weight_bits(wl, 0, O=O, I=I)
     g = (rng.standard_normal((O, I)) * 2e-2).astype(np.float32)
@@ -262,20 +272,20 @@ def test_sgd_project_pack_batch_whole_model_sized_launch(sste, master):
     Wd = [W0.clone() for _ in range(n)]
     betas = [float(np.float32(1.0 + k / 256.0)) for k in range(n)]
     alpha = 0.3
-    batch = sste.UpdateBatch(Wd, [G] * n, betas, sste.BF16, [1.0] * n)
+    batch = sste.UpdateBatch(Wd, [G] * n, betas, dt(sste, dtype), [vscale] * n)
     assert batch.total_blocks > (1 << 18)
     vals, metas = batch.launch(alpha)
     for k in range(n):
         Wk = W0.clone()
-        v1, m1 = sste.sgd_project_pack(Wk, G, alpha, betas[k], sste.BF16, 1.0)
+        v1, m1 = sste.sgd_project_pack(Wk, G, alpha, betas[k], dt(sste, dtype), vscale)
         assert torch.equal(Wk, Wd[k]) and torch.equal(v1, vals[k]) and torch.equal(m1, metas[k]), k
     k = n - 1
-    w_next, rv, rm = OP.sgd_project_pack(w0, g, alpha, np.float32(betas[k]), master, "bf16", np.float32(1.0))
+    w_next, rv, rm = OP.sgd_project_pack(w0, g, alpha, np.float32(betas[k]), master, dtype, np.float32(vscale))
     if master == "bf16":
         assert np.array_equal(host(Wd[k]).view(torch.int16).numpy().view(np.uint16), w_next)
     else:
         assert np.array_equal(host(Wd[k]).numpy().view(np.uint32), w_next.view(np.uint32))
-    fv, fm = OP.to_fragment_major(rv, rm, "bf16")
+    fv, fm = OP.to_fragment_major(rv, rm, dtype)
     assert np.array_equal(host(metas[k]).numpy().reshape(-1), fm)
     assert np.array_equal(host(vals[k]).numpy().view(fv.dtype).reshape(-1), fv)
 
@@ -616,6 +626,9 @@ def test_linear_fwd_matches_oracle(sste, dtype, T, O, I):
     ("e4m3", 2100, 1040, 256),       # 256 x 128 four-wave tiles
     ("bf16", 16424, 528, 128),       # pipelined 256 x 256 tiles, ragged tails
     ("e4m3", 33344, 272, 128),       # two tile shapes in one grid
+    ("bf16", 2100, 1040, 128),       # 256 x 128 four-wave tiles, bf16 operands
+    ("bf16", 33344, 272, 128),       # two tile shapes in one grid, bf16 operands
+    ("e4m3", 16424, 528, 128),       # pipelined 256 x 256 tiles, 8-bit operands
 ])
 def test_linear_fwd_e4m3_output_and_amax(sste, dtype, T, O, I):
     """The forward product cast to e4m3 where it is produced (Sec. 5.2) and its largest magnitude.  Both sides
@@ -810,6 +823,19 @@ def test_linear_wgrad_strided_output_and_errors(sste):
     with pytest.raises(sste.SsteError) as ei:
         sste.linear_wgrad(dY, X, 0, 0)
     assert ei.value.status == 2
+
+
+def test_linear_wgrad_of_an_empty_batch(sste):
+    """T = 0: the sum over no tokens is zero -- dW is cleared (its padding columns are not), or left as it
+    is when the call accumulates."""
+    O, I = 48, 40
+    dY = torch.empty((0, O), dtype=torch.bfloat16, device="cuda")
+    X = torch.empty((0, I), dtype=torch.bfloat16, device="cuda")
+    big = torch.full((O, I + 8), 2.5, dtype=torch.float32, device="cuda")
+    sste.linear_wgrad(dY, X, 1, 2, dW=big[:, :I], accumulate=True)
+    assert bool((big == 2.5).all())
+    sste.linear_wgrad(dY, X, 1, 2, dW=big[:, :I])
+    assert bool((big[:, :I] == 0.0).all()) and bool((big[:, I:] == 2.5).all())
 
 
 # ------------------------------------------------------------------------------------------ strided operands, large-problem kernels
