@@ -157,6 +157,20 @@ __device__ __forceinline__ void dma_b32(i32x4 rsrc, uint32_t lds_addr, uint32_t 
                : "memory", "m0");
 }
 #pragma clang diagnostic pop
+// XOR key of the LDS tiles that are read with the transposing loads (ds_read_b64_tr_b16 / _b8): the X tile of
+// the weight-gradient GEMM and the expanded S(W) tile of the input-gradient GEMM.  A tile row (one index of the
+// contraction) is 512 B (bf16) or 256 B (8-bit), so every row starts at bank 0, and the 32-byte (16-byte) unit
+// u of row r is stored at position u ^ x_swizzle(r).  One transposing read gathers, per 16 lanes, 4 (8)
+// consecutive rows with the four lane quarters 8 (16) rows apart; the units of one such read must fall on
+// different banks, and so must the 16 consecutive rows that 16 lanes of the input-gradient kernel write at
+// once.  bf16: bits (r0, r1, r3) pick the 32-byte bank group, r2 the half of the row.  8-bit: bits
+// (r0, r1, r2, r3 ^ r4).  (With r % 16 as the key the lane quarters of a read collided pairwise: bank
+// conflicts were 25...45 % of these kernels' LDS cycles.)
+template <bool FP8>
+__device__ __forceinline__ int x_swizzle(int r) {
+  return FP8 ? ((r & 7) | ((((r >> 3) ^ (r >> 4)) & 1) << 3))
+             : ((r & 3) | (((r >> 3) & 1) << 2) | (((r >> 2) & 1) << 3));
+}
 __device__ __forceinline__ i32x4 rsrc_words(const void* base, uint32_t bytes) {
   uint64_t p = (uint64_t)base;
   i32x4 r;

@@ -13,8 +13,10 @@
 //     values plus their position bits into registers, expands every group of four (two values, two
 //     2-bit positions -> four bf16) and writes dense rows [channel][feature] into a three-slot LDS
 //     ring, in the layout and swizzle the weight-gradient GEMM uses for X (512-byte rows, 32-byte
-//     feature pair p of row r at position p ^ (r % 16)).  The contraction index is strided there, so
-//     the fragments are read with the transposing LDS load (ds_read_b64_tr_b16).
+//     feature pair p of row r at position p ^ x_swizzle(r), see common.h; here the two 16-byte halves
+//     of a pair also swap places in rows with bit 2 set, which spreads the expansion's 16-byte writes
+//     over all banks).  The contraction index is strided there, so the fragments are read with the
+//     transposing LDS load (ds_read_b64_tr_b16).
 // Pipeline per k-step s: wait for everything issued during s - 1 (grad_Z tile s + 1 in LDS, packed
 // blocks s + 2 in registers), barrier, decode blocks s + 2 into LDS, then eight groups of MFMAs during
 // which the grad_Z fragments of s + 1 are read (register double buffer), the S(W) fragments roll one
@@ -26,7 +28,7 @@
 // grad_Z row of the tile is again 128 bytes and both LDS rings keep their size.  One
 // v_mfma_f32_16x16x128_f8f6f4 per tile and k-step; the only layout requirement of that instruction
 // used here is that byte e of lane (., q) of both operands is the same channel.  The decoded tile has
-// 256-byte channel rows of 16-byte feature chunks (chunk c of row r at position c ^ (r % 16)), read
+// 256-byte channel rows of 16-byte feature chunks (chunk c of row r at position c ^ x_swizzle(r)), read
 // with ds_read_b64_tr_b8; a group expands with one byte permute.
 #include "common.h"
 
@@ -120,7 +122,10 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
     pm_off[e] = live ? (uint32_t)((rbl * isteps + cs) * MBLK + lane * (MBLK / 64)) : 0x80000000u;
     // the lane's 32 dense bytes: bf16 one 32-byte feature pair, e4m3 two 16-byte chunks (second at ^ 16)
     const int row = 16 * rbl + j, p = FP8 ? 8 * csl + 2 * q : 4 * csl + q;
-    dec_off[e] = (uint32_t)(row * AROW + ((p ^ (row & 15)) * (FP8 ? 16 : 32)));
+    // bf16: the two 16-byte halves of the pair swap places in rows with bit 2 set, so that the 16 lanes
+    // (16 consecutive rows) of one write cover all sixteen 16-byte bank groups
+    dec_off[e] = FP8 ? (uint32_t)(row * AROW + ((p ^ x_swizzle<true>(row)) * 16))
+                     : (uint32_t)(row * AROW + ((p ^ x_swizzle<false>(row)) * 32) + 16 * ((row >> 2) & 1));
   }
   uint4 pk[2], pk2[2];                // packed blocks in flight / being expanded (second set: 256 x 128 tile only)
   uint32_t pmeta[2], pmeta2[2];
@@ -154,7 +159,7 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
     }                                                                                                     \
     if ((g) == 3) {                                                                                       \
       uint8_t* dst_ = smemA + (slot_) * ASLOT + dec_off[e];                                               \
-      uint8_t* dst2_ = smemA + (slot_) * ASLOT + (FP8 ? (dec_off[e] ^ 16u) : (dec_off[e] + 16u));         \
+      uint8_t* dst2_ = smemA + (slot_) * ASLOT + (dec_off[e] ^ 16u);                                      \
       *(uint4*)dst_ = make_uint4(dec[0], dec[1], dec[2], dec[3]);                                         \
       *(uint4*)dst2_ = make_uint4(dec[4], dec[5], dec[6], dec[7]);                                        \
     }                                                                                                     \
@@ -182,10 +187,10 @@ __device__ __forceinline__ void dgrad_tile(uint8_t* smem, const uint8_t* __restr
   for (int r = 0; r < 4; r++) {
     if (FP8) {
       int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
-      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ (row & 15)) * 16) + 8 * (j & 1));
+      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ x_swizzle<true>(row)) * 16) + 8 * (j & 1));
     } else {
       int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
-      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+      fa_off[r] = (uint32_t)(row * AROW + (((8 * wm) ^ x_swizzle<false>(row)) * 32) + ((((j & 3) >> 1) ^ ((row >> 2) & 1)) * 16) + 8 * (j & 1));
     }
   }
   const int rb0 = 16 * NI_ * wn + j;

@@ -163,8 +163,9 @@ hipError_t launch_mvue_materialize(const void* dY, int64_t T, int64_t O, int64_t
 // groups, separate three-slot rings for the two operands, one barrier per k-step.
 // X tile in LDS: one row per token, 512 B (bf16: 256 features) or 256 B (fp8) whatever the tile width;
 // narrower tiles leave the tail of each row unused.  32-byte feature pair p (bf16) / 16-byte chunk c
-// (fp8) of token row r is stored at position p ^ (r % 16): the transposing reads below, which gather
-// 4 (8) token rows x 16 features per 16 lanes, then hit distinct banks.
+// (fp8) of token row r is stored at position p ^ x_swizzle(r) (common.h), which keeps the transposing
+// reads below -- 4 (8) consecutive token rows x 16 features per 16 lanes, the four lane quarters 8 (16)
+// rows apart -- off each other's banks.
 
 template <bool FP8, int MI_, int NI_, bool BF8>
 __global__ void __launch_bounds__(512, 1)
@@ -223,7 +224,7 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
   for (int i = 0; i < LB; i++) {
     int wl = LB * wave + i;
     int r = RPL * wl + lane / CPR, cs = lane % CPR;          // token row inside the k-step, stored chunk
-    int c = FP8 ? (cs ^ (r & 15)) : ((((cs >> 1) ^ (r & 15)) << 1) | (cs & 1));   // source chunk
+    int c = FP8 ? (cs ^ x_swizzle<true>(r)) : ((((cs >> 1) ^ x_swizzle<false>(r)) << 1) | (cs & 1));   // source chunk
     // chunks past the last feature column of the tile must read as zeros
     offb[i] = (c * 16 < cols_b * EB) ? (uint32_t)(r * ldx_bytes + c * 16) : 0x80000000u;
   }
@@ -269,10 +270,10 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
       int p = NI_ * wn + ni;                                      // feature pair (bf16) / chunk (fp8) of the tile
       if (FP8) {
         int row = 16 * q + 8 * (r & 1) + 64 * (r >> 1) + (j >> 1);
-        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ (row & 15)) * 16) + 8 * (j & 1));
+        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ x_swizzle<true>(row)) * 16) + 8 * (j & 1));
       } else {
         int row = 8 * q + 4 * (r & 1) + 32 * (r >> 1) + (j >> 2);
-        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ (row & 15)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
+        fb_off[ni][r] = (uint32_t)(row * ROWB + ((p ^ x_swizzle<false>(row)) * 32) + ((j & 3) >> 1) * 16 + 8 * (j & 1));
       }
     }
 
