@@ -171,7 +171,8 @@ template <bool FP8, int MI_, int NI_, bool BF8>
 __global__ void __launch_bounds__(512, 1)
 k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int64_t O, int64_t total_steps,
              const uint8_t* __restrict__ X, int64_t I, int64_t ldx_bytes, int steps_per_split, float scale,
-             int accumulate, float* __restrict__ out, int64_t ld_out, int64_t split_stride, int m_tiles, int n_tiles) {
+             int accumulate, float* __restrict__ out, int64_t ld_out, int64_t split_stride, int m_tiles, int n_tiles,
+             int features_fastest) {
   constexpr int WN = 4, NW = 8, NR = 3;
   constexpr int BM = 32 * MI_, BN = 64 * NI_;
   constexpr int EB = FP8 ? 1 : 2;
@@ -191,11 +192,13 @@ k_wgrad_gemm(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta,
   uint8_t* const smemA = smem;
   uint8_t* const smemB = smem + NR * ASTAGE;
 
-  // tile order: XCD x owns a contiguous range of (tile, split) units, channel tiles fastest
+  // tile order: XCD x owns a contiguous range of (tile, split) units; inside a split either the channel
+  // tiles or the feature tiles run fastest (the host picks what costs the XCD's L2 fewer operand bytes)
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
   const int tiles = m_tiles * n_tiles;
   const int z = logical / tiles, tile = logical % tiles;
-  const int tm = tile % m_tiles, tn = tile / m_tiles;
+  const int tm = features_fastest ? tile / n_tiles : tile % m_tiles;
+  const int tn = features_fastest ? tile % n_tiles : tile / m_tiles;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -519,8 +522,23 @@ static void launch_wgrad_gemm_cfg(const void* vals, const void* meta, int64_t O,
                                   float* out, int64_t ld_out, int64_t split_stride, hipStream_t s) {
   int m_tiles = (int)((O + 32 * MI_ - 1) / (32 * MI_)), n_tiles = (int)((I + 64 * NI_ - 1) / (64 * NI_));
   dim3 grid((unsigned)(m_tiles * n_tiles * splits)), block(512);
+  // Tile order inside a split.  The workgroups of one XCD (an eighth of the grid, consecutive logical numbers)
+  // share an L2: with channel tiles fastest they cover many channel tiles of few feature tiles, with feature
+  // tiles fastest the other way round.  Each channel tile costs the XCD a slice of the packed operand
+  // (0.5625 bytes per element), each feature tile a slice of X (1 byte per element): take the cheaper order
+  // (measured 1...4 % on the layers where the choice differs from channel tiles fastest).
+  const int per_xcd = (m_tiles * n_tiles * splits + 7) / 8;
+  auto xcd_cost = [&](int fast, int slow, double fast_bytes, double slow_bytes) {
+    const int nfast = per_xcd < fast ? per_xcd : fast;
+    int nslow = (per_xcd + fast - 1) / fast;
+    if (nslow > slow) nslow = slow;
+    return nfast * fast_bytes + nslow * slow_bytes;
+  };
+  const double a_bytes = 32.0 * MI_ * 0.5625, x_bytes = 64.0 * NI_;
+  int features_fastest = xcd_cost(n_tiles, m_tiles, x_bytes, a_bytes) < xcd_cost(m_tiles, n_tiles, a_bytes, x_bytes) ? 1 : 0;
   SSTE_LAUNCH(SSTE_K_WGRAD, (k_wgrad_gemm<FP8, MI_, NI_, BF8>), grid, block, s, (const uint8_t*)vals, (const uint8_t*)meta, O, steps,
-              (const uint8_t*)X, I, ldx_bytes, steps_per_split, scale, accumulate, out, ld_out, split_stride, m_tiles, n_tiles);
+              (const uint8_t*)X, I, ldx_bytes, steps_per_split, scale, accumulate, out, ld_out, split_stride, m_tiles, n_tiles,
+              features_fastest);
 }
 
 static void launch_wgrad_gemm(bool fp8, bool bf8, int mi, int ni, const void* vals, const void* meta, int64_t O, int64_t steps,
