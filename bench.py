@@ -436,6 +436,33 @@ def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context):
             casts[name] = {"ms": ms, "GB_per_s": T * cols * 3 / ms * 1e-6, "frac_hbm_peak": T * cols * 3 / ms * 1e-6 / PEAK_HBM_GBS}
             del src, q
         out["cast_fp8"] = casts
+        # the forward product written as e4m3 where it is produced (Sec. 5.2: the next layer's operand), with its
+        # largest magnitude, beside the bf16 output the step uses: half the output bytes
+        outs = {}
+        for st in layers:
+            Z8 = torch.empty((st.T, st.O), dtype=torch.uint8, device="cuda")
+            amax = torch.empty(1, dtype=torch.float32, device="cuda")
+
+            def run8(i, st=st, Z8=Z8, amax=amax):
+                sste.linear_fwd_ex(st.Xs[i % st.nsets], st.vals, st.meta, st.O, st.dt, st.xs, st.w_scale, sste.F8E4M3, 1.0,
+                                   Z=Z8, amax_out=amax)
+
+            def run16(i, st=st):
+                sste.linear_fwd(st.Xs[i % st.nsets], st.vals, st.meta, st.O, st.dt, st.xs, st.w_scale, Z=st.Zs[i % st.nsets])
+            row = {}
+            for key, fn in (("bf16_out_ms", run16), ("e4m3_out_with_amax_ms", run8)):
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                f0 = time.perf_counter()
+                for i in range(20):
+                    fn(i)
+                torch.cuda.synchronize()
+                row[key] = (time.perf_counter() - f0) * 1e3 / 20
+            row["e4m3_out_frac_sparse_mfma_peak"] = st.flops / (row["e4m3_out_with_amax_ms"] * 1e-3) * 1e-12 / (2 * PEAK_DENSE_TFLOPS[wl.dtype])
+            outs[st.name] = row
+            del Z8
+        out["fwd_e4m3_output"] = outs
     if wl.cfg == 4:
         # workload 4: the dense weight moves a little every step and is re-projected with the frozen beta; the
         # fraction of positions whose kept / pruned state changes (flip rate, Sec. 3.3) is a sanity number
