@@ -3,9 +3,10 @@
 // Large problems run in three kernels on the caller's stream:
 //   1. k_mvue_pack: the estimator is applied once per group of four tokens and the result is written
 //      to the workspace as a packed 2:4 operand in sparse-MFMA fragment order (the format of
-//      include/sste.h with rows = output channels, columns = tokens).  It streams dY once: about
-//      100 vector instructions per group put the bf16 kernel at 73 % of the HBM copy rate, the e4m3
-//      kernel (twice the groups per byte) is bound by the vector pipe.
+//      include/sste.h with rows = output channels, columns = tokens).  It streams dY once: at about
+//      90 vector instructions per group (three of them quarter-rate 32-bit multiplies of the hash) the
+//      bf16 kernel runs at the rate of a plain copy, the e4m3 kernel (twice the groups per byte) is
+//      bound by the vector pipe.
 //   2. k_wgrad_gemm: sparse MFMA GEMM, rows = channels o, columns = input features i, contraction =
 //      tokens, split over the token axis.  The packed operand is loaded like the packed weight of the
 //      forward GEMM; X arrives with the contraction index strided (X is [t][i]) and its fragments are
@@ -15,7 +16,8 @@
 // Why not fuse the estimator into the GEMM's operand load everywhere: a GEMM tile that is N columns
 // wide re-derives every group I / N times.  With a 128-wide tile that is 6 to 40 times per group and
 // the vector pipe, not the matrix pipe or HBM, sets the time (measured: 176 us fused against 55 us
-// here for the 3072 x 768 layer at 8192 tokens).  The fused kernel (gemm_wgrad_fused.hip) is kept for
+// here for the 3072 x 768 layer at 8192 tokens; on the 5120 x 1280 layer a 256-wide tile would issue
+// five times the pre-pass's vector work, about 280 us against the 110 us of the whole GEMM).  The fused kernel (gemm_wgrad_fused.hip) is kept for
 // small problems, where one launch and no workspace matter more.
 #include "common.h"
 #include "mvue_device.h"
