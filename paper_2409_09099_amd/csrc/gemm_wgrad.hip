@@ -4,7 +4,7 @@
 //   1. k_mvue_pack: the estimator is applied once per group of four tokens and the result is written
 //      to the workspace as a packed 2:4 operand in sparse-MFMA fragment order (the format of
 //      include/sste.h with rows = output channels, columns = tokens).  It streams dY once: at about
-//      90 vector instructions per group (three of them quarter-rate 32-bit multiplies of the hash) the
+//      90 vector instructions per group (three of them half-rate 32-bit multiplies of the hash) the
 //      bf16 kernel runs at the rate of a plain copy, the e4m3 kernel (twice the groups per byte) is
 //      bound by the vector pipe.
 //   2. k_wgrad_gemm: sparse MFMA GEMM, rows = channels o, columns = input features i, contraction =
