@@ -578,6 +578,103 @@ def ffn_block(sste, torch, np, WL, cfg=4, iters=30):
                               "speedup_over_dense": ms_dense / ms}}
 
 
+def ffn_block_fp8(sste, torch, np, WL, cfg=5, iters=20, grad_e5m2=True):
+    """The same feed-forward step in the 8-bit recipe of Sec. 5.2 at workload 5's shapes: e4m3 weights and
+    activations, e5m2 (or e4m3) gradients, per-tensor scales taken from a calibration pass and then held (delayed
+    scaling: no value is read back inside the step).  X arrives as e4m3 (what the preceding layer's output stage
+    writes), dY as bf16 and is cast inside the step; fc1's epilogue writes the pre-activation (bf16, for the
+    backward pass) and the e4m3 activation; fc2's input-gradient epilogue applies the activation's derivative, and
+    its bf16 result is cast once for the two products that consume it.  Context: the dense bf16 block in torch at
+    the same shapes."""
+    wl = WL.WORKLOADS[cfg]
+    names = [l.name for l in wl.layers]
+    l1 = wl.layers[names.index("fc1")]
+    T, d, h = wl.T, l1.I, l1.O
+    gfmt, gmax = (sste.F8E5M2, FMT_MAX["e5m2"]) if grad_e5m2 else (sste.F8E4M3, FMT_MAX["e4m3"])
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits.view(np.int16))).cuda().view(torch.bfloat16)
+
+    def amax_of(t):
+        return float(sste.cast_fp8(t, 1.0, sste.F8E4M3, store=False)[1].cpu()[0])
+    W1, W2 = up(WL.weight_bits(wl, names.index("fc1"))), up(WL.weight_bits(wl, names.index("fc2")))
+    Xb = up(WL.activations(wl, names.index("fc1"))[0])
+    dYb = up(WL.output_gradient(wl, names.index("fc2"))[0])
+    beta = 1.4830322
+    f32 = lambda v: float(np.float32(v))
+    # calibration pass (untimed): the scales a window of earlier iterations would have left behind
+    xs = f32(amax_of(Xb) / 448.0)
+    X8, _ = sste.cast_fp8(Xb, xs, sste.F8E4M3)
+    del Xb
+    am = torch.zeros(1, dtype=torch.float32, device="cuda")
+    sste.project_pack(W1, beta, sste.BF16, 1.0, amax_out=am)
+    ws1 = f32(float(am.cpu()[0]) / 448.0)
+    sste.project_pack(W2, beta, sste.BF16, 1.0, amax_out=am)
+    ws2 = f32(float(am.cpu()[0]) / 448.0)
+    v1, m1 = sste.packed_buffers(h, d, sste.F8E4M3, "cuda")
+    v2, m2 = sste.packed_buffers(d, h, sste.F8E4M3, "cuda")
+    sste.project_pack(W1, beta, sste.F8E4M3, ws1, vals=v1, meta=m1)
+    sste.project_pack(W2, beta, sste.F8E4M3, ws2, vals=v2, meta=m2)
+    H = torch.empty((T, h), dtype=torch.bfloat16, device="cuda")
+    A16 = torch.empty_like(H)
+    sste.linear_fwd_act(X8, v1, m1, h, sste.F8E4M3, xs, ws1, H=H, A=A16)
+    a_scale = f32(1.25 * amax_of(A16) / 448.0)
+    del A16
+    A8 = torch.empty((T, h), dtype=torch.uint8, device="cuda")
+    dys = f32(1.25 * amax_of(dYb) / gmax)
+    dY8 = torch.empty((T, d), dtype=torch.uint8, device="cuda")
+    sste.cast_fp8(dYb, dys, gfmt, Q=dY8, amax_out=am)
+    dH = torch.empty((T, h), dtype=torch.bfloat16, device="cuda")
+    sste.linear_dgrad_act(dY8, v2, m2, h, H, gfmt, dys, ws2, dX=dH)
+    dhs = f32(1.25 * amax_of(dH) / gmax)
+    dH8 = torch.empty((T, h), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    dW1 = torch.empty((h, d), dtype=torch.float32, device="cuda")
+    dW2 = torch.empty((d, h), dtype=torch.float32, device="cuda")
+    wsb1 = torch.empty(max(16, sste.wgrad_workspace_bytes(T, h, d, gfmt)), dtype=torch.uint8, device="cuda")
+    wsb2 = torch.empty(max(16, sste.wgrad_workspace_bytes(T, d, h, gfmt)), dtype=torch.uint8, device="cuda")
+    amaxes = [torch.zeros(1, dtype=torch.float32, device="cuda") for _ in range(3)]
+
+    def step(i):
+        sste.project_pack(W1, beta, sste.F8E4M3, ws1, vals=v1, meta=m1)
+        sste.project_pack(W2, beta, sste.F8E4M3, ws2, vals=v2, meta=m2)
+        sste.linear_fwd_act(X8, v1, m1, h, sste.F8E4M3, xs, ws1, a_dtype=sste.F8E4M3, a_scale=a_scale, H=H, A=A8, amax_out=amaxes[0])
+        sste.linear_fwd(A8, v2, m2, d, sste.F8E4M3, a_scale, ws2, Z=Y)
+        sste.cast_fp8(dYb, dys, gfmt, Q=dY8, amax_out=amaxes[1])
+        sste.linear_dgrad_act(dY8, v2, m2, h, H, gfmt, dys, ws2, dX=dH)
+        sste.cast_fp8(dH, dhs, gfmt, Q=dH8, amax_out=amaxes[2])
+        sste.linear_wgrad(dY8, A8, seed=cfg, offset=2 * i, dtype=gfmt, dy_scale=dys, x_scale=a_scale, dW=dW2, workspace=wsb2)
+        sste.linear_wgrad(dH8, X8, seed=cfg, offset=2 * i + 1, dtype=gfmt, dy_scale=dhs, x_scale=xs, dW=dW1, workspace=wsb1)
+        sste.linear_dgrad(dH8, v1, m1, d, gfmt, dhs, ws1, dX=dX)
+
+    def timed(fn, n):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+    ms = timed(step, iters)
+    del H, A8, dH, dH8, dY8, Y, dX
+    Xr = (X8.float() * xs).to(torch.bfloat16).requires_grad_(True)     # any bf16 data of the shape: the context is a timing
+    W1r, W2r = W1.clone().requires_grad_(True), W2.clone().requires_grad_(True)
+
+    def dense(i):
+        Xr.grad = W1r.grad = W2r.grad = None
+        out = torch.nn.functional.gelu(Xr @ W1r.t(), approximate="tanh") @ W2r.t()
+        out.backward(dYb)
+    ms_dense = timed(dense, max(5, iters // 2))
+    flops = 6 * 2.0 * T * d * h
+    return {"workload": "cfg%d FFN block: fc1 %dx%d, GELU, fc2 %dx%d, %d tokens, e4m3 weights and activations, %s gradients, held scales"
+                        % (cfg, h, d, d, h, T, "e5m2" if grad_e5m2 else "e4m3"),
+            "ms_per_step": ms, "dense_equiv_TFLOP_per_s": flops / (ms * 1e-3) * 1e-12,
+            "dense_context": {"library": "torch.matmul + torch gelu(tanh) + autograd, bf16", "ms_per_step": ms_dense,
+                              "speedup_over_dense_bf16": ms_dense / ms}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -643,6 +740,8 @@ def main():
         out["secondary"] = secondary
     if not args.no_secondary:
         out["ffn_block"] = ffn_block(sste, torch, np, WL)
+        torch.cuda.empty_cache()
+        out["ffn_block_fp8"] = ffn_block_fp8(sste, torch, np, WL)
         torch.cuda.empty_cache()
     if not args.no_prune_model:
         out["prune_pack_model"] = prune_model(sste, torch)
