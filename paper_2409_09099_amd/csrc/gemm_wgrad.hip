@@ -83,6 +83,9 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
   const uint32_t gid_lo0 = (uint32_t)gid_base;
   const uint32_t hi_term = (uint32_t)(gid_base >> 32) * 0x9E3779B9u;
   const int q = kg / GPQ, g = kg % GPQ;
+  // 8-bit: the four token rows' dwords of four channels, transposed 4 x 4 bytes at a time (eight byte permutes
+  // for four groups): grp[k] holds channel 4 (e / 4) + k with token 0 in byte 0
+  uint32_t grp[4] = {0, 0, 0, 0};
 #pragma unroll
   for (int e = 0; e < CH; e++) {
     uint32_t x = draw_u32_pre(key.k0, key.k1, gid_lo0 + (uint32_t)e, hi_term);
@@ -90,12 +93,16 @@ k_mvue_pack(const uint8_t* __restrict__ dY, int64_t T, int64_t O, int64_t lddy_b
     int c = oc * CH + e;                           // channel inside the tile
     uint8_t* slot = sV + (c >> 4) * VPITCH + (16 * q + (c & 15)) * 16;
     if (FP8) {
-      uint32_t w0 = comp4(rdy[0], e >> 2), w1 = comp4(rdy[1], e >> 2), w2 = comp4(rdy[2], e >> 2), w3 = comp4(rdy[3], e >> 2);
-      // byte e % 4 of the four token rows -> one dword (token 0 in byte 0): three byte permutes
-      const uint32_t bsel = (uint32_t)(e & 3) | ((uint32_t)(4 + (e & 3)) << 8) | 0x0c0c0000u;
-      uint32_t t01 = __builtin_amdgcn_perm(w1, w0, bsel), t23 = __builtin_amdgcn_perm(w3, w2, bsel);
-      uint32_t gw = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
-      v = mvue_group_f8<BF8>(gw, x, nib);
+      if ((e & 3) == 0) {
+        uint32_t w0 = comp4(rdy[0], e >> 2), w1 = comp4(rdy[1], e >> 2), w2 = comp4(rdy[2], e >> 2), w3 = comp4(rdy[3], e >> 2);
+        uint32_t a01 = __builtin_amdgcn_perm(w1, w0, 0x05010400u), b01 = __builtin_amdgcn_perm(w1, w0, 0x07030602u);
+        uint32_t a23 = __builtin_amdgcn_perm(w3, w2, 0x05010400u), b23 = __builtin_amdgcn_perm(w3, w2, 0x07030602u);
+        grp[0] = __builtin_amdgcn_perm(a23, a01, 0x05040100u);
+        grp[1] = __builtin_amdgcn_perm(a23, a01, 0x07060302u);
+        grp[2] = __builtin_amdgcn_perm(b23, b01, 0x05040100u);
+        grp[3] = __builtin_amdgcn_perm(b23, b01, 0x07060302u);
+      }
+      v = mvue_group_f8<BF8>(grp[e & 3], x, nib);
       *(uint16_t*)(slot + 2 * g) = (uint16_t)v;
     } else {
       uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;

@@ -113,18 +113,20 @@ __device__ __forceinline__ uint32_t mvue_group_f8(uint32_t g, uint32_t x, uint32
     m2 = __builtin_amdgcn_cvt_f32_fp8(ga, 2), m3 = __builtin_amdgcn_cvt_f32_fp8(ga, 3);
   }
   Sel s = mvue_select(m0, m1, m2, m3, x);
-  // recorded elements: shift their code down to byte 0 (the conversion reads byte 0 only)
-  uint32_t sh0 = s.pos0 << 3, sh1 = s.pos1 << 3;
-  float mp0 = cvt8<BF8>(ga >> sh0), mp1 = cvt8<BF8>(ga >> sh1);
+  // the two recorded codes side by side in bytes 0 and 1 (one byte permute; selector bytes 0x0c give zero)
+  const uint32_t rec = __builtin_amdgcn_perm(g, g, s.pos0 | (s.pos1 << 8) | 0x0c0c0000u);
+  const uint32_t reca = rec & 0x7F7Fu;
+  float mp0, mp1;
+  if (BF8) mp0 = __builtin_amdgcn_cvt_f32_bf8((int)reca, 0), mp1 = __builtin_amdgcn_cvt_f32_bf8((int)reca, 1);
+  else mp0 = __builtin_amdgcn_cvt_f32_fp8((int)reca, 0), mp1 = __builtin_amdgcn_cvt_f32_fp8((int)reca, 1);
   // stored magnitudes: 0.5 * m_p where g_p is kept as it is, else 0.5 * h; all within the format's range
   bool own0 = (f2u(mp0) - 1u) >= f2u(s.h);
   bool own1 = (f2u(mp1) - 1u) >= f2u(s.h);
   float v0 = 0.5f * (own0 ? mp0 : s.h);
   float v1 = 0.5f * (own1 ? mp1 : s.h);
   uint32_t q = BF8 ? ((uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(v0, v1, 0, false) & 0xFFFFu) : e4m3_rne_pack(v0, v1);
-  uint32_t s0 = (g >> sh0) & 0x80u, s1 = (g >> sh1) & 0x80u;
   nib = s.pos0 | (s.pos1 << 2);
-  return q | s0 | (s1 << 8);
+  return q | (rec & 0x8080u);
 }
 __device__ __forceinline__ uint32_t mvue_group_e4m3(uint32_t g, uint32_t x, uint32_t& nib) {
   return mvue_group_f8<false>(g, x, nib);
