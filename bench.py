@@ -397,7 +397,7 @@ def prune_model(sste, torch, iters=20):
     return out
 
 
-def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context):
+def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context, output_variants=True):
     """Figures that are not part of `value`: the layer's third GEMM (input gradient, dense by the paper's
     choice), the 8-bit operand casts, the flip rate of workload 4, the vendor's dense GEMM as context."""
     out = {}
@@ -436,6 +436,7 @@ def extras(sste, torch, np, WL, cfg, layers, steps, grad_e5m2, dense_context):
             casts[name] = {"ms": ms, "GB_per_s": T * cols * 3 / ms * 1e-6, "frac_hbm_peak": T * cols * 3 / ms * 1e-6 / PEAK_HBM_GBS}
             del src, q
         out["cast_fp8"] = casts
+    if wl.dtype == "e4m3" and output_variants:
         # the forward product written as e4m3 where it is produced (Sec. 5.2: the next layer's operand), with its
         # largest magnitude, beside the bf16 output the step uses: half the output bytes
         outs = {}
@@ -726,7 +727,8 @@ def main():
               "ms_per_step_with_kernel_events", "frac_sparse_mfma_peak_whole_step", "kernels", "layers", "roofline", "roofline_row"):
         if k in head:
             out[k] = head[k]
-    out.update(extras(sste, torch, np, WL, args.config, layers, args.steps, args.grad_e5m2, args.dense_context))
+    out.update(extras(sste, torch, np, WL, args.config, layers, args.steps, args.grad_e5m2, args.dense_context,
+                      output_variants=not args.no_secondary))
     del layers
     torch.cuda.empty_cache()
 
