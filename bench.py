@@ -6,7 +6,7 @@ workload, back to back on one stream:
   project + scale + pack of W  ->  forward sparse GEMM  ->  MVUE weight-gradient sparse GEMM.
 The default (headline) workload is the largest one: the four linears of a GPT-2-774M block in the 8-bit
 format (e4m3 weights, activations and gradients, 32768 tokens).  The same measurement on the bf16 block
-(16384 tokens) and on the GPT-2-124M fc1 layer rides along in `secondary`.
+(16384 tokens), the GPT-2-350M FFN pair and the GPT-2-124M fc1 layer rides along in `secondary`.
 Prints ONE JSON line.  `value` = dense-equivalent TFLOP/s of forward + weight gradient of all layers
 (sum of 2 * 2*T*I*O flops) over the whole step time, pruning included.
 """
@@ -734,7 +734,7 @@ def main():
 
     if not args.no_secondary and args.layer < 0 and args.config == 5:
         secondary = {}
-        for cfg in (4, 2):
+        for cfg in (4, 3, 2):
             sec, sl = measure(sste, torch, np, WL, cfg, -1, max(20, args.steps // 2), args.warmup, 0, False, events, traffic)
             del sl
             torch.cuda.empty_cache()
