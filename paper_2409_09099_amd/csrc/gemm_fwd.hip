@@ -257,14 +257,16 @@ k_linear_fwd(const uint8_t* __restrict__ X, int64_t T, int64_t k_bytes, int64_t 
   wait_vmcnt<0>();
   __syncthreads();
   if (AMAX) {
-    uint32_t m = 0;
+    // float maxima of magnitudes: the absolute value is a free source modifier and two values go into one
+    // three-operand maximum (the accumulators are finite)
+    float mf = 0.0f;
 #pragma unroll
     for (int mi = 0; mi < MI; mi++)
 #pragma unroll
       for (int ni = 0; ni < NI; ni++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) m = max(m, f2u(acc[mi][ni][r]) & 0x7FFFFFFFu);
-    publish_tile_amax<NW>(m, out.amax_scale, out.amax_bits, (uint32_t*)smem);
+        for (int r = 0; r < 4; r++) mf = __builtin_fmaxf(mf, __builtin_fabsf(acc[mi][ni][r]));
+    publish_tile_amax<NW>(f2u(mf), out.amax_scale, out.amax_bits, (uint32_t*)smem);
   }
   uint8_t* eb = smem + wave * (64 * EPI_ROW);
   if (ZF8) {
@@ -505,14 +507,16 @@ __device__ __forceinline__ void fwd_pipe_tile(uint8_t* smem, const uint8_t* __re
   wait_vmcnt<0>();
   __syncthreads();
   if (AMAX) {
-    uint32_t m = 0;
+    // float maxima of magnitudes: the absolute value is a free source modifier and two values go into one
+    // three-operand maximum (the accumulators are finite)
+    float mf = 0.0f;
 #pragma unroll
     for (int mi = 0; mi < MI_; mi++)
 #pragma unroll
       for (int ni = 0; ni < NI_; ni++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) m = max(m, f2u(acc[mi][ni][r]) & 0x7FFFFFFFu);
-    publish_tile_amax<NW>(m, out.amax_scale, out.amax_bits, (uint32_t*)smem);
+        for (int r = 0; r < 4; r++) mf = __builtin_fmaxf(mf, __builtin_fabsf(acc[mi][ni][r]));
+    publish_tile_amax<NW>(f2u(mf), out.amax_scale, out.amax_bits, (uint32_t*)smem);
   }
   uint8_t* eb = smem + wave * (16 * NI_ * EROW);
   if (ZF8) {
