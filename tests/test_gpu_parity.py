@@ -465,6 +465,34 @@ def test_cast_fp8_bit_exact(sste, fmt, case):
         assert np.array_equal(codes, ref_codes)
 
 
+@pytest.mark.parametrize("fmt", ["e4m3", "e5m2"])
+def test_cast_fp8_every_finite_bf16_value(sste, fmt):
+    """Every finite bf16 pattern (both zeros, subnormals, the largest value) under scales with awkward
+    significands, inside and outside the range in which the kernel forms the quotient without a division
+    instruction sequence, at its edges, and far enough out that results saturate or vanish: codes are the
+    oracle's (a float32 division, then the encoder) for every one."""
+    pats = np.arange(65536, dtype=np.uint32)
+    pats = pats[(pats & 0x7F80) != 0x7F80].astype(np.uint16)               # no infinities, no NaNs
+    assert pats.size == 65280
+    xb = pats.reshape(255, 256)
+    X = bf16_dev(xb)
+    scales = [1.0, 0.012345679, 3.0000001e-5, 0.99999994, 1.9999999, 447.99997, 2.0 ** -40, 2.0 ** -41, 2.0 ** 40, 2.0 ** 41,
+              7.77e11, 1.7e-13, 2.0 ** -100, 3.1e30, 1.0000001, 5.960465e-8]
+    for sc in scales:
+        scale = np.float32(sc)
+        q, _ = sste.cast_fp8(X, float(scale), dt(sste, fmt))
+        codes, _ = F.cast_fp8(xb, scale, fmt)
+        got = host(q).numpy()
+        bad = np.argwhere(got != codes)
+        assert bad.size == 0, (float(scale), bad[:4], [hex(int(xb[tuple(b)])) for b in bad[:4]])
+    # a strided view takes the row-addressed instantiations through the same values
+    big = torch.zeros((255, 256 + 32), dtype=torch.bfloat16, device="cuda")
+    big[:, :256] = X
+    for sc in (0.012345679, 2.0 ** -41):
+        q, _ = sste.cast_fp8(big[:, :256], float(np.float32(sc)), dt(sste, fmt))
+        assert np.array_equal(host(q).numpy(), F.cast_fp8(xb, np.float32(sc), fmt)[0])
+
+
 def test_cast_fp8_empty_and_errors(sste):
     e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     q, amax = sste.cast_fp8(e, 1.0)
