@@ -493,6 +493,20 @@ def test_cast_fp8_every_finite_bf16_value(sste, fmt):
         assert np.array_equal(host(q).numpy(), F.cast_fp8(xb, np.float32(sc), fmt)[0])
 
 
+def test_cast_fp8_largest_magnitude_of_tiny_tensors(sste):
+    """The reported largest magnitude is exact also when it is a subnormal bf16 value or zero."""
+    for top in (0x0000, 0x0001, 0x007F, 0x0080, 0x8003):
+        xb = np.zeros((16, 64), dtype=np.uint16)
+        xb[3, 5] = top
+        xb[9, 60] = 0x8001 if top else 0x8000
+        _, amax = sste.cast_fp8(bf16_dev(xb), 1.0, sste.F8E4M3, store=False)
+        want = np.float32(np.max(np.abs(F.bf16_to_f32(xb))))
+        assert host(amax).numpy().view(np.uint32)[0] == want.view(np.uint32), hex(top)
+        q, amax2 = sste.cast_fp8(bf16_dev(xb), 1.0, sste.F8E4M3)
+        assert host(amax2).numpy().view(np.uint32)[0] == want.view(np.uint32), hex(top)
+        assert np.array_equal(host(q).numpy(), F.cast_fp8(xb, np.float32(1.0), "e4m3")[0])
+
+
 def test_cast_fp8_empty_and_errors(sste):
     e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     q, amax = sste.cast_fp8(e, 1.0)
