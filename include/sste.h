@@ -460,8 +460,9 @@ int sste_compute_beta_ex(const void* W, int64_t O, int64_t I, int64_t ldw, int k
  * the FP8 GEMMs are rescaled per tensor before they are cast; e4m3 for activations, e5m2 or e4m3 for
  * the output gradient).
  *
- *   Q[r][c] = RNE_fmt(clamp(X[r][c] / scale, +-max_fmt)),   one float32 division per element;
- *   *amax_out = max |X[r][c]| (exact; 0 for an empty tensor).
+ *   Q[r][c] = RNE_fmt(clamp(X[r][c] / scale, +-max_fmt)),   the quotient being the IEEE float32 division
+ *             (the kernel forms exactly that value; for 2^-40 <= scale <= 2^40 without a division sequence);
+ *   *amax_out = max |X[r][c]| (exact, subnormal values included; 0 for an empty tensor).
  *
  * The GEMM calls then take Q with x_scale / dy_scale = scale.  A caller that scales by the current
  * tensor calls once with Q == NULL (largest magnitude only), sets scale = amax / max_fmt, and calls
